@@ -1,0 +1,116 @@
+"""TEST INFRASTRUCTURE ONLY: CPU fp64 oracle for stride-2 transpose convolution.
+
+Only the tests, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py`` may
+import this package.  It shares nothing with the HIP library: no kernels, headers, helpers or
+tables.  The arithmetic lives in ``ukst_oracle.c`` (plain C, fp64); this module compiles it with
+gcc, loads it through ctypes and converts numpy arrays.
+
+``naive`` is the oracle of record (Algorithm 1 of the paper: bed-of-nails upsample, pad by P,
+stride-1 n x n window).  ``scatter`` and ``segregated`` (Algorithm 2 / Eqs. 1-4 / Sec. 3.4) are
+independent formulations used only to pin ``naive``.  Every function is pinned by
+``tests/test_oracle_pins.py``; none is "parity unpinned".
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ukst_oracle.c")
+_LIB = os.path.join(_HERE, "libukst_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (-O2, OpenMP).  Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        dp = ctypes.POINTER(ctypes.c_double)
+        ip = ctypes.POINTER(ctypes.c_int)
+        i = ctypes.c_int
+        lib.ukst_oracle_naive.argtypes = [dp, dp, dp, dp, i, i, i, i, i, i, i, ip, i]
+        lib.ukst_oracle_naive.restype = i
+        for f in (lib.ukst_oracle_scatter, lib.ukst_oracle_segregated):
+            f.argtypes = [dp, dp, dp, dp, i, i, i, i, i, i, i]
+            f.restype = i
+        lib.ukst_oracle_threads.restype = i
+        _lib = lib
+    return _lib
+
+
+def threads() -> int:
+    """Number of OpenMP threads the naive oracle will use."""
+    return int(_load().ukst_oracle_threads())
+
+
+def out_shape(H: int, W: int, n: int, P: int):
+    """Sec. 1: an N x N map gives (2N-n) x (2N-n); padding the upsampled map by P adds 2P."""
+    return 2 * H + 2 * P - n, 2 * W + 2 * P - n
+
+
+def _prep(x, w):
+    x = np.ascontiguousarray(np.asarray(x, dtype=np.float64))
+    w = np.ascontiguousarray(np.asarray(w, dtype=np.float64))
+    if x.ndim != 4 or w.ndim != 4 or w.shape[2] != w.shape[3] or w.shape[1] != x.shape[1]:
+        raise ValueError("expected x[B,Cin,H,W] and w[Cout,Cin,n,n]")
+    return x, w
+
+
+def _dp(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _call(name, x, w, P, planes=None):
+    x, w = _prep(x, w)
+    B, Cin, H, W = x.shape
+    Cout, _, n, _ = w.shape
+    OH, OW = out_shape(H, W, n, P)
+    if OH < 1 or OW < 1 or P < 0:
+        raise ValueError("empty output")
+    y = np.zeros((B, Cout, OH, OW), dtype=np.float64)
+    S = np.zeros_like(y)
+    lib = _load()
+    if name == "naive":
+        if planes is None:
+            rc = lib.ukst_oracle_naive(_dp(x), _dp(w), _dp(y), _dp(S), B, Cin, Cout, H, W, n, P,
+                                       None, 0)
+        else:
+            pl = np.ascontiguousarray(np.asarray(planes, dtype=np.int32))
+            rc = lib.ukst_oracle_naive(_dp(x), _dp(w), _dp(y), _dp(S), B, Cin, Cout, H, W, n, P,
+                                       pl.ctypes.data_as(ctypes.POINTER(ctypes.c_int)), len(pl))
+    else:
+        rc = getattr(lib, "ukst_oracle_" + name)(_dp(x), _dp(w), _dp(y), _dp(S), B, Cin, Cout,
+                                                 H, W, n, P)
+    if rc != 0:
+        raise RuntimeError(f"oracle {name} failed with code {rc}")
+    return y, S
+
+
+def naive(x, w, P, planes=None):
+    """Oracle of record.  Returns (y, S) in fp64; S = sum |x*w| per output (tolerance scale).
+
+    ``planes``: optional list of plane ids b*Cout+co; other planes of the result stay zero.
+    """
+    return _call("naive", x, w, P, planes)
+
+
+def scatter(x, w, P):
+    """Check-only formulation: each input pixel adds x*w at stride 2."""
+    return _call("scatter", x, w, P)
+
+
+def segregated(x, w, P):
+    """Check-only formulation: four parity sub-kernels selected per output pixel."""
+    return _call("segregated", x, w, P)
