@@ -1,0 +1,185 @@
+#!/usr/bin/env python3
+"""Benchmark of the ukst hot path on one MI355X.
+
+One "step" is one call of ukst_conv_transpose2d on the headline workload (cfg2a: 16 images of
+224x224x3, n = 3, P = 0, odd 445x445 output -- the paper's dataset shape), with inputs resident
+in HBM.  Steps rotate over enough distinct (x, y) buffer sets to exceed the 256 MB last-level
+cache, so every launch reads its input from, and writes its output to, HBM.
+
+Prints ONE JSON line.  Besides the contract fields it carries
+  roofline      for the headline kernel (algorithmic bytes / average launch duration from HIP
+                events on the launch stream, against the 8 TB/s HBM peak),
+  cpu_baseline  the fp64 CPU oracle timed on this machine's host cores on the same workload,
+  per_config    the same measurements for every other benchmark configuration (each against the
+                roofline that bounds it).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+PEAK_TFLOPS = {"mfma_bf16": 2500.0, "mfma_f32": 157.3, "alu_f32": 78.6}
+LLC_BYTES = 256 << 20
+
+HEADLINE = "cfg2a"
+# which roofline bounds each configuration (algorithmic intensity vs. the ridge)
+BOUND = {"cfg1": "hbm", "cfg2a": "hbm", "cfg2b": "hbm", "cfg3_L4": "hbm",
+         "cfg3_L1": "mfma_f32", "cfg3_L2": "mfma_f32", "cfg3_L3": "mfma_f32",
+         "cfg4a": "mfma_f32", "cfg4b": "mfma_f32", "cfg5a": "mfma_bf16", "cfg5b": "mfma_bf16"}
+
+
+def _device_tensors(w, data):
+    import numpy as np
+    import torch
+    if w.dtype == "bf16":
+        x = torch.from_numpy(data["x_bits"].view(np.int16)).view(torch.bfloat16).cuda()
+        k = torch.from_numpy(data["w_bits"].view(np.int16)).view(torch.bfloat16).cuda()
+    else:
+        x, k = torch.from_numpy(data["x"]).cuda(), torch.from_numpy(data["w"]).cuda()
+    return x, k
+
+
+def algorithmic_bytes(w, OH, OW):
+    es = 2 if w.dtype == "bf16" else 4
+    return (w.B * w.Cin * w.H * w.W * es + w.Cout * w.Cin * w.n * w.n * es
+            + w.B * w.Cout * OH * OW * 4)
+
+
+def measure(w, steps, warmup, rotate_bytes=LLC_BYTES + (64 << 20)):
+    """Time `steps` launches of workload w.  Returns a dict of rates."""
+    import torch
+    from paper_2502_20493_amd import binding as ukst
+    from paper_2502_20493_amd import workloads as wl
+
+    data = wl.generate(w)
+    x0, k = _device_tensors(w, data)
+    OH, OW = ukst.ukst_output_shape(w.H, w.W, w.n, w.P)
+    nbytes = algorithmic_bytes(w, OH, OW)
+    nsets = max(1, min(16, -(-rotate_bytes // nbytes)))
+    xs = [x0] + [x0.clone() for _ in range(nsets - 1)]
+    ys = [torch.empty((w.B, w.Cout, OH, OW), dtype=torch.float32, device="cuda")
+          for _ in range(nsets)]
+    dt = ukst.UKST_BF16_F32 if w.dtype == "bf16" else ukst.UKST_F32
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        ukst.ukst_conv_transpose2d(xs[i % nsets], k, w.P, y=ys[i % nsets], stream=stream)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for i in range(steps):
+        step(i)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ev_ms = e0.elapsed_time(e1)
+
+    exact = 2 * ukst.ukst_mac_count(w.B, w.Cin, w.Cout, w.H, w.W, w.n, w.P, 0)
+    nominal = 2 * ukst.ukst_mac_count(w.B, w.Cin, w.Cout, w.H, w.W, w.n, w.P, 1)
+    per_launch_s = ev_ms / 1e3 / steps
+    bound = BOUND.get(w.name, "hbm")
+    gflops = exact / per_launch_s / 1e9
+    gbs = nbytes / per_launch_s / 1e9
+    if bound == "hbm":
+        roof = {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None}
+    else:
+        peak = PEAK_TFLOPS[bound]
+        roof = {"bound": "mfma", "achieved": round(gflops / 1e3, 2), "peak": peak,
+                "unit": "TFLOP/s", "frac": round(gflops / 1e3 / peak, 4), "traffic": None}
+    roof["kernel"] = ukst.ukst_kernel_name(w.B, w.Cin, w.Cout, w.H, w.W, w.n, w.P, dt)
+    roof["us_per_launch"] = round(per_launch_s * 1e6, 2)
+    roof["algorithmic_bytes"] = nbytes
+    return {
+        "workload": w.name, "shape": f"B{w.B} {w.Cin}->{w.Cout} {w.H}x{w.W} n{w.n} P{w.P} {w.dtype}",
+        "out": f"{OH}x{OW}", "useful_gflops": round(gflops, 1),
+        "nominal_gflops": round(nominal / per_launch_s / 1e9, 1),
+        "out_gpixels": round(w.B * w.Cout * OH * OW / per_launch_s / 1e9, 3),
+        "gbs": round(gbs, 1), "us": round(per_launch_s * 1e6, 2),
+        "wall_ms_per_step": wall_ms / steps, "buffer_sets": nsets, "roofline": roof,
+        "_data": data, "_exact_flop": exact,
+    }
+
+
+def cpu_baseline(w, data):
+    """Time the CPU oracle (as it stands) on the headline workload, all host cores."""
+    import oracle
+    from paper_2502_20493_amd import binding as ukst
+    t0 = time.perf_counter()
+    oracle.naive(data["x"], data["w"], w.P)
+    dt = time.perf_counter() - t0
+    exact = 2 * ukst.ukst_mac_count(w.B, w.Cin, w.Cout, w.H, w.W, w.n, w.P, 0)
+    return {"value": round(exact / dt / 1e9, 3), "unit": "GFLOP/s", "cores": oracle.threads(),
+            "kind": "oracle", "seconds": round(dt, 3),
+            "sample": f"full {w.name} batch ({w.B} images), naive fp64 Algorithm 1, "
+                      f"useful FLOPs counted as for the GPU"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--configs", default="all",
+                    help="'all', 'none' or comma-separated extra configs for per_config")
+    ap.add_argument("--only", default=None, help="time just this workload as the headline")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path shards by batch with no "
+              "exchange; no multi-GPU figure is produced). Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2502_20493_amd import build as b
+    from paper_2502_20493_amd import workloads as wl
+    if not os.path.exists(b.LIB):
+        b.build_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+
+    head = wl.WORKLOADS[args.only or HEADLINE]
+    m = measure(head, args.steps, args.warmup)
+    data = m.pop("_data")
+    m.pop("_exact_flop")
+    cpu = None if args.no_cpu else cpu_baseline(head, data)
+    del data
+
+    per = []
+    if args.configs != "none" and not args.only:
+        names = [n for n in wl.WORKLOADS if n not in (HEADLINE, "cfg1_int")] \
+            if args.configs == "all" else args.configs.split(",")
+        for name in names:
+            w = wl.WORKLOADS[name]
+            r = measure(w, max(5, min(args.steps, 30)), max(2, min(args.warmup, 5)))
+            r.pop("_data"); r.pop("_exact_flop")
+            per.append(r)
+            torch.cuda.empty_cache()
+
+    line = {
+        "metric": "useful (zero-free) GFLOP/s", "value": m["useful_gflops"], "unit": "GFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(m["wall_ms_per_step"], 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32" if head.dtype == "f32" else "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{head.name}: {m['shape']} -> {m['out']}",
+                   "buffer_sets_rotated": m["buffer_sets"],
+                   "out_gpixels_per_s": m["out_gpixels"], "nominal_gflops": m["nominal_gflops"]},
+        "roofline": m["roofline"], "cpu_baseline": cpu,
+        "per_config": [{k: v for k, v in r.items() if k != "wall_ms_per_step"} for r in per],
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,124 @@
+/*
+ * ukst -- unified kernel-segregated stride-2 2-D transpose convolution for AMD MI355X (gfx950).
+ *
+ * C ABI, stateless: no allocation, no cached weights, no synchronisation inside any call.
+ *
+ * What is computed (Algorithm 1 of the paper is the definition, Algorithm 2 + Eqs. 1-4 + the
+ * padding rule of Sec. 3.4 are how it is evaluated):
+ *
+ *   the input map is zero-inserted ("bed of nails") to (2H-1) x (2W-1), zero-padded by P on every
+ *   side, and an n x n window slides over it with stride 1 and NO kernel flip:
+ *
+ *     y[b,co,oy,ox] = sum_ci sum_{a<n} sum_{c<n} U_P[b,ci,oy+a,ox+c] * w[co,ci,a,c]
+ *     OH = 2H + 2P - n,  OW = 2W + 2P - n          (Sec. 1: (2N-n) x (2N-n) for P = 0)
+ *
+ *   The kernels never build U_P.  Each output pixel selects, from the parity of (oy+P, ox+P), one
+ *   of the four sub-kernels k_rs[u][v] = w[r+2u][s+2v] (sizes ceil/floor(n/2), Sec. 3.1-3.2) and
+ *   reads only the original input; the reduced padding floor(P/2) of Sec. 3.4 is a bounds
+ *   predicate.  Odd output sizes are produced exactly: nothing is computed into, or stored to,
+ *   elements outside [0,OH) x [0,OW) (Sec. 1, Sec. 3.4).
+ *
+ * Stride is 2, dilation 1, groups 1, no bias, no output padding: none of these appear in the paper.
+ */
+#ifndef UKST_H
+#define UKST_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Element types.  Accumulation is always fp32. */
+typedef enum {
+    UKST_F32 = 0,      /* x, w, y are IEEE fp32 */
+    UKST_BF16_F32 = 1  /* x, w are bfloat16 (upper half of an fp32), y is fp32, stored unrounded */
+} ukst_dtype;
+
+typedef enum {
+    UKST_OK = 0,
+    UKST_ERR_NULL = 1,        /* x, w, y (or an output pointer) is NULL */
+    UKST_ERR_SHAPE = 2,       /* a dimension < 1, P < 0, or an empty output (2H+2P-n < 1 ...) */
+    UKST_ERR_DTYPE = 3,       /* dtype is not a ukst_dtype */
+    UKST_ERR_UNSUPPORTED = 4, /* n > UKST_MAX_N, unknown path id, or path cannot run this shape */
+    UKST_ERR_LAUNCH = 5       /* the HIP runtime reported an error at launch */
+} ukst_status;
+
+/* Kernel families ("paths").  UKST_PATH_AUTO picks by channel width. */
+typedef enum {
+    UKST_PATH_AUTO = 0,
+    UKST_PATH_DIRECT = 1, /* one thread = one 2x2 output quad (all four parity classes), input tile
+                             + halo staged once in LDS; any shape, either dtype */
+    UKST_PATH_MFMA = 2    /* parity-class implicit GEMM on the matrix cores, wide channels */
+} ukst_path;
+
+#define UKST_MAX_N 7 /* largest kernel side compiled in */
+
+/* Library version: major*10000 + minor*100 + patch. */
+int ukst_version(void);
+
+/* Static, NUL-terminated description of a ukst_status value (never NULL). */
+const char* ukst_status_string(int status);
+
+/*
+ * Output size of Sec. 1 / Fig. 2: *OH = 2H+2P-n, *OW = 2W+2P-n.
+ * Host arithmetic only.  Returns UKST_ERR_NULL, UKST_ERR_SHAPE (as above) or UKST_OK.
+ */
+int ukst_output_shape(int H, int W, int n, int P, int* OH, int* OW);
+
+/*
+ * Multiply-accumulate counts of one call (host arithmetic only; 0 on invalid shapes).
+ *   kind 0: exact   -- products of an in-range input pixel with a kernel tap (no bed-of-nails
+ *                      zero and no padding zero is counted); this is the "useful" work.
+ *   kind 1: nominal -- what Algorithm 2 executes with its floor(P/2) padding: every tap of the
+ *                      selected sub-kernel for every output pixel (25 per 2x2 outputs for n = 5,
+ *                      Sec. 3.1).
+ *   kind 2: naive   -- what Algorithm 1 executes: n*n per output pixel.
+ */
+unsigned long long ukst_mac_count(int B, int Cin, int Cout, int H, int W, int n, int P, int kind);
+
+/*
+ * The path UKST_PATH_AUTO resolves to for this problem (UKST_PATH_DIRECT or UKST_PATH_MFMA),
+ * or a negative ukst_status on invalid arguments.  Host arithmetic only.
+ */
+int ukst_select_path(int B, int Cin, int Cout, int H, int W, int n, int P, int dtype);
+
+/*
+ * Stride-2 transpose convolution, Algorithm 2 (unified kernel segregation).
+ *
+ *   x       DEVICE pointer, [B][Cin][H][W] contiguous (NCHW), element type per dtype, read-only
+ *   w       DEVICE pointer, [Cout][Cin][n][n] contiguous, same element type as x, read-only,
+ *           used as printed in Eqs. 1-4 (no flip; note torch's ConvTranspose2d weight is
+ *           [Cin][Cout][k][k] and flipped relative to this)
+ *   y       DEVICE pointer, [B][Cout][OH][OW] contiguous fp32, every element overwritten,
+ *           nothing outside it touched; must not overlap x or w
+ *   B..P    sizes as above; 1 <= n <= UKST_MAX_N, P >= 0 (any P, also P > n-1: windows that
+ *           meet no input give +0)
+ *   dtype   a ukst_dtype
+ *   stream  a hipStream_t (as void*), or NULL for the default stream
+ *
+ * Only element alignment is assumed (4 bytes fp32, 2 bytes bf16).  The caller owns all buffers;
+ * the call enqueues work on `stream` and returns without synchronising.  Arguments are validated
+ * on the host before anything touches the GPU; on any error nothing is launched.
+ * Returns a ukst_status.
+ */
+int ukst_conv_transpose2d(const void* x, const void* w, void* y, int B, int Cin, int Cout, int H,
+                          int W, int n, int P, int dtype, void* stream);
+
+/*
+ * Same operation with the kernel family forced (tests and benchmarks compare the families on one
+ * shape).  path = UKST_PATH_AUTO behaves exactly like ukst_conv_transpose2d.  Returns
+ * UKST_ERR_UNSUPPORTED if that family cannot run the shape.
+ */
+int ukst_conv_transpose2d_path(const void* x, const void* w, void* y, int B, int Cin, int Cout,
+                               int H, int W, int n, int P, int dtype, int path, void* stream);
+
+/*
+ * Name of the device kernel the given path launches for this problem, as it appears in a
+ * profiler's kernel trace (substring match), or "" on invalid arguments.  Static storage.
+ */
+const char* ukst_kernel_name(int B, int Cin, int Cout, int H, int W, int n, int P, int dtype,
+                             int path);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* UKST_H */

@@ -1,0 +1,133 @@
+"""Thin ctypes binding of libukst: same names as include/ukst.h, argument marshalling only.
+
+Every step of the computation runs in the HIP kernels behind the C ABI.  There is no CPU
+fallback: if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libukst.so")
+
+UKST_F32, UKST_BF16_F32 = 0, 1
+UKST_OK, UKST_ERR_NULL, UKST_ERR_SHAPE, UKST_ERR_DTYPE, UKST_ERR_UNSUPPORTED, UKST_ERR_LAUNCH = range(6)
+UKST_PATH_AUTO, UKST_PATH_DIRECT, UKST_PATH_MFMA = 0, 1, 2
+UKST_MAX_N = 7
+
+# every symbol include/ukst.h declares
+EXPORTS = ["ukst_version", "ukst_status_string", "ukst_output_shape", "ukst_mac_count",
+           "ukst_select_path", "ukst_conv_transpose2d", "ukst_conv_transpose2d_path",
+           "ukst_kernel_name"]
+
+_lib = None
+
+
+class UkstError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"ukst status {status}: {message}")
+        self.status = status
+
+
+def lib():
+    """Load libukst.so (once).  Raises if it is missing: build it with
+    ``python -m paper_2502_20493_amd.build`` (or ``__graft_entry__.build()``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: the HIP library has not been built "
+                "(python -m paper_2502_20493_amd.build). There is no fallback path.")
+        L = ctypes.CDLL(LIB_PATH)
+        i, vp = ctypes.c_int, ctypes.c_void_p
+        ip = ctypes.POINTER(ctypes.c_int)
+        L.ukst_version.argtypes, L.ukst_version.restype = [], i
+        L.ukst_status_string.argtypes, L.ukst_status_string.restype = [i], ctypes.c_char_p
+        L.ukst_output_shape.argtypes, L.ukst_output_shape.restype = [i, i, i, i, ip, ip], i
+        L.ukst_mac_count.argtypes = [i] * 8
+        L.ukst_mac_count.restype = ctypes.c_ulonglong
+        L.ukst_select_path.argtypes, L.ukst_select_path.restype = [i] * 8, i
+        L.ukst_conv_transpose2d.argtypes = [vp, vp, vp] + [i] * 8 + [vp]
+        L.ukst_conv_transpose2d.restype = i
+        L.ukst_conv_transpose2d_path.argtypes = [vp, vp, vp] + [i] * 9 + [vp]
+        L.ukst_conv_transpose2d_path.restype = i
+        L.ukst_kernel_name.argtypes, L.ukst_kernel_name.restype = [i] * 9, ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(status: int):
+    if status != UKST_OK:
+        raise UkstError(status, ukst_status_string(status))
+
+
+def ukst_version() -> int:
+    return int(lib().ukst_version())
+
+
+def ukst_status_string(status: int) -> str:
+    return lib().ukst_status_string(int(status)).decode()
+
+
+def ukst_output_shape(H: int, W: int, n: int, P: int):
+    oh, ow = ctypes.c_int(0), ctypes.c_int(0)
+    _check(lib().ukst_output_shape(H, W, n, P, ctypes.byref(oh), ctypes.byref(ow)))
+    return oh.value, ow.value
+
+
+def ukst_mac_count(B, Cin, Cout, H, W, n, P, kind: int) -> int:
+    return int(lib().ukst_mac_count(B, Cin, Cout, H, W, n, P, kind))
+
+
+def ukst_select_path(B, Cin, Cout, H, W, n, P, dtype) -> int:
+    r = int(lib().ukst_select_path(B, Cin, Cout, H, W, n, P, dtype))
+    if r < 0:
+        _check(-r)
+    return r
+
+
+def ukst_kernel_name(B, Cin, Cout, H, W, n, P, dtype, path=UKST_PATH_AUTO) -> str:
+    return lib().ukst_kernel_name(B, Cin, Cout, H, W, n, P, dtype, path).decode()
+
+
+def ukst_conv_transpose2d_raw(x_ptr, w_ptr, y_ptr, B, Cin, Cout, H, W, n, P, dtype,
+                              path=UKST_PATH_AUTO, stream_ptr=None) -> int:
+    """Direct call with raw device addresses (ints or None).  Returns the status code."""
+    return int(lib().ukst_conv_transpose2d_path(x_ptr, w_ptr, y_ptr, B, Cin, Cout, H, W, n, P,
+                                                dtype, path, stream_ptr))
+
+
+def ukst_conv_transpose2d(x, w, P: int, y=None, path: int = UKST_PATH_AUTO, stream=None):
+    """Marshal torch device tensors into ukst_conv_transpose2d.
+
+    x: [B,Cin,H,W] float32 or bfloat16, w: [Cout,Cin,n,n] same dtype, both contiguous on the GPU.
+    y: optional preallocated float32 [B,Cout,OH,OW]; allocated with torch when omitted.
+    The call is asynchronous on ``stream`` (default: torch's current stream).
+    """
+    import torch
+
+    if not (x.is_cuda and w.is_cuda):
+        raise ValueError("x and w must be device tensors")
+    if not (x.is_contiguous() and w.is_contiguous()):
+        raise ValueError("x and w must be contiguous")
+    if x.dtype != w.dtype or x.dtype not in (torch.float32, torch.bfloat16):
+        raise ValueError("x and w must both be float32 or both bfloat16")
+    if x.dim() != 4 or w.dim() != 4 or w.shape[2] != w.shape[3] or w.shape[1] != x.shape[1]:
+        raise ValueError("expected x[B,Cin,H,W] and w[Cout,Cin,n,n]")
+    B, Cin, H, W = x.shape
+    Cout, _, n, _ = w.shape
+    dtype = UKST_F32 if x.dtype == torch.float32 else UKST_BF16_F32
+    OH, OW = ukst_output_shape(H, W, n, P)
+    if y is None:
+        y = torch.empty((B, Cout, OH, OW), dtype=torch.float32, device=x.device)
+    elif (tuple(y.shape) != (B, Cout, OH, OW) or y.dtype != torch.float32
+          or not y.is_contiguous() or not y.is_cuda):
+        raise ValueError("y must be a contiguous float32 device tensor [B,Cout,OH,OW]")
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device)
+    sp = stream.cuda_stream if hasattr(stream, "cuda_stream") else stream
+    with torch.cuda.device(x.device):
+        _check(ukst_conv_transpose2d_raw(x.data_ptr(), w.data_ptr(), y.data_ptr(), B, Cin, Cout,
+                                         H, W, n, P, dtype, path, sp))
+    return y

@@ -1,0 +1,145 @@
+// C-ABI boundary of libukst: argument validation, geometry, path selection.  See include/ukst.h.
+#include "../../include/ukst.h"
+#include "ukst_internal.h"
+
+namespace {
+
+int validate_shape(int B, int Cin, int Cout, int H, int W, int n, int P)
+{
+    if (B < 1 || Cin < 1 || Cout < 1 || H < 1 || W < 1 || n < 1 || P < 0) return UKST_ERR_SHAPE;
+    // sizes are ints: keep 2H+2P and friends inside int32
+    if (H > (1 << 28) || W > (1 << 28) || P > (1 << 28)) return UKST_ERR_SHAPE;
+    if (2 * H + 2 * P - n < 1 || 2 * W + 2 * P - n < 1) return UKST_ERR_SHAPE;
+    return UKST_OK;
+}
+
+// Taps of one output row (or column) that meet an in-range input row: tap a of output o lands on
+// upsampled coordinate o + a - P, which holds input row (o + a - P)/2 when even and inside.
+unsigned long long exact_line_taps(int L, int OL, int n, int P)
+{
+    unsigned long long t = 0;
+    for (int o = 0; o < OL; ++o)
+        for (int a = 0; a < n; ++a) {
+            const int u = o + a - P;
+            if (u >= 0 && (u & 1) == 0 && u / 2 < L) ++t;
+        }
+    return t;
+}
+
+// Taps Algorithm 2 executes per line: ceil(n/2) for class 0 outputs, floor(n/2) for class 1.
+unsigned long long nominal_line_taps(int OL, int n, int P)
+{
+    unsigned long long t = 0;
+    for (int o = 0; o < OL; ++o) t += (unsigned)((n - ((o + P) & 1) + 1) >> 1);
+    return t;
+}
+
+int resolve_path(const ukst::Geom& g, int dtype, int path)
+{
+    if (path == UKST_PATH_DIRECT) return UKST_PATH_DIRECT;
+    if (path == UKST_PATH_MFMA) return ukst::mfma_supported(g, dtype) ? UKST_PATH_MFMA : -1;
+    // AUTO: the matrix cores pay off once both channel counts fill an MFMA tile
+    if (ukst::mfma_supported(g, dtype) && g.Cin >= 16 && g.Cout >= 16) return UKST_PATH_MFMA;
+    return UKST_PATH_DIRECT;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ukst_version(void) { return 100; }
+
+const char* ukst_status_string(int status)
+{
+    switch (status) {
+        case UKST_OK: return "ok";
+        case UKST_ERR_NULL: return "null pointer argument";
+        case UKST_ERR_SHAPE: return "invalid shape: a dimension < 1, P < 0, or empty output";
+        case UKST_ERR_DTYPE: return "unknown dtype";
+        case UKST_ERR_UNSUPPORTED: return "unsupported: kernel side above UKST_MAX_N or path cannot run this shape";
+        case UKST_ERR_LAUNCH: return "HIP launch error";
+        default: return "unknown status";
+    }
+}
+
+int ukst_output_shape(int H, int W, int n, int P, int* OH, int* OW)
+{
+    if (!OH || !OW) return UKST_ERR_NULL;
+    if (H < 1 || W < 1 || n < 1 || P < 0 || H > (1 << 28) || W > (1 << 28) || P > (1 << 28))
+        return UKST_ERR_SHAPE;
+    if (2 * H + 2 * P - n < 1 || 2 * W + 2 * P - n < 1) return UKST_ERR_SHAPE;
+    *OH = 2 * H + 2 * P - n;
+    *OW = 2 * W + 2 * P - n;
+    return UKST_OK;
+}
+
+unsigned long long ukst_mac_count(int B, int Cin, int Cout, int H, int W, int n, int P, int kind)
+{
+    if (validate_shape(B, Cin, Cout, H, W, n, P) != UKST_OK) return 0;
+    const int OH = 2 * H + 2 * P - n, OW = 2 * W + 2 * P - n;
+    unsigned long long rows, cols;
+    if (kind == 0) {
+        rows = exact_line_taps(H, OH, n, P);
+        cols = exact_line_taps(W, OW, n, P);
+    } else if (kind == 1) {
+        rows = nominal_line_taps(OH, n, P);
+        cols = nominal_line_taps(OW, n, P);
+    } else if (kind == 2) {
+        rows = (unsigned long long)OH * n;
+        cols = (unsigned long long)OW * n;
+    } else {
+        return 0;
+    }
+    return (unsigned long long)B * Cin * Cout * rows * cols;
+}
+
+int ukst_select_path(int B, int Cin, int Cout, int H, int W, int n, int P, int dtype)
+{
+    const int st = validate_shape(B, Cin, Cout, H, W, n, P);
+    if (st != UKST_OK) return -st;
+    if (dtype != UKST_F32 && dtype != UKST_BF16_F32) return -UKST_ERR_DTYPE;
+    if (n > UKST_MAX_N) return -UKST_ERR_UNSUPPORTED;
+    return resolve_path(ukst::make_geom(B, Cin, Cout, H, W, n, P), dtype, UKST_PATH_AUTO);
+}
+
+int ukst_conv_transpose2d_path(const void* x, const void* w, void* y, int B, int Cin, int Cout,
+                               int H, int W, int n, int P, int dtype, int path, void* stream)
+{
+    if (!x || !w || !y) return UKST_ERR_NULL;
+    const int st = validate_shape(B, Cin, Cout, H, W, n, P);
+    if (st != UKST_OK) return st;
+    if (dtype != UKST_F32 && dtype != UKST_BF16_F32) return UKST_ERR_DTYPE;
+    if (n > UKST_MAX_N) return UKST_ERR_UNSUPPORTED;
+    if (path != UKST_PATH_AUTO && path != UKST_PATH_DIRECT && path != UKST_PATH_MFMA)
+        return UKST_ERR_UNSUPPORTED;
+    const ukst::Geom g = ukst::make_geom(B, Cin, Cout, H, W, n, P);
+    const int chosen = resolve_path(g, dtype, path);
+    if (chosen < 0) return UKST_ERR_UNSUPPORTED;
+    hipError_t e;
+    if (chosen == UKST_PATH_MFMA)
+        e = ukst::launch_mfma(g, x, w, (float*)y, dtype, (hipStream_t)stream);
+    else
+        e = ukst::launch_direct(g, x, w, (float*)y, dtype, (hipStream_t)stream);
+    return e == hipSuccess ? UKST_OK : UKST_ERR_LAUNCH;
+}
+
+int ukst_conv_transpose2d(const void* x, const void* w, void* y, int B, int Cin, int Cout, int H,
+                          int W, int n, int P, int dtype, void* stream)
+{
+    return ukst_conv_transpose2d_path(x, w, y, B, Cin, Cout, H, W, n, P, dtype, UKST_PATH_AUTO,
+                                      stream);
+}
+
+const char* ukst_kernel_name(int B, int Cin, int Cout, int H, int W, int n, int P, int dtype,
+                             int path)
+{
+    if (validate_shape(B, Cin, Cout, H, W, n, P) != UKST_OK) return "";
+    if ((dtype != UKST_F32 && dtype != UKST_BF16_F32) || n > UKST_MAX_N) return "";
+    const ukst::Geom g = ukst::make_geom(B, Cin, Cout, H, W, n, P);
+    const int chosen = resolve_path(g, dtype, path);
+    if (chosen < 0) return "";
+    return chosen == UKST_PATH_MFMA ? ukst::mfma_kernel_name(g, dtype)
+                                    : ukst::direct_kernel_name(g, dtype);
+}
+
+}  // extern "C"

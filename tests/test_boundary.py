@@ -1,0 +1,120 @@
+"""Host-side checks of the C-ABI library (no GPU): it loads, exports what include/ukst.h declares,
+validates arguments before touching the GPU, and its host arithmetic is right."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2502_20493_amd import binding as ukst
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "ukst.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ukst_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ctypes.CDLL(ukst.LIB_PATH)
+    declared = _declared_symbols()
+    assert len(declared) >= 8
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert sorted(ukst.EXPORTS) == declared
+
+
+def test_version_and_status_strings():
+    assert ukst.ukst_version() >= 100
+    seen = {ukst.ukst_status_string(s) for s in range(6)}
+    assert len(seen) == 6 and ukst.ukst_status_string(0) == "ok"
+    assert ukst.ukst_status_string(99) == "unknown status"
+
+
+def test_output_shape():
+    assert ukst.ukst_output_shape(4, 4, 3, 0) == (5, 5)      # Sec. 1
+    assert ukst.ukst_output_shape(4, 4, 3, 2) == (9, 9)      # Fig. 2
+    assert ukst.ukst_output_shape(4, 4, 5, 2) == (7, 7)      # Figs. 5-6
+    assert ukst.ukst_output_shape(224, 200, 3, 0) == (445, 397)
+    for bad in [(1, 4, 3, 0), (4, 1, 3, 0), (0, 4, 3, 2), (4, 4, 0, 0), (4, 4, 3, -1)]:
+        with pytest.raises(ukst.UkstError) as e:
+            ukst.ukst_output_shape(*bad)
+        assert e.value.status == ukst.UKST_ERR_SHAPE
+    oh = ctypes.c_int(0)
+    assert ukst.lib().ukst_output_shape(4, 4, 3, 0, None, ctypes.byref(oh)) == ukst.UKST_ERR_NULL
+
+
+def test_validation_happens_on_the_host():
+    # fake non-null addresses: validation must reject before any launch
+    X = W = Y = 0x1000
+    call = ukst.ukst_conv_transpose2d_raw
+    ok_shape = (1, 1, 1, 4, 4, 3, 0)
+    assert call(None, W, Y, *ok_shape, 0) == ukst.UKST_ERR_NULL
+    assert call(X, None, Y, *ok_shape, 0) == ukst.UKST_ERR_NULL
+    assert call(X, W, None, *ok_shape, 0) == ukst.UKST_ERR_NULL
+    for bad in [(0, 1, 1, 4, 4, 3, 0), (1, 0, 1, 4, 4, 3, 0), (1, 1, 0, 4, 4, 3, 0),
+                (1, 1, 1, 0, 4, 3, 0), (1, 1, 1, 4, 0, 3, 0), (1, 1, 1, 4, 4, 0, 0),
+                (1, 1, 1, 4, 4, 3, -1), (1, 1, 1, 1, 4, 3, 0), (1, 1, 1, 4, 1, 3, 0)]:
+        assert call(X, W, Y, *bad, 0) == ukst.UKST_ERR_SHAPE, bad
+    assert call(X, W, Y, *ok_shape, 2) == ukst.UKST_ERR_DTYPE
+    assert call(X, W, Y, *ok_shape, -1) == ukst.UKST_ERR_DTYPE
+    assert call(X, W, Y, 1, 1, 1, 8, 8, ukst.UKST_MAX_N + 1, 0, 0) == ukst.UKST_ERR_UNSUPPORTED
+    assert call(X, W, Y, *ok_shape, 0, path=7) == ukst.UKST_ERR_UNSUPPORTED
+    # MFMA path cannot run a 1-channel problem
+    assert call(X, W, Y, *ok_shape, 0, path=ukst.UKST_PATH_MFMA) == ukst.UKST_ERR_UNSUPPORTED
+
+
+def _brute_macs(H, W, n, P):
+    """Count products by walking the padded upsampled map of Algorithm 1."""
+    OH, OW = 2 * H + 2 * P - n, 2 * W + 2 * P - n
+    U = np.zeros((2 * H - 1 + 2 * P, 2 * W - 1 + 2 * P), dtype=np.int64)
+    U[P:P + 2 * H - 1:2, P:P + 2 * W - 1:2] = 1
+    exact = sum(int(U[oy:oy + n, ox:ox + n].sum()) for oy in range(OH) for ox in range(OW))
+    hi, lo = (n + 1) // 2, n // 2
+    nominal = sum((hi if (oy + P) % 2 == 0 else lo) * (hi if (ox + P) % 2 == 0 else lo)
+                  for oy in range(OH) for ox in range(OW))
+    return exact, nominal, OH * OW * n * n
+
+
+def test_mac_counts():
+    for (H, W, n, P) in [(4, 4, 3, 0), (4, 4, 4, 2), (5, 3, 5, 0), (5, 3, 5, 3), (3, 6, 2, 1),
+                         (4, 4, 7, 6), (2, 2, 1, 0), (2, 3, 2, 4)]:
+        e, nom, nv = _brute_macs(H, W, n, P)
+        for kind, want in ((0, e), (1, nom), (2, nv)):
+            assert ukst.ukst_mac_count(2, 3, 5, H, W, n, P, kind) == 2 * 3 * 5 * want
+        assert e <= nom <= nv
+    # Sec. 3.1: 25 multiplications per four outputs for n = 5 instead of 100
+    assert ukst.ukst_mac_count(1, 1, 1, 8, 8, 5, 0, 1) * 4 < ukst.ukst_mac_count(1, 1, 1, 8, 8, 5, 0, 2) * 1.1
+    assert ukst.ukst_mac_count(1, 1, 1, 1, 8, 5, 0, 0) == 0  # invalid shape
+    # figures used by the benchmark (GFLOP = 2 * MAC / 1e9)
+    assert ukst.ukst_mac_count(16, 3, 3, 224, 224, 3, 0, 0) == 16 * 9 * 668 * 668  # rows: 223 even outputs x 2 taps + 222 odd x 1
+    assert abs(2 * ukst.ukst_mac_count(32, 128, 128, 64, 64, 5, 0, 0) / 1e9 - 99.47) < 0.01
+
+
+def test_select_path():
+    assert ukst.ukst_select_path(16, 3, 3, 224, 224, 3, 0, ukst.UKST_F32) == ukst.UKST_PATH_DIRECT
+    assert ukst.ukst_select_path(64, 64, 3, 32, 32, 4, 2, ukst.UKST_F32) == ukst.UKST_PATH_DIRECT
+    with pytest.raises(ukst.UkstError):
+        ukst.ukst_select_path(16, 3, 3, 1, 224, 3, 0, ukst.UKST_F32)
+    assert "direct" in ukst.ukst_kernel_name(16, 3, 3, 224, 224, 3, 0, 0)
+    assert ukst.ukst_kernel_name(16, 3, 3, 1, 224, 3, 0, 0) == ""
+
+
+def test_workloads_are_seeded_and_shaped():
+    from paper_2502_20493_amd import workloads as wl
+    a = wl.generate(wl.WORKLOADS["cfg1"])
+    b = wl.generate(wl.WORKLOADS["cfg1"])
+    assert a["x"].shape == (1, 1, 32, 32) and a["w"].shape == (1, 1, 3, 3)
+    assert np.array_equal(a["x"], b["x"]) and np.array_equal(a["w"], b["w"])
+    i = wl.generate(wl.WORKLOADS["cfg1_int"])
+    assert set(np.unique(i["x"])).issubset(set(range(-3, 4)))
+    small = wl.WORKLOADS["cfg5b"].with_(B=1, Cin=8, Cout=4)
+    d = wl.generate(small)
+    assert d["x_bits"].dtype == np.uint16
+    # bf16 values survive a second rounding unchanged, and rounding is to nearest even
+    assert np.array_equal(wl.round_to_bf16_bits(d["x"]), d["x_bits"])
+    t = np.array([1.0, 1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8, 1.0 + 2 ** -7], dtype=np.float32)
+    assert wl.bf16_bits_to_f32(wl.round_to_bf16_bits(t)).tolist() == [1.0, 1.0, 1.0 + 2 ** -6, 1.0 + 2 ** -7]

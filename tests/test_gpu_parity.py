@@ -1,0 +1,145 @@
+"""GPU parity: the HIP library, called through the C ABI, against the fp64 CPU oracle on the same
+seeded inputs.  Tolerances: fp32 max|err| <= 1e-5 * sum|x*w| per output, bf16-in/fp32-accumulate
+<= 1e-2 * sum|x*w|; integer-valued inputs must match exactly."""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2502_20493_amd import binding as ukst
+from paper_2502_20493_amd import workloads as wl
+from gpu_util import TOL, check_against_oracle, run_gpu
+
+pytestmark = pytest.mark.gpu
+
+PATHS = {"direct": ukst.UKST_PATH_DIRECT, "mfma": ukst.UKST_PATH_MFMA, "auto": ukst.UKST_PATH_AUTO}
+
+
+def _mk(name, idx, B, Cin, Cout, H, W, n, P, dtype="f32"):
+    return wl.Workload(name, idx, B, Cin, Cout, H, W, n, P, dtype, "normal", "normal:0.5")
+
+
+def _supported(w, path):
+    if path != ukst.UKST_PATH_MFMA:
+        return True
+    dt = ukst.UKST_F32 if w.dtype == "f32" else ukst.UKST_BF16_F32
+    return bool(ukst.ukst_kernel_name(w.B, w.Cin, w.Cout, w.H, w.W, w.n, w.P, dt, path))
+
+
+def _parity(w, path, integer=False, guard=4096, planes=None):
+    print(f"case {w.name} B={w.B} Cin={w.Cin} Cout={w.Cout} H={w.H} W={w.W} n={w.n} P={w.P} "
+          f"{w.dtype} path={path} integer={integer}", flush=True)
+    data = wl.generate(w, integer=integer)
+    y_ref, S = oracle.naive(data["x"], data["w"], w.P, planes=planes)
+    y = run_gpu(data, w.dtype, w.P, path=path, guard=guard)
+    assert y.shape == y_ref.shape
+    return check_against_oracle(y, y_ref, S, TOL[w.dtype], planes=planes, exact=integer)
+
+
+# ------------------------------------------------------------------ edge sweep, direct path
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 5, 6, 7])
+def test_direct_edge_sweep(n):
+    idx = 0
+    for P in range(0, n + 2):
+        for (B, Cin, Cout, H, W) in [(1, 1, 1, 4, 4), (2, 3, 3, 5, 9), (1, 9, 5, 1, 37),
+                                     (1, 17, 2, 11, 1), (2, 2, 4, 33, 70)]:
+            if 2 * H + 2 * P - n < 1 or 2 * W + 2 * P - n < 1:
+                continue
+            idx += 1
+            w = _mk(f"edge_n{n}", 1000 * n + idx, B, Cin, Cout, H, W, n, P)
+            _parity(w, PATHS["direct"], integer=True)
+            if P in (0, n // 2):
+                _parity(w, PATHS["direct"], integer=False)
+                _parity(w.with_(dtype="bf16"), PATHS["direct"], integer=False)
+
+
+# ------------------------------------------------------------------ the benchmark configs
+def test_cfg1_toy_case():
+    _parity(wl.WORKLOADS["cfg1"], PATHS["auto"])
+    _parity(wl.WORKLOADS["cfg1_int"], PATHS["auto"], integer=True)
+    _parity(wl.WORKLOADS["cfg1"], PATHS["auto"], integer=True)
+
+
+@pytest.mark.parametrize("name", ["cfg2a", "cfg2b"])
+def test_cfg2_images_full_size(name):
+    w = wl.WORKLOADS[name]
+    _parity(w, PATHS["auto"], guard=1 << 16)
+    _parity(w.with_(B=2), PATHS["auto"], integer=True)
+
+
+def _sample_planes(w, k=16):
+    rng = np.random.default_rng(w.index)
+    total = w.B * w.Cout
+    extra = rng.choice(total, size=min(k, total) - 2, replace=False).tolist() if total > 2 else []
+    return sorted(set([0, total - 1] + extra))
+
+
+@pytest.mark.parametrize("name", ["cfg3_L1", "cfg3_L2", "cfg3_L3", "cfg3_L4"])
+def test_cfg3_dcgan_layers_full_size(name):
+    w = wl.WORKLOADS[name]
+    planes = _sample_planes(w, 64)
+    _parity(w, PATHS["auto"], planes=planes)
+    _parity(w, PATHS["auto"], planes=planes, integer=True)
+
+
+@pytest.mark.parametrize("name", ["cfg4a", "cfg4b", "cfg5a", "cfg5b"])
+def test_cfg45_full_size_sampled_planes(name):
+    # the naive oracle is too slow for every plane at these sizes: it computes a seeded sample of
+    # complete (b, co) planes (always the first and the last); each still reduces over all Cin and
+    # holds every parity class and edge
+    w = wl.WORKLOADS[name]
+    planes = _sample_planes(w, 16)
+    _parity(w, PATHS["auto"], planes=planes, guard=1 << 16)
+    _parity(w, PATHS["auto"], planes=planes, integer=True)
+
+
+@pytest.mark.parametrize("name", ["cfg3_L2", "cfg4a", "cfg4b", "cfg5b"])
+def test_reduced_configs_every_element_both_paths(name):
+    # same layer shapes with fewer images / channels so that the oracle covers every element
+    w = wl.WORKLOADS[name]
+    small = w.with_(B=2, Cin=min(w.Cin, 48), Cout=min(w.Cout, 40), H=min(w.H, 23), W=min(w.W, 31))
+    for pname in ("direct", "mfma"):
+        if _supported(small, PATHS[pname]):
+            _parity(small, PATHS[pname])
+            _parity(small, PATHS[pname], integer=True)
+
+
+def test_paths_agree_at_full_size():
+    # property that holds at any size: both kernel families compute the same tensor
+    import torch
+    from gpu_util import to_device
+    for name in ["cfg4b", "cfg3_L3"]:
+        w = wl.WORKLOADS[name]
+        if not _supported(w, PATHS["mfma"]):
+            pytest.skip("MFMA path not available for this shape")
+        data = wl.generate(w)
+        x, wt = to_device(data, w.dtype)
+        ya = ukst.ukst_conv_transpose2d(x, wt, w.P, path=PATHS["direct"])
+        yb = ukst.ukst_conv_transpose2d(x, wt, w.P, path=PATHS["mfma"])
+        scale = ukst.ukst_conv_transpose2d(x.abs(), wt.abs(), w.P, path=PATHS["direct"])
+        torch.cuda.synchronize()
+        assert bool(((ya - yb).abs() <= 2e-5 * scale).all())
+
+
+def test_repeat_runs_are_bit_identical():
+    w = wl.WORKLOADS["cfg2a"].with_(B=2)
+    data = wl.generate(w)
+    a = run_gpu(data, w.dtype, w.P)
+    b = run_gpu(data, w.dtype, w.P)
+    assert np.array_equal(a, b)
+
+
+def test_non_default_stream():
+    import torch
+    from gpu_util import to_device
+    w = wl.WORKLOADS["cfg1"]
+    data = wl.generate(w)
+    x, wt = to_device(data, w.dtype)
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        y = ukst.ukst_conv_transpose2d(x, wt, w.P)
+    s.synchronize()
+    y_ref, S = oracle.naive(data["x"], data["w"], w.P)
+    check_against_oracle(y.cpu().numpy(), y_ref, S, TOL["f32"])
