@@ -140,6 +140,7 @@ hipError_t launch_n(const Geom& g, const void* x, const void* w, float* y, int d
 hipError_t launch_direct(const Geom& g, const void* x, const void* w, float* y, int dtype,
                          hipStream_t stream)
 {
+    if (narrow_supported(g, dtype)) return launch_narrow(g, x, w, y, stream);
     switch (g.n) {
         case 1: return launch_n<1>(g, x, w, y, dtype, stream);
         case 2: return launch_n<2>(g, x, w, y, dtype, stream);
@@ -152,6 +153,9 @@ hipError_t launch_direct(const Geom& g, const void* x, const void* w, float* y, 
     }
 }
 
-const char* direct_kernel_name(const Geom&, int) { return "ukst_direct_kernel"; }
+const char* direct_kernel_name(const Geom& g, int dtype)
+{
+    return narrow_supported(g, dtype) ? "ukst_narrow_kernel" : "ukst_direct_kernel";
+}
 
 }  // namespace ukst

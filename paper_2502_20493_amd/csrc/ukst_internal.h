@@ -40,6 +40,10 @@ hipError_t launch_direct(const Geom& g, const void* x, const void* w, float* y, 
                          hipStream_t stream);
 const char* direct_kernel_name(const Geom& g, int dtype);
 
+// Narrow-channel kernel (fp32, Cin and Cout <= 4): register-blocked quads, buffer addressing.
+bool narrow_supported(const Geom& g, int dtype);
+hipError_t launch_narrow(const Geom& g, const void* x, const void* w, float* y, hipStream_t stream);
+
 bool mfma_supported(const Geom& g, int dtype);
 hipError_t launch_mfma(const Geom& g, const void* x, const void* w, float* y, int dtype,
                        hipStream_t stream);

@@ -99,7 +99,8 @@ def test_select_path():
     assert ukst.ukst_select_path(64, 64, 3, 32, 32, 4, 2, ukst.UKST_F32) == ukst.UKST_PATH_DIRECT
     with pytest.raises(ukst.UkstError):
         ukst.ukst_select_path(16, 3, 3, 1, 224, 3, 0, ukst.UKST_F32)
-    assert "direct" in ukst.ukst_kernel_name(16, 3, 3, 224, 224, 3, 0, 0)
+    assert "narrow" in ukst.ukst_kernel_name(16, 3, 3, 224, 224, 3, 0, 0)
+    assert "direct" in ukst.ukst_kernel_name(16, 8, 8, 224, 224, 3, 0, 0)
     assert ukst.ukst_kernel_name(16, 3, 3, 1, 224, 3, 0, 0) == ""
 
 
