@@ -1,12 +1,366 @@
-// MFMA path (placeholder until the implicit-GEMM kernels land): reports "not supported" so that
-// UKST_PATH_AUTO resolves to the direct path and UKST_PATH_MFMA returns UKST_ERR_UNSUPPORTED.
+// MFMA path: parity-class implicit GEMM on the matrix cores for wide layers.
+//
+// GEMM view (per quad, see ukst_internal.h): the four parity classes of a quad read the SAME
+// ceil(n/2) x ceil(n/2) input window, so for window position (u, v) and input channel ci the
+// activation x[ci][k-P+u][m-P+v] is one B operand shared by every class, and class (r, s)
+// multiplies it by its own sub-kernel tap w[co][ci][r+2u][s+2v] (Eqs. 1-4).  Hence
+//
+//     D_rs[co][quad] += sum_ci  W_tap(r,s,u,v)[co][ci] * X_(u,v)[ci][quad]
+//
+// i.e. one MFMA B fragment feeds up to four MFMAs (one per class), and the kernel's n*n taps are
+// each used once per quad (Sec. 3.1).  M = output channels, N = quads (flattened over batch, quad
+// rows and quad columns so that tiles stay full whatever the image size), K = input channels.
+// Lanes of an accumulator tile run along N = consecutive quad columns, so the epilogue writes the
+// two column classes of a quad as one 8-byte store and a wave covers runs of 64 consecutive
+// floats of an output row: the classes are interleaved in place, there is no re-arrangement pass
+// and no second copy of the output (the cost Sec. 5 attributes to a GEMM formulation).
+//
+// Block = 256 threads = 4 waves; block tile = 64 output channels x 256 quads x 4 classes; wave
+// tile = 32 channels x 128 quads x 4 classes = 16 accumulator tiles of 32x32 (256 registers).
+// K advances 16 input channels per stage; stages are double-buffered in LDS: while the matrix
+// cores work on stage s the global loads of stage s+1 are in flight.  NCHW keeps the K axis (ci)
+// slowest, while an MFMA lane wants 8 consecutive K values in one register group: both operands
+// are transposed in registers (8x8 b16 transposes out of v_perm_b32) on their way into LDS, which
+// is where the sub-kernels get gathered per tap.
 #include "ukst_internal.h"
 
 namespace ukst {
-bool mfma_supported(const Geom&, int) { return false; }
-hipError_t launch_mfma(const Geom&, const void*, const void*, float*, int, hipStream_t)
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned u2v __attribute__((ext_vector_type(2)));
+typedef unsigned u4v __attribute__((ext_vector_type(4)));
+
+constexpr int kRsrcFlags = 0x00020000;      // raw 32-bit buffer, gfx9 family
+constexpr unsigned kInvalid = 0xFFFFFF00u;  // byte offset that is out of range for any buffer
+
+constexpr int TM = 64;    // output channels per block
+constexpr int TN = 256;   // quads per block
+constexpr int KC = 16;    // input channels per stage (one MFMA K step)
+constexpr int W_PLANE = (TM + 1) * 16;  // bytes of one [tap][k-half] plane, padded against bank conflicts
+constexpr int XS_STAGE_MAX = 40960;     // bytes reserved per activation stage buffer
+
+struct MfmaArgs {
+    Geom g;
+    int Q;        // total quads = B * KH * KW
+    int EH;       // distinct input rows one image's quad rows touch = KH + ceil(n/2) - 1
+    int ROWS;     // input rows an activation stage buffer holds
+    int LWS;      // 16-byte slots per staged row (columns + one pad slot per 8 + halo)
+    int OFFS;     // LDS column of input column 0 (multiple of 8, >= floor(P/2))
+    int C8;       // 8-column groups per input row
+    int nco;      // channel blocks
+    int nqt;      // quad tiles
+};
+
+__device__ __forceinline__ int xcd_contiguous(int bid, int nb)
 {
-    return hipErrorNotSupported;
+    constexpr int X = 8;
+    const int xcd = bid % X, idx = bid / X;
+    const int fl = nb / X, rem = nb % X;
+    return xcd * fl + (xcd < rem ? xcd : rem) + idx;
 }
-const char* mfma_kernel_name(const Geom&, int) { return ""; }
+
+// 8x8 transpose of 16-bit elements held as 8 rows of 4 dwords: out[t] collects element t of every
+// input row.
+__device__ __forceinline__ void transpose8x8_b16(const u4v (&in)[8], u4v (&out)[8])
+{
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            out[2 * q][p] = __builtin_amdgcn_perm(in[2 * p + 1][q], in[2 * p][q], 0x05040100u);
+            out[2 * q + 1][p] = __builtin_amdgcn_perm(in[2 * p + 1][q], in[2 * p][q], 0x07060302u);
+        }
+}
+
+template <int N>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w,
+                           float* __restrict__ y, MfmaArgs a)
+{
+    static_assert(N == 4, "bf16 MFMA path: in-register sub-kernel gather is written for n = 4");
+    constexpr int HI = (N + 1) / 2;
+    constexpr int NN = N * N;
+    constexpr int WS_STAGE = NN * 2 * W_PLANE;  // 33280 bytes
+    extern __shared__ __align__(16) unsigned char lds[];
+    // layout: weights stage 0, weights stage 1, activations stage 0, activations stage 1
+    constexpr int XS_OFF = 2 * WS_STAGE;
+
+    const Geom& g = a.g;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int cw = wave & 1;   // which 32-channel half of the block tile
+    const int qh = wave >> 1;  // which 128-quad half of the block tile
+    const int l32 = lane & 31, gk = lane >> 5;
+
+    const int bid = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int cb = bid % a.nco, qt = bid / a.nco;
+    const int co0 = cb * TM;
+    const int q0 = qt * TN;
+    const int KHW = g.KH * g.KW;
+
+    // rows this tile needs: quad row rho = b*KH + kk uses input rows e = b*EH + kk + u
+    const int q_last = (q0 + TN - 1 < a.Q ? q0 + TN - 1 : a.Q - 1);
+    const int bf = q0 / KHW, kf = (q0 - bf * KHW) / g.KW;
+    const int e_first = bf * a.EH + kf;
+
+    // ---- zero the activation buffers once: halo columns are never written again
+    {
+        const int n16 = 2 * XS_STAGE_MAX / 16;
+        u4v z = {0u, 0u, 0u, 0u};
+        for (int i = tid; i < n16; i += 256) *reinterpret_cast<u4v*>(lds + XS_OFF + i * 16) = z;
+    }
+
+    // ---- per-thread staging units (fixed for the whole K loop)
+    // weights: lane = channel co0 + lane, wave = (k-half g, tap-half h): 8 input channels
+    // ci0+8g.. of taps 8h..8h+7; lanes then write consecutive 16-byte LDS slots (no conflicts)
+    const int w_co = lane, w_g = wave & 1, w_h = wave >> 1;
+    const unsigned w_voff = (unsigned)(((co0 + w_co) * g.Cin + 8 * w_g) * (NN * 2) + w_h * 16);
+    const int w_lds = ((8 * w_h) * 2 + w_g) * W_PLANE + w_co * 16;  // + t * 2 * W_PLANE
+    // activations: thread = (row r, k-half g, 8-column group c8)
+    unsigned x_voff = kInvalid;
+    int x_lds = 0;
+    bool x_unit = false;
+    {
+        const int units = a.ROWS * 2 * a.C8;
+        if (tid < units) {
+            const int c8 = tid % a.C8;
+            const int rg = tid / a.C8;
+            const int xg = rg & 1, r = rg >> 1;
+            const int e = e_first + r;
+            const int b = e / a.EH, ii = e - b * a.EH;
+            const int i = g.k_min - g.P + ii;
+            x_unit = true;
+            if (b < g.B && i >= 0 && i < g.H)
+                x_voff = (unsigned)((((b * g.Cin + 8 * xg) * g.H + i) * g.W + 8 * c8) * 2);
+            // column c sits in slot c + c/8: the pad slot after every 8 columns spreads the
+            // 128-byte stride between neighbouring units over the LDS banks
+            x_lds = ((xg * a.ROWS + r) * a.LWS + (a.OFFS + 8 * c8) / 8 * 9) * 16;
+        }
+    }
+    const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)x, 0, (int)((size_t)g.B * g.Cin * g.H * g.W * 2), kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)w, 0, (int)((size_t)g.Cout * g.Cin * NN * 2), kRsrcFlags);
+    const unsigned x_cstride = (unsigned)(g.H * g.W * 2);  // bytes between input channels
+
+    // ---- per-lane operand addresses
+    // A (weights): lane = channel co0 + cw*32 + l32, k-half gk
+    const int a_lds = gk * W_PLANE + (cw * 32 + l32) * 16;
+    // B (activations): lane = quad q0 + qh*128 + nt*32 + l32, k-half gk
+    int b_lds[4][HI][HI];
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) {
+        int q = q0 + qh * 128 + nt * 32 + l32;
+        if (q >= a.Q) q = q_last;
+        const int b = q / KHW;
+        const int rem = q - b * KHW;
+        const int kk = rem / g.KW, mm = rem - kk * g.KW;
+        const int r = b * a.EH + kk - e_first;
+#pragma unroll
+        for (int u = 0; u < HI; ++u)
+#pragma unroll
+            for (int v = 0; v < HI; ++v) {
+                const int c = mm + v + (a.OFFS - (g.P >> 1));  // LDS column of window column v
+                b_lds[nt][u][v] = XS_OFF + ((gk * a.ROWS + r + u) * a.LWS + c + (c >> 3)) * 16;
+            }
+    }
+
+    f32x16 acc[4][2][2];
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[nt][r][s][i] = 0.f;
+
+    u4v wreg[8], xreg[8];
+    auto stage_load = [&](int ci0) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+            wreg[c] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, w_voff,
+                                                            (unsigned)((ci0 + c) * (NN * 2)), 0);
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+            xreg[c] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, x_voff,
+                                                            (unsigned)(ci0 + c) * x_cstride, 0);
+    };
+    auto stage_store = [&](int buf) {
+        u4v t[8];
+        transpose8x8_b16(wreg, t);
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            *reinterpret_cast<u4v*>(lds + buf * WS_STAGE + w_lds + k * 2 * W_PLANE) = t[k];
+        if (x_unit) {
+            transpose8x8_b16(xreg, t);
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                *reinterpret_cast<u4v*>(lds + XS_OFF + buf * XS_STAGE_MAX + x_lds + k * 16) = t[k];
+        }
+    };
+    // operand fragments of window position p = u*HI + v: one B fragment per quad tile, one A
+    // fragment per parity class that owns a tap at this position
+    auto load_frags = [&](int buf, int p, bf16x8 (&bf)[4], bf16x8 (&af)[4]) {
+        const int u = p / HI, v = p % HI;
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+            bf[nt] = *reinterpret_cast<const bf16x8*>(lds + b_lds[nt][u][v] + buf * XS_STAGE_MAX);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int r = c >> 1, sc = c & 1;
+            if (r + 2 * u >= N || sc + 2 * v >= N) continue;  // class has no tap here
+            const int tap = (r + 2 * u) * N + (sc + 2 * v);
+            af[c] = *reinterpret_cast<const bf16x8*>(lds + buf * WS_STAGE + a_lds +
+                                                     tap * 2 * W_PLANE);
+        }
+    };
+    auto compute = [&](int buf) {
+        bf16x8 bf[2][4], af[2][4];
+        load_frags(buf, 0, bf[0], af[0]);
+#pragma unroll
+        for (int p = 0; p < HI * HI; ++p) {
+            const int u = p / HI, v = p % HI;
+            // fragments of the next position are requested before this position's MFMAs issue
+            if (p + 1 < HI * HI) load_frags(buf, p + 1, bf[(p + 1) & 1], af[(p + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const int r = c >> 1, sc = c & 1;
+                if (r + 2 * u >= N || sc + 2 * v >= N) continue;
+#pragma unroll
+                for (int nt = 0; nt < 4; ++nt)
+                    acc[nt][r][sc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        af[p & 1][c], bf[p & 1][nt], acc[nt][r][sc], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    const int stages = g.Cin / KC;
+    stage_load(0);
+    __syncthreads();  // zero fill done before the first activation writes
+    stage_store(0);
+    __syncthreads();
+    int buf = 0;
+    for (int s = 1; s < stages; ++s) {
+        stage_load(s * KC);   // global loads of the next stage fly while this one is computed
+        compute(buf);
+        stage_store(buf ^ 1);
+        __syncthreads();
+        buf ^= 1;
+    }
+    compute(buf);
+
+    // ---- epilogue: accumulator register i of a tile holds channel 8*(i/4) + 4*gk + (i%4) of the
+    // wave's 32, for the lane's quad; column classes s = 1, 0 are neighbours in memory
+    const __amdgpu_buffer_rsrc_t rs_y = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)y, 0, (int)((size_t)g.B * g.Cout * g.OH * g.OW * 4), kRsrcFlags);
+    const unsigned plane = (unsigned)(g.OH * g.OW * 4);
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) {
+        const int q = q0 + qh * 128 + nt * 32 + l32;
+        const bool qv = q < a.Q;
+        const int qq = qv ? q : q_last;
+        const int b = qq / KHW;
+        const int rem = qq - b * KHW;
+        const int kk = rem / g.KW, mm = rem - kk * g.KW;
+        const int k = g.k_min + kk, m = g.m_min + mm;
+        const int oy1 = 2 * k - 1 - g.P, ox1 = 2 * m - 1 - g.P;  // row / column of class 1
+        const bool vcol1 = ox1 >= 0 && ox1 < g.OW, vcol0 = ox1 + 1 < g.OW;
+        // byte offset of (channel co0 + cw*32 + 4*gk, row oy1, column ox1); unsigned wrap-around
+        // keeps the arithmetic right when oy1 or ox1 is -1 and only the other class exists
+        const unsigned y_off =
+            (unsigned)((((b * g.Cout + co0 + cw * 32 + 4 * gk) * g.OH + oy1) * g.OW + ox1) * 4);
+#pragma unroll
+        for (int r = 1; r >= 0; --r) {
+            const bool vrow = qv && (r ? (oy1 >= 0 && oy1 < g.OH) : (oy1 + 1 < g.OH));
+            const unsigned base = y_off + (r ? 0u : (unsigned)(g.OW * 4));
+            const unsigned off_pair = (vrow && vcol1 && vcol0) ? base : kInvalid;
+            const unsigned off_s1 = (vrow && vcol1 && !vcol0) ? base : kInvalid;
+            const unsigned off_s0 = (vrow && !vcol1 && vcol0) ? base + 4u : kInvalid;
+            const bool edge = (off_s1 != kInvalid) || (off_s0 != kInvalid);
+            const bool any_edge = __builtin_amdgcn_ballot_w64(edge) != 0;  // wave-uniform
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const unsigned soff = (unsigned)(8 * (i / 4) + (i % 4)) * plane;
+                u2v d;
+                const float v1 = acc[nt][r][1][i], v0 = acc[nt][r][0][i];  // by value, then bits
+                d.x = __float_as_uint(v1);
+                d.y = __float_as_uint(v0);
+                __builtin_amdgcn_raw_buffer_store_b64(d, rs_y, off_pair, soff, 0);
+                if (any_edge) {
+                    __builtin_amdgcn_raw_buffer_store_b32(d.x, rs_y, off_s1, soff, 0);
+                    __builtin_amdgcn_raw_buffer_store_b32(d.y, rs_y, off_s0, soff, 0);
+                }
+            }
+        }
+    }
+}
+
+bool make_args(const Geom& g, int dtype, MfmaArgs& a)
+{
+    if (dtype != 1) return false;                // fp32 operands: not on this path yet
+    if (g.n != 4) return false;
+    if (g.Cin % KC != 0 || g.Cout % TM != 0) return false;
+    if (g.W % 8 != 0) return false;              // 16-byte row chunks
+    const size_t xbytes = (size_t)g.B * g.Cin * g.H * g.W * 2;
+    const size_t wbytes = (size_t)g.Cout * g.Cin * g.n * g.n * 2;
+    const size_t ybytes = (size_t)g.B * g.Cout * g.OH * g.OW * 4;
+    const size_t lim = 0x7FFFFFF0u;              // single buffer descriptors, 32-bit byte offsets
+    if (xbytes > lim || wbytes > lim || ybytes > lim) return false;
+    const int HI = (g.n + 1) / 2;
+    a.g = g;
+    const long long Q = (long long)g.B * g.KH * g.KW;
+    if (Q > 0x7FFFFFFFLL - TN) return false;
+    a.Q = (int)Q;
+    a.EH = g.KH + HI - 1;
+    // 256 consecutive flattened quads touch at most this many quad rows / images
+    const int nrho = (TN - 2) / g.KW + 2;
+    const int nimg = (TN - 2) / (g.KH * g.KW) + 2;
+    a.ROWS = nrho + (HI - 1) * nimg;
+    a.OFFS = ((g.P >> 1) + 7) & ~7;
+    int LW = a.OFFS + g.W + HI;  // columns: left halo, the row, right halo
+    const int need = g.KW + HI - 1 + (a.OFFS - (g.P >> 1));
+    if (LW < need) LW = need;
+    a.LWS = LW + (LW >> 3) + 1;
+    a.C8 = g.W / 8;
+    if (2 * a.ROWS * a.LWS * 16 > XS_STAGE_MAX) return false;
+    if (a.ROWS * 2 * a.C8 > 256) return false;   // one staging unit per thread
+    a.nco = g.Cout / TM;
+    a.nqt = (int)((Q + TN - 1) / TN);
+    if ((long long)a.nco * a.nqt > 0x7FFFFFFFLL) return false;
+    return true;
+}
+
+}  // namespace
+
+bool mfma_supported(const Geom& g, int dtype)
+{
+    MfmaArgs a;
+    return make_args(g, dtype, a);
+}
+
+hipError_t launch_mfma(const Geom& g, const void* x, const void* w, float* y, int dtype,
+                       hipStream_t stream)
+{
+    MfmaArgs a;
+    if (!make_args(g, dtype, a)) return hipErrorInvalidValue;
+    constexpr int N = 4;
+    const size_t lds = 2 * (size_t)(N * N * 2 * W_PLANE) + 2 * (size_t)XS_STAGE_MAX;
+    // more than 64 KiB of dynamic LDS has to be allowed per device (a property of the loaded
+    // kernel, not library state); cheap enough to repeat on every call
+    hipError_t e = hipFuncSetAttribute((const void*)ukst_mfma_bf16_kernel<N>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((ukst_mfma_bf16_kernel<N>), dim3((unsigned)(a.nco * a.nqt)), dim3(256), lds,
+                       stream, (const uint16_t*)x, (const uint16_t*)w, y, a);
+    return hipGetLastError();
+}
+
+const char* mfma_kernel_name(const Geom&, int) { return "ukst_mfma_bf16_kernel"; }
+
 }  // namespace ukst
