@@ -39,6 +39,10 @@ def lib():
             raise RuntimeError(
                 f"{LIB_PATH} is missing: the HIP library has not been built "
                 "(python -m paper_2502_20493_amd.build). There is no fallback path.")
+        # PyTorch bundles its own HIP runtime.  It has to be in the process before this library
+        # is loaded, otherwise the two ends see different runtimes and the first HIP call made
+        # from here reports that there is no device.
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         i, vp = ctypes.c_int, ctypes.c_void_p
         ip = ctypes.POINTER(ctypes.c_int)

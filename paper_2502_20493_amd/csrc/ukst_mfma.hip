@@ -38,7 +38,8 @@ constexpr unsigned kInvalid = 0xFFFFFF00u;  // byte offset that is out of range 
 constexpr int TM = 64;    // output channels per block
 constexpr int TN = 256;   // quads per block
 constexpr int KC = 16;    // input channels per stage (one MFMA K step)
-constexpr int W_PLANE = (TM + 1) * 16;  // bytes of one [tap][k-half] plane, padded against bank conflicts
+constexpr int W_PLANE = (TM + 1) * 16;  // bytes of one tap plane of a k-half (64 channels + 1 pad slot)
+constexpr int W_HALF = 16 * W_PLANE + 64;  // bytes of one k-half (16 tap planes), skewed by 4 slots
 constexpr int XS_STAGE_MAX = 40960;     // bytes reserved per activation stage buffer
 
 struct MfmaArgs {
@@ -82,7 +83,7 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
     static_assert(N == 4, "bf16 MFMA path: in-register sub-kernel gather is written for n = 4");
     constexpr int HI = (N + 1) / 2;
     constexpr int NN = N * N;
-    constexpr int WS_STAGE = NN * 2 * W_PLANE;  // 33280 bytes
+    constexpr int WS_STAGE = 2 * W_HALF;  // 33408 bytes: [k-half][tap][channel][8 ci]
     extern __shared__ __align__(16) unsigned char lds[];
     // layout: weights stage 0, weights stage 1, activations stage 0, activations stage 1
     constexpr int XS_OFF = 2 * WS_STAGE;
@@ -114,25 +115,29 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
     }
 
     // ---- per-thread staging units (fixed for the whole K loop)
-    // weights: lane = channel co0 + lane, wave = (k-half g, tap-half h): 8 input channels
-    // ci0+8g.. of taps 8h..8h+7; lanes then write consecutive 16-byte LDS slots (no conflicts)
-    const int w_co = lane, w_g = wave & 1, w_h = wave >> 1;
+    // weights: thread = (channel co_l, k-half g, tap-half h), h fastest: the 8 loads of a thread
+    // walk 8 input channels (32 bytes apart) and neighbouring lanes read neighbouring 16-byte
+    // pieces, so every 64-byte line is consumed by consecutive instructions of one wave.  In LDS
+    // the planes are skewed so that the 16 lanes of a write phase (4 channels x g x h) hit
+    // distinct bank groups: co -> +1 slot, g -> +4 slots, h (8 planes) -> +8 slots (mod 16).
+    const int w_co = tid >> 2, w_g = (tid >> 1) & 1, w_h = tid & 1;
     const unsigned w_voff = (unsigned)(((co0 + w_co) * g.Cin + 8 * w_g) * (NN * 2) + w_h * 16);
-    const int w_lds = ((8 * w_h) * 2 + w_g) * W_PLANE + w_co * 16;  // + t * 2 * W_PLANE
+    const int w_lds = w_g * W_HALF + (8 * w_h) * W_PLANE + w_co * 16;  // + t * W_PLANE
     // activations: thread = (row r, k-half g, 8-column group c8)
     unsigned x_voff = kInvalid;
     int x_lds = 0;
-    bool x_unit = false;
     {
+        // threads beyond the unit count repeat a unit: same loads, same LDS writes, no branch
         const int units = a.ROWS * 2 * a.C8;
-        if (tid < units) {
-            const int c8 = tid % a.C8;
-            const int rg = tid / a.C8;
-            const int xg = rg & 1, r = rg >> 1;
+        {
+            const int un = tid % units;
+            // 8-column group fastest, then row, then k-half: lanes walk contiguous memory
+            const int c8 = un % a.C8;
+            const int t2 = un / a.C8;
+            const int r = t2 % a.ROWS, xg = t2 / a.ROWS;
             const int e = e_first + r;
             const int b = e / a.EH, ii = e - b * a.EH;
             const int i = g.k_min - g.P + ii;
-            x_unit = true;
             if (b < g.B && i >= 0 && i < g.H)
                 x_voff = (unsigned)((((b * g.Cin + 8 * xg) * g.H + i) * g.W + 8 * c8) * 2);
             // column c sits in slot c + c/8: the pad slot after every 8 columns spreads the
@@ -148,7 +153,7 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
 
     // ---- per-lane operand addresses
     // A (weights): lane = channel co0 + cw*32 + l32, k-half gk
-    const int a_lds = gk * W_PLANE + (cw * 32 + l32) * 16;
+    const int a_lds = gk * W_HALF + (cw * 32 + l32) * 16;
     // B (activations): lane = quad q0 + qh*128 + nt*32 + l32, k-half gk
     int b_lds[4][HI][HI];
 #pragma unroll
@@ -178,82 +183,98 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[nt][r][s][i] = 0.f;
 
-    u4v wreg[8], xreg[8];
-    auto stage_load = [&](int ci0) {
-#pragma unroll
-        for (int c = 0; c < 8; ++c)
-            wreg[c] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, w_voff,
-                                                            (unsigned)((ci0 + c) * (NN * 2)), 0);
-#pragma unroll
-        for (int c = 0; c < 8; ++c)
-            xreg[c] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, x_voff,
-                                                            (unsigned)(ci0 + c) * x_cstride, 0);
+    // ---- software pipeline ----------------------------------------------------------------
+    // Stage s lives in LDS buffer s&1 and passes through register set s&1.  Global loads are
+    // requested two stages ahead of their use: one stage of MFMA work (64 x 8 passes) is shorter
+    // than the memory latency under load.  Inside a stage every non-MFMA instruction is slotted
+    // between groups of four MFMAs (one group = one parity class at one window position), so that
+    // its issue time hides under the matrix pipe: per group one global load of stage s+2, two
+    // fragment reads for the next window position, and four v_perm + one LDS write that move one
+    // tap (weights) or one column (activations) of stage s+1 into the other LDS buffer.
+    const int stages = g.Cin / KC;
+    u4v wreg[2][8], xreg[2][8];
+    auto load_one = [&](int ci0, unsigned wv, unsigned xv, int j, u4v (&wr)[8], u4v (&xr)[8]) {
+        if (j < 8)
+            wr[j] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, wv,
+                                                          (unsigned)((ci0 + j) * (NN * 2)), 0);
+        else
+            xr[j - 8] = __builtin_amdgcn_raw_buffer_load_b128(
+                rs_x, xv, (unsigned)(ci0 + j - 8) * x_cstride, 0);
     };
-    auto stage_store = [&](int buf) {
-        u4v t[8];
-        transpose8x8_b16(wreg, t);
+    // element k of the 8x8 b16 transpose of rows in[0..7] (see transpose8x8_b16)
+    auto transposed_row = [&](const u4v (&in)[8], int k) {
+        u4v t;
+        const int q = k >> 1;
+        const unsigned sel = (k & 1) ? 0x07060302u : 0x05040100u;
 #pragma unroll
-        for (int k = 0; k < 8; ++k)
-            *reinterpret_cast<u4v*>(lds + buf * WS_STAGE + w_lds + k * 2 * W_PLANE) = t[k];
-        if (x_unit) {
-            transpose8x8_b16(xreg, t);
-#pragma unroll
-            for (int k = 0; k < 8; ++k)
-                *reinterpret_cast<u4v*>(lds + XS_OFF + buf * XS_STAGE_MAX + x_lds + k * 16) = t[k];
-        }
+        for (int pp = 0; pp < 4; ++pp) t[pp] = __builtin_amdgcn_perm(in[2 * pp + 1][q], in[2 * pp][q], sel);
+        return t;
     };
-    // operand fragments of window position p = u*HI + v: one B fragment per quad tile, one A
-    // fragment per parity class that owns a tap at this position
-    auto load_frags = [&](int buf, int p, bf16x8 (&bf)[4], bf16x8 (&af)[4]) {
-        const int u = p / HI, v = p % HI;
-#pragma unroll
-        for (int nt = 0; nt < 4; ++nt)
-            bf[nt] = *reinterpret_cast<const bf16x8*>(lds + b_lds[nt][u][v] + buf * XS_STAGE_MAX);
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const int r = c >> 1, sc = c & 1;
-            if (r + 2 * u >= N || sc + 2 * v >= N) continue;  // class has no tap here
-            const int tap = (r + 2 * u) * N + (sc + 2 * v);
-            af[c] = *reinterpret_cast<const bf16x8*>(lds + buf * WS_STAGE + a_lds +
-                                                     tap * 2 * W_PLANE);
-        }
+    auto store_one = [&](int buf, int j, const u4v (&wr)[8], const u4v (&xr)[8]) {
+        if (j < 8)
+            *reinterpret_cast<u4v*>(lds + buf * WS_STAGE + w_lds + j * W_PLANE) = transposed_row(wr, j);
+        else
+            *reinterpret_cast<u4v*>(lds + XS_OFF + buf * XS_STAGE_MAX + x_lds + (j - 8) * 16) =
+                transposed_row(xr, j - 8);
     };
-    auto compute = [&](int buf) {
-        bf16x8 bf[2][4], af[2][4];
-        load_frags(buf, 0, bf[0], af[0]);
-#pragma unroll
-        for (int p = 0; p < HI * HI; ++p) {
-            const int u = p / HI, v = p % HI;
-            // fragments of the next position are requested before this position's MFMAs issue
-            if (p + 1 < HI * HI) load_frags(buf, p + 1, bf[(p + 1) & 1], af[(p + 1) & 1]);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const int r = c >> 1, sc = c & 1;
-                if (r + 2 * u >= N || sc + 2 * v >= N) continue;
-#pragma unroll
-                for (int nt = 0; nt < 4; ++nt)
-                    acc[nt][r][sc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        af[p & 1][c], bf[p & 1][nt], acc[nt][r][sc], 0, 0, 0);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
+    auto a_frag = [&](int buf, int p, int c) {
+        const int u = p / HI, v = p % HI, r = c >> 1, sc = c & 1;
+        const int tap = (r + 2 * u) * N + (sc + 2 * v);
+        return *reinterpret_cast<const bf16x8*>(lds + buf * WS_STAGE + a_lds + tap * W_PLANE);
+    };
+    auto b_frag = [&](int buf, int p, int nt) {
+        return *reinterpret_cast<const bf16x8*>(lds + b_lds[nt][p / HI][p % HI] + buf * XS_STAGE_MAX);
     };
 
-    const int stages = g.Cin / KC;
-    stage_load(0);
-    __syncthreads();  // zero fill done before the first activation writes
-    stage_store(0);
-    __syncthreads();
-    int buf = 0;
-    for (int s = 1; s < stages; ++s) {
-        stage_load(s * KC);   // global loads of the next stage fly while this one is computed
-        compute(buf);
-        stage_store(buf ^ 1);
-        __syncthreads();
-        buf ^= 1;
+    // one K stage; `set` is a literal at every call site so that all indices fold
+    auto stage = [&](int set, int t_next) {
+        // stage t_next does not exist past the end: request zeros (out-of-range offsets)
+        const bool real = t_next < stages;
+        const int ci_next = (real ? t_next : 0) * KC;
+        const unsigned wv = real ? w_voff : kInvalid, xv = real ? x_voff : kInvalid;
+        bf16x8 bf[2][4], af[2];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) bf[0][i] = b_frag(set, 0, i);
+        af[0] = a_frag(set, 0, 0);
+#pragma unroll
+        for (int grp = 0; grp < 16; ++grp) {
+            const int p = grp >> 2, c = grp & 3;
+            // requested now, needed by the next group / the next window position
+            if (grp + 1 < 16) af[(grp + 1) & 1] = a_frag(set, (grp + 1) >> 2, (grp + 1) & 3);
+            if (p + 1 < 4) bf[(p + 1) & 1][c] = b_frag(set, p + 1, c);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt)
+                acc[nt][c >> 1][c & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    af[grp & 1], bf[p & 1][nt], acc[nt][c >> 1][c & 1], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            load_one(ci_next, wv, xv, grp, wreg[set], xreg[set]);
+            store_one(set ^ 1, grp, wreg[set ^ 1], xreg[set ^ 1]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+#pragma unroll
+    for (int j = 0; j < 16; ++j) load_one(0, w_voff, x_voff, j, wreg[0], xreg[0]);
+    {
+        const bool real = stages > 1;
+        const unsigned wv = real ? w_voff : kInvalid, xv = real ? x_voff : kInvalid;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) load_one(real ? KC : 0, wv, xv, j, wreg[1], xreg[1]);
     }
-    compute(buf);
+    __syncthreads();  // zero fill done before the first activation writes
+#pragma unroll
+    for (int j = 0; j < 16; ++j) store_one(0, j, wreg[0], xreg[0]);
+    __syncthreads();
+    // In iteration s the loads of stage s+2 go into register set s&1 (its previous content,
+    // stage s, is already in LDS) and set (s+1)&1 is transposed into LDS buffer (s+1)&1.  The
+    // loop always runs an even number of stages; an odd count is padded with a stage of zeros.
+    for (int s = 0; s < stages; s += 2) {
+        stage(0, s + 2);
+        __syncthreads();
+        stage(1, s + 3);
+        __syncthreads();
+    }
 
     // ---- epilogue: accumulator register i of a tile holds channel 8*(i/4) + 4*gk + (i%4) of the
     // wave's 32, for the lane's quad; column classes s = 1, 0 are neighbours in memory
@@ -350,7 +371,7 @@ hipError_t launch_mfma(const Geom& g, const void* x, const void* w, float* y, in
     MfmaArgs a;
     if (!make_args(g, dtype, a)) return hipErrorInvalidValue;
     constexpr int N = 4;
-    const size_t lds = 2 * (size_t)(N * N * 2 * W_PLANE) + 2 * (size_t)XS_STAGE_MAX;
+    const size_t lds = 2 * (size_t)(2 * W_HALF) + 2 * (size_t)XS_STAGE_MAX;
     // more than 64 KiB of dynamic LDS has to be allowed per device (a property of the loaded
     // kernel, not library state); cheap enough to repeat on every call
     hipError_t e = hipFuncSetAttribute((const void*)ukst_mfma_bf16_kernel<N>,
