@@ -17,8 +17,12 @@
 //
 // Block = 256 threads = 4 waves; block tile = 64 output channels x 256 quads x 4 classes; wave
 // tile = 32 channels x 128 quads x 4 classes = 16 accumulator tiles of 32x32 (256 registers).
+// Blocks are persistent: one block per compute unit walks over tiles, and the K pipeline runs
+// across tile boundaries (while the last stages of a tile are multiplied, the first stages of
+// the next tile are already being fetched and laid out in LDS), so only the accumulator drain
+// sits between two tiles.
 // K advances 16 input channels per stage; stages are double-buffered in LDS: while the matrix
-// cores work on stage s the global loads of stage s+1 are in flight.  NCHW keeps the K axis (ci)
+// cores work on stage s the global loads of stage s+2 are in flight.  NCHW keeps the K axis (ci)
 // slowest, while an MFMA lane wants 8 consecutive K values in one register group: both operands
 // are transposed in registers (8x8 b16 transposes out of v_perm_b32) on their way into LDS, which
 // is where the sub-kernels get gathered per tap.
@@ -42,6 +46,24 @@ constexpr int W_PLANE = (TM + 1) * 16;  // bytes of one tap plane of a k-half (6
 constexpr int W_HALF = 16 * W_PLANE + 64;  // bytes of one k-half (16 tap planes), skewed by 4 slots
 constexpr int XS_STAGE_MAX = 40960;     // bytes reserved per activation stage buffer
 
+// Exact division of n < 2^31 by a run-time constant: q = umulhi(n, M) >> sh.
+struct FastDiv { unsigned M; int sh; unsigned d; };
+inline FastDiv make_fastdiv(unsigned d)
+{
+    FastDiv f;
+    f.d = d; f.M = 0; f.sh = 0;
+    if (d <= 1) return f;
+    int l = 0;
+    while ((1ull << l) < d) ++l;
+    f.M = (unsigned)(((1ull << (31 + l)) / d) + 1);
+    f.sh = l - 1;
+    return f;
+}
+__device__ __forceinline__ int fdiv(int n, const FastDiv& f)
+{
+    return f.d == 1 ? n : (int)(__umulhi((unsigned)n, f.M) >> f.sh);
+}
+
 struct MfmaArgs {
     Geom g;
     int Q;        // total quads = B * KH * KW
@@ -52,27 +74,22 @@ struct MfmaArgs {
     int C8;       // 8-column groups per input row
     int nco;      // channel blocks
     int nqt;      // quad tiles
+    int ntiles;   // nco * nqt
+    int cb_major; // tile order: 1 = consecutive tiles share the channel block (big weights),
+                  //             0 = consecutive tiles share the quad tile (big activations)
+    FastDiv dKHW, dKW, dEH, dC8, dROWS, dNCO, dNQT;
 };
 
-__device__ __forceinline__ int xcd_contiguous(int bid, int nb)
+// 8x8 transpose of 16-bit elements held as 8 rows of 4 dwords: row k of the result collects
+// element k of every input row.
+__device__ __forceinline__ u4v transposed_row(const u4v (&in)[8], int k)
 {
-    constexpr int X = 8;
-    const int xcd = bid % X, idx = bid / X;
-    const int fl = nb / X, rem = nb % X;
-    return xcd * fl + (xcd < rem ? xcd : rem) + idx;
-}
-
-// 8x8 transpose of 16-bit elements held as 8 rows of 4 dwords: out[t] collects element t of every
-// input row.
-__device__ __forceinline__ void transpose8x8_b16(const u4v (&in)[8], u4v (&out)[8])
-{
+    u4v t;
+    const int q = k >> 1;
+    const unsigned sel = (k & 1) ? 0x07060302u : 0x05040100u;
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            out[2 * q][p] = __builtin_amdgcn_perm(in[2 * p + 1][q], in[2 * p][q], 0x05040100u);
-            out[2 * q + 1][p] = __builtin_amdgcn_perm(in[2 * p + 1][q], in[2 * p][q], 0x07060302u);
-        }
+    for (int pp = 0; pp < 4; ++pp) t[pp] = __builtin_amdgcn_perm(in[2 * pp + 1][q], in[2 * pp][q], sel);
+    return t;
 }
 
 template <int N>
@@ -95,17 +112,20 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
     const int cw = wave & 1;   // which 32-channel half of the block tile
     const int qh = wave >> 1;  // which 128-quad half of the block tile
     const int l32 = lane & 31, gk = lane >> 5;
-
-    const int bid = xcd_contiguous(blockIdx.x, gridDim.x);
-    const int cb = bid % a.nco, qt = bid / a.nco;
-    const int co0 = cb * TM;
-    const int q0 = qt * TN;
     const int KHW = g.KH * g.KW;
+    const int G = gridDim.x;
 
-    // rows this tile needs: quad row rho = b*KH + kk uses input rows e = b*EH + kk + u
-    const int q_last = (q0 + TN - 1 < a.Q ? q0 + TN - 1 : a.Q - 1);
-    const int bf = q0 / KHW, kf = (q0 - bf * KHW) / g.KW;
-    const int e_first = bf * a.EH + kf;
+    // Tile walked in round rho by this block.  Blocks are spread over the 8 XCDs round-robin, so
+    // within a round the blocks of one XCD get 32 consecutive tile numbers: the tiles that share
+    // weights or activations meet in the same L2 at the same time.
+    const int xcd_rank = (blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3);  // G is a multiple of 8
+    auto tile_of = [&](int rho, int& cb, int& qt) -> bool {
+        const int t = rho * G + xcd_rank;
+        if (t >= a.ntiles) return false;
+        if (a.cb_major) { cb = fdiv(t, a.dNQT); qt = t - cb * a.nqt; }
+        else            { qt = fdiv(t, a.dNCO); cb = t - qt * a.nco; }
+        return true;
+    };
 
     // ---- zero the activation buffers once: halo columns are never written again
     {
@@ -114,74 +134,53 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
         for (int i = tid; i < n16; i += 256) *reinterpret_cast<u4v*>(lds + XS_OFF + i * 16) = z;
     }
 
-    // ---- per-thread staging units (fixed for the whole K loop)
+    // ---- per-thread staging units
     // weights: thread = (channel co_l, k-half g, tap-half h), h fastest: the 8 loads of a thread
     // walk 8 input channels (32 bytes apart) and neighbouring lanes read neighbouring 16-byte
     // pieces, so every 64-byte line is consumed by consecutive instructions of one wave.  In LDS
     // the planes are skewed so that the 16 lanes of a write phase (4 channels x g x h) hit
     // distinct bank groups: co -> +1 slot, g -> +4 slots, h (8 planes) -> +8 slots (mod 16).
     const int w_co = tid >> 2, w_g = (tid >> 1) & 1, w_h = tid & 1;
-    const unsigned w_voff = (unsigned)(((co0 + w_co) * g.Cin + 8 * w_g) * (NN * 2) + w_h * 16);
     const int w_lds = w_g * W_HALF + (8 * w_h) * W_PLANE + w_co * 16;  // + t * W_PLANE
-    // activations: thread = (row r, k-half g, 8-column group c8)
-    unsigned x_voff = kInvalid;
-    int x_lds = 0;
+    // activations: thread = (8-column group c8, row r, k-half g), c8 fastest so that lanes walk
+    // contiguous memory; threads beyond the unit count repeat a unit (same loads, same LDS
+    // writes, no branch).  Column c sits in slot c + c/8: the pad slot after every 8 columns
+    // spreads the 128-byte stride between neighbouring units over the LDS banks.
+    int x_r, x_g, x_c8;
     {
-        // threads beyond the unit count repeat a unit: same loads, same LDS writes, no branch
         const int units = a.ROWS * 2 * a.C8;
-        {
-            const int un = tid % units;
-            // 8-column group fastest, then row, then k-half: lanes walk contiguous memory
-            const int c8 = un % a.C8;
-            const int t2 = un / a.C8;
-            const int r = t2 % a.ROWS, xg = t2 / a.ROWS;
-            const int e = e_first + r;
-            const int b = e / a.EH, ii = e - b * a.EH;
-            const int i = g.k_min - g.P + ii;
-            if (b < g.B && i >= 0 && i < g.H)
-                x_voff = (unsigned)((((b * g.Cin + 8 * xg) * g.H + i) * g.W + 8 * c8) * 2);
-            // column c sits in slot c + c/8: the pad slot after every 8 columns spreads the
-            // 128-byte stride between neighbouring units over the LDS banks
-            x_lds = ((xg * a.ROWS + r) * a.LWS + (a.OFFS + 8 * c8) / 8 * 9) * 16;
-        }
+        const int un = tid % units;
+        const int t2 = fdiv(un, a.dC8);
+        x_c8 = un - t2 * a.C8;
+        x_g = fdiv(t2, a.dROWS);
+        x_r = t2 - x_g * a.ROWS;
     }
+    const int x_lds = ((x_g * a.ROWS + x_r) * a.LWS + (a.OFFS + 8 * x_c8) / 8 * 9) * 16;
+
+    // global offsets of this thread's staging units for tile (cb, qt)
+    auto staging_offsets = [&](int cb, int qt, unsigned& wv, unsigned& xv) {
+        wv = (unsigned)(((cb * TM + w_co) * g.Cin + 8 * w_g) * (NN * 2) + w_h * 16);
+        const int q0 = qt * TN;
+        const int bf = fdiv(q0, a.dKHW), kf = fdiv(q0 - bf * KHW, a.dKW);
+        const int e = bf * a.EH + kf + x_r;  // input row index over the whole batch
+        const int b = fdiv(e, a.dEH), ii = e - b * a.EH;
+        const int i = g.k_min - g.P + ii;
+        xv = kInvalid;
+        if (b < g.B && i >= 0 && i < g.H)
+            xv = (unsigned)((((b * g.Cin + 8 * x_g) * g.H + i) * g.W + 8 * x_c8) * 2);
+    };
+
     const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc(
         (void*)x, 0, (int)((size_t)g.B * g.Cin * g.H * g.W * 2), kRsrcFlags);
     const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc(
         (void*)w, 0, (int)((size_t)g.Cout * g.Cin * NN * 2), kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t rs_y = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)y, 0, (int)((size_t)g.B * g.Cout * g.OH * g.OW * 4), kRsrcFlags);
     const unsigned x_cstride = (unsigned)(g.H * g.W * 2);  // bytes between input channels
+    const unsigned plane = (unsigned)(g.OH * g.OW * 4);
 
-    // ---- per-lane operand addresses
-    // A (weights): lane = channel co0 + cw*32 + l32, k-half gk
+    // A (weights): lane = channel cw*32 + l32 of the block tile, k-half gk
     const int a_lds = gk * W_HALF + (cw * 32 + l32) * 16;
-    // B (activations): lane = quad q0 + qh*128 + nt*32 + l32, k-half gk
-    int b_lds[4][HI][HI];
-#pragma unroll
-    for (int nt = 0; nt < 4; ++nt) {
-        int q = q0 + qh * 128 + nt * 32 + l32;
-        if (q >= a.Q) q = q_last;
-        const int b = q / KHW;
-        const int rem = q - b * KHW;
-        const int kk = rem / g.KW, mm = rem - kk * g.KW;
-        const int r = b * a.EH + kk - e_first;
-#pragma unroll
-        for (int u = 0; u < HI; ++u)
-#pragma unroll
-            for (int v = 0; v < HI; ++v) {
-                const int c = mm + v + (a.OFFS - (g.P >> 1));  // LDS column of window column v
-                b_lds[nt][u][v] = XS_OFF + ((gk * a.ROWS + r + u) * a.LWS + c + (c >> 3)) * 16;
-            }
-    }
-
-    f32x16 acc[4][2][2];
-#pragma unroll
-    for (int nt = 0; nt < 4; ++nt)
-#pragma unroll
-        for (int r = 0; r < 2; ++r)
-#pragma unroll
-            for (int s = 0; s < 2; ++s)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) acc[nt][r][s][i] = 0.f;
 
     // ---- software pipeline ----------------------------------------------------------------
     // Stage s lives in LDS buffer s&1 and passes through register set s&1.  Global loads are
@@ -189,10 +188,14 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
     // than the memory latency under load.  Inside a stage every non-MFMA instruction is slotted
     // between groups of four MFMAs (one group = one parity class at one window position), so that
     // its issue time hides under the matrix pipe: per group one global load of stage s+2, two
-    // fragment reads for the next window position, and four v_perm + one LDS write that move one
-    // tap (weights) or one column (activations) of stage s+1 into the other LDS buffer.
-    const int stages = g.Cin / KC;
+    // fragment reads for the next group / window position, and four v_perm + one LDS write that
+    // move one tap (weights) or one column (activations) of stage s+1 into the other LDS buffer.
+    const int stages = g.Cin / KC;            // real stages per tile
+    const int stages_even = (stages + 1) & ~1;  // an odd count is padded with a stage of zeros
     u4v wreg[2][8], xreg[2][8];
+    f32x16 acc[4][2][2];
+    int b_lds[4][HI][HI];
+
     auto load_one = [&](int ci0, unsigned wv, unsigned xv, int j, u4v (&wr)[8], u4v (&xr)[8]) {
         if (j < 8)
             wr[j] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, wv,
@@ -200,15 +203,6 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
         else
             xr[j - 8] = __builtin_amdgcn_raw_buffer_load_b128(
                 rs_x, xv, (unsigned)(ci0 + j - 8) * x_cstride, 0);
-    };
-    // element k of the 8x8 b16 transpose of rows in[0..7] (see transpose8x8_b16)
-    auto transposed_row = [&](const u4v (&in)[8], int k) {
-        u4v t;
-        const int q = k >> 1;
-        const unsigned sel = (k & 1) ? 0x07060302u : 0x05040100u;
-#pragma unroll
-        for (int pp = 0; pp < 4; ++pp) t[pp] = __builtin_amdgcn_perm(in[2 * pp + 1][q], in[2 * pp][q], sel);
-        return t;
     };
     auto store_one = [&](int buf, int j, const u4v (&wr)[8], const u4v (&xr)[8]) {
         if (j < 8)
@@ -225,100 +219,166 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
     auto b_frag = [&](int buf, int p, int nt) {
         return *reinterpret_cast<const bf16x8*>(lds + b_lds[nt][p / HI][p % HI] + buf * XS_STAGE_MAX);
     };
-
-    // one K stage; `set` is a literal at every call site so that all indices fold
-    auto stage = [&](int set, int t_next) {
-        // stage t_next does not exist past the end: request zeros (out-of-range offsets)
-        const bool real = t_next < stages;
-        const int ci_next = (real ? t_next : 0) * KC;
-        const unsigned wv = real ? w_voff : kInvalid, xv = real ? x_voff : kInvalid;
-        bf16x8 bf[2][4], af[2];
+    // one K stage; `set` is a literal at every call site so that all indices fold.  (ci_next, wv,
+    // xv) describe the stage requested from memory during this one.
+    auto stage = [&](int set, int ci_next, unsigned wv, unsigned xv) {
+        bf16x8 bf[2][4], af[3];
 #pragma unroll
         for (int i = 0; i < 4; ++i) bf[0][i] = b_frag(set, 0, i);
         af[0] = a_frag(set, 0, 0);
+        af[1] = a_frag(set, 0, 1);
 #pragma unroll
         for (int grp = 0; grp < 16; ++grp) {
             const int p = grp >> 2, c = grp & 3;
-            // requested now, needed by the next group / the next window position
-            if (grp + 1 < 16) af[(grp + 1) & 1] = a_frag(set, (grp + 1) >> 2, (grp + 1) & 3);
-            if (p + 1 < 4) bf[(p + 1) & 1][c] = b_frag(set, p + 1, c);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int nt = 0; nt < 4; ++nt)
+            // A wave issues in order and waits for the matrix pipe at every MFMA, so the other
+            // instructions are spread one by one into the shadows of the four MFMAs of a group:
+            // global load | fragment reads (two groups ahead: LDS latency under load exceeds
+            // one group) | v_perm | LDS write.
+            auto mfma = [&](int nt) {
+                __builtin_amdgcn_sched_barrier(0);
                 acc[nt][c >> 1][c & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    af[grp & 1], bf[p & 1][nt], acc[nt][c >> 1][c & 1], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
+                    af[grp % 3], bf[p & 1][nt], acc[nt][c >> 1][c & 1], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            mfma(0);
             load_one(ci_next, wv, xv, grp, wreg[set], xreg[set]);
-            store_one(set ^ 1, grp, wreg[set ^ 1], xreg[set ^ 1]);
+            mfma(1);
+            if (grp + 2 < 16) af[(grp + 2) % 3] = a_frag(set, (grp + 2) >> 2, (grp + 2) & 3);
+            if (p + 1 < 4 && c < 2) {
+                bf[(p + 1) & 1][2 * c] = b_frag(set, p + 1, 2 * c);
+                bf[(p + 1) & 1][2 * c + 1] = b_frag(set, p + 1, 2 * c + 1);
+            }
+            mfma(2);
+            const u4v t = grp < 8 ? transposed_row(wreg[set ^ 1], grp)
+                                  : transposed_row(xreg[set ^ 1], grp - 8);
+            mfma(3);
+            if (grp < 8)
+                *reinterpret_cast<u4v*>(lds + (set ^ 1) * WS_STAGE + w_lds + grp * W_PLANE) = t;
+            else
+                *reinterpret_cast<u4v*>(lds + XS_OFF + (set ^ 1) * XS_STAGE_MAX + x_lds +
+                                        (grp - 8) * 16) = t;
         }
         __builtin_amdgcn_sched_barrier(0);
     };
 
+    // ---- first tile of this block: fill the pipeline
+    int cb = 0, qt = 0;
+    bool have = tile_of(0, cb, qt);
+    unsigned wv_c = kInvalid, xv_c = kInvalid;
+    if (have) staging_offsets(cb, qt, wv_c, xv_c);
 #pragma unroll
-    for (int j = 0; j < 16; ++j) load_one(0, w_voff, x_voff, j, wreg[0], xreg[0]);
+    for (int j = 0; j < 16; ++j) load_one(0, wv_c, xv_c, j, wreg[0], xreg[0]);
     {
         const bool real = stages > 1;
-        const unsigned wv = real ? w_voff : kInvalid, xv = real ? x_voff : kInvalid;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) load_one(real ? KC : 0, wv, xv, j, wreg[1], xreg[1]);
+        for (int j = 0; j < 16; ++j)
+            load_one(real ? KC : 0, real ? wv_c : kInvalid, real ? xv_c : kInvalid, j, wreg[1], xreg[1]);
     }
     __syncthreads();  // zero fill done before the first activation writes
 #pragma unroll
     for (int j = 0; j < 16; ++j) store_one(0, j, wreg[0], xreg[0]);
     __syncthreads();
-    // In iteration s the loads of stage s+2 go into register set s&1 (its previous content,
-    // stage s, is already in LDS) and set (s+1)&1 is transposed into LDS buffer (s+1)&1.  The
-    // loop always runs an even number of stages; an odd count is padded with a stage of zeros.
-    for (int s = 0; s < stages; s += 2) {
-        stage(0, s + 2);
-        __syncthreads();
-        stage(1, s + 3);
-        __syncthreads();
-    }
 
-    // ---- epilogue: accumulator register i of a tile holds channel 8*(i/4) + 4*gk + (i%4) of the
-    // wave's 32, for the lane's quad; column classes s = 1, 0 are neighbours in memory
-    const __amdgpu_buffer_rsrc_t rs_y = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)y, 0, (int)((size_t)g.B * g.Cout * g.OH * g.OW * 4), kRsrcFlags);
-    const unsigned plane = (unsigned)(g.OH * g.OW * 4);
+    for (int rho = 0; have; ++rho) {
+        // next tile of this block (its first two stages are fetched during this tile's last two)
+        int cb_n = 0, qt_n = 0;
+        const bool have_n = tile_of(rho + 1, cb_n, qt_n);
+        unsigned wv_n = kInvalid, xv_n = kInvalid;
+        if (have_n) staging_offsets(cb_n, qt_n, wv_n, xv_n);
+
+        // B (activations): lane = quad q0 + qh*128 + nt*32 + l32 of this tile, k-half gk
+        const int q0 = qt * TN;
+        const int q_last = (q0 + TN - 1 < a.Q ? q0 + TN - 1 : a.Q - 1);
+        const int bf0 = fdiv(q0, a.dKHW), kf0 = fdiv(q0 - bf0 * KHW, a.dKW);
+        const int e_first = bf0 * a.EH + kf0;
 #pragma unroll
-    for (int nt = 0; nt < 4; ++nt) {
-        const int q = q0 + qh * 128 + nt * 32 + l32;
-        const bool qv = q < a.Q;
-        const int qq = qv ? q : q_last;
-        const int b = qq / KHW;
-        const int rem = qq - b * KHW;
-        const int kk = rem / g.KW, mm = rem - kk * g.KW;
-        const int k = g.k_min + kk, m = g.m_min + mm;
-        const int oy1 = 2 * k - 1 - g.P, ox1 = 2 * m - 1 - g.P;  // row / column of class 1
-        const bool vcol1 = ox1 >= 0 && ox1 < g.OW, vcol0 = ox1 + 1 < g.OW;
-        // byte offset of (channel co0 + cw*32 + 4*gk, row oy1, column ox1); unsigned wrap-around
-        // keeps the arithmetic right when oy1 or ox1 is -1 and only the other class exists
-        const unsigned y_off =
-            (unsigned)((((b * g.Cout + co0 + cw * 32 + 4 * gk) * g.OH + oy1) * g.OW + ox1) * 4);
+        for (int nt = 0; nt < 4; ++nt) {
+            int q = q0 + qh * 128 + nt * 32 + l32;
+            if (q >= a.Q) q = q_last;
+            const int b = fdiv(q, a.dKHW);
+            const int rem = q - b * KHW;
+            const int kk = fdiv(rem, a.dKW), mm = rem - kk * g.KW;
+            const int r = b * a.EH + kk - e_first;
 #pragma unroll
-        for (int r = 1; r >= 0; --r) {
-            const bool vrow = qv && (r ? (oy1 >= 0 && oy1 < g.OH) : (oy1 + 1 < g.OH));
-            const unsigned base = y_off + (r ? 0u : (unsigned)(g.OW * 4));
-            const unsigned off_pair = (vrow && vcol1 && vcol0) ? base : kInvalid;
-            const unsigned off_s1 = (vrow && vcol1 && !vcol0) ? base : kInvalid;
-            const unsigned off_s0 = (vrow && !vcol1 && vcol0) ? base + 4u : kInvalid;
-            const bool edge = (off_s1 != kInvalid) || (off_s0 != kInvalid);
-            const bool any_edge = __builtin_amdgcn_ballot_w64(edge) != 0;  // wave-uniform
+            for (int u = 0; u < HI; ++u)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const unsigned soff = (unsigned)(8 * (i / 4) + (i % 4)) * plane;
-                u2v d;
-                const float v1 = acc[nt][r][1][i], v0 = acc[nt][r][0][i];  // by value, then bits
-                d.x = __float_as_uint(v1);
-                d.y = __float_as_uint(v0);
-                __builtin_amdgcn_raw_buffer_store_b64(d, rs_y, off_pair, soff, 0);
-                if (any_edge) {
-                    __builtin_amdgcn_raw_buffer_store_b32(d.x, rs_y, off_s1, soff, 0);
-                    __builtin_amdgcn_raw_buffer_store_b32(d.y, rs_y, off_s0, soff, 0);
+                for (int v = 0; v < HI; ++v) {
+                    const int c = mm + v + (a.OFFS - (g.P >> 1));  // LDS column of window column v
+                    b_lds[nt][u][v] = XS_OFF + ((gk * a.ROWS + r + u) * a.LWS + c + (c >> 3)) * 16;
+                }
+        }
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+            for (int r = 0; r < 2; ++r)
+#pragma unroll
+                for (int sc = 0; sc < 2; ++sc)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[nt][r][sc][i] = 0.f;
+
+        // In iteration s the loads of stage s+2 go into register set 0 and those of s+3 into set 1
+        // (their previous contents are already in LDS), while sets 1 / 0 are transposed into the
+        // other LDS buffer.  The last iteration requests stages 0 and 1 of the next tile instead.
+        for (int s = 0; s < stages_even; s += 2) {
+            const bool last = s + 2 >= stages_even;
+            {
+                const int t = last ? 0 : s + 2;
+                stage(0, t * KC, last ? wv_n : wv_c, last ? xv_n : xv_c);
+            }
+            __syncthreads();
+            {
+                const int t = last ? 1 : s + 3;
+                const bool real = t < stages;
+                stage(1, real ? t * KC : 0, real ? (last ? wv_n : wv_c) : kInvalid,
+                      real ? (last ? xv_n : xv_c) : kInvalid);
+            }
+            __syncthreads();
+        }
+
+        // ---- drain: accumulator register i of a tile holds channel 8*(i/4) + 4*gk + (i%4) of the
+        // wave's 32, for the lane's quad; column classes s = 1, 0 are neighbours in memory
+        const int co0 = cb * TM;
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) {
+            const int q = q0 + qh * 128 + nt * 32 + l32;
+            const bool qv = q < a.Q;
+            const int qq = qv ? q : q_last;
+            const int b = fdiv(qq, a.dKHW);
+            const int rem = qq - b * KHW;
+            const int kk = fdiv(rem, a.dKW), mm = rem - kk * g.KW;
+            const int k = g.k_min + kk, m = g.m_min + mm;
+            const int oy1 = 2 * k - 1 - g.P, ox1 = 2 * m - 1 - g.P;  // row / column of class 1
+            const bool vcol1 = ox1 >= 0 && ox1 < g.OW, vcol0 = ox1 + 1 < g.OW;
+            // byte offset of (channel co0 + cw*32 + 4*gk, row oy1, column ox1); unsigned
+            // wrap-around keeps the arithmetic right when oy1 or ox1 is -1 and only the other
+            // class exists
+            const unsigned y_off =
+                (unsigned)((((b * g.Cout + co0 + cw * 32 + 4 * gk) * g.OH + oy1) * g.OW + ox1) * 4);
+#pragma unroll
+            for (int r = 1; r >= 0; --r) {
+                const bool vrow = qv && (r ? (oy1 >= 0 && oy1 < g.OH) : (oy1 + 1 < g.OH));
+                const unsigned base = y_off + (r ? 0u : (unsigned)(g.OW * 4));
+                const unsigned off_pair = (vrow && vcol1 && vcol0) ? base : kInvalid;
+                const unsigned off_s1 = (vrow && vcol1 && !vcol0) ? base : kInvalid;
+                const unsigned off_s0 = (vrow && !vcol1 && vcol0) ? base + 4u : kInvalid;
+                const bool edge = (off_s1 != kInvalid) || (off_s0 != kInvalid);
+                const bool any_edge = __builtin_amdgcn_ballot_w64(edge) != 0;  // wave-uniform
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const unsigned soff = (unsigned)(8 * (i / 4) + (i % 4)) * plane;
+                    u2v d;
+                    const float v1 = acc[nt][r][1][i], v0 = acc[nt][r][0][i];  // by value, then bits
+                    d.x = __float_as_uint(v1);
+                    d.y = __float_as_uint(v0);
+                    __builtin_amdgcn_raw_buffer_store_b64(d, rs_y, off_pair, soff, 0);
+                    if (any_edge) {
+                        __builtin_amdgcn_raw_buffer_store_b32(d.x, rs_y, off_s1, soff, 0);
+                        __builtin_amdgcn_raw_buffer_store_b32(d.y, rs_y, off_s0, soff, 0);
+                    }
                 }
             }
         }
+        have = have_n; cb = cb_n; qt = qt_n; wv_c = wv_n; xv_c = xv_n;
     }
 }
 
@@ -353,7 +413,17 @@ bool make_args(const Geom& g, int dtype, MfmaArgs& a)
     if (a.ROWS * 2 * a.C8 > 256) return false;   // one staging unit per thread
     a.nco = g.Cout / TM;
     a.nqt = (int)((Q + TN - 1) / TN);
-    if ((long long)a.nco * a.nqt > 0x7FFFFFFFLL) return false;
+    if ((long long)a.nco * a.nqt > 0x3FFFFFFFLL) return false;
+    a.ntiles = a.nco * a.nqt;
+    // keep in one L2 what is bigger: the weights of a channel block or a tile's activations
+    a.cb_major = ((size_t)TM * g.Cin * g.n * g.n * 2 > (size_t)(1 << 20)) ? 1 : 0;
+    a.dKHW = make_fastdiv((unsigned)(g.KH * g.KW));
+    a.dKW = make_fastdiv((unsigned)g.KW);
+    a.dEH = make_fastdiv((unsigned)a.EH);
+    a.dC8 = make_fastdiv((unsigned)a.C8);
+    a.dROWS = make_fastdiv((unsigned)a.ROWS);
+    a.dNCO = make_fastdiv((unsigned)a.nco);
+    a.dNQT = make_fastdiv((unsigned)a.nqt);
     return true;
 }
 
@@ -377,8 +447,17 @@ hipError_t launch_mfma(const Geom& g, const void* x, const void* w, float* y, in
     hipError_t e = hipFuncSetAttribute((const void*)ukst_mfma_bf16_kernel<N>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((ukst_mfma_bf16_kernel<N>), dim3((unsigned)(a.nco * a.nqt)), dim3(256), lds,
-                       stream, (const uint16_t*)x, (const uint16_t*)w, y, a);
+    // persistent blocks: one per compute unit (a multiple of the 8 XCDs), never more than tiles
+    int dev = 0, cus = 0;
+    if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+    if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess)
+        return e;
+    int grid = (cus / 8) * 8;
+    if (grid < 8) grid = 8;
+    const int need = ((a.ntiles + 7) / 8) * 8;
+    if (grid > need) grid = need;
+    hipLaunchKernelGGL((ukst_mfma_bf16_kernel<N>), dim3((unsigned)grid), dim3(256), lds, stream,
+                       (const uint16_t*)x, (const uint16_t*)w, y, a);
     return hipGetLastError();
 }
 
