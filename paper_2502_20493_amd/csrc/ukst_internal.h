@@ -49,4 +49,8 @@ hipError_t launch_mfma(const Geom& g, const void* x, const void* w, float* y, in
                        hipStream_t stream);
 const char* mfma_kernel_name(const Geom& g, int dtype);
 
+// fp32-operand MFMA kernel (used by the three functions above for dtype 0)
+bool mfma_f32_supported(const Geom& g);
+hipError_t launch_mfma_f32(const Geom& g, const void* x, const void* w, float* y, hipStream_t stream);
+
 }  // namespace ukst

@@ -396,7 +396,7 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
 
 bool make_args(const Geom& g, int dtype, MfmaArgs& a)
 {
-    if (dtype != 1) return false;                // fp32 operands: not on this path yet
+    if (dtype != 1) return false;                // fp32 operands: see ukst_mfma_f32.hip
     if (g.n != 4) return false;
     if (g.Cin % KC != 0 || g.Cout % TM != 0) return false;
     if (g.W % 8 != 0) return false;              // 16-byte row chunks
@@ -444,6 +444,7 @@ bool make_args(const Geom& g, int dtype, MfmaArgs& a)
 
 bool mfma_supported(const Geom& g, int dtype)
 {
+    if (dtype == 0) return mfma_f32_supported(g);
     MfmaArgs a;
     return make_args(g, dtype, a);
 }
@@ -451,6 +452,7 @@ bool mfma_supported(const Geom& g, int dtype)
 hipError_t launch_mfma(const Geom& g, const void* x, const void* w, float* y, int dtype,
                        hipStream_t stream)
 {
+    if (dtype == 0) return launch_mfma_f32(g, x, w, y, stream);
     MfmaArgs a;
     if (!make_args(g, dtype, a)) return hipErrorInvalidValue;
     constexpr int N = 4;
@@ -476,6 +478,9 @@ hipError_t launch_mfma(const Geom& g, const void* x, const void* w, float* y, in
     return hipGetLastError();
 }
 
-const char* mfma_kernel_name(const Geom&, int) { return "ukst_mfma_bf16_kernel"; }
+const char* mfma_kernel_name(const Geom&, int dtype)
+{
+    return dtype == 0 ? "ukst_mfma_f32_kernel" : "ukst_mfma_bf16_kernel";
+}
 
 }  // namespace ukst

@@ -1,0 +1,394 @@
+// MFMA path for fp32 operands: the same parity-class implicit GEMM as the bf16 kernel
+// (ukst_mfma.hip), on v_mfma_f32_32x32x2_f32.
+//
+// Per quad the four parity classes of Algorithm 2 share one ceil(n/2) x ceil(n/2) input window,
+// so one B fragment (activations at window position (u, v), two input channels) feeds one MFMA
+// per class that owns a tap there, with that class's tap w[co][ci][r+2u][s+2v] as A fragment
+// (Eqs. 1-4): n*n MFMA columns per quad tile and channel pair, none spent on a bed-of-nails zero.
+// M = output channels, N = quads flattened over (image, quad row, quad column), K = input
+// channels.  An fp32 MFMA lane holds ONE K value per operand, so NCHW data needs no transposition:
+// activations go to LDS as [k][row][col], weights as [k][tap][channel], with plain 4-byte loads
+// (any W, any n <= 5, no alignment requirement).  The matrix pipe needs 16 passes per
+// instruction, so staging is cheap next to it: global loads for the next stage are issued before
+// the current stage is multiplied and written to the other LDS buffer afterwards.
+//
+// Block = 4 waves; tile = 64 channels x (64*NW) quads x 4 classes; wave = 32 channels x 32*NW
+// quads (NW = 4, 2 or 1 so that small layers still fill the chip).  The epilogue stores the two
+// column classes of a quad as one 8-byte element, classes interleaved in place.
+#include "ukst_internal.h"
+
+namespace ukst {
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned u2v __attribute__((ext_vector_type(2)));
+
+constexpr int kRsrcFlags = 0x00020000;      // raw 32-bit buffer, gfx9 family
+constexpr unsigned kInvalid = 0xFFFFFF00u;  // byte offset that is out of range for any buffer
+constexpr int TM = 64;      // output channels per block
+constexpr int KC = 8;       // input channels per stage (4 MFMA K steps)
+constexpr int PW = 65;      // floats per (k, tap) weight row in LDS: 64 channels + 1, so that the
+                            // staging lanes (consecutive rows, one channel) hit consecutive banks
+constexpr int NXL_MAX = 24; // activation elements one thread stages per K stage, at most
+constexpr int LDS_LIMIT = 160 * 1024;
+
+struct FastDiv { unsigned M; int sh; unsigned d; };
+inline FastDiv make_fastdiv(unsigned d)
+{
+    FastDiv f;
+    f.d = d; f.M = 0; f.sh = 0;
+    if (d <= 1) return f;
+    int l = 0;
+    while ((1ull << l) < d) ++l;
+    f.M = (unsigned)(((1ull << (31 + l)) / d) + 1);
+    f.sh = l - 1;
+    return f;
+}
+// exact for 0 <= n < 2^31
+__device__ __forceinline__ int fdiv(int n, const FastDiv& f)
+{
+    return f.d == 1 ? n : (int)(__umulhi((unsigned)n, f.M) >> f.sh);
+}
+
+struct F32Args {
+    Geom g;
+    int Q;       // total quads = B * KH * KW
+    int EH;      // input rows one image's quad rows touch = KH + ceil(n/2) - 1
+    int ROWS;    // input rows an activation stage holds
+    int LWX;     // floats per staged row: left halo + W + right halo
+    int XP;      // floats per k plane of the activation stage
+    int SH;      // LDS column of input column 0 = floor(P/2)
+    int nxl;     // activation elements per thread and stage
+    int nco, nqt;
+    int xs_stage_bytes;
+    FastDiv dKHW, dKW, dEH, dRW, dW;
+};
+
+__device__ __forceinline__ int xcd_contiguous(int bid, int nb)
+{
+    constexpr int X = 8;
+    const int xcd = bid % X, idx = bid / X;
+    const int fl = nb / X, rem = nb % X;
+    return xcd * fl + (xcd < rem ? xcd : rem) + idx;
+}
+
+template <int N, int NW>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void ukst_mfma_f32_kernel(const float* __restrict__ x, const float* __restrict__ w,
+                          float* __restrict__ y, F32Args a)
+{
+    constexpr int HI = (N + 1) / 2;
+    constexpr int NN = N * N;
+    constexpr int TN = 64 * NW;                 // quads per block
+    constexpr int WS_STAGE = NN * KC * PW * 4;  // bytes of one weight stage
+    constexpr int NWL = (TM * KC * NN + 255) / 256;  // weight elements per thread and stage
+    extern __shared__ __align__(16) unsigned char lds[];
+    float* const ldsf = reinterpret_cast<float*>(lds);
+    // layout: weights stage 0 | weights stage 1 | activations stage 0 | activations stage 1
+    constexpr int XS_OFF = 2 * WS_STAGE;
+
+    const Geom& g = a.g;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int cw = wave & 1;   // which 32-channel half of the block tile
+    const int qh = wave >> 1;  // which half of the block's quads
+    const int l32 = lane & 31, gk = lane >> 5;
+    const int KHW = g.KH * g.KW;
+
+    const int bid = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int cb = bid % a.nco, qt = bid / a.nco;
+    const int co0 = cb * TM;
+    const int q0 = qt * TN;
+    const int q_last = (q0 + TN - 1 < a.Q ? q0 + TN - 1 : a.Q - 1);
+    // quad row rho = b*KH + kk uses input rows e = b*EH + kk + u (u < HI)
+    const int bf0 = fdiv(q0, a.dKHW), kf0 = fdiv(q0 - bf0 * KHW, a.dKW);
+    const int e_first = bf0 * a.EH + kf0;
+
+    // ---- zero both activation buffers once: halo columns are never written again
+    {
+        const int nf = 2 * a.xs_stage_bytes / 4;
+        for (int i = tid; i < nf; i += 256) ldsf[XS_OFF / 4 + i] = 0.f;
+    }
+
+    // ---- activation staging: element e = tid + 256*j -> (k, row, col) of the stage
+    unsigned x_goff[NXL_MAX];  // global byte offset (for ci0 = 0), kInvalid for rows that do not exist
+    int x_loff[NXL_MAX];       // LDS float index inside an activation stage, -1 = nothing to do
+#pragma unroll
+    for (int j = 0; j < NXL_MAX; ++j) {
+        x_goff[j] = kInvalid;
+        x_loff[j] = -1;
+        if (j < a.nxl) {
+            const int e = tid + 256 * j;
+            const int k = fdiv(e, a.dRW);
+            const int rem = e - k * (a.ROWS * g.W);
+            const int row = fdiv(rem, a.dW), col = rem - row * g.W;
+            if (k < KC) {
+                const int er = e_first + row;
+                const int b = fdiv(er, a.dEH), ii = er - b * a.EH;
+                const int i = g.k_min - g.P + ii;
+                if (b < g.B && i >= 0 && i < g.H)
+                    x_goff[j] = (unsigned)((((b * g.Cin + k) * g.H + i) * g.W + col) * 4);
+                x_loff[j] = k * a.XP + row * a.LWX + a.SH + col;
+            }
+        }
+    }
+    const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)x, 0, (int)((size_t)g.B * g.Cin * g.H * g.W * 4), kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)w, 0, (int)((size_t)g.Cout * g.Cin * NN * 4), kRsrcFlags);
+    const unsigned x_cstride = (unsigned)(g.H * g.W * 4);  // bytes between input channels
+
+    // ---- per-lane operand positions
+    // A (weights): lane = channel cw*32 + l32, k parity gk
+    const int a_base = gk * NN * PW + cw * 32 + l32;  // + (2*ks*NN + tap) * PW
+    // B (activations): lane = quad q0 + (qh*NW + nt)*32 + l32, k parity gk
+    int b_base[NW];
+#pragma unroll
+    for (int nt = 0; nt < NW; ++nt) {
+        int q = q0 + (qh * NW + nt) * 32 + l32;
+        if (q > q_last) q = q_last;
+        const int b = fdiv(q, a.dKHW);
+        const int rem = q - b * KHW;
+        const int kk = fdiv(rem, a.dKW), mm = rem - kk * g.KW;
+        const int r = b * a.EH + kk - e_first;
+        // window column v of quad column mm is input column m_min + mm - P + v
+        b_base[nt] = XS_OFF / 4 + gk * a.XP + r * a.LWX + mm + (a.SH + g.m_min - g.P);
+    }
+
+    f32x16 acc[NW][2][2];
+#pragma unroll
+    for (int nt = 0; nt < NW; ++nt)
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+#pragma unroll
+            for (int sc = 0; sc < 2; ++sc)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[nt][r][sc][i] = 0.f;
+
+    float wreg[NWL], xreg[NXL_MAX];
+    // weight element e = tid + 256*j -> channel co = e / (KC*NN), then (k, tap) contiguous in
+    // memory: lanes read consecutive floats
+    auto stage_load = [&](int ci0) {
+#pragma unroll
+        for (int j = 0; j < NWL; ++j) {
+            const int e = tid + 256 * j;
+            const int co = e / (KC * NN), rem = e - co * (KC * NN);
+            const unsigned voff = (co < TM) ? (unsigned)(((co0 + co) * g.Cin * NN + rem) * 4) : kInvalid;
+            wreg[j] = __builtin_bit_cast(
+                float, __builtin_amdgcn_raw_buffer_load_b32(rs_w, voff, (unsigned)(ci0 * NN * 4), 0));
+        }
+#pragma unroll
+        for (int j = 0; j < NXL_MAX; ++j)
+            if (j < a.nxl)
+                xreg[j] = __builtin_bit_cast(
+                    float, __builtin_amdgcn_raw_buffer_load_b32(rs_x, x_goff[j],
+                                                                (unsigned)ci0 * x_cstride, 0));
+    };
+    auto stage_store = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < NWL; ++j) {
+            const int e = tid + 256 * j;
+            const int co = e / (KC * NN), rem = e - co * (KC * NN);
+            if (co < TM) ldsf[buf * (WS_STAGE / 4) + rem * PW + co] = wreg[j];  // rem = k*NN + tap
+        }
+#pragma unroll
+        for (int j = 0; j < NXL_MAX; ++j)
+            if (j < a.nxl && x_loff[j] >= 0)
+                ldsf[XS_OFF / 4 + buf * (a.xs_stage_bytes / 4) + x_loff[j]] = xreg[j];
+    };
+    auto compute = [&](int buf) {
+        const float* ws = ldsf + buf * (WS_STAGE / 4) + a_base;
+        const int xb = buf * (a.xs_stage_bytes / 4);
+#pragma unroll
+        for (int ks = 0; ks < KC / 2; ++ks)
+#pragma unroll
+            for (int u = 0; u < HI; ++u)
+#pragma unroll
+                for (int v = 0; v < HI; ++v) {
+                    float bfr[NW];
+                    const int xo = xb + 2 * ks * a.XP + u * a.LWX + v;
+#pragma unroll
+                    for (int nt = 0; nt < NW; ++nt) bfr[nt] = ldsf[b_base[nt] + xo];
+#pragma unroll
+                    for (int r = 0; r < 2; ++r)
+#pragma unroll
+                        for (int sc = 0; sc < 2; ++sc) {
+                            if (r + 2 * u >= N || sc + 2 * v >= N) continue;  // no tap here
+                            const int tap = (r + 2 * u) * N + (sc + 2 * v);
+                            const float afr = ws[(2 * ks * NN + tap) * PW];
+#pragma unroll
+                            for (int nt = 0; nt < NW; ++nt)
+                                acc[nt][r][sc] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                                    afr, bfr[nt], acc[nt][r][sc], 0, 0, 0);
+                        }
+                }
+    };
+
+    const int stages = (g.Cin + KC - 1) / KC;  // channels past Cin read as zero (range check)
+    stage_load(0);
+    __syncthreads();  // zero fill done before the first activation writes
+    stage_store(0);
+    __syncthreads();
+    int buf = 0;
+    for (int s = 1; s < stages; ++s) {
+        stage_load(s * KC);  // in flight while this stage is multiplied
+        compute(buf);
+        stage_store(buf ^ 1);
+        __syncthreads();
+        buf ^= 1;
+    }
+    compute(buf);
+
+    // ---- epilogue: accumulator register i of a tile holds channel 8*(i/4) + 4*gk + (i%4) of the
+    // wave's 32, for the lane's quad; column classes s = 1, 0 are neighbours in memory
+    const __amdgpu_buffer_rsrc_t rs_y = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)y, 0, (int)((size_t)g.B * g.Cout * g.OH * g.OW * 4), kRsrcFlags);
+    const unsigned plane = (unsigned)(g.OH * g.OW * 4);
+#pragma unroll
+    for (int nt = 0; nt < NW; ++nt) {
+        const int q = q0 + (qh * NW + nt) * 32 + l32;
+        const bool qv = q <= q_last;
+        const int qq = qv ? q : q_last;
+        const int b = fdiv(qq, a.dKHW);
+        const int rem = qq - b * KHW;
+        const int kk = fdiv(rem, a.dKW), mm = rem - kk * g.KW;
+        const int k = g.k_min + kk, m = g.m_min + mm;
+        const int oy1 = 2 * k - 1 - g.P, ox1 = 2 * m - 1 - g.P;  // row / column of class 1
+        const bool vcol1 = ox1 >= 0 && ox1 < g.OW, vcol0 = ox1 + 1 < g.OW;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int co = co0 + cw * 32 + 8 * (i / 4) + 4 * gk + (i % 4);
+            const bool cv = co < g.Cout;  // ragged last channel block
+            // unsigned wrap-around keeps the arithmetic right when oy1 or ox1 is -1
+            const unsigned y_off = (unsigned)((((b * g.Cout + co) * g.OH + oy1) * g.OW + ox1) * 4);
+#pragma unroll
+            for (int r = 1; r >= 0; --r) {
+                const bool vrow = cv && qv && (r ? (oy1 >= 0 && oy1 < g.OH) : (oy1 + 1 < g.OH));
+                const unsigned base = y_off + (r ? 0u : (unsigned)(g.OW * 4));
+                const float v1 = acc[nt][r][1][i], v0 = acc[nt][r][0][i];  // by value, then bits
+                u2v d;
+                d.x = __float_as_uint(v1);
+                d.y = __float_as_uint(v0);
+                if (vrow && vcol1 && vcol0)
+                    __builtin_amdgcn_raw_buffer_store_b64(d, rs_y, base, 0, 0);
+                else if (vrow && vcol1)
+                    __builtin_amdgcn_raw_buffer_store_b32(d.x, rs_y, base, 0, 0);
+                else if (vrow && vcol0)
+                    __builtin_amdgcn_raw_buffer_store_b32(d.y, rs_y, base + 4u, 0, 0);
+            }
+        }
+    }
+    (void)plane;
+}
+
+template <int NW>
+bool make_args(const Geom& g, F32Args& a)
+{
+    constexpr int TN = 64 * NW;
+    if (g.n < 2 || g.n > 5) return false;
+    if (g.Cin % KC != 0) return false;  // a stage never straddles the channel count
+    const size_t xbytes = (size_t)g.B * g.Cin * g.H * g.W * 4;
+    const size_t wbytes = (size_t)g.Cout * g.Cin * g.n * g.n * 4;
+    const size_t ybytes = (size_t)g.B * g.Cout * g.OH * g.OW * 4;
+    const size_t lim = 0x7FFFFFF0u;  // single buffer descriptors, 32-bit byte offsets
+    if (xbytes > lim || wbytes > lim || ybytes > lim) return false;
+    const int HI = (g.n + 1) / 2;
+    a.g = g;
+    const long long Q = (long long)g.B * g.KH * g.KW;
+    if (Q > 0x3FFFFFFFLL) return false;
+    a.Q = (int)Q;
+    a.EH = g.KH + HI - 1;
+    // TN consecutive flattened quads touch at most this many quad rows / images
+    const int nrho = (TN - 2) / g.KW + 2;
+    const int nimg = (TN - 2) / (g.KH * g.KW) + 2;
+    a.ROWS = nrho + (HI - 1) * nimg;
+    a.SH = g.P >> 1;
+    a.LWX = a.SH + g.W + HI;
+    const int need = g.KW + HI - 1;  // largest LDS column read: KW-1 + HI-1
+    if (a.LWX < need + 1) a.LWX = need + 1;
+    int xp = a.ROWS * a.LWX;
+    xp = ((xp + 63) / 64) * 64 + 32;  // k planes 32 banks apart: the two k parities do not collide
+    a.XP = xp;
+    a.xs_stage_bytes = KC * xp * 4;
+    const long long elems = (long long)KC * a.ROWS * g.W;
+    a.nxl = (int)((elems + 255) / 256);
+    if (a.nxl > NXL_MAX) return false;
+    const int ws_stage = g.n * g.n * KC * PW * 4;
+    if (2 * (ws_stage + a.xs_stage_bytes) > LDS_LIMIT) return false;
+    a.nco = (g.Cout + TM - 1) / TM;
+    a.nqt = (int)((Q + TN - 1) / TN);
+    if ((long long)a.nco * a.nqt > 0x3FFFFFFFLL) return false;
+    a.dKHW = make_fastdiv((unsigned)(g.KH * g.KW));
+    a.dKW = make_fastdiv((unsigned)g.KW);
+    a.dEH = make_fastdiv((unsigned)a.EH);
+    a.dRW = make_fastdiv((unsigned)(a.ROWS * g.W));
+    a.dW = make_fastdiv((unsigned)g.W);
+    return true;
+}
+
+template <int N, int NW>
+hipError_t launch_t(const F32Args& a, const float* x, const float* w, float* y, hipStream_t stream)
+{
+    const size_t lds = 2 * (size_t)(N * N * KC * PW * 4 + a.xs_stage_bytes);
+    // more than 64 KiB of dynamic LDS has to be allowed per device (a property of the loaded
+    // kernel, not library state); cheap enough to repeat on every call
+    hipError_t e = hipFuncSetAttribute((const void*)ukst_mfma_f32_kernel<N, NW>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((ukst_mfma_f32_kernel<N, NW>), dim3((unsigned)(a.nco * a.nqt)), dim3(256),
+                       lds, stream, x, w, y, a);
+    return hipGetLastError();
+}
+
+template <int NW>
+hipError_t launch_n(const F32Args& a, const float* x, const float* w, float* y, hipStream_t st)
+{
+    switch (a.g.n) {
+        case 2: return launch_t<2, NW>(a, x, w, y, st);
+        case 3: return launch_t<3, NW>(a, x, w, y, st);
+        case 4: return launch_t<4, NW>(a, x, w, y, st);
+        case 5: return launch_t<5, NW>(a, x, w, y, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+// Quads per wave: as wide as possible while the grid still covers the chip about twice.
+int pick_nw(const Geom& g, F32Args& a)
+{
+    const long long want = 512;
+    F32Args t;
+    int best = 0;
+    for (int nw : {4, 2, 1}) {
+        bool ok = nw == 4 ? make_args<4>(g, t) : nw == 2 ? make_args<2>(g, t) : make_args<1>(g, t);
+        if (!ok) continue;
+        best = nw;
+        a = t;
+        if ((long long)t.nco * t.nqt >= want) break;
+    }
+    return best;
+}
+
+}  // namespace
+
+bool mfma_f32_supported(const Geom& g)
+{
+    F32Args a;
+    return pick_nw(g, a) != 0;
+}
+
+hipError_t launch_mfma_f32(const Geom& g, const void* x, const void* w, float* y, hipStream_t stream)
+{
+    F32Args a;
+    const int nw = pick_nw(g, a);
+    const float* xf = (const float*)x;
+    const float* wf = (const float*)w;
+    switch (nw) {
+        case 4: return launch_n<4>(a, xf, wf, y, stream);
+        case 2: return launch_n<2>(a, xf, wf, y, stream);
+        case 1: return launch_n<1>(a, xf, wf, y, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace ukst

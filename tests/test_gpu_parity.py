@@ -130,6 +130,30 @@ def test_mfma_bf16_small_shapes_every_element(shape):
     _parity(w, PATHS["direct"], integer=False)
 
 
+MFMA_F32_SHAPES = [
+    # B, Cin, Cout, H, W, n, P      (Cin % 8 == 0; any W, any Cout, n in 2..5)
+    (1, 8, 64, 4, 8, 4, 2),
+    (3, 16, 64, 5, 7, 3, 0),      # odd W, tiles span images
+    (2, 24, 40, 9, 13, 5, 0),     # ragged channel block (Cout = 40), n = 5: 9/6/6/4 taps
+    (2, 8, 96, 7, 21, 5, 2),
+    (2, 16, 64, 6, 16, 4, 1),     # odd P: class order flips (Sec. 3.4)
+    (1, 8, 70, 3, 37, 3, 3),      # P > n-1: outer ring meets no input
+    (5, 8, 64, 2, 5, 2, 0),       # n = 2, tiny images
+    (1, 16, 128, 33, 31, 3, 0),   # several row tiles of one image, two channel blocks
+    (1, 8, 64, 1, 9, 4, 2),       # single input row
+    (2, 32, 64, 63, 63, 3, 0),    # cfg4b spatial shape: wide tiles (NW = 4)
+]
+
+
+@pytest.mark.parametrize("shape", MFMA_F32_SHAPES)
+def test_mfma_f32_small_shapes_every_element(shape):
+    B, Cin, Cout, H, W, n, P = shape
+    w = _mk("mfma_f32", 8000 + sum(shape), B, Cin, Cout, H, W, n, P, dtype="f32")
+    assert _supported(w, PATHS["mfma"]), "shape should be runnable by the MFMA path"
+    _parity(w, PATHS["mfma"], integer=True)
+    _parity(w, PATHS["mfma"], integer=False)
+
+
 def test_paths_agree_at_full_size():
     # property that holds at any size: both kernel families compute the same tensor
     import torch
