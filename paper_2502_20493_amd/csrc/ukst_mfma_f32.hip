@@ -22,14 +22,18 @@ namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned u2v __attribute__((ext_vector_type(2)));
+typedef unsigned u4v __attribute__((ext_vector_type(4)));
 
 constexpr int kRsrcFlags = 0x00020000;      // raw 32-bit buffer, gfx9 family
 constexpr unsigned kInvalid = 0xFFFFFF00u;  // byte offset that is out of range for any buffer
 constexpr int TM = 64;      // output channels per block
-constexpr int KC = 8;       // input channels per stage (4 MFMA K steps)
+// input channels per K stage: small kernels get longer stages so that the fixed cost of a stage
+// (loads, LDS writes, barrier) is spread over enough MFMAs
+constexpr int kc_for(int n) { return n <= 3 ? 16 : 8; }
 constexpr int PW = 65;      // floats per (k, tap) weight row in LDS: 64 channels + 1, so that the
                             // staging lanes (consecutive rows, one channel) hit consecutive banks
-constexpr int NXL_MAX = 24; // activation elements one thread stages per K stage, at most
+// activation elements one thread stages per K stage, at most (register arrays of that size)
+constexpr int nxl_max_for(int n) { return n <= 3 ? 32 : 24; }
 constexpr int LDS_LIMIT = 160 * 1024;
 
 struct FastDiv { unsigned M; int sh; unsigned d; };
@@ -72,7 +76,7 @@ __device__ __forceinline__ int xcd_contiguous(int bid, int nb)
     return xcd * fl + (xcd < rem ? xcd : rem) + idx;
 }
 
-template <int N, int NW>
+template <int N, int NW, int KC>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void ukst_mfma_f32_kernel(const float* __restrict__ x, const float* __restrict__ w,
                           float* __restrict__ y, F32Args a)
@@ -81,7 +85,8 @@ void ukst_mfma_f32_kernel(const float* __restrict__ x, const float* __restrict__
     constexpr int NN = N * N;
     constexpr int TN = 64 * NW;                 // quads per block
     constexpr int WS_STAGE = NN * KC * PW * 4;  // bytes of one weight stage
-    constexpr int NWL = (TM * KC * NN + 255) / 256;  // weight elements per thread and stage
+    constexpr int NXL_MAX = nxl_max_for(N);
+    constexpr int NWL = (TM * KC * NN / 4 + 255) / 256;  // 16-byte weight pieces per thread and stage
     extern __shared__ __align__(16) unsigned char lds[];
     float* const ldsf = reinterpret_cast<float*>(lds);
     // layout: weights stage 0 | weights stage 1 | activations stage 0 | activations stage 1
@@ -166,17 +171,19 @@ void ukst_mfma_f32_kernel(const float* __restrict__ x, const float* __restrict__
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[nt][r][sc][i] = 0.f;
 
-    float wreg[NWL], xreg[NXL_MAX];
-    // weight element e = tid + 256*j -> channel co = e / (KC*NN), then (k, tap) contiguous in
-    // memory: lanes read consecutive floats
+    u4v wreg[NWL];
+    float xreg[NXL_MAX];
+    // weight piece e = tid + 256*j: four consecutive floats of channel co = 4e / (KC*NN); the
+    // (k, tap) pairs of a channel are contiguous in memory and a stage's chunk of a channel starts
+    // on a 16-byte boundary (Cin and ci0 are multiples of 8), so lanes read consecutive 16-byte
+    // pieces
     auto stage_load = [&](int ci0) {
 #pragma unroll
         for (int j = 0; j < NWL; ++j) {
-            const int e = tid + 256 * j;
+            const int e = (tid + 256 * j) * 4;
             const int co = e / (KC * NN), rem = e - co * (KC * NN);
             const unsigned voff = (co < TM) ? (unsigned)(((co0 + co) * g.Cin * NN + rem) * 4) : kInvalid;
-            wreg[j] = __builtin_bit_cast(
-                float, __builtin_amdgcn_raw_buffer_load_b32(rs_w, voff, (unsigned)(ci0 * NN * 4), 0));
+            wreg[j] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, voff, (unsigned)(ci0 * NN * 4), 0);
         }
 #pragma unroll
         for (int j = 0; j < NXL_MAX; ++j)
@@ -184,45 +191,61 @@ void ukst_mfma_f32_kernel(const float* __restrict__ x, const float* __restrict__
                 xreg[j] = __builtin_bit_cast(
                     float, __builtin_amdgcn_raw_buffer_load_b32(rs_x, x_goff[j],
                                                                 (unsigned)ci0 * x_cstride, 0));
+        __builtin_amdgcn_sched_barrier(0);  // requested before the stage is multiplied
     };
     auto stage_store = [&](int buf) {
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int j = 0; j < NWL; ++j) {
-            const int e = tid + 256 * j;
-            const int co = e / (KC * NN), rem = e - co * (KC * NN);
-            if (co < TM) ldsf[buf * (WS_STAGE / 4) + rem * PW + co] = wreg[j];  // rem = k*NN + tap
+            const int e = (tid + 256 * j) * 4;
+            const int co = e / (KC * NN), rem = e - co * (KC * NN);  // rem = k*NN + tap, multiple of 4
+            if (co < TM) {
+                float* dst = ldsf + buf * (WS_STAGE / 4) + rem * PW + co;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) dst[t * PW] = __uint_as_float(wreg[j][t]);
+            }
         }
 #pragma unroll
         for (int j = 0; j < NXL_MAX; ++j)
             if (j < a.nxl && x_loff[j] >= 0)
                 ldsf[XS_OFF / 4 + buf * (a.xs_stage_bytes / 4) + x_loff[j]] = xreg[j];
     };
+    // One step = one window position (u, v) at one K pair.  The fragments of step t+1 are
+    // requested before the MFMAs of step t are issued, so LDS latency hides under the matrix pipe.
+    constexpr int NP = HI * HI, NSTEP = (KC / 2) * NP;
     auto compute = [&](int buf) {
         const float* ws = ldsf + buf * (WS_STAGE / 4) + a_base;
         const int xb = buf * (a.xs_stage_bytes / 4);
+        auto load_step = [&](int t, float (&bfr)[NW], float (&afr)[4]) {
+            const int ks = t / NP, p = t % NP, u = p / HI, v = p % HI;
+            const int xo = xb + 2 * ks * a.XP + u * a.LWX + v;
 #pragma unroll
-        for (int ks = 0; ks < KC / 2; ++ks)
+            for (int nt = 0; nt < NW; ++nt) bfr[nt] = ldsf[b_base[nt] + xo];
 #pragma unroll
-            for (int u = 0; u < HI; ++u)
+            for (int c = 0; c < 4; ++c) {
+                const int r = c >> 1, sc = c & 1;
+                if (r + 2 * u >= N || sc + 2 * v >= N) continue;  // class has no tap here
+                afr[c] = ws[(2 * ks * NN + (r + 2 * u) * N + (sc + 2 * v)) * PW];
+            }
+        };
+        float bfr[2][NW], afr[2][4];
+        load_step(0, bfr[0], afr[0]);
 #pragma unroll
-                for (int v = 0; v < HI; ++v) {
-                    float bfr[NW];
-                    const int xo = xb + 2 * ks * a.XP + u * a.LWX + v;
+        for (int t = 0; t < NSTEP; ++t) {
+            const int p = t % NP, u = p / HI, v = p % HI;
+            if (t + 1 < NSTEP) load_step(t + 1, bfr[(t + 1) & 1], afr[(t + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int nt = 0; nt < NW; ++nt) bfr[nt] = ldsf[b_base[nt] + xo];
+            for (int c = 0; c < 4; ++c) {
+                const int r = c >> 1, sc = c & 1;
+                if (r + 2 * u >= N || sc + 2 * v >= N) continue;
 #pragma unroll
-                    for (int r = 0; r < 2; ++r)
-#pragma unroll
-                        for (int sc = 0; sc < 2; ++sc) {
-                            if (r + 2 * u >= N || sc + 2 * v >= N) continue;  // no tap here
-                            const int tap = (r + 2 * u) * N + (sc + 2 * v);
-                            const float afr = ws[(2 * ks * NN + tap) * PW];
-#pragma unroll
-                            for (int nt = 0; nt < NW; ++nt)
-                                acc[nt][r][sc] = __builtin_amdgcn_mfma_f32_32x32x2f32(
-                                    afr, bfr[nt], acc[nt][r][sc], 0, 0, 0);
-                        }
-                }
+                for (int nt = 0; nt < NW; ++nt)
+                    acc[nt][r][sc] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                        afr[t & 1][c], bfr[t & 1][nt], acc[nt][r][sc], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
 
     const int stages = (g.Cin + KC - 1) / KC;  // channels past Cin read as zero (range check)
@@ -245,6 +268,8 @@ void ukst_mfma_f32_kernel(const float* __restrict__ x, const float* __restrict__
     const __amdgpu_buffer_rsrc_t rs_y = __builtin_amdgcn_make_buffer_rsrc(
         (void*)y, 0, (int)((size_t)g.B * g.Cout * g.OH * g.OW * 4), kRsrcFlags);
     const unsigned plane = (unsigned)(g.OH * g.OW * 4);
+    // Cout is a multiple of 8, so a group of 8 channels (4 per k parity) exists or not as a whole
+    const int co_w = co0 + cw * 32;  // first channel of this wave
 #pragma unroll
     for (int nt = 0; nt < NW; ++nt) {
         const int q = q0 + (qh * NW + nt) * 32 + l32;
@@ -256,38 +281,44 @@ void ukst_mfma_f32_kernel(const float* __restrict__ x, const float* __restrict__
         const int k = g.k_min + kk, m = g.m_min + mm;
         const int oy1 = 2 * k - 1 - g.P, ox1 = 2 * m - 1 - g.P;  // row / column of class 1
         const bool vcol1 = ox1 >= 0 && ox1 < g.OW, vcol0 = ox1 + 1 < g.OW;
+        // byte offset of (channel co_w + 4*gk, row oy1, column ox1); unsigned wrap-around keeps
+        // the arithmetic right when oy1 or ox1 is -1 and only the other class exists
+        const unsigned y_off =
+            (unsigned)((((b * g.Cout + co_w + 4 * gk) * g.OH + oy1) * g.OW + ox1) * 4);
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int co = co0 + cw * 32 + 8 * (i / 4) + 4 * gk + (i % 4);
-            const bool cv = co < g.Cout;  // ragged last channel block
-            // unsigned wrap-around keeps the arithmetic right when oy1 or ox1 is -1
-            const unsigned y_off = (unsigned)((((b * g.Cout + co) * g.OH + oy1) * g.OW + ox1) * 4);
+        for (int r = 1; r >= 0; --r) {
+            const bool vrow = qv && (r ? (oy1 >= 0 && oy1 < g.OH) : (oy1 + 1 < g.OH));
+            const unsigned base = y_off + (r ? 0u : (unsigned)(g.OW * 4));
+            // interior quads store both column classes as one 8-byte element; a quad on the left
+            // or right edge of an odd-sized output has one class only and stores 4 bytes
+            const unsigned off_pair = (vrow && vcol1 && vcol0) ? base : kInvalid;
+            const bool only1 = vrow && vcol1 && !vcol0, only0 = vrow && !vcol1 && vcol0;
+            const unsigned off_edge = only1 ? base : (only0 ? base + 4u : kInvalid);
+            const bool any_edge = __builtin_amdgcn_ballot_w64(only1 || only0) != 0;  // uniform
 #pragma unroll
-            for (int r = 1; r >= 0; --r) {
-                const bool vrow = cv && qv && (r ? (oy1 >= 0 && oy1 < g.OH) : (oy1 + 1 < g.OH));
-                const unsigned base = y_off + (r ? 0u : (unsigned)(g.OW * 4));
+            for (int i = 0; i < 16; ++i) {
+                if (co_w + 8 * (i / 4) >= g.Cout) continue;  // uniform: ragged last channel block
+                const unsigned soff = (unsigned)(8 * (i / 4) + (i % 4)) * plane;
                 const float v1 = acc[nt][r][1][i], v0 = acc[nt][r][0][i];  // by value, then bits
                 u2v d;
                 d.x = __float_as_uint(v1);
                 d.y = __float_as_uint(v0);
-                if (vrow && vcol1 && vcol0)
-                    __builtin_amdgcn_raw_buffer_store_b64(d, rs_y, base, 0, 0);
-                else if (vrow && vcol1)
-                    __builtin_amdgcn_raw_buffer_store_b32(d.x, rs_y, base, 0, 0);
-                else if (vrow && vcol0)
-                    __builtin_amdgcn_raw_buffer_store_b32(d.y, rs_y, base + 4u, 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b64(d, rs_y, off_pair, soff, 0);
+                if (any_edge)
+                    __builtin_amdgcn_raw_buffer_store_b32(only1 ? d.x : d.y, rs_y, off_edge, soff, 0);
             }
         }
     }
-    (void)plane;
 }
 
 template <int NW>
 bool make_args(const Geom& g, F32Args& a)
 {
     constexpr int TN = 64 * NW;
+    const int KC = kc_for(g.n);
     if (g.n < 2 || g.n > 5) return false;
     if (g.Cin % KC != 0) return false;  // a stage never straddles the channel count
+    if (g.Cout % 8 != 0) return false;  // channel groups of the accumulator layout stay whole
     const size_t xbytes = (size_t)g.B * g.Cin * g.H * g.W * 4;
     const size_t wbytes = (size_t)g.Cout * g.Cin * g.n * g.n * 4;
     const size_t ybytes = (size_t)g.B * g.Cout * g.OH * g.OW * 4;
@@ -313,7 +344,7 @@ bool make_args(const Geom& g, F32Args& a)
     a.xs_stage_bytes = KC * xp * 4;
     const long long elems = (long long)KC * a.ROWS * g.W;
     a.nxl = (int)((elems + 255) / 256);
-    if (a.nxl > NXL_MAX) return false;
+    if (a.nxl > nxl_max_for(g.n)) return false;
     const int ws_stage = g.n * g.n * KC * PW * 4;
     if (2 * (ws_stage + a.xs_stage_bytes) > LDS_LIMIT) return false;
     a.nco = (g.Cout + TM - 1) / TM;
@@ -330,13 +361,14 @@ bool make_args(const Geom& g, F32Args& a)
 template <int N, int NW>
 hipError_t launch_t(const F32Args& a, const float* x, const float* w, float* y, hipStream_t stream)
 {
+    constexpr int KC = kc_for(N);
     const size_t lds = 2 * (size_t)(N * N * KC * PW * 4 + a.xs_stage_bytes);
     // more than 64 KiB of dynamic LDS has to be allowed per device (a property of the loaded
     // kernel, not library state); cheap enough to repeat on every call
-    hipError_t e = hipFuncSetAttribute((const void*)ukst_mfma_f32_kernel<N, NW>,
+    hipError_t e = hipFuncSetAttribute((const void*)ukst_mfma_f32_kernel<N, NW, KC>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((ukst_mfma_f32_kernel<N, NW>), dim3((unsigned)(a.nco * a.nqt)), dim3(256),
+    hipLaunchKernelGGL((ukst_mfma_f32_kernel<N, NW, KC>), dim3((unsigned)(a.nco * a.nqt)), dim3(256),
                        lds, stream, x, w, y, a);
     return hipGetLastError();
 }

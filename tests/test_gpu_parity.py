@@ -131,14 +131,14 @@ def test_mfma_bf16_small_shapes_every_element(shape):
 
 
 MFMA_F32_SHAPES = [
-    # B, Cin, Cout, H, W, n, P      (Cin % 8 == 0; any W, any Cout, n in 2..5)
+    # B, Cin, Cout, H, W, n, P   (Cout % 8 == 0, Cin % 8 == 0 for n = 4, 5 and % 16 for n = 2, 3; any W)
     (1, 8, 64, 4, 8, 4, 2),
     (3, 16, 64, 5, 7, 3, 0),      # odd W, tiles span images
     (2, 24, 40, 9, 13, 5, 0),     # ragged channel block (Cout = 40), n = 5: 9/6/6/4 taps
     (2, 8, 96, 7, 21, 5, 2),
     (2, 16, 64, 6, 16, 4, 1),     # odd P: class order flips (Sec. 3.4)
-    (1, 8, 70, 3, 37, 3, 3),      # P > n-1: outer ring meets no input
-    (5, 8, 64, 2, 5, 2, 0),       # n = 2, tiny images
+    (1, 16, 72, 3, 37, 3, 3),      # P > n-1: outer ring meets no input
+    (5, 16, 64, 2, 5, 2, 0),       # n = 2, tiny images
     (1, 16, 128, 33, 31, 3, 0),   # several row tiles of one image, two channel blocks
     (1, 8, 64, 1, 9, 4, 2),       # single input row
     (2, 32, 64, 63, 63, 3, 0),    # cfg4b spatial shape: wide tiles (NW = 4)
