@@ -53,7 +53,7 @@ def algorithmic_bytes(w, OH, OW):
             + w.B * w.Cout * OH * OW * 4)
 
 
-def measure(w, steps, warmup, rotate_bytes=LLC_BYTES + (64 << 20)):
+def measure(w, steps, warmup, rotate_bytes=LLC_BYTES + (64 << 20), warm_seconds=0.0):
     """Time `steps` launches of workload w.  Returns a dict of rates."""
     import torch
     from paper_2502_20493_amd import binding as ukst
@@ -86,6 +86,13 @@ def measure(w, steps, warmup, rotate_bytes=LLC_BYTES + (64 << 20)):
     for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
+    # extra configs: keep launching until the clocks have settled (the first ~100 ms after idle
+    # run at a much lower core clock, which matters for the matrix-core kernels)
+    t_w = time.perf_counter()
+    while warm_seconds > 0 and time.perf_counter() - t_w < warm_seconds:
+        for i in range(20):
+            step(i)
+        torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     e0.record(stream)
@@ -162,8 +169,8 @@ def measured_traffic(kernel_workload):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=500)
     ap.add_argument("--configs", default="all",
                     help="'all', 'none' or comma-separated extra configs for per_config")
     ap.add_argument("--only", default=None, help="time just this workload as the headline")
@@ -194,7 +201,7 @@ def main():
             if args.configs == "all" else args.configs.split(",")
         for name in names:
             w = wl.WORKLOADS[name]
-            r = measure(w, max(5, min(args.steps, 30)), max(2, min(args.warmup, 5)))
+            r = measure(w, max(5, min(args.steps, 50)), max(2, min(args.warmup, 5)), warm_seconds=0.3)
             r.pop("_data"); r.pop("_exact_flop")
             per.append(r)
             torch.cuda.empty_cache()

@@ -350,6 +350,8 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
         // ---- drain: accumulator register i of a tile holds channel 8*(i/4) + 4*gk + (i%4) of the
         // wave's 32, for the lane's quad; column classes s = 1, 0 are neighbours in memory
         const int co0 = cb * TM;
+        unsigned off_pair[4][2], off_s1[4][2], off_s0[4][2];
+        bool any_edge[4][2];
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) {
             const int q = q0 + qh * 128 + nt * 32 + l32;
@@ -361,34 +363,38 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
             const int k = g.k_min + kk, m = g.m_min + mm;
             const int oy1 = 2 * k - 1 - g.P, ox1 = 2 * m - 1 - g.P;  // row / column of class 1
             const bool vcol1 = ox1 >= 0 && ox1 < g.OW, vcol0 = ox1 + 1 < g.OW;
-            // byte offset of (channel co0 + cw*32 + 4*gk, row oy1, column ox1); unsigned
-            // wrap-around keeps the arithmetic right when oy1 or ox1 is -1 and only the other
-            // class exists
             const unsigned y_off =
                 (unsigned)((((b * g.Cout + co0 + cw * 32 + 4 * gk) * g.OH + oy1) * g.OW + ox1) * 4);
 #pragma unroll
             for (int r = 1; r >= 0; --r) {
                 const bool vrow = qv && (r ? (oy1 >= 0 && oy1 < g.OH) : (oy1 + 1 < g.OH));
                 const unsigned base = y_off + (r ? 0u : (unsigned)(g.OW * 4));
-                const unsigned off_pair = (vrow && vcol1 && vcol0) ? base : kInvalid;
-                const unsigned off_s1 = (vrow && vcol1 && !vcol0) ? base : kInvalid;
-                const unsigned off_s0 = (vrow && !vcol1 && vcol0) ? base + 4u : kInvalid;
-                const bool edge = (off_s1 != kInvalid) || (off_s0 != kInvalid);
-                const bool any_edge = __builtin_amdgcn_ballot_w64(edge) != 0;  // wave-uniform
+                off_pair[nt][r] = (vrow && vcol1 && vcol0) ? base : kInvalid;
+                off_s1[nt][r] = (vrow && vcol1 && !vcol0) ? base : kInvalid;
+                off_s0[nt][r] = (vrow && !vcol1 && vcol0) ? base + 4u : kInvalid;
+                const bool edge = (off_s1[nt][r] != kInvalid) || (off_s0[nt][r] != kInvalid);
+                any_edge[nt][r] = __builtin_amdgcn_ballot_w64(edge) != 0;  // wave-uniform
+            }
+        }
+        // channel outermost, quad tiles innermost: the four stores of an inner loop write one
+        // contiguous run of an output row
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const unsigned soff = (unsigned)(8 * (i / 4) + (i % 4)) * plane;
+        for (int i = 0; i < 16; ++i) {
+            const unsigned soff = (unsigned)(8 * (i / 4) + (i % 4)) * plane;
+#pragma unroll
+            for (int r = 1; r >= 0; --r)
+#pragma unroll
+                for (int nt = 0; nt < 4; ++nt) {
                     u2v d;
                     const float v1 = acc[nt][r][1][i], v0 = acc[nt][r][0][i];  // by value, then bits
                     d.x = __float_as_uint(v1);
                     d.y = __float_as_uint(v0);
-                    __builtin_amdgcn_raw_buffer_store_b64(d, rs_y, off_pair, soff, 0);
-                    if (any_edge) {
-                        __builtin_amdgcn_raw_buffer_store_b32(d.x, rs_y, off_s1, soff, 0);
-                        __builtin_amdgcn_raw_buffer_store_b32(d.y, rs_y, off_s0, soff, 0);
+                    __builtin_amdgcn_raw_buffer_store_b64(d, rs_y, off_pair[nt][r], soff, 0);
+                    if (any_edge[nt][r]) {
+                        __builtin_amdgcn_raw_buffer_store_b32(d.x, rs_y, off_s1[nt][r], soff, 0);
+                        __builtin_amdgcn_raw_buffer_store_b32(d.y, rs_y, off_s0[nt][r], soff, 0);
                     }
                 }
-            }
         }
         have = have_n; cb = cb_n; qt = qt_n; wv_c = wv_n; xv_c = xv_n;
     }
