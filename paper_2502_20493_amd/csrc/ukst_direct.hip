@@ -141,6 +141,7 @@ hipError_t launch_direct(const Geom& g, const void* x, const void* w, float* y, 
                          hipStream_t stream)
 {
     if (narrow_supported(g, dtype)) return launch_narrow(g, x, w, y, stream);
+    if (thin_supported(g, dtype)) return launch_thin(g, x, w, y, stream);
     switch (g.n) {
         case 1: return launch_n<1>(g, x, w, y, dtype, stream);
         case 2: return launch_n<2>(g, x, w, y, dtype, stream);
@@ -155,7 +156,8 @@ hipError_t launch_direct(const Geom& g, const void* x, const void* w, float* y, 
 
 const char* direct_kernel_name(const Geom& g, int dtype)
 {
-    return narrow_supported(g, dtype) ? "ukst_narrow_kernel" : "ukst_direct_kernel";
+    return narrow_supported(g, dtype) ? "ukst_narrow_kernel"
+           : thin_supported(g, dtype) ? "ukst_thin_kernel" : "ukst_direct_kernel";
 }
 
 }  // namespace ukst

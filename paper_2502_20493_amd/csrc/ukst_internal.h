@@ -44,6 +44,10 @@ const char* direct_kernel_name(const Geom& g, int dtype);
 bool narrow_supported(const Geom& g, int dtype);
 hipError_t launch_narrow(const Geom& g, const void* x, const void* w, float* y, hipStream_t stream);
 
+// Thin-output kernel (fp32, Cout <= 4, many input channels): channel-split reduction on the VALUs.
+bool thin_supported(const Geom& g, int dtype);
+hipError_t launch_thin(const Geom& g, const void* x, const void* w, float* y, hipStream_t stream);
+
 bool mfma_supported(const Geom& g, int dtype);
 hipError_t launch_mfma(const Geom& g, const void* x, const void* w, float* y, int dtype,
                        hipStream_t stream);

@@ -43,7 +43,8 @@ def test_direct_edge_sweep(n):
     idx = 0
     for P in range(0, n + 2):
         for (B, Cin, Cout, H, W) in [(1, 1, 1, 4, 4), (2, 3, 3, 5, 9), (1, 9, 5, 1, 37),
-                                     (1, 17, 2, 11, 1), (2, 2, 4, 33, 70), (1, 4, 3, 6, 131)]:
+                                     (1, 17, 2, 11, 1), (2, 2, 4, 33, 70), (1, 4, 3, 6, 131),
+                                     (2, 7, 3, 6, 19), (1, 6, 1, 3, 131)]:
             if 2 * H + 2 * P - n < 1 or 2 * W + 2 * P - n < 1:
                 continue
             idx += 1
