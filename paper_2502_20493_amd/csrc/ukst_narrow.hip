@@ -12,8 +12,7 @@ hipError_t launch_narrow_n5(const Geom&, const float*, const float*, float*, hip
 
 bool narrow_supported(const Geom& g, int dtype)
 {
-    // buffer offsets are 32-bit byte offsets inside the image of one batch item, and the marker
-    // for a missing column must stay out of range when a row offset is added to it
+    // buffer offsets are 32-bit byte offsets inside the image of one batch item
     const long long xbytes = 4LL * g.Cin * g.H * g.W, ybytes = 4LL * g.Cout * g.OH * g.OW;
     return dtype == 0 && g.Cin <= 4 && g.Cout <= 4 && g.n <= 5 && xbytes < (1LL << 30) &&
            ybytes < (1LL << 30) && g.P < (1 << 20);

@@ -22,10 +22,11 @@
 namespace ukst {
 namespace narrow {
 
+typedef unsigned u2v __attribute__((ext_vector_type(2)));
+typedef unsigned u3v __attribute__((ext_vector_type(3)));
 typedef unsigned u4v __attribute__((ext_vector_type(4)));
 
 constexpr int kRsrcFlags = 0x00020000;  // raw 32-bit buffer, gfx9 family
-constexpr unsigned kNoColumn = 0x80000000u;  // beyond the size field of any row (images < 1 GiB)
 constexpr int kFarBand = 0x20000000;         // a quad row whose input and output rows do not exist
 
 __device__ __forceinline__ int xcd_contiguous(int bid, int nb)
@@ -69,15 +70,19 @@ __global__ __launch_bounds__(256) void ukst_narrow_kernel(const float* __restric
     const int lg = strip * 64 + lane;  // the lane's column group
     const int j0 = 2 * lg - (P >> 1);  // first input column of the lane's window
 
-    // byte offsets of the window columns inside an input row
-    unsigned voff[WC];
-#pragma unroll
-    for (int v = 0; v < WC; ++v) voff[v] = (j0 + v >= 0) ? (unsigned)(j0 + v) * 4u : kNoColumn;
-
     const float* xb = x + (size_t)b * CI * H * W;
     const unsigned xrow = (unsigned)W * 4u, xplane = (unsigned)H * xrow;
     // window of the band whose first quad row is k0: tap row a of output row 2k - P - (a & 1)
     // meets input row k - P + a/2
+    // One load fetches the lane's WC consecutive window columns of a row: the address unit takes
+    // as long for a 4-byte load as for a 16-byte one, and it is what bounds the read phase of
+    // this kernel.  Dwords past the end of the row come back as 0 one by one, but a load whose
+    // first byte lies left of the row returns nothing at all: a lane whose window starts left of
+    // the map (leftmost strip, floor(P/2) > 0) loads from column 0 instead and shifts the
+    // result to the right afterwards.
+    const int left = j0 < 0 ? (-j0 < WC ? -j0 : WC) : 0;  // window columns left of the map
+    const unsigned woff = j0 < 0 ? 0u : (unsigned)j0 * 4u;
+    const bool shifts = strip == 0 && (P >> 1) > 0;        // wave-uniform
     auto load_window = [&](int k0, float (&win)[WR][WC][CI]) {
         const int i0 = k0 - P;
 #pragma unroll
@@ -90,11 +95,38 @@ __global__ __launch_bounds__(256) void ukst_narrow_kernel(const float* __restric
                 const unsigned start = (unsigned)ci * xplane + (unsigned)i * xrow;
                 const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
                     (void*)xb, 0, rowok ? (int)(start + xrow) : 0, kRsrcFlags);
+                unsigned e[WC];  // elements by value: a bit cast of a vector element reads element 0
+                if constexpr (WC == 4) {
+                    const u4v t = __builtin_amdgcn_raw_buffer_load_b128(rs, woff, start, 0);
+                    e[0] = t.x; e[1] = t.y; e[2] = t.z; e[3] = t.w;
+                } else if constexpr (WC == 3) {
+                    const u3v t = __builtin_amdgcn_raw_buffer_load_b96(rs, woff, start, 0);
+                    e[0] = t.x; e[1] = t.y; e[2] = t.z;
+                } else if constexpr (WC == 2) {
+                    const u2v t = __builtin_amdgcn_raw_buffer_load_b64(rs, woff, start, 0);
+                    e[0] = t.x; e[1] = t.y;
+                } else {
+                    e[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, woff, start, 0);
+                }
 #pragma unroll
-                for (int v = 0; v < WC; ++v)
-                    win[u][v][ci] = __builtin_bit_cast(
-                        float, __builtin_amdgcn_raw_buffer_load_b32(rs, voff[v], start, 0));
+                for (int v = 0; v < WC; ++v) win[u][v][ci] = __uint_as_float(e[v]);
             }
+        }
+    };
+    // moves a freshly loaded window `left` columns to the right, zeros coming in
+    auto shift_window = [&](float (&win)[WR][WC][CI]) {
+        if (!shifts) return;
+#pragma unroll
+        for (int s = 1; s <= WC; ++s) {
+            const bool m = left >= s;
+#pragma unroll
+            for (int u = 0; u < WR; ++u)
+#pragma unroll
+                for (int ci = 0; ci < CI; ++ci) {
+#pragma unroll
+                    for (int v = WC - 1; v >= 1; --v) win[u][v][ci] = m ? win[u][v - 1][ci] : win[u][v][ci];
+                    win[u][0][ci] = m ? 0.f : win[u][0][ci];
+                }
         }
     };
 
@@ -179,6 +211,7 @@ __global__ __launch_bounds__(256) void ukst_narrow_kernel(const float* __restric
     }
     __syncthreads();
 
+    shift_window(win);
     emit(k0, win);
 }
 
@@ -197,10 +230,12 @@ hipError_t launch_q(const Geom& g, const float* x, const float* w, float* y, hip
 template <int N, int CI, int CO, bool PE>
 hipError_t launch_t(const Geom& g, const float* x, const float* w, float* y, hipStream_t stream)
 {
-    // Taller lane blocks re-read fewer halo rows and measured faster on HBM-cold data, as long as
-    // there are still enough waves to cover the chip (256 CUs x 4 SIMDs).
+    // Taller lane blocks re-read fewer halo rows but mean fewer, heavier waves; measured on
+    // 224x224x3 images, 4 quad rows per lane win for n <= 3 and 2 for the larger kernels (whose
+    // lanes already carry more multiplications per output), and 4 only pay off while there are
+    // still enough waves to cover the chip (256 CUs x 4 SIMDs).
     const long long waves4 = (long long)((g.OW + 255) / 256) * ((g.KH + 3) / 4) * g.B;
-    if (waves4 >= 1024) return launch_q<N, CI, CO, 4, PE>(g, x, w, y, stream);
+    if (N <= 3 && waves4 >= 1024) return launch_q<N, CI, CO, 4, PE>(g, x, w, y, stream);
     return launch_q<N, CI, CO, 2, PE>(g, x, w, y, stream);
 }
 
