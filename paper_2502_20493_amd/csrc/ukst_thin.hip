@@ -23,6 +23,8 @@
 namespace ukst {
 namespace {
 
+typedef unsigned u2v __attribute__((ext_vector_type(2)));
+typedef unsigned u3v __attribute__((ext_vector_type(3)));
 typedef unsigned u4v __attribute__((ext_vector_type(4)));
 
 constexpr int kRsrcFlags = 0x00020000;       // raw 32-bit buffer, gfx9 family
@@ -67,45 +69,67 @@ __global__ __launch_bounds__(256) void ukst_thin_kernel(const float* __restrict_
     const int j0 = 2 * lg - (P >> 1);                            // first input column of the window
     const int i0 = k0 - P;                                       // first input row of the window
 
-    // byte offsets of the window columns inside an input row
-    unsigned voff[WC];
+    // One load fetches the lane's WC consecutive window columns of a row (the address unit takes
+    // as long for 4 bytes as for 16).  The descriptor ends with the channel plane, so columns
+    // outside the map are not clipped by the hardware here: a lane whose window starts left of
+    // the map loads from column 0 and shifts, and elements right of the map are zeroed, both
+    // with per-lane masks computed once.  A missing row gets an offset beyond any plane.
+    const int left = j0 < 0 ? (-j0 < WC ? -j0 : WC) : 0;  // window columns left of the map
+    const unsigned woff = j0 < 0 ? 0u : (unsigned)j0 * 4u;
+    bool keep[WC];                                         // column exists (after the shift)
 #pragma unroll
-    for (int v = 0; v < WC; ++v) voff[v] = (j0 + v >= 0) ? (unsigned)(j0 + v) * 4u : kNoColumn;
-    // rows differ between lanes here (bands are folded into the wave), so the row part of the
-    // address and the row's existence go into the per-lane offset as well
+    for (int v = 0; v < WC; ++v) keep[v] = j0 + v >= 0 && j0 + v < W;
     unsigned roff[WR];
 #pragma unroll
     for (int u = 0; u < WR; ++u) {
         const int i = i0 + u;
-        roff[u] = (i >= 0 && i < H) ? (unsigned)i * (unsigned)W * 4u : kNoColumn;
+        roff[u] = (i >= 0 && i < H && j0 < W) ? (unsigned)i * (unsigned)W * 4u + woff : kNoColumn;
     }
 
     const float* xb = x + (size_t)b * Cin * H * W;
     const unsigned xrow = (unsigned)W * 4u, xplane = (unsigned)H * xrow;
-    // The descriptor ends with the channel plane; a column offset is valid only below the row
-    // width, which the hardware cannot check once the row offset is added, so columns right of
-    // the map are marked here.
-#pragma unroll
-    for (int v = 0; v < WC; ++v)
-        if (j0 + v >= W) voff[v] = kNoColumn;
-
     const int cps = (Cin + 3) >> 2;                 // channels per wave
     const int ci_begin = wave * cps;
     const int ci_end = (ci_begin + cps < Cin) ? ci_begin + cps : Cin;
-    auto load_window = [&](int ci, float (&win)[WR][WC]) {
+    const bool any_left = __builtin_amdgcn_ballot_w64(left > 0) != 0;  // wave-uniform
+    auto load_window = [&](int ci, unsigned (&raw)[WR][WC]) {
         const bool ok = ci < ci_end;  // wave-uniform
         const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
             (void*)xb, 0, ok ? (int)((unsigned)(ci + 1) * xplane) : 0, kRsrcFlags);
         const unsigned start = (unsigned)ci * xplane;
 #pragma unroll
-        for (int u = 0; u < WR; ++u)
-#pragma unroll
-            for (int v = 0; v < WC; ++v) {
-                // either part may carry the out-of-range marker; their sum stays out of range
-                const unsigned off = (roff[u] | voff[v]) >= kNoColumn ? kNoColumn : roff[u] + voff[v];
-                win[u][v] = __builtin_bit_cast(
-                    float, __builtin_amdgcn_raw_buffer_load_b32(rs, off, start, 0));
+        for (int u = 0; u < WR; ++u) {
+            // elements by value: a bit cast of a vector element reads element 0
+            if constexpr (WC == 4) {
+                const u4v t = __builtin_amdgcn_raw_buffer_load_b128(rs, roff[u], start, 0);
+                raw[u][0] = t.x; raw[u][1] = t.y; raw[u][2] = t.z; raw[u][3] = t.w;
+            } else if constexpr (WC == 3) {
+                const u3v t = __builtin_amdgcn_raw_buffer_load_b96(rs, roff[u], start, 0);
+                raw[u][0] = t.x; raw[u][1] = t.y; raw[u][2] = t.z;
+            } else {
+                const u2v t = __builtin_amdgcn_raw_buffer_load_b64(rs, roff[u], start, 0);
+                raw[u][0] = t.x; raw[u][1] = t.y;
             }
+        }
+    };
+    // raw window -> window: shift right by `left` columns, zero what lies outside the map
+    auto fix_window = [&](const unsigned (&raw)[WR][WC], float (&win)[WR][WC]) {
+#pragma unroll
+        for (int u = 0; u < WR; ++u) {
+            unsigned e[WC];
+#pragma unroll
+            for (int v = 0; v < WC; ++v) e[v] = raw[u][v];
+            if (any_left) {
+#pragma unroll
+                for (int s = 1; s <= WC; ++s) {
+                    const bool m = left >= s;
+#pragma unroll
+                    for (int v = WC - 1; v >= 1; --v) e[v] = m ? e[v - 1] : e[v];
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < WC; ++v) win[u][v] = keep[v] ? __uint_as_float(e[v]) : 0.f;
+        }
     };
 
     float acc[CO][QH][2][4];
@@ -143,8 +167,9 @@ __global__ __launch_bounds__(256) void ukst_thin_kernel(const float* __restrict_
     };
 
     // first window in flight, then the block's weights: [ci][co][tap] in LDS, padded taps zero
-    float winA[WR][WC], winB[WR][WC];
-    load_window(ci_begin, winA);
+    unsigned rawA[WR][WC], rawB[WR][WC];
+    float win[WR][WC];
+    load_window(ci_begin, rawA);
     __builtin_amdgcn_sched_barrier(0);
     for (int e = tid; e < Cin * CO * NNP; e += 256) {
         const int t = e % NNP, pair = e / NNP;  // pair = ci * CO + co
@@ -156,10 +181,14 @@ __global__ __launch_bounds__(256) void ukst_thin_kernel(const float* __restrict_
     // channels two at a time so that the two window buffers keep their names; a channel past the
     // wave's share loads zeros and is not multiplied
     for (int ci = ci_begin; ci < ci_end; ci += 2) {
-        load_window(ci + 1, winB);
-        accumulate(ci, winA);
-        load_window(ci + 2, winA);
-        if (ci + 1 < ci_end) accumulate(ci + 1, winB);
+        load_window(ci + 1, rawB);
+        fix_window(rawA, win);
+        accumulate(ci, win);
+        load_window(ci + 2, rawA);
+        if (ci + 1 < ci_end) {
+            fix_window(rawB, win);
+            accumulate(ci + 1, win);
+        }
     }
 
     // ---- the four partial sums of every output meet in LDS; wave 0 adds and stores
