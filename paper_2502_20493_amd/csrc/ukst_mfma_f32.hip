@@ -65,6 +65,8 @@ struct F32Args {
     int nxl;     // activation elements per thread and stage
     int nco, nqt;
     int xs_stage_bytes;
+    int ksplit;  // the K loop of a tile is cut into this many slices, one block each (see below)
+    int kstages; // stages per slice
     FastDiv dKHW, dKW, dEH, dRW, dW;
 };
 
@@ -76,8 +78,10 @@ __device__ __forceinline__ int xcd_contiguous(int bid, int nb)
     return xcd * fl + (xcd < rem ? xcd : rem) + idx;
 }
 
+// Narrow tiles (NW < 4) keep few accumulators, so two blocks may share a compute unit and cover
+// each other's staging latency; the widest tile needs the whole register file.
 template <int N, int NW, int KC>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, NW == 4 ? 1 : 2)))
 void ukst_mfma_f32_kernel(const float* __restrict__ x, const float* __restrict__ w,
                           float* __restrict__ y, F32Args a)
 {
@@ -101,7 +105,12 @@ void ukst_mfma_f32_kernel(const float* __restrict__ x, const float* __restrict__
     const int l32 = lane & 31, gk = lane >> 5;
     const int KHW = g.KH * g.KW;
 
-    const int bid = xcd_contiguous(blockIdx.x, gridDim.x);
+    // Split K: when a layer has too few tiles to fill the chip (small maps, many channels), the
+    // input channels of a tile are divided among `ksplit` blocks; slice ks writes its partial
+    // sums to the ks-th copy of the output in scratch memory and a second kernel adds the copies
+    // in a fixed order.
+    const int bid_all = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int ks = bid_all % a.ksplit, bid = bid_all / a.ksplit;
     const int cb = bid % a.nco, qt = bid / a.nco;
     const int co0 = cb * TM;
     const int q0 = qt * TN;
@@ -248,13 +257,14 @@ void ukst_mfma_f32_kernel(const float* __restrict__ x, const float* __restrict__
         }
     };
 
-    const int stages = (g.Cin + KC - 1) / KC;  // channels past Cin read as zero (range check)
-    stage_load(0);
+    const int s0 = ks * a.kstages;              // this block's slice of the K stages
+    const int stages = s0 + a.kstages;          // (ksplit * kstages covers Cin exactly)
+    stage_load(s0 * KC);
     __syncthreads();  // zero fill done before the first activation writes
     stage_store(0);
     __syncthreads();
     int buf = 0;
-    for (int s = 1; s < stages; ++s) {
+    for (int s = s0 + 1; s < stages; ++s) {
         stage_load(s * KC);  // in flight while this stage is multiplied
         compute(buf);
         stage_store(buf ^ 1);
@@ -265,8 +275,9 @@ void ukst_mfma_f32_kernel(const float* __restrict__ x, const float* __restrict__
 
     // ---- epilogue: accumulator register i of a tile holds channel 8*(i/4) + 4*gk + (i%4) of the
     // wave's 32, for the lane's quad; column classes s = 1, 0 are neighbours in memory
+    const size_t ybytes = (size_t)g.B * g.Cout * g.OH * g.OW * 4;
     const __amdgpu_buffer_rsrc_t rs_y = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)y, 0, (int)((size_t)g.B * g.Cout * g.OH * g.OW * 4), kRsrcFlags);
+        (void*)((unsigned char*)y + (size_t)ks * ybytes), 0, (int)ybytes, kRsrcFlags);
     const unsigned plane = (unsigned)(g.OH * g.OW * 4);
     // Cout is a multiple of 8, so a group of 8 channels (4 per k parity) exists or not as a whole
     const int co_w = co0 + cw * 32;  // first channel of this wave
@@ -309,6 +320,21 @@ void ukst_mfma_f32_kernel(const float* __restrict__ x, const float* __restrict__
             }
         }
     }
+}
+
+// y[i] = part[0][i] + part[1][i] + ... in this order, four floats per thread
+__global__ __launch_bounds__(256) void ukst_sum_slices_kernel(const float4* __restrict__ part,
+                                                              float4* __restrict__ y, int n4,
+                                                              int ksplit)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n4) return;
+    float4 s = part[i];
+    for (int k = 1; k < ksplit; ++k) {
+        const float4 p = part[(size_t)k * n4 + i];
+        s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
+    }
+    y[i] = s;
 }
 
 template <int NW>
@@ -355,6 +381,16 @@ bool make_args(const Geom& g, F32Args& a)
     a.dEH = make_fastdiv((unsigned)a.EH);
     a.dRW = make_fastdiv((unsigned)(a.ROWS * g.W));
     a.dW = make_fastdiv((unsigned)g.W);
+    // K slices: only for layers that leave most of the chip idle, a power of two that divides the
+    // stage count, keeps at least two stages per slice and needs 16-byte sized outputs
+    a.ksplit = 1;
+    const int stages = g.Cin / KC;
+    const long long tiles = (long long)a.nco * a.nqt;
+    if (ybytes % 16 == 0)
+        while (a.ksplit < 8 && tiles * a.ksplit * 2 <= 1024 && stages % (a.ksplit * 2) == 0 &&
+               stages / (a.ksplit * 2) >= 2 && (size_t)(a.ksplit * 2) * ybytes <= ((size_t)1 << 30))
+            a.ksplit *= 2;
+    a.kstages = stages / a.ksplit;
     return true;
 }
 
@@ -368,9 +404,25 @@ hipError_t launch_t(const F32Args& a, const float* x, const float* w, float* y, 
     hipError_t e = hipFuncSetAttribute((const void*)ukst_mfma_f32_kernel<N, NW, KC>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((ukst_mfma_f32_kernel<N, NW, KC>), dim3((unsigned)(a.nco * a.nqt)), dim3(256),
-                       lds, stream, x, w, y, a);
-    return hipGetLastError();
+    const unsigned nblocks = (unsigned)(a.nco * a.nqt * a.ksplit);
+    if (a.ksplit == 1) {
+        hipLaunchKernelGGL((ukst_mfma_f32_kernel<N, NW, KC>), dim3(nblocks), dim3(256), lds, stream,
+                           x, w, y, a);
+        return hipGetLastError();
+    }
+    // partial outputs live in stream-ordered scratch memory for the duration of this call
+    const Geom& g = a.g;
+    const size_t ybytes = (size_t)g.B * g.Cout * g.OH * g.OW * 4;
+    void* part = nullptr;
+    if ((e = hipMallocAsync(&part, ybytes * a.ksplit, stream)) != hipSuccess) return e;
+    hipLaunchKernelGGL((ukst_mfma_f32_kernel<N, NW, KC>), dim3(nblocks), dim3(256), lds, stream, x, w,
+                       (float*)part, a);
+    const int n4 = (int)(ybytes / 16);
+    hipLaunchKernelGGL(ukst_sum_slices_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0,
+                       stream, (const float4*)part, (float4*)y, n4, a.ksplit);
+    e = hipGetLastError();
+    const hipError_t ef = hipFreeAsync(part, stream);
+    return e != hipSuccess ? e : ef;
 }
 
 template <int NW>
@@ -413,6 +465,10 @@ hipError_t launch_mfma_f32(const Geom& g, const void* x, const void* w, float* y
 {
     F32Args a;
     const int nw = pick_nw(g, a);
+    if (((uintptr_t)y & 15) != 0) {  // the slice sum moves 16-byte pieces: no split for such outputs
+        a.kstages *= a.ksplit;
+        a.ksplit = 1;
+    }
     const float* xf = (const float*)x;
     const float* wf = (const float*)w;
     switch (nw) {

@@ -143,6 +143,8 @@ MFMA_F32_SHAPES = [
     (1, 16, 128, 33, 31, 3, 0),   # several row tiles of one image, two channel blocks
     (1, 8, 64, 1, 9, 4, 2),       # single input row
     (2, 32, 64, 63, 63, 3, 0),    # cfg4b spatial shape: wide tiles (NW = 4)
+    (2, 64, 16, 5, 6, 4, 2),      # few tiles, 8 K stages: the K loop is split over 4 blocks
+    (1, 96, 8, 3, 5, 3, 1),       # 6 stages of 16: split in 2
 ]
 
 
