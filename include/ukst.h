@@ -1,7 +1,11 @@
 /*
  * ukst -- unified kernel-segregated stride-2 2-D transpose convolution for AMD MI355X (gfx950).
  *
- * C ABI, stateless: no allocation, no cached weights, no synchronisation inside any call.
+ * C ABI, stateless: nothing is cached or kept between calls (weights are re-read and re-gathered
+ * by every call) and no call synchronises.  One kernel family takes scratch memory for the
+ * duration of a call: the fp32 matrix-core path splits the input channels of layers with very few
+ * output tiles over several blocks and keeps their partial outputs in memory obtained with
+ * hipMallocAsync / hipFreeAsync on the caller's stream (no other allocation anywhere).
  *
  * What is computed (Algorithm 1 of the paper is the definition, Algorithm 2 + Eqs. 1-4 + the
  * padding rule of Sec. 3.4 are how it is evaluated):
@@ -45,8 +49,10 @@ typedef enum {
 /* Kernel families ("paths").  UKST_PATH_AUTO picks by channel width. */
 typedef enum {
     UKST_PATH_AUTO = 0,
-    UKST_PATH_DIRECT = 1, /* one thread = one 2x2 output quad (all four parity classes), input tile
-                             + halo staged once in LDS; any shape, either dtype */
+    UKST_PATH_DIRECT = 1, /* vector-ALU kernels: a lane owns whole 2x2 output quads (all four parity
+                             classes) and their shared input window; specialised for few channels
+                             (narrow: Cin, Cout <= 4; thin: Cout <= 4), general otherwise; any
+                             shape, either dtype */
     UKST_PATH_MFMA = 2    /* parity-class implicit GEMM on the matrix cores, wide channels */
 } ukst_path;
 
@@ -97,7 +103,8 @@ int ukst_select_path(int B, int Cin, int Cout, int H, int W, int n, int P, int d
  *
  * Only element alignment is assumed (4 bytes fp32, 2 bytes bf16).  The caller owns all buffers;
  * the call enqueues work on `stream` and returns without synchronising.  Arguments are validated
- * on the host before anything touches the GPU; on any error nothing is launched.
+ * on the host before anything touches the GPU; on a validation error nothing is launched.  A
+ * failing scratch allocation or launch is reported as UKST_ERR_LAUNCH.
  * Returns a ukst_status.
  */
 int ukst_conv_transpose2d(const void* x, const void* w, void* y, int B, int Cin, int Cout, int H,
