@@ -101,7 +101,9 @@ int ukst_select_path(int B, int Cin, int Cout, int H, int W, int n, int P, int d
  *   dtype   a ukst_dtype
  *   stream  a hipStream_t (as void*), or NULL for the default stream
  *
- * Only element alignment is assumed (4 bytes fp32, 2 bytes bf16).  The caller owns all buffers;
+ * Only element alignment is required (4 bytes fp32, 2 bytes bf16; UKST_ERR_UNSUPPORTED otherwise).
+ * The matrix-core kernels additionally want w (and x for bf16) aligned to 16 bytes: when they are
+ * not, ukst_conv_transpose2d uses the vector-ALU kernels instead.  The caller owns all buffers;
  * the call enqueues work on `stream` and returns without synchronising.  Arguments are validated
  * on the host before anything touches the GPU; on a validation error nothing is launched.  A
  * failing scratch allocation or launch is reported as UKST_ERR_LAUNCH.
@@ -113,7 +115,8 @@ int ukst_conv_transpose2d(const void* x, const void* w, void* y, int B, int Cin,
 /*
  * Same operation with the kernel family forced (tests and benchmarks compare the families on one
  * shape).  path = UKST_PATH_AUTO behaves exactly like ukst_conv_transpose2d.  Returns
- * UKST_ERR_UNSUPPORTED if that family cannot run the shape.
+ * UKST_ERR_UNSUPPORTED if that family cannot run the shape (or, for UKST_PATH_MFMA, buffers that
+ * are not 16-byte aligned).
  */
 int ukst_conv_transpose2d_path(const void* x, const void* w, void* y, int B, int Cin, int Cout,
                                int H, int W, int n, int P, int dtype, int path, void* stream);

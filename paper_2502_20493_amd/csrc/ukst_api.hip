@@ -113,7 +113,13 @@ int ukst_conv_transpose2d_path(const void* x, const void* w, void* y, int B, int
     if (path != UKST_PATH_AUTO && path != UKST_PATH_DIRECT && path != UKST_PATH_MFMA)
         return UKST_ERR_UNSUPPORTED;
     const ukst::Geom g = ukst::make_geom(B, Cin, Cout, H, W, n, P);
-    const int chosen = resolve_path(g, dtype, path);
+    // element alignment is required of every buffer; the matrix-core kernels move the weights
+    // (and bf16 activations) in 16-byte pieces and need those buffers aligned to that
+    const uintptr_t esz = dtype == UKST_BF16_F32 ? 2 : 4;
+    if (((uintptr_t)x | (uintptr_t)w) & (esz - 1) || ((uintptr_t)y & 3)) return UKST_ERR_UNSUPPORTED;
+    const bool wide_ok = (((uintptr_t)w | (dtype == UKST_BF16_F32 ? (uintptr_t)x : 0)) & 15) == 0;
+    int chosen = resolve_path(g, dtype, path);
+    if (chosen == UKST_PATH_MFMA && !wide_ok) chosen = (path == UKST_PATH_AUTO) ? UKST_PATH_DIRECT : -1;
     if (chosen < 0) return UKST_ERR_UNSUPPORTED;
     hipError_t e;
     if (chosen == UKST_PATH_MFMA)

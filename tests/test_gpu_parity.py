@@ -200,3 +200,33 @@ def test_non_default_stream():
     s.synchronize()
     y_ref, S = oracle.naive(data["x"], data["w"], w.P)
     check_against_oracle(y.cpu().numpy(), y_ref, S, TOL["f32"])
+
+
+# ------------------------------------------------------------------ buffers with element alignment only
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_unaligned_buffers_take_the_vector_alu_kernels(dtype):
+    """x, w one element past a 16-byte boundary: AUTO must still be right, forced MFMA must refuse."""
+    import torch
+    w = _mk("unaligned", 8100, 2, 32, 64, 6, 16, 4, 2, dtype=dtype)
+    data = wl.generate(w)
+    y_ref, S = oracle.naive(data["x"], data["w"], w.P)
+    if dtype == "bf16":
+        tx = torch.from_numpy(data["x_bits"].view(np.int16)).view(torch.bfloat16)
+        tk = torch.from_numpy(data["w_bits"].view(np.int16)).view(torch.bfloat16)
+    else:
+        tx, tk = torch.from_numpy(data["x"]), torch.from_numpy(data["w"])
+
+    def shifted(t):  # same values, storage starting one element after an aligned address
+        buf = torch.empty(t.numel() + 1, dtype=t.dtype, device="cuda")
+        v = buf[1:].view(t.shape)
+        v.copy_(t)
+        assert v.data_ptr() % 16 != 0
+        return v
+
+    x, k = shifted(tx), shifted(tk)
+    y = ukst.ukst_conv_transpose2d(x, k, w.P)
+    torch.cuda.synchronize()
+    check_against_oracle(y.cpu().numpy(), y_ref, S, TOL[dtype])
+    with pytest.raises(ukst.UkstError):
+        ukst.ukst_conv_transpose2d(x, k, w.P, path=PATHS["mfma"])
+    torch.cuda.synchronize()
