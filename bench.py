@@ -154,6 +154,29 @@ def cpu_baseline(w, data, budget_s=2.0):
                       f"counted exactly as for the GPU"}
 
 
+def copy_ceiling(nbytes, steps=200):
+    """Measured ceiling shown next to the published peak: a plain device-to-device copy (torch's
+    copy kernel) of buffers of the workload's size, rotated beyond the last-level cache; bytes
+    read plus bytes written per second."""
+    import torch
+    n = max(1 << 20, nbytes // 2 // 4)
+    nsets = max(2, min(16, -(-(LLC_BYTES + (64 << 20)) // (8 * n))))
+    src = [torch.empty(n, dtype=torch.float32, device="cuda").normal_() for _ in range(nsets)]
+    dst = [torch.empty(n, dtype=torch.float32, device="cuda") for _ in range(nsets)]
+    for i in range(20):
+        dst[i % nsets].copy_(src[i % nsets])
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(steps):
+        dst[i % nsets].copy_(src[i % nsets])
+    e1.record()
+    torch.cuda.synchronize()
+    s = e0.elapsed_time(e1) / 1e3 / steps
+    return {"d2d_copy_GBps": round(8 * n / s / 1e9, 1), "d2d_copy_bytes": 8 * n,
+            "d2d_copy_us": round(s * 1e6, 2)}
+
+
 def measured_traffic(kernel_workload):
     """HBM bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE / WRITE_SIZE,
     each scaled by what the counter reads for a plain copy of known size), or None."""
@@ -194,6 +217,7 @@ def main():
     m.pop("_exact_flop")
     cpu = None if args.no_cpu else cpu_baseline(head, data)
     del data
+    m["roofline"]["measured_ceiling"] = copy_ceiling(m["roofline"]["algorithmic_bytes"])
 
     per = []
     if args.configs != "none" and not args.only:
