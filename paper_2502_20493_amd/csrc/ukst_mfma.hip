@@ -477,6 +477,14 @@ hipError_t launch_mfma(const Geom& g, const void* x, const void* w, float* y, in
     if (grid < 8) grid = 8;
     const int need = ((a.ntiles + 7) / 8) * 8;
     if (grid > need) grid = need;
+    // The slowest block walks ceil(tiles / grid) tiles whatever the rest do: use only as many
+    // blocks as that round count needs (584 tiles take 3 rounds on 256 blocks and on 200), the
+    // idle compute units leave power for the clock of the busy ones.
+    {
+        const int rounds = (a.ntiles + grid - 1) / grid;
+        const int fewer = (((a.ntiles + rounds - 1) / rounds + 7) / 8) * 8;
+        if (fewer < grid) grid = fewer;
+    }
     // worth the idle stages only when every block walks over many tiles
     a.stagger = (a.ntiles >= 8 * grid) ? 1 : 0;
     hipLaunchKernelGGL((ukst_mfma_bf16_kernel<N>), dim3((unsigned)grid), dim3(256), lds, stream,
