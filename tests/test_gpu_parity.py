@@ -187,19 +187,25 @@ def test_repeat_runs_are_bit_identical():
     assert np.array_equal(a, b)
 
 
-def test_non_default_stream():
+@pytest.mark.parametrize("case", ["narrow", "mfma_f32_split_k", "mfma_bf16"])
+def test_non_default_stream(case):
+    """Work (including the split-K scratch memory and its slice sum) follows the caller's stream."""
     import torch
     from gpu_util import to_device
-    w = wl.WORKLOADS["cfg1"]
+    w = {"narrow": wl.WORKLOADS["cfg1"],
+         "mfma_f32_split_k": _mk("stream_f32", 8201, 2, 64, 16, 5, 6, 4, 2),
+         "mfma_bf16": _mk("stream_bf16", 8202, 2, 32, 64, 6, 16, 4, 2, dtype="bf16")}[case]
     data = wl.generate(w)
     x, wt = to_device(data, w.dtype)
     s = torch.cuda.Stream()
     torch.cuda.synchronize()
     with torch.cuda.stream(s):
-        y = ukst.ukst_conv_transpose2d(x, wt, w.P)
+        y1 = ukst.ukst_conv_transpose2d(x, wt, w.P)
+        y2 = ukst.ukst_conv_transpose2d(x, wt, w.P)  # back to back: scratch is reused stream-ordered
     s.synchronize()
     y_ref, S = oracle.naive(data["x"], data["w"], w.P)
-    check_against_oracle(y.cpu().numpy(), y_ref, S, TOL["f32"])
+    check_against_oracle(y1.cpu().numpy(), y_ref, S, TOL[w.dtype])
+    assert torch.equal(y1, y2)
 
 
 # ------------------------------------------------------------------ buffers with element alignment only
