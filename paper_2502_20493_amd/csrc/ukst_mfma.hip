@@ -75,8 +75,6 @@ struct MfmaArgs {
     int nco;      // channel blocks
     int nqt;      // quad tiles
     int ntiles;   // nco * nqt
-    int stagger;  // 1: blocks start with 0..7/8 of a tile of idle stages so that they do not all
-                  //    drain their accumulators (and saturate HBM writes) at the same moment
     int cb_major; // tile order: 1 = consecutive tiles share the channel block (big weights),
                   //             0 = consecutive tiles share the quad tile (big activations)
     FastDiv dKHW, dKW, dEH, dC8, dROWS, dNCO, dNQT;
@@ -263,16 +261,11 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    // ---- first tile of this block: fill the pipeline.  With staggering, the first "tile" is a
-    // virtual one of `idle` stages (all loads out of range, i.e. zeros, nothing stored), so that
-    // neighbouring blocks reach their drains at different times.
-    int idle = 0;
-    if (a.stagger) idle = ((int)((blockIdx.x >> 3) & 7) * stages_even / 8) & ~1;
-    bool virt = idle > 0;
+    // ---- first tile of this block: fill the pipeline
     int cb = 0, qt = 0;
     bool have = tile_of(0, cb, qt);
     unsigned wv_c = kInvalid, xv_c = kInvalid;
-    if (have && !virt) staging_offsets(cb, qt, wv_c, xv_c);
+    if (have) staging_offsets(cb, qt, wv_c, xv_c);
 #pragma unroll
     for (int j = 0; j < 16; ++j) load_one(0, wv_c, xv_c, j, wreg[0], xreg[0]);
     {
@@ -286,11 +279,10 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
     for (int j = 0; j < 16; ++j) store_one(0, j, wreg[0], xreg[0]);
     __syncthreads();
 
-    for (int rho = virt ? -1 : 0; have; ++rho) {
+    for (int rho = 0; have; ++rho) {
         // next tile of this block (its first two stages are fetched during this tile's last two)
         int cb_n = 0, qt_n = 0;
         const bool have_n = tile_of(rho + 1, cb_n, qt_n);
-        const int S_cur = virt ? idle : stages_even;
         unsigned wv_n = kInvalid, xv_n = kInvalid;
         if (have_n) staging_offsets(cb_n, qt_n, wv_n, xv_n);
 
@@ -327,8 +319,8 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
         // In iteration s the loads of stage s+2 go into register set 0 and those of s+3 into set 1
         // (their previous contents are already in LDS), while sets 1 / 0 are transposed into the
         // other LDS buffer.  The last iteration requests stages 0 and 1 of the next tile instead.
-        for (int s = 0; s < S_cur; s += 2) {
-            const bool last = s + 2 >= S_cur;
+        for (int s = 0; s < stages_even; s += 2) {
+            const bool last = s + 2 >= stages_even;
             {
                 const int t = last ? 0 : s + 2;
                 stage(0, t * KC, last ? wv_n : wv_c, last ? xv_n : xv_c);
@@ -343,10 +335,6 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
             __syncthreads();
         }
 
-        if (virt) {  // nothing to store; the real first tile is already in the pipeline
-            virt = false; have = have_n; cb = cb_n; qt = qt_n; wv_c = wv_n; xv_c = xv_n;
-            continue;
-        }
         // ---- drain: accumulator register i of a tile holds channel 8*(i/4) + 4*gk + (i%4) of the
         // wave's 32, for the lane's quad; column classes s = 1, 0 are neighbours in memory
         const int co0 = cb * TM;
@@ -435,7 +423,6 @@ bool make_args(const Geom& g, int dtype, MfmaArgs& a)
     a.ntiles = a.nco * a.nqt;
     // keep in one L2 what is bigger: the weights of a channel block or a tile's activations
     a.cb_major = ((size_t)TM * g.Cin * g.n * g.n * 2 > (size_t)(1 << 20)) ? 1 : 0;
-    a.stagger = 0;  // set at launch, when the grid size is known
     a.dKHW = make_fastdiv((unsigned)(g.KH * g.KW));
     a.dKW = make_fastdiv((unsigned)g.KW);
     a.dEH = make_fastdiv((unsigned)a.EH);
@@ -485,8 +472,6 @@ hipError_t launch_mfma(const Geom& g, const void* x, const void* w, float* y, in
         const int fewer = (((a.ntiles + rounds - 1) / rounds + 7) / 8) * 8;
         if (fewer < grid) grid = fewer;
     }
-    // worth the idle stages only when every block walks over many tiles
-    a.stagger = (a.ntiles >= 8 * grid) ? 1 : 0;
     hipLaunchKernelGGL((ukst_mfma_bf16_kernel<N>), dim3((unsigned)grid), dim3(256), lds, stream,
                        (const uint16_t*)x, (const uint16_t*)w, y, a);
     return hipGetLastError();
