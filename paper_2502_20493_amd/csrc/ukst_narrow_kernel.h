@@ -118,6 +118,7 @@ __global__ __launch_bounds__(256) void ukst_narrow_kernel(const float* __restric
         if (!shifts) return;
 #pragma unroll
         for (int s = 1; s <= WC; ++s) {
+            if (s > (P >> 1)) break;  // wave-uniform: no lane is further left than floor(P/2)
             const bool m = left >= s;
 #pragma unroll
             for (int u = 0; u < WR; ++u)
