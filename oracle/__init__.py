@@ -80,7 +80,7 @@ def _call(name, x, w, P, planes=None):
     if OH < 1 or OW < 1 or P < 0:
         raise ValueError("empty output")
     y = np.zeros((B, Cout, OH, OW), dtype=np.float64)
-    S = np.zeros_like(y)
+    S = np.zeros(y.shape, dtype=np.float64)  # untouched planes stay unmapped pages
     lib = _load()
     if name == "naive":
         if planes is None:

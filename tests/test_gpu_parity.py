@@ -157,6 +157,51 @@ def test_mfma_f32_small_shapes_every_element(shape):
     _parity(w, PATHS["mfma"], integer=False)
 
 
+def _parity_sampled_on_device(w, planes, expect_kernel):
+    """Large outputs: only the sampled planes (and a guard band on either side of the output)
+    travel back to the host."""
+    import torch
+    from gpu_util import to_device
+    print(f"case {w.name} B={w.B} Cin={w.Cin} Cout={w.Cout} H={w.H} W={w.W} n={w.n} P={w.P} "
+          f"{w.dtype} planes={planes}", flush=True)
+    dt = ukst.UKST_F32 if w.dtype == "f32" else ukst.UKST_BF16_F32
+    assert ukst.ukst_kernel_name(w.B, w.Cin, w.Cout, w.H, w.W, w.n, w.P, dt,
+                                 PATHS["auto"]) == expect_kernel
+    data = wl.generate(w, integer=True)
+    y_ref, S = oracle.naive(data["x"], data["w"], w.P, planes=planes)
+    x, wt = to_device(data, w.dtype)
+    OH, OW = ukst.ukst_output_shape(w.H, w.W, w.n, w.P)
+    numel, guard, sentinel = w.B * w.Cout * OH * OW, 1 << 16, -777.0
+    buf = torch.full((numel + 2 * guard,), sentinel, dtype=torch.float32, device="cuda")
+    y = buf[guard:guard + numel].view(w.B, w.Cout, OH, OW)
+    ukst.ukst_conv_transpose2d(x, wt, w.P, y=y)
+    torch.cuda.synchronize()
+    assert bool((buf[:guard] == sentinel).all()) and bool((buf[guard + numel:] == sentinel).all())
+    yp = y.view(w.B * w.Cout, OH, OW)
+    for p in planes:
+        got = yp[p].cpu().numpy().astype(np.float64)
+        assert np.array_equal(got, y_ref.reshape(w.B * w.Cout, OH, OW)[p]), f"plane {p}"
+    return numel
+
+
+def test_output_beyond_32bit_byte_offsets():
+    # 4.7 GB of output: the last plane starts past 2^32 bytes, which only the general kernel
+    # (64-bit addressing) may take; integer data, so the comparison is exact
+    w = _mk("big_f32", 9101, 2, 2, 3, 7000, 7000, 3, 0)
+    numel = _parity_sampled_on_device(w, [0, 3, 5], "ukst_direct_kernel")
+    assert numel * 4 > 1 << 32
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_matrix_core_shapes_beyond_their_buffer_limit_fall_back(dtype):
+    # a layer the matrix-core kernels would take, but whose output exceeds their single 2 GiB
+    # buffer descriptor: automatic selection has to hand it to the general kernel
+    w = _mk("big_mfma_shape", 9102, 33, 16, 64, 256, 256, 4, 2, dtype=dtype)
+    assert not _supported(w, PATHS["mfma"])
+    numel = _parity_sampled_on_device(w, [0, 1000, 33 * 64 - 1], "ukst_direct_kernel")
+    assert numel * 4 > (1 << 31)
+
+
 def test_paths_agree_at_full_size():
     # property that holds at any size: both kernel families compute the same tensor
     import torch
