@@ -381,15 +381,23 @@ bool make_args(const Geom& g, F32Args& a)
     a.dEH = make_fastdiv((unsigned)a.EH);
     a.dRW = make_fastdiv((unsigned)(a.ROWS * g.W));
     a.dW = make_fastdiv((unsigned)g.W);
-    // K slices: only for layers that leave most of the chip idle, a power of two that divides the
-    // stage count, keeps at least two stages per slice and needs 16-byte sized outputs
+    // K slices: only for layers with fewer tiles than compute units.  Two blocks share a compute
+    // unit, so about 512 blocks fill the chip once: take the power of two that brings the block
+    // count closest to that (in ratio), as long as it divides the stage count, leaves at least
+    // two stages per slice and the outputs are 16-byte sized (the slice sum moves such pieces).
     a.ksplit = 1;
     const int stages = g.Cin / KC;
     const long long tiles = (long long)a.nco * a.nqt;
-    if (ybytes % 16 == 0)
-        while (a.ksplit < 8 && tiles * a.ksplit * 2 <= 1024 && stages % (a.ksplit * 2) == 0 &&
-               stages / (a.ksplit * 2) >= 2 && (size_t)(a.ksplit * 2) * ybytes <= ((size_t)1 << 30))
-            a.ksplit *= 2;
+    if (ybytes % 16 == 0 && tiles < 256) {
+        auto distance = [&](int ks) {
+            const double r = (double)(tiles * ks) / 512.0;
+            return r >= 1.0 ? r : 1.0 / r;
+        };
+        for (int ks = 2; ks <= 8; ks *= 2) {
+            if (stages % ks != 0 || stages / ks < 2 || (size_t)ks * ybytes > ((size_t)1 << 30)) break;
+            if (distance(ks) < distance(a.ksplit)) a.ksplit = ks;
+        }
+    }
     a.kstages = stages / a.ksplit;
     return true;
 }
