@@ -53,7 +53,7 @@ typedef enum {
                              classes) and their shared input window; specialised for few channels
                              (narrow: Cin, Cout <= 4; thin: Cout <= 4), general otherwise; any
                              shape, either dtype */
-    UKST_PATH_MFMA = 2    /* parity-class implicit GEMM on the matrix cores, wide channels */
+    UKST_PATH_MFMA = 2    /* parity-class implicit GEMM on the matrix cores: wide channels, or <= 4 output channels (fp32) */
 } ukst_path;
 
 #define UKST_MAX_N 7 /* largest kernel side compiled in */
@@ -102,8 +102,8 @@ int ukst_select_path(int B, int Cin, int Cout, int H, int W, int n, int P, int d
  *   stream  a hipStream_t (as void*), or NULL for the default stream
  *
  * Only element alignment is required (4 bytes fp32, 2 bytes bf16; UKST_ERR_UNSUPPORTED otherwise).
- * The matrix-core kernels additionally want w (and x for bf16) aligned to 16 bytes: when they are
- * not, ukst_conv_transpose2d uses the vector-ALU kernels instead.  The caller owns all buffers;
+ * The matrix-core kernels additionally want w (and x, for bf16 and for fp32 layers with at most 4
+ * output channels) aligned to 16 bytes: when they are not, ukst_conv_transpose2d uses the vector-ALU kernels instead.  The caller owns all buffers;
  * the call enqueues work on `stream` and returns without synchronising.  Arguments are validated
  * on the host before anything touches the GPU; on a validation error nothing is launched.  A
  * failing scratch allocation or launch is reported as UKST_ERR_LAUNCH.

@@ -38,8 +38,11 @@ int resolve_path(const ukst::Geom& g, int dtype, int path)
 {
     if (path == UKST_PATH_DIRECT) return UKST_PATH_DIRECT;
     if (path == UKST_PATH_MFMA) return ukst::mfma_supported(g, dtype) ? UKST_PATH_MFMA : -1;
-    // AUTO: the matrix cores pay off once both channel counts fill an MFMA tile
-    if (ukst::mfma_supported(g, dtype) && g.Cin >= 16 && g.Cout >= 16) return UKST_PATH_MFMA;
+    // AUTO: the matrix cores pay off once both channel counts fill an MFMA tile, or, for layers
+    // with very few output channels, once the parity classes can fill its columns instead
+    if (ukst::mfma_supported(g, dtype) &&
+        ((g.Cin >= 16 && g.Cout >= 16) || ukst::thin_mfma_supported(g, dtype)))
+        return UKST_PATH_MFMA;
     return UKST_PATH_DIRECT;
 }
 
@@ -117,8 +120,9 @@ int ukst_conv_transpose2d_path(const void* x, const void* w, void* y, int B, int
     // (and bf16 activations) in 16-byte pieces and need those buffers aligned to that
     const uintptr_t esz = dtype == UKST_BF16_F32 ? 2 : 4;
     if (((uintptr_t)x | (uintptr_t)w) & (esz - 1) || ((uintptr_t)y & 3)) return UKST_ERR_UNSUPPORTED;
-    const bool wide_ok = (((uintptr_t)w | (dtype == UKST_BF16_F32 ? (uintptr_t)x : 0)) & 15) == 0;
     int chosen = resolve_path(g, dtype, path);
+    const bool x16 = chosen == UKST_PATH_MFMA && ukst::mfma_needs_aligned_x(g, dtype);
+    const bool wide_ok = (((uintptr_t)w | (x16 ? (uintptr_t)x : 0)) & 15) == 0;
     if (chosen == UKST_PATH_MFMA && !wide_ok) chosen = (path == UKST_PATH_AUTO) ? UKST_PATH_DIRECT : -1;
     if (chosen < 0) return UKST_ERR_UNSUPPORTED;
     hipError_t e;

@@ -437,15 +437,22 @@ bool make_args(const Geom& g, int dtype, MfmaArgs& a)
 
 bool mfma_supported(const Geom& g, int dtype)
 {
-    if (dtype == 0) return mfma_f32_supported(g);
+    if (dtype == 0) return mfma_f32_supported(g) || thin_mfma_supported(g, dtype);
     MfmaArgs a;
     return make_args(g, dtype, a);
+}
+
+bool mfma_needs_aligned_x(const Geom& g, int dtype)
+{
+    return dtype != 0 || (!mfma_f32_supported(g) && thin_mfma_supported(g, dtype));
 }
 
 hipError_t launch_mfma(const Geom& g, const void* x, const void* w, float* y, int dtype,
                        hipStream_t stream)
 {
-    if (dtype == 0) return launch_mfma_f32(g, x, w, y, stream);
+    if (dtype == 0)
+        return mfma_f32_supported(g) ? launch_mfma_f32(g, x, w, y, stream)
+                                     : launch_thin_mfma(g, x, w, y, stream);
     MfmaArgs a;
     if (!make_args(g, dtype, a)) return hipErrorInvalidValue;
     constexpr int N = 4;
@@ -477,9 +484,10 @@ hipError_t launch_mfma(const Geom& g, const void* x, const void* w, float* y, in
     return hipGetLastError();
 }
 
-const char* mfma_kernel_name(const Geom&, int dtype)
+const char* mfma_kernel_name(const Geom& g, int dtype)
 {
-    return dtype == 0 ? "ukst_mfma_f32_kernel" : "ukst_mfma_bf16_kernel";
+    if (dtype != 0) return "ukst_mfma_bf16_kernel";
+    return mfma_f32_supported(g) ? "ukst_mfma_f32_kernel" : "ukst_thin_mfma_kernel";
 }
 
 }  // namespace ukst

@@ -96,7 +96,12 @@ def test_mac_counts():
 
 def test_select_path():
     assert ukst.ukst_select_path(16, 3, 3, 224, 224, 3, 0, ukst.UKST_F32) == ukst.UKST_PATH_DIRECT
-    assert ukst.ukst_select_path(64, 64, 3, 32, 32, 4, 2, ukst.UKST_F32) == ukst.UKST_PATH_DIRECT
+    # few output channels: the parity classes fill the MFMA columns when Cin % 16 == 0, W % 4 == 0
+    assert ukst.ukst_select_path(64, 64, 3, 32, 32, 4, 2, ukst.UKST_F32) == ukst.UKST_PATH_MFMA
+    assert ukst.ukst_kernel_name(64, 64, 3, 32, 32, 4, 2, 0) == "ukst_thin_mfma_kernel"
+    assert ukst.ukst_select_path(64, 24, 3, 32, 31, 4, 2, ukst.UKST_F32) == ukst.UKST_PATH_DIRECT
+    assert ukst.ukst_kernel_name(64, 24, 3, 32, 31, 4, 2, 0) == "ukst_thin_kernel"
+    assert ukst.ukst_select_path(32, 256, 128, 128, 128, 4, 2, ukst.UKST_BF16_F32) == ukst.UKST_PATH_MFMA
     with pytest.raises(ukst.UkstError):
         ukst.ukst_select_path(16, 3, 3, 1, 224, 3, 0, ukst.UKST_F32)
     assert "narrow" in ukst.ukst_kernel_name(16, 3, 3, 224, 224, 3, 0, 0)

@@ -157,6 +157,34 @@ def test_mfma_f32_small_shapes_every_element(shape):
     _parity(w, PATHS["mfma"], integer=False)
 
 
+THIN_MFMA_SHAPES = [
+    # B, Cin, Cout, H, W, n, P      (fp32, Cout <= 4, n in {3, 4}, Cin % 16 == 0, W % 4 == 0)
+    (1, 16, 3, 4, 4, 4, 2),      # one partial tile
+    (3, 32, 3, 5, 8, 4, 2),      # tiles span images, ragged last tile
+    (2, 48, 4, 9, 12, 4, 2),     # four output channels: all 16 MFMA columns in use
+    (2, 16, 1, 7, 8, 4, 0),      # P = 0, one output channel
+    (2, 16, 2, 6, 16, 4, 1),     # odd P: class order flips (Sec. 3.4)
+    (1, 32, 3, 3, 20, 4, 3),     # odd P > 1
+    (5, 16, 3, 2, 4, 4, 2),      # many tiny images inside one tile
+    (1, 16, 3, 40, 64, 4, 2),    # several tiles per image, wide rows
+    (1, 16, 3, 1, 4, 4, 2),      # single input row
+    (2, 32, 3, 9, 12, 3, 0),     # n = 3: odd output, classes with fewer taps (Sec. 3.1)
+    (2, 16, 4, 6, 8, 3, 1),      # n = 3, odd P
+    (1, 16, 2, 5, 8, 3, 2),      # n = 3, P = 2
+    (2, 16, 3, 8, 8, 4, 5),      # padding beyond the kernel: zero border
+]
+
+
+@pytest.mark.parametrize("shape", THIN_MFMA_SHAPES)
+def test_thin_mfma_small_shapes_every_element(shape):
+    B, Cin, Cout, H, W, n, P = shape
+    w = _mk("thin_mfma", 8000 + sum(shape), B, Cin, Cout, H, W, n, P)
+    assert ukst.ukst_kernel_name(B, Cin, Cout, H, W, n, P, ukst.UKST_F32,
+                                 PATHS["mfma"]) == "ukst_thin_mfma_kernel"
+    _parity(w, PATHS["mfma"], integer=True)
+    _parity(w, PATHS["mfma"], integer=False)
+
+
 def _parity_sampled_on_device(w, planes, expect_kernel):
     """Large outputs: only the sampled planes (and a guard band on either side of the output)
     travel back to the host."""
@@ -254,11 +282,11 @@ def test_non_default_stream(case):
 
 
 # ------------------------------------------------------------------ buffers with element alignment only
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_unaligned_buffers_take_the_vector_alu_kernels(dtype):
+@pytest.mark.parametrize("dtype,cout", [("f32", 64), ("bf16", 64), ("f32", 3)])
+def test_unaligned_buffers_take_the_vector_alu_kernels(dtype, cout):
     """x, w one element past a 16-byte boundary: AUTO must still be right, forced MFMA must refuse."""
     import torch
-    w = _mk("unaligned", 8100, 2, 32, 64, 6, 16, 4, 2, dtype=dtype)
+    w = _mk("unaligned", 8100, 2, 32, cout, 6, 16, 4, 2, dtype=dtype)
     data = wl.generate(w)
     y_ref, S = oracle.naive(data["x"], data["w"], w.P)
     if dtype == "bf16":
