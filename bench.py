@@ -11,7 +11,8 @@ Prints ONE JSON line.  Besides the contract fields it carries
                 events on the launch stream, against the 8 TB/s HBM peak),
   cpu_baseline  the fp64 CPU oracle timed on this machine's host cores on the same workload,
   per_config    the same measurements for every other benchmark configuration (each against the
-                roofline that bounds it).
+                roofline that bounds it), and for the four cfg3 generator layers chained on one
+                stream (cfg3_stack).
 """
 from __future__ import annotations
 
@@ -131,6 +132,68 @@ def measure(w, steps, warmup, rotate_bytes=LLC_BYTES + (64 << 20), warm_seconds=
     }
 
 
+def measure_stack(steps, warm_seconds=0.3, nsets=8):
+    """The four generator layers of cfg3 chained on one stream: the output of layer k is the input
+    of layer k+1 (Table 4 reports such a stack as one total).  One step = four launches; steps
+    rotate over `nsets` complete sets of activations and weights (about 45 MB each)."""
+    import torch
+    from paper_2502_20493_amd import binding as ukst
+    from paper_2502_20493_amd import workloads as wl
+
+    names = ["cfg3_L1", "cfg3_L2", "cfg3_L3", "cfg3_L4"]
+    layers = [wl.WORKLOADS[n] for n in names]
+    for a, b in zip(layers, layers[1:]):
+        oh, ow = ukst.ukst_output_shape(a.H, a.W, a.n, a.P)
+        assert (a.B, a.Cout, oh, ow) == (b.B, b.Cin, b.H, b.W), "layers do not chain"
+    stream = torch.cuda.current_stream()
+    sp = stream.cuda_stream
+    fn = ukst.lib().ukst_conv_transpose2d
+    sets, flop, nbytes = [], 0, 0
+    for j in range(nsets):
+        x = torch.from_numpy(wl.generate(layers[0])["x"]).cuda()
+        calls, keep = [], [x]
+        for w in layers:
+            k = torch.from_numpy(wl.generate(w)["w"]).cuda()
+            oh, ow = ukst.ukst_output_shape(w.H, w.W, w.n, w.P)
+            y = torch.empty((w.B, w.Cout, oh, ow), dtype=torch.float32, device="cuda")
+            if j == 0:
+                ukst.ukst_conv_transpose2d(x, k, w.P, y=y, stream=stream)  # checked call
+                flop += 2 * ukst.ukst_mac_count(w.B, w.Cin, w.Cout, w.H, w.W, w.n, w.P, 0)
+                nbytes += algorithmic_bytes(w, oh, ow)
+            calls.append(functools.partial(fn, x.data_ptr(), k.data_ptr(), y.data_ptr(), w.B, w.Cin,
+                                           w.Cout, w.H, w.W, w.n, w.P, ukst.UKST_F32, sp))
+            keep += [k, y]
+            x = y
+        sets.append((calls, keep))
+
+    def step(i):
+        for c in sets[i % nsets][0]:
+            if c() != 0:
+                raise RuntimeError("ukst_conv_transpose2d failed")
+
+    t_w = time.perf_counter()
+    while time.perf_counter() - t_w < warm_seconds:
+        for i in range(10):
+            step(i)
+        torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for i in range(steps):
+        step(i)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    per_s = e0.elapsed_time(e1) / 1e3 / steps
+    tf = flop / per_s / 1e12
+    return {"workload": "cfg3_stack", "shape": "B64 512->256->128->64->3, 4x4 -> 64x64, n4 P2 f32, "
+            "four chained launches on one stream", "out": "64x64",
+            "useful_gflops": round(flop / per_s / 1e9, 1), "us": round(per_s * 1e6, 2),
+            "buffer_sets": nsets,
+            "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": PEAK_TFLOPS["mfma_f32"],
+                         "unit": "TFLOP/s", "frac": round(tf / PEAK_TFLOPS["mfma_f32"], 4),
+                         "traffic": None, "kernel": "ukst_mfma_f32_kernel x3 + ukst_thin_mfma_kernel",
+                         "us_per_launch": round(per_s * 1e6 / 4, 2), "algorithmic_bytes": nbytes}}
+
+
 def cpu_baseline(w, data, budget_s=2.0):
     """Time the CPU oracle (as it stands) on the headline workload, all host cores.
 
@@ -228,6 +291,9 @@ def main():
             r = measure(w, max(5, min(args.steps, 50)), max(2, min(args.warmup, 5)), warm_seconds=0.3)
             r.pop("_data"); r.pop("_exact_flop")
             per.append(r)
+            torch.cuda.empty_cache()
+        if args.configs == "all":
+            per.append(measure_stack(max(5, min(args.steps, 50))))
             torch.cuda.empty_cache()
 
     line = {

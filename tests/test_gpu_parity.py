@@ -84,6 +84,29 @@ def test_cfg3_dcgan_layers_full_size(name):
     _parity(w, PATHS["auto"], planes=planes, integer=True)
 
 
+def test_cfg3_generator_stack_chained():
+    # the four generator layers back to back on one stream, each fed the previous layer's fp32
+    # output (Table 4 reports such a stack as one total): every layer is checked against the
+    # oracle applied to the very input the GPU consumed, so the per-layer tolerance holds
+    import torch
+    layers = [wl.WORKLOADS[n] for n in ("cfg3_L1", "cfg3_L2", "cfg3_L3", "cfg3_L4")]
+    x = torch.from_numpy(wl.generate(layers[0])["x"]).cuda()
+    ks = [torch.from_numpy(wl.generate(w)["w"]).cuda() for w in layers]
+    outs = []
+    for w, k in zip(layers, ks):              # all four enqueued before anything is read back
+        assert tuple(x.shape) == (w.B, w.Cin, w.H, w.W)
+        x = ukst.ukst_conv_transpose2d(x, k, w.P)
+        outs.append(x)
+    torch.cuda.synchronize()
+    xin = wl.generate(layers[0])["x"]
+    for w, k, y in zip(layers, ks, outs):
+        print(f"stack layer {w.name}", flush=True)
+        planes = _sample_planes(w, 24)
+        y_ref, S = oracle.naive(xin, k.cpu().numpy(), w.P, planes=planes)
+        check_against_oracle(y.cpu().numpy(), y_ref, S, TOL["f32"], planes=planes)
+        xin = y.cpu().numpy()
+
+
 @pytest.mark.parametrize("name", ["cfg4a", "cfg4b", "cfg5a", "cfg5b"])
 def test_cfg45_full_size_sampled_planes(name):
     # the naive oracle is too slow for every plane at these sizes: it computes a seeded sample of
