@@ -240,6 +240,33 @@ def copy_ceiling(nbytes, steps=200):
             "d2d_copy_us": round(s * 1e6, 2)}
 
 
+def mfma_ceiling(dtype_name, seconds=0.3):
+    """Measured ceiling shown next to the published MFMA peak: a register-resident loop of
+    independent MFMAs (no memory traffic), launched until the clocks have settled and then timed
+    with events on the launch stream."""
+    import torch
+    from paper_2502_20493_amd import binding as ukst
+    dt = ukst.UKST_BF16_F32 if dtype_name == "mfma_bf16" else ukst.UKST_F32
+    iters = 20000 if dt == ukst.UKST_BF16_F32 else 10000
+    sink = torch.zeros(64, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+    t_w = time.perf_counter()
+    while time.perf_counter() - t_w < seconds:
+        ukst.ukst_bench_mfma_ceiling(dt, iters, sink, stream)
+        torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps, flop = 5, 0.0
+    e0.record(stream)
+    for _ in range(reps):
+        flop += ukst.ukst_bench_mfma_ceiling(dt, iters, sink, stream)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    if flop <= 0:
+        return None
+    return {"mfma_loop_TFLOPs": round(flop / (e0.elapsed_time(e1) / 1e3) / 1e12, 1),
+            "what": "register-resident loop of independent MFMAs, 8 waves per compute unit"}
+
+
 def measured_traffic(kernel_workload):
     """HBM bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE / WRITE_SIZE,
     each scaled by what the counter reads for a plain copy of known size), or None."""
@@ -283,6 +310,7 @@ def main():
     m["roofline"]["measured_ceiling"] = copy_ceiling(m["roofline"]["algorithmic_bytes"])
 
     per = []
+    ceilings = {}
     if args.configs != "none" and not args.only:
         names = [n for n in wl.WORKLOADS if n not in (HEADLINE, "cfg1_int")] \
             if args.configs == "all" else args.configs.split(",")
@@ -290,6 +318,11 @@ def main():
             w = wl.WORKLOADS[name]
             r = measure(w, max(5, min(args.steps, 50)), max(2, min(args.warmup, 5)), warm_seconds=0.3)
             r.pop("_data"); r.pop("_exact_flop")
+            b = BOUND.get(name, "hbm")
+            if b != "hbm":
+                if b not in ceilings:
+                    ceilings[b] = mfma_ceiling(b)
+                r["roofline"]["measured_ceiling"] = ceilings[b]
             per.append(r)
             torch.cuda.empty_cache()
         if args.configs == "all":

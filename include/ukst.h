@@ -128,6 +128,17 @@ int ukst_conv_transpose2d_path(const void* x, const void* w, void* y, int B, int
 const char* ukst_kernel_name(int B, int Cin, int Cout, int H, int W, int n, int P, int dtype,
                              int path);
 
+/*
+ * Benchmark helper, not part of the operation: enqueues on `stream` one launch of a
+ * register-resident loop of independent MFMAs (dtype UKST_BF16_F32: 32x32x16 bf16, UKST_F32:
+ * 32x32x2 fp32; `iters` rounds of 4 per wave, two blocks of four waves per compute unit) and
+ * returns the floating-point operations that launch performs, or 0 on a bad argument or a failed
+ * launch.  The caller times the launch: the rate is the ceiling the matrix pipes sustain at the
+ * clock the chip settles on, to be printed next to the published peak.  `sink` is a DEVICE
+ * buffer of at least 64 floats that is practically never written.
+ */
+double ukst_bench_mfma_ceiling(int dtype, int iters, void* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

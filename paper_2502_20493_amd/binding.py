@@ -19,7 +19,7 @@ UKST_MAX_N = 7
 # every symbol include/ukst.h declares
 EXPORTS = ["ukst_version", "ukst_status_string", "ukst_output_shape", "ukst_mac_count",
            "ukst_select_path", "ukst_conv_transpose2d", "ukst_conv_transpose2d_path",
-           "ukst_kernel_name"]
+           "ukst_kernel_name", "ukst_bench_mfma_ceiling"]
 
 _lib = None
 
@@ -57,6 +57,8 @@ def lib():
         L.ukst_conv_transpose2d_path.argtypes = [vp, vp, vp] + [i] * 9 + [vp]
         L.ukst_conv_transpose2d_path.restype = i
         L.ukst_kernel_name.argtypes, L.ukst_kernel_name.restype = [i] * 9, ctypes.c_char_p
+        L.ukst_bench_mfma_ceiling.argtypes = [i, i, vp, vp]
+        L.ukst_bench_mfma_ceiling.restype = ctypes.c_double
         _lib = L
     return _lib
 
@@ -93,6 +95,19 @@ def ukst_select_path(B, Cin, Cout, H, W, n, P, dtype) -> int:
 
 def ukst_kernel_name(B, Cin, Cout, H, W, n, P, dtype, path=UKST_PATH_AUTO) -> str:
     return lib().ukst_kernel_name(B, Cin, Cout, H, W, n, P, dtype, path).decode()
+
+
+def ukst_bench_mfma_ceiling(dtype: int, iters: int, sink, stream=None) -> float:
+    """Enqueue the register-resident MFMA loop; returns the FLOPs of that launch (0.0 on failure).
+    sink: float32 device tensor with at least 64 elements."""
+    import torch
+
+    if not (sink.is_cuda and sink.dtype == torch.float32 and sink.numel() >= 64):
+        raise ValueError("sink must be a float32 device tensor with at least 64 elements")
+    if stream is None:
+        stream = torch.cuda.current_stream(sink.device)
+    return float(lib().ukst_bench_mfma_ceiling(int(dtype), int(iters), sink.data_ptr(),
+                                               stream.cuda_stream))
 
 
 def ukst_conv_transpose2d_raw(x_ptr, w_ptr, y_ptr, B, Cin, Cout, H, W, n, P, dtype,
