@@ -54,8 +54,9 @@ def algorithmic_bytes(w, OH, OW):
             + w.B * w.Cout * OH * OW * 4)
 
 
-def measure(w, steps, warmup, rotate_bytes=LLC_BYTES + (64 << 20), warm_seconds=0.0):
-    """Time `steps` launches of workload w.  Returns a dict of rates."""
+def measure(w, steps, warmup, rotate_bytes=LLC_BYTES + (64 << 20), warm_seconds=0.0, fused=False):
+    """Time `steps` launches of workload w.  Returns a dict of rates.  fused: the same launches
+    through ukst_conv_transpose2d_bias_act with a bias vector and ReLU in the store."""
     import torch
     from paper_2502_20493_amd import binding as ukst
     from paper_2502_20493_amd import workloads as wl
@@ -74,11 +75,20 @@ def measure(w, steps, warmup, rotate_bytes=LLC_BYTES + (64 << 20), warm_seconds=
     # arguments are marshalled once (the binding's checks and pointer lookups stay outside the
     # timed loop, which then is one C call per step); the first call goes through the checking
     # binding so that a bad shape fails loudly
-    ukst.ukst_conv_transpose2d(xs[0], k, w.P, y=ys[0], stream=stream)
-    fn = ukst.lib().ukst_conv_transpose2d
     sp = stream.cuda_stream
-    calls = [functools.partial(fn, xs[j].data_ptr(), k.data_ptr(), ys[j].data_ptr(), w.B, w.Cin,
-                               w.Cout, w.H, w.W, w.n, w.P, dt, sp) for j in range(nsets)]
+    if fused:
+        bias = torch.randn(w.Cout, dtype=torch.float32, device="cuda")
+        ukst.ukst_conv_transpose2d_bias_act(xs[0], k, w.P, bias=bias, act=ukst.UKST_ACT_RELU,
+                                            y=ys[0], stream=stream)
+        fn = ukst.lib().ukst_conv_transpose2d_bias_act
+        calls = [functools.partial(fn, xs[j].data_ptr(), k.data_ptr(), bias.data_ptr(),
+                                   ys[j].data_ptr(), w.B, w.Cin, w.Cout, w.H, w.W, w.n, w.P, dt,
+                                   ukst.UKST_ACT_RELU, ukst.UKST_PATH_AUTO, sp) for j in range(nsets)]
+    else:
+        ukst.ukst_conv_transpose2d(xs[0], k, w.P, y=ys[0], stream=stream)
+        fn = ukst.lib().ukst_conv_transpose2d
+        calls = [functools.partial(fn, xs[j].data_ptr(), k.data_ptr(), ys[j].data_ptr(), w.B, w.Cin,
+                                   w.Cout, w.H, w.W, w.n, w.P, dt, sp) for j in range(nsets)]
 
     def step(i):
         if calls[i % nsets]() != 0:
@@ -122,7 +132,9 @@ def measure(w, steps, warmup, rotate_bytes=LLC_BYTES + (64 << 20), warm_seconds=
     roof["us_per_launch"] = round(per_launch_s * 1e6, 2)
     roof["algorithmic_bytes"] = nbytes
     return {
-        "workload": w.name, "shape": f"B{w.B} {w.Cin}->{w.Cout} {w.H}x{w.W} n{w.n} P{w.P} {w.dtype}",
+        "workload": w.name + ("+bias+relu" if fused else ""),
+        "shape": f"B{w.B} {w.Cin}->{w.Cout} {w.H}x{w.W} n{w.n} P{w.P} {w.dtype}"
+                 + (", bias and ReLU fused into the store" if fused else ""),
         "out": f"{OH}x{OW}", "useful_gflops": round(gflops, 1),
         "nominal_gflops": round(nominal / per_launch_s / 1e9, 1),
         "out_gpixels": round(w.B * w.Cout * OH * OW / per_launch_s / 1e9, 3),
@@ -328,6 +340,13 @@ def main():
         if args.configs == "all":
             per.append(measure_stack(max(5, min(args.steps, 50))))
             torch.cuda.empty_cache()
+            # the fused epilogue on the two ends of the range: HBM-bound images, MFMA-bound layer
+            for name in ("cfg2a", "cfg5a"):
+                r = measure(wl.WORKLOADS[name], max(5, min(args.steps, 50)), max(2, min(args.warmup, 5)),
+                            warm_seconds=0.3, fused=True)
+                r.pop("_data"); r.pop("_exact_flop")
+                per.append(r)
+                torch.cuda.empty_cache()
 
     line = {
         "metric": "useful (zero-free) GFLOP/s", "value": m["useful_gflops"], "unit": "GFLOP/s",

@@ -121,6 +121,25 @@ int ukst_conv_transpose2d(const void* x, const void* w, void* y, int B, int Cin,
 int ukst_conv_transpose2d_path(const void* x, const void* w, void* y, int B, int Cin, int Cout,
                                int H, int W, int n, int P, int dtype, int path, void* stream);
 
+typedef enum { UKST_ACT_NONE = 0, UKST_ACT_RELU = 1, UKST_ACT_TANH = 2 } ukst_activation;
+
+/*
+ * The same transpose convolution with the epilogue of a generator layer fused into the store:
+ *     y[b][co] = act( (x (*) w)[b][co] + bias[co] )
+ * so that the output is written once instead of being read and rewritten by an elementwise pass
+ * (the unified kernel of Sec. 3 produces every output element exactly once, which is what makes
+ * the fusion possible; bias and activation themselves are not part of the paper).
+ *   bias  DEVICE pointer to Cout fp32 values, or NULL for none
+ *   act   a ukst_activation (ReLU: max(v, 0); tanh: fp32, absolute error below 1e-6)
+ *   path  as in ukst_conv_transpose2d_path
+ * Everything else, including error behaviour, as ukst_conv_transpose2d; an unknown `act` gives
+ * UKST_ERR_UNSUPPORTED.  With bias == NULL and act == UKST_ACT_NONE the result is bit-identical
+ * to ukst_conv_transpose2d_path.
+ */
+int ukst_conv_transpose2d_bias_act(const void* x, const void* w, const float* bias, void* y, int B,
+                                   int Cin, int Cout, int H, int W, int n, int P, int dtype,
+                                   int act, int path, void* stream);
+
 /*
  * Name of the device kernel the given path launches for this problem, as it appears in a
  * profiler's kernel trace (substring match), or "" on invalid arguments.  Static storage.

@@ -15,11 +15,12 @@ UKST_F32, UKST_BF16_F32 = 0, 1
 UKST_OK, UKST_ERR_NULL, UKST_ERR_SHAPE, UKST_ERR_DTYPE, UKST_ERR_UNSUPPORTED, UKST_ERR_LAUNCH = range(6)
 UKST_PATH_AUTO, UKST_PATH_DIRECT, UKST_PATH_MFMA = 0, 1, 2
 UKST_MAX_N = 7
+UKST_ACT_NONE, UKST_ACT_RELU, UKST_ACT_TANH = 0, 1, 2
 
 # every symbol include/ukst.h declares
 EXPORTS = ["ukst_version", "ukst_status_string", "ukst_output_shape", "ukst_mac_count",
            "ukst_select_path", "ukst_conv_transpose2d", "ukst_conv_transpose2d_path",
-           "ukst_kernel_name", "ukst_bench_mfma_ceiling"]
+           "ukst_kernel_name", "ukst_bench_mfma_ceiling", "ukst_conv_transpose2d_bias_act"]
 
 _lib = None
 
@@ -58,6 +59,8 @@ def lib():
         L.ukst_conv_transpose2d_path.restype = i
         L.ukst_kernel_name.argtypes, L.ukst_kernel_name.restype = [i] * 9, ctypes.c_char_p
         L.ukst_bench_mfma_ceiling.argtypes = [i, i, vp, vp]
+        L.ukst_conv_transpose2d_bias_act.argtypes = [vp, vp, vp, vp] + [i] * 10 + [vp]
+        L.ukst_conv_transpose2d_bias_act.restype = i
         L.ukst_bench_mfma_ceiling.restype = ctypes.c_double
         _lib = L
     return _lib
@@ -117,7 +120,21 @@ def ukst_conv_transpose2d_raw(x_ptr, w_ptr, y_ptr, B, Cin, Cout, H, W, n, P, dty
                                                 dtype, path, stream_ptr))
 
 
-def ukst_conv_transpose2d(x, w, P: int, y=None, path: int = UKST_PATH_AUTO, stream=None):
+def ukst_conv_transpose2d_bias_act(x, w, P: int, bias=None, act: int = UKST_ACT_NONE, y=None,
+                                   path: int = UKST_PATH_AUTO, stream=None):
+    """Marshal torch device tensors into ukst_conv_transpose2d_bias_act:
+    y = act(conv_transpose(x, w) + bias[co]); bias: float32 device tensor [Cout] or None."""
+    import torch
+
+    if bias is not None:
+        if not (bias.is_cuda and bias.dtype == torch.float32 and bias.is_contiguous()
+                and tuple(bias.shape) == (w.shape[0],)):
+            raise ValueError("bias must be a contiguous float32 device tensor [Cout]")
+    return ukst_conv_transpose2d(x, w, P, y=y, path=path, stream=stream, _bias=bias, _act=act)
+
+
+def ukst_conv_transpose2d(x, w, P: int, y=None, path: int = UKST_PATH_AUTO, stream=None,
+                          _bias=None, _act=None):
     """Marshal torch device tensors into ukst_conv_transpose2d.
 
     x: [B,Cin,H,W] float32 or bfloat16, w: [Cout,Cin,n,n] same dtype, both contiguous on the GPU.
@@ -147,6 +164,11 @@ def ukst_conv_transpose2d(x, w, P: int, y=None, path: int = UKST_PATH_AUTO, stre
         stream = torch.cuda.current_stream(x.device)
     sp = stream.cuda_stream if hasattr(stream, "cuda_stream") else stream
     with torch.cuda.device(x.device):
-        _check(ukst_conv_transpose2d_raw(x.data_ptr(), w.data_ptr(), y.data_ptr(), B, Cin, Cout,
-                                         H, W, n, P, dtype, path, sp))
+        if _act is None:
+            _check(ukst_conv_transpose2d_raw(x.data_ptr(), w.data_ptr(), y.data_ptr(), B, Cin, Cout,
+                                             H, W, n, P, dtype, path, sp))
+        else:
+            _check(int(lib().ukst_conv_transpose2d_bias_act(
+                x.data_ptr(), w.data_ptr(), None if _bias is None else _bias.data_ptr(),
+                y.data_ptr(), B, Cin, Cout, H, W, n, P, dtype, int(_act), path, sp)))
     return y

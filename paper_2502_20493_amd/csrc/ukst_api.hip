@@ -105,8 +105,9 @@ int ukst_select_path(int B, int Cin, int Cout, int H, int W, int n, int P, int d
     return resolve_path(ukst::make_geom(B, Cin, Cout, H, W, n, P), dtype, UKST_PATH_AUTO);
 }
 
-int ukst_conv_transpose2d_path(const void* x, const void* w, void* y, int B, int Cin, int Cout,
-                               int H, int W, int n, int P, int dtype, int path, void* stream)
+static int run_checked(const void* x, const void* w, const float* bias, int act, void* y, int B,
+                       int Cin, int Cout, int H, int W, int n, int P, int dtype, int path,
+                       void* stream)
 {
     if (!x || !w || !y) return UKST_ERR_NULL;
     const int st = validate_shape(B, Cin, Cout, H, W, n, P);
@@ -115,11 +116,16 @@ int ukst_conv_transpose2d_path(const void* x, const void* w, void* y, int B, int
     if (n > UKST_MAX_N) return UKST_ERR_UNSUPPORTED;
     if (path != UKST_PATH_AUTO && path != UKST_PATH_DIRECT && path != UKST_PATH_MFMA)
         return UKST_ERR_UNSUPPORTED;
-    const ukst::Geom g = ukst::make_geom(B, Cin, Cout, H, W, n, P);
+    if (act != UKST_ACT_NONE && act != UKST_ACT_RELU && act != UKST_ACT_TANH)
+        return UKST_ERR_UNSUPPORTED;
+    ukst::Geom g = ukst::make_geom(B, Cin, Cout, H, W, n, P);
+    g.ep.bias = bias;
+    g.ep.act = act;
     // element alignment is required of every buffer; the matrix-core kernels move the weights
     // (and bf16 activations) in 16-byte pieces and need those buffers aligned to that
     const uintptr_t esz = dtype == UKST_BF16_F32 ? 2 : 4;
-    if (((uintptr_t)x | (uintptr_t)w) & (esz - 1) || ((uintptr_t)y & 3)) return UKST_ERR_UNSUPPORTED;
+    if (((uintptr_t)x | (uintptr_t)w) & (esz - 1) || ((uintptr_t)y & 3) || ((uintptr_t)bias & 3))
+        return UKST_ERR_UNSUPPORTED;
     int chosen = resolve_path(g, dtype, path);
     const bool x16 = chosen == UKST_PATH_MFMA && ukst::mfma_needs_aligned_x(g, dtype);
     const bool wide_ok = (((uintptr_t)w | (x16 ? (uintptr_t)x : 0)) & 15) == 0;
@@ -131,6 +137,19 @@ int ukst_conv_transpose2d_path(const void* x, const void* w, void* y, int B, int
     else
         e = ukst::launch_direct(g, x, w, (float*)y, dtype, (hipStream_t)stream);
     return e == hipSuccess ? UKST_OK : UKST_ERR_LAUNCH;
+}
+
+int ukst_conv_transpose2d_path(const void* x, const void* w, void* y, int B, int Cin, int Cout,
+                               int H, int W, int n, int P, int dtype, int path, void* stream)
+{
+    return run_checked(x, w, nullptr, UKST_ACT_NONE, y, B, Cin, Cout, H, W, n, P, dtype, path, stream);
+}
+
+int ukst_conv_transpose2d_bias_act(const void* x, const void* w, const float* bias, void* y, int B,
+                                   int Cin, int Cout, int H, int W, int n, int P, int dtype,
+                                   int act, int path, void* stream)
+{
+    return run_checked(x, w, bias, act, y, B, Cin, Cout, H, W, n, P, dtype, path, stream);
 }
 
 int ukst_conv_transpose2d(const void* x, const void* w, void* y, int B, int Cin, int Cout, int H,

@@ -22,8 +22,9 @@ __device__ __forceinline__ float to_f32(uint16_t v) { return __uint_as_float((ui
 template <int N, int CO_BLK, int TW, int TH, int CI_CHUNK, typename TIn>
 __global__ __launch_bounds__(TW* TH) void ukst_direct_kernel(const TIn* __restrict__ x,
                                                             const TIn* __restrict__ w,
-                                                            float* __restrict__ y, Geom g,
-                                                            int tilesX, int tilesY, int coBlocks)
+                                                            float* __restrict__ y, GeomBase g,
+                                                            int tilesX, int tilesY, int coBlocks,
+                                                            Epilogue ep)
 {
     constexpr int HI = (N + 1) / 2;   // window side = ceil(n/2) (Sec. 3.2)
     constexpr int LR = TH + HI - 1;   // staged rows: tile + halo
@@ -98,6 +99,13 @@ __global__ __launch_bounds__(TW* TH) void ukst_direct_kernel(const TIn* __restri
     for (int c = 0; c < CO_BLK; ++c) {
         if (co0 + c >= g.Cout) break;
         float* yp = y + ((size_t)b * g.Cout + co0 + c) * OH * OW;
+        if (has_epilogue(ep)) {  // uniform
+            const float bv = ep.bias ? ep.bias[co0 + c] : 0.f;
+#pragma unroll
+            for (int r = 0; r < 2; ++r)
+#pragma unroll
+                for (int sc = 0; sc < 2; ++sc) acc[c][r][sc] = epilogue(acc[c][r][sc], bv, ep.act);
+        }
         if (vy1) {
             float* row = yp + (size_t)oy1 * OW;
             if (vx1) row[ox1] = acc[c][1][1];
@@ -120,8 +128,8 @@ hipError_t launch_one(const Geom& g, const void* x, const void* w, float* y, hip
     const long long nb = (long long)tilesX * tilesY * coBlocks * g.B;
     if (nb > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     hipLaunchKernelGGL((ukst_direct_kernel<N, CO_BLK, TW, TH, CI_CHUNK, TIn>), dim3((unsigned)nb),
-                       dim3(TW * TH), 0, stream, (const TIn*)x, (const TIn*)w, y, g, tilesX,
-                       tilesY, coBlocks);
+                       dim3(TW * TH), 0, stream, (const TIn*)x, (const TIn*)w, y, (GeomBase)g, tilesX,
+                       tilesY, coBlocks, g.ep);
     return hipGetLastError();
 }
 

@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace ukst {
 
@@ -15,12 +16,59 @@ namespace ukst {
 // Class (r, s) uses the taps w[r + 2u][s + 2v] of that window (Eqs. 1-4), so across the quad
 // every one of the n*n taps is used exactly once.  Members that fall outside the output (first /
 // last row or column of an odd-sized output) are predicated off, never stored.
-struct Geom {
+// Optional fused epilogue, applied to the finished sum on its way to memory:
+// y = act(sum + bias[co]); bias == nullptr means no bias, act 0 none, 1 ReLU, 2 tanh.
+struct Epilogue {
+    const float* bias;
+    int act;
+};
+
+// The part of the geometry the kernels take as their argument.
+struct GeomBase {
     int B, Cin, Cout, H, W, n, P;
     int OH, OW;
     int k_min, m_min;  // first quad row / column that owns an in-range output
     int KH, KW;        // number of quad rows / columns
 };
+
+// Host side: geometry plus the epilogue of this call.  Kernels receive the epilogue as their LAST
+// argument (or last member of their argument block), so that the argument layout, and with it
+// the code, of the instances that do not use it stays what it is without one.
+struct Geom : GeomBase {
+    Epilogue ep;
+};
+
+// true if the stores have anything to apply (uniform over the launch)
+__host__ __device__ inline bool has_epilogue(const Epilogue& e) { return e.bias != nullptr || e.act != 0; }
+
+// tanh(v) = 1 - 2 / (exp(2v) + 1): saturates to +-1 without overflow trouble (exp -> inf gives 1,
+// exp -> 0 gives -1); hardware exp2 and reciprocal, absolute error of a few 1e-7
+__device__ __forceinline__ float fast_tanh(float v)
+{
+    const float e = __builtin_amdgcn_exp2f(v * 2.8853900817779268f);  // exp(2v) = 2^(2v log2 e)
+    return fmaf(-2.f, __builtin_amdgcn_rcpf(e + 1.f), 1.f);
+}
+// activation known at compile time (kernels with long drains branch once, outside their loops)
+template <int ACT>
+__device__ __forceinline__ float epilogue_t(float v, float b)
+{
+    v += b;
+    if constexpr (ACT == 1) v = fmaxf(v, 0.f);
+    if constexpr (ACT == 2) v = fast_tanh(v);
+    return v;
+}
+__device__ __forceinline__ float epilogue(float v, float b, int act)
+{
+    return act == 1 ? epilogue_t<1>(v, b) : act == 2 ? epilogue_t<2>(v, b) : epilogue_t<0>(v, b);
+}
+// calls f(integral_constant<int, act>) for the run-time activation code (uniform branch)
+template <class F>
+__device__ __forceinline__ void with_activation(int act, F&& f)
+{
+    if (act == 1) f(std::integral_constant<int, 1>{});
+    else if (act == 2) f(std::integral_constant<int, 2>{});
+    else f(std::integral_constant<int, 0>{});
+}
 
 inline Geom make_geom(int B, int Cin, int Cout, int H, int W, int n, int P)
 {
@@ -32,6 +80,8 @@ inline Geom make_geom(int B, int Cin, int Cout, int H, int W, int n, int P)
     g.m_min = (P + 1) >> 1;
     g.KH = ((P + g.OH - 1 + 1) >> 1) - g.k_min + 1;  // largest k: ceil((P+OH-1)/2)
     g.KW = ((P + g.OW - 1 + 1) >> 1) - g.m_min + 1;
+    g.ep.bias = nullptr;
+    g.ep.act = 0;
     return g;
 }
 

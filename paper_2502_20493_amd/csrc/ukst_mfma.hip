@@ -65,7 +65,7 @@ __device__ __forceinline__ int fdiv(int n, const FastDiv& f)
 }
 
 struct MfmaArgs {
-    Geom g;
+    GeomBase g;
     int Q;        // total quads = B * KH * KW
     int EH;       // distinct input rows one image's quad rows touch = KH + ceil(n/2) - 1
     int ROWS;     // input rows an activation stage buffer holds
@@ -92,10 +92,12 @@ __device__ __forceinline__ u4v transposed_row(const u4v (&in)[8], int k)
     return t;
 }
 
-template <int N>
+// EPI: the fused epilogue (bias, activation) is compiled into the drain; the plain instance keeps
+// the register allocation of its drain to itself.
+template <int N, bool EPI>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w,
-                           float* __restrict__ y, MfmaArgs a)
+                           float* __restrict__ y, MfmaArgs a, Epilogue ep)
 {
     static_assert(N == 4, "bf16 MFMA path: in-register sub-kernel gather is written for n = 4");
     constexpr int HI = (N + 1) / 2;
@@ -105,7 +107,7 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
     // layout: weights stage 0, weights stage 1, activations stage 0, activations stage 1
     constexpr int XS_OFF = 2 * WS_STAGE;
 
-    const Geom& g = a.g;
+    const GeomBase& g = a.g;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -366,24 +368,36 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
         }
         // channel outermost, quad tiles innermost: the four stores of an inner loop write one
         // contiguous run of an output row
+        auto drain = [&](auto act_tag) {
+            constexpr int ACT = decltype(act_tag)::value;  // -1: no epilogue at all
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const unsigned soff = (unsigned)(8 * (i / 4) + (i % 4)) * plane;
+            for (int i = 0; i < 16; ++i) {
+                const unsigned soff = (unsigned)(8 * (i / 4) + (i % 4)) * plane;
+                float bv = 0.f;
+                if constexpr (ACT >= 0)
+                    if (ep.bias) bv = ep.bias[co0 + cw * 32 + 8 * (i / 4) + 4 * gk + (i % 4)];
 #pragma unroll
-            for (int r = 1; r >= 0; --r)
+                for (int r = 1; r >= 0; --r)
 #pragma unroll
-                for (int nt = 0; nt < 4; ++nt) {
-                    u2v d;
-                    const float v1 = acc[nt][r][1][i], v0 = acc[nt][r][0][i];  // by value, then bits
-                    d.x = __float_as_uint(v1);
-                    d.y = __float_as_uint(v0);
-                    __builtin_amdgcn_raw_buffer_store_b64(d, rs_y, off_pair[nt][r], soff, 0);
-                    if (any_edge[nt][r]) {
-                        __builtin_amdgcn_raw_buffer_store_b32(d.x, rs_y, off_s1[nt][r], soff, 0);
-                        __builtin_amdgcn_raw_buffer_store_b32(d.y, rs_y, off_s0[nt][r], soff, 0);
+                    for (int nt = 0; nt < 4; ++nt) {
+                        u2v d;
+                        float v1 = acc[nt][r][1][i], v0 = acc[nt][r][0][i];  // by value, then bits
+                        if constexpr (ACT >= 0) {
+                            v1 = epilogue_t<ACT>(v1, bv);
+                            v0 = epilogue_t<ACT>(v0, bv);
+                        }
+                        d.x = __float_as_uint(v1);
+                        d.y = __float_as_uint(v0);
+                        __builtin_amdgcn_raw_buffer_store_b64(d, rs_y, off_pair[nt][r], soff, 0);
+                        if (any_edge[nt][r]) {
+                            __builtin_amdgcn_raw_buffer_store_b32(d.x, rs_y, off_s1[nt][r], soff, 0);
+                            __builtin_amdgcn_raw_buffer_store_b32(d.y, rs_y, off_s0[nt][r], soff, 0);
+                        }
                     }
-                }
-        }
+            }
+        };
+        if constexpr (EPI) with_activation(ep.act, drain);  // one uniform branch per tile
+        else drain(std::integral_constant<int, -1>{});
         have = have_n; cb = cb_n; qt = qt_n; wv_c = wv_n; xv_c = xv_n;
     }
 }
@@ -459,8 +473,10 @@ hipError_t launch_mfma(const Geom& g, const void* x, const void* w, float* y, in
     const size_t lds = 2 * (size_t)(2 * W_HALF) + 2 * (size_t)XS_STAGE_MAX;
     // more than 64 KiB of dynamic LDS has to be allowed per device (a property of the loaded
     // kernel, not library state); cheap enough to repeat on every call
-    hipError_t e = hipFuncSetAttribute((const void*)ukst_mfma_bf16_kernel<N>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    const bool epi = has_epilogue(g.ep);
+    const void* kfn = epi ? (const void*)ukst_mfma_bf16_kernel<N, true>
+                          : (const void*)ukst_mfma_bf16_kernel<N, false>;
+    hipError_t e = hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     // persistent blocks: one per compute unit (a multiple of the 8 XCDs), never more than tiles
     int dev = 0, cus = 0;
@@ -479,8 +495,12 @@ hipError_t launch_mfma(const Geom& g, const void* x, const void* w, float* y, in
         const int fewer = (((a.ntiles + rounds - 1) / rounds + 7) / 8) * 8;
         if (fewer < grid) grid = fewer;
     }
-    hipLaunchKernelGGL((ukst_mfma_bf16_kernel<N>), dim3((unsigned)grid), dim3(256), lds, stream,
-                       (const uint16_t*)x, (const uint16_t*)w, y, a);
+    if (epi)
+        hipLaunchKernelGGL((ukst_mfma_bf16_kernel<N, true>), dim3((unsigned)grid), dim3(256), lds,
+                           stream, (const uint16_t*)x, (const uint16_t*)w, y, a, g.ep);
+    else
+        hipLaunchKernelGGL((ukst_mfma_bf16_kernel<N, false>), dim3((unsigned)grid), dim3(256), lds,
+                           stream, (const uint16_t*)x, (const uint16_t*)w, y, a, g.ep);
     return hipGetLastError();
 }
 

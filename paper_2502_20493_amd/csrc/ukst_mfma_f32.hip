@@ -55,7 +55,7 @@ __device__ __forceinline__ int fdiv(int n, const FastDiv& f)
 }
 
 struct F32Args {
-    Geom g;
+    GeomBase g;
     int Q;       // total quads = B * KH * KW
     int EH;      // input rows one image's quad rows touch = KH + ceil(n/2) - 1
     int ROWS;    // input rows an activation stage holds
@@ -80,10 +80,12 @@ __device__ __forceinline__ int xcd_contiguous(int bid, int nb)
 
 // Narrow tiles (NW < 4) keep few accumulators, so two blocks may share a compute unit and cover
 // each other's staging latency; the widest tile needs the whole register file.
-template <int N, int NW, int KC>
+// EPI: the fused epilogue (bias, activation) is compiled into the drain; the plain instance keeps
+// the register allocation and schedule of its drain to itself.
+template <int N, int NW, int KC, bool EPI>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, NW == 4 ? 1 : 2)))
 void ukst_mfma_f32_kernel(const float* __restrict__ x, const float* __restrict__ w,
-                          float* __restrict__ y, F32Args a)
+                          float* __restrict__ y, F32Args a, Epilogue ep)
 {
     constexpr int HI = (N + 1) / 2;
     constexpr int NN = N * N;
@@ -96,7 +98,7 @@ void ukst_mfma_f32_kernel(const float* __restrict__ x, const float* __restrict__
     // layout: weights stage 0 | weights stage 1 | activations stage 0 | activations stage 1
     constexpr int XS_OFF = 2 * WS_STAGE;
 
-    const Geom& g = a.g;
+    const GeomBase& g = a.g;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -281,51 +283,71 @@ void ukst_mfma_f32_kernel(const float* __restrict__ x, const float* __restrict__
     const unsigned plane = (unsigned)(g.OH * g.OW * 4);
     // Cout is a multiple of 8, so a group of 8 channels (4 per k parity) exists or not as a whole
     const int co_w = co0 + cw * 32;  // first channel of this wave
+    // fused epilogue (whole sums only: with a split K loop the slice sum applies it instead)
+    float bias_i[16];
+    if constexpr (EPI) {
 #pragma unroll
-    for (int nt = 0; nt < NW; ++nt) {
-        const int q = q0 + (qh * NW + nt) * 32 + l32;
-        const bool qv = q <= q_last;
-        const int qq = qv ? q : q_last;
-        const int b = fdiv(qq, a.dKHW);
-        const int rem = qq - b * KHW;
-        const int kk = fdiv(rem, a.dKW), mm = rem - kk * g.KW;
-        const int k = g.k_min + kk, m = g.m_min + mm;
-        const int oy1 = 2 * k - 1 - g.P, ox1 = 2 * m - 1 - g.P;  // row / column of class 1
-        const bool vcol1 = ox1 >= 0 && ox1 < g.OW, vcol0 = ox1 + 1 < g.OW;
-        // byte offset of (channel co_w + 4*gk, row oy1, column ox1); unsigned wrap-around keeps
-        // the arithmetic right when oy1 or ox1 is -1 and only the other class exists
-        const unsigned y_off =
-            (unsigned)((((b * g.Cout + co_w + 4 * gk) * g.OH + oy1) * g.OW + ox1) * 4);
-#pragma unroll
-        for (int r = 1; r >= 0; --r) {
-            const bool vrow = qv && (r ? (oy1 >= 0 && oy1 < g.OH) : (oy1 + 1 < g.OH));
-            const unsigned base = y_off + (r ? 0u : (unsigned)(g.OW * 4));
-            // interior quads store both column classes as one 8-byte element; a quad on the left
-            // or right edge of an odd-sized output has one class only and stores 4 bytes
-            const unsigned off_pair = (vrow && vcol1 && vcol0) ? base : kInvalid;
-            const bool only1 = vrow && vcol1 && !vcol0, only0 = vrow && !vcol1 && vcol0;
-            const unsigned off_edge = only1 ? base : (only0 ? base + 4u : kInvalid);
-            const bool any_edge = __builtin_amdgcn_ballot_w64(only1 || only0) != 0;  // uniform
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                if (co_w + 8 * (i / 4) >= g.Cout) continue;  // uniform: ragged last channel block
-                const unsigned soff = (unsigned)(8 * (i / 4) + (i % 4)) * plane;
-                const float v1 = acc[nt][r][1][i], v0 = acc[nt][r][0][i];  // by value, then bits
-                u2v d;
-                d.x = __float_as_uint(v1);
-                d.y = __float_as_uint(v0);
-                __builtin_amdgcn_raw_buffer_store_b64(d, rs_y, off_pair, soff, 0);
-                if (any_edge)
-                    __builtin_amdgcn_raw_buffer_store_b32(only1 ? d.x : d.y, rs_y, off_edge, soff, 0);
-            }
+        for (int i = 0; i < 16; ++i) {
+            const int ch = co_w + 8 * (i / 4) + 4 * gk + (i % 4);
+            bias_i[i] = (ep.bias && ch < g.Cout) ? ep.bias[ch] : 0.f;
         }
     }
+    auto drain = [&](auto act_tag) {
+        constexpr int ACT = decltype(act_tag)::value;  // -1: no epilogue at all
+#pragma unroll
+        for (int nt = 0; nt < NW; ++nt) {
+            const int q = q0 + (qh * NW + nt) * 32 + l32;
+            const bool qv = q <= q_last;
+            const int qq = qv ? q : q_last;
+            const int b = fdiv(qq, a.dKHW);
+            const int rem = qq - b * KHW;
+            const int kk = fdiv(rem, a.dKW), mm = rem - kk * g.KW;
+            const int k = g.k_min + kk, m = g.m_min + mm;
+            const int oy1 = 2 * k - 1 - g.P, ox1 = 2 * m - 1 - g.P;  // row / column of class 1
+            const bool vcol1 = ox1 >= 0 && ox1 < g.OW, vcol0 = ox1 + 1 < g.OW;
+            // byte offset of (channel co_w + 4*gk, row oy1, column ox1); unsigned wrap-around keeps
+            // the arithmetic right when oy1 or ox1 is -1 and only the other class exists
+            const unsigned y_off =
+                (unsigned)((((b * g.Cout + co_w + 4 * gk) * g.OH + oy1) * g.OW + ox1) * 4);
+#pragma unroll
+            for (int r = 1; r >= 0; --r) {
+                const bool vrow = qv && (r ? (oy1 >= 0 && oy1 < g.OH) : (oy1 + 1 < g.OH));
+                const unsigned base = y_off + (r ? 0u : (unsigned)(g.OW * 4));
+                // interior quads store both column classes as one 8-byte element; a quad on the left
+                // or right edge of an odd-sized output has one class only and stores 4 bytes
+                const unsigned off_pair = (vrow && vcol1 && vcol0) ? base : kInvalid;
+                const bool only1 = vrow && vcol1 && !vcol0, only0 = vrow && !vcol1 && vcol0;
+                const unsigned off_edge = only1 ? base : (only0 ? base + 4u : kInvalid);
+                const bool any_edge = __builtin_amdgcn_ballot_w64(only1 || only0) != 0;  // uniform
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    if (co_w + 8 * (i / 4) >= g.Cout) continue;  // uniform: ragged last channel block
+                    const unsigned soff = (unsigned)(8 * (i / 4) + (i % 4)) * plane;
+                    float v1 = acc[nt][r][1][i], v0 = acc[nt][r][0][i];  // by value, then bits
+                    if constexpr (ACT >= 0) {
+                        v1 = epilogue_t<ACT>(v1, bias_i[i]);
+                        v0 = epilogue_t<ACT>(v0, bias_i[i]);
+                    }
+                    u2v d;
+                    d.x = __float_as_uint(v1);
+                    d.y = __float_as_uint(v0);
+                    __builtin_amdgcn_raw_buffer_store_b64(d, rs_y, off_pair, soff, 0);
+                    if (any_edge)
+                        __builtin_amdgcn_raw_buffer_store_b32(only1 ? d.x : d.y, rs_y, off_edge, soff, 0);
+                }
+            }
+        }
+    };
+    if constexpr (EPI) with_activation(ep.act, drain);  // one uniform branch per block
+    else drain(std::integral_constant<int, -1>{});
 }
 
-// y[i] = part[0][i] + part[1][i] + ... in this order, four floats per thread
+// y[i] = part[0][i] + part[1][i] + ... in this order, four floats per thread; the fused epilogue
+// (bias of the element's channel, activation) is applied to the finished sums
 __global__ __launch_bounds__(256) void ukst_sum_slices_kernel(const float4* __restrict__ part,
                                                               float4* __restrict__ y, int n4,
-                                                              int ksplit)
+                                                              int ksplit, const float* __restrict__ bias,
+                                                              int act, unsigned plane, unsigned cout)
 {
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= n4) return;
@@ -333,6 +355,16 @@ __global__ __launch_bounds__(256) void ukst_sum_slices_kernel(const float4* __re
     for (int k = 1; k < ksplit; ++k) {
         const float4 p = part[(size_t)k * n4 + i];
         s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
+    }
+    if (bias != nullptr || act != 0) {  // uniform
+        float v[4] = {s.x, s.y, s.z, s.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const unsigned idx = 4u * (unsigned)i + e;  // element of y[B][Cout][plane]
+            const float bv = bias ? bias[(idx / plane) % cout] : 0.f;
+            v[e] = epilogue(v[e], bv, act);
+        }
+        s = make_float4(v[0], v[1], v[2], v[3]);
     }
     y[i] = s;
 }
@@ -403,44 +435,54 @@ bool make_args(const Geom& g, F32Args& a)
 }
 
 template <int N, int NW>
-hipError_t launch_t(const F32Args& a, const float* x, const float* w, float* y, hipStream_t stream)
+hipError_t launch_t(const F32Args& a, const Epilogue& ep, const float* x, const float* w, float* y,
+                    hipStream_t stream)
 {
     constexpr int KC = kc_for(N);
     const size_t lds = 2 * (size_t)(N * N * KC * PW * 4 + a.xs_stage_bytes);
     // more than 64 KiB of dynamic LDS has to be allowed per device (a property of the loaded
     // kernel, not library state); cheap enough to repeat on every call
-    hipError_t e = hipFuncSetAttribute((const void*)ukst_mfma_f32_kernel<N, NW, KC>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    // the epilogue belongs to whole sums: with a split K loop the slice sum applies it
+    const bool epi = a.ksplit == 1 && has_epilogue(ep);
+    const void* kfn = epi ? (const void*)ukst_mfma_f32_kernel<N, NW, KC, true>
+                          : (const void*)ukst_mfma_f32_kernel<N, NW, KC, false>;
+    hipError_t e = hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     const unsigned nblocks = (unsigned)(a.nco * a.nqt * a.ksplit);
     if (a.ksplit == 1) {
-        hipLaunchKernelGGL((ukst_mfma_f32_kernel<N, NW, KC>), dim3(nblocks), dim3(256), lds, stream,
-                           x, w, y, a);
+        if (epi)
+            hipLaunchKernelGGL((ukst_mfma_f32_kernel<N, NW, KC, true>), dim3(nblocks), dim3(256), lds,
+                               stream, x, w, y, a, ep);
+        else
+            hipLaunchKernelGGL((ukst_mfma_f32_kernel<N, NW, KC, false>), dim3(nblocks), dim3(256), lds,
+                               stream, x, w, y, a, ep);
         return hipGetLastError();
     }
     // partial outputs live in stream-ordered scratch memory for the duration of this call
-    const Geom& g = a.g;
+    const GeomBase& g = a.g;
     const size_t ybytes = (size_t)g.B * g.Cout * g.OH * g.OW * 4;
     void* part = nullptr;
     if ((e = hipMallocAsync(&part, ybytes * a.ksplit, stream)) != hipSuccess) return e;
-    hipLaunchKernelGGL((ukst_mfma_f32_kernel<N, NW, KC>), dim3(nblocks), dim3(256), lds, stream, x, w,
-                       (float*)part, a);
+    hipLaunchKernelGGL((ukst_mfma_f32_kernel<N, NW, KC, false>), dim3(nblocks), dim3(256), lds, stream,
+                       x, w, (float*)part, a, ep);
     const int n4 = (int)(ybytes / 16);
     hipLaunchKernelGGL(ukst_sum_slices_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0,
-                       stream, (const float4*)part, (float4*)y, n4, a.ksplit);
+                       stream, (const float4*)part, (float4*)y, n4, a.ksplit, ep.bias, ep.act,
+                       (unsigned)(g.OH * g.OW), (unsigned)g.Cout);
     e = hipGetLastError();
     const hipError_t ef = hipFreeAsync(part, stream);
     return e != hipSuccess ? e : ef;
 }
 
 template <int NW>
-hipError_t launch_n(const F32Args& a, const float* x, const float* w, float* y, hipStream_t st)
+hipError_t launch_n(const F32Args& a, const Epilogue& ep, const float* x, const float* w, float* y,
+                    hipStream_t st)
 {
     switch (a.g.n) {
-        case 2: return launch_t<2, NW>(a, x, w, y, st);
-        case 3: return launch_t<3, NW>(a, x, w, y, st);
-        case 4: return launch_t<4, NW>(a, x, w, y, st);
-        case 5: return launch_t<5, NW>(a, x, w, y, st);
+        case 2: return launch_t<2, NW>(a, ep, x, w, y, st);
+        case 3: return launch_t<3, NW>(a, ep, x, w, y, st);
+        case 4: return launch_t<4, NW>(a, ep, x, w, y, st);
+        case 5: return launch_t<5, NW>(a, ep, x, w, y, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -480,9 +522,9 @@ hipError_t launch_mfma_f32(const Geom& g, const void* x, const void* w, float* y
     const float* xf = (const float*)x;
     const float* wf = (const float*)w;
     switch (nw) {
-        case 4: return launch_n<4>(a, xf, wf, y, stream);
-        case 2: return launch_n<2>(a, xf, wf, y, stream);
-        case 1: return launch_n<1>(a, xf, wf, y, stream);
+        case 4: return launch_n<4>(a, g.ep, xf, wf, y, stream);
+        case 2: return launch_n<2>(a, g.ep, xf, wf, y, stream);
+        case 1: return launch_n<1>(a, g.ep, xf, wf, y, stream);
         default: return hipErrorInvalidValue;
     }
 }

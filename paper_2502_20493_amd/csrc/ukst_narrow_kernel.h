@@ -39,11 +39,14 @@ __device__ __forceinline__ int xcd_contiguous(int bid, int nb)
 
 __device__ __forceinline__ unsigned fbits(float f) { return __builtin_bit_cast(unsigned, f); }
 
-template <int N, int CI, int CO, int QH, bool PE>
+// EPI: the fused epilogue (bias, activation) is compiled in between the sums and the stores; the
+// plain instances keep sums and stores in one block of straight-line code.
+template <int N, int CI, int CO, int QH, bool PE, bool EPI>
 __global__ __launch_bounds__(256) void ukst_narrow_kernel(const float* __restrict__ x,
                                                          const float* __restrict__ w,
-                                                         float* __restrict__ y, Geom g,
-                                                         int strips, int bands, int nwork)
+                                                         float* __restrict__ y, GeomBase g,
+                                                         int strips, int bands, int nwork,
+                                                         Epilogue ep)
 {
     constexpr int HI = (N + 1) / 2;  // taps of even parity along one axis, ceil(n/2)
     constexpr int LO = N / 2;        // taps of odd parity, floor(n/2)
@@ -168,6 +171,15 @@ __global__ __launch_bounds__(256) void ukst_narrow_kernel(const float* __restric
                             }
             }
 
+            if constexpr (EPI) {
+                const float bv = ep.bias ? ep.bias[co] : 0.f;
+#pragma unroll
+                for (int qy = 0; qy < QH; ++qy)
+#pragma unroll
+                    for (int r = 0; r < 2; ++r)
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) acc[qy][r][c] = epilogue(acc[qy][r][c], bv, ep.act);
+            }
 #pragma unroll
             for (int qy = 0; qy < QH; ++qy)
 #pragma unroll
@@ -223,8 +235,17 @@ hipError_t launch_q(const Geom& g, const float* x, const float* w, float* y, hip
     const int bands = (g.KH + QH - 1) / QH;                 // QH quad rows each
     const long long nwork = (long long)strips * bands * g.B;
     if (nwork > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL((ukst_narrow_kernel<N, CI, CO, QH, PE>), dim3((unsigned)((nwork + 3) / 4)),
-                       dim3(256), 0, stream, x, w, y, g, strips, bands, (int)nwork);
+    // the instances with an epilogue exist for QH = 2 only (see launch_t)
+    if constexpr (QH == 2) {
+        if (has_epilogue(g.ep)) {
+            hipLaunchKernelGGL((ukst_narrow_kernel<N, CI, CO, QH, PE, true>),
+                               dim3((unsigned)((nwork + 3) / 4)), dim3(256), 0, stream, x, w, y,
+                               (GeomBase)g, strips, bands, (int)nwork, g.ep);
+            return hipGetLastError();
+        }
+    }
+    hipLaunchKernelGGL((ukst_narrow_kernel<N, CI, CO, QH, PE, false>), dim3((unsigned)((nwork + 3) / 4)),
+                       dim3(256), 0, stream, x, w, y, (GeomBase)g, strips, bands, (int)nwork, g.ep);
     return hipGetLastError();
 }
 
@@ -236,7 +257,7 @@ hipError_t launch_t(const Geom& g, const float* x, const float* w, float* y, hip
     // lanes already carry more multiplications per output), and 4 only pay off while there are
     // still enough waves to cover the chip (256 CUs x 4 SIMDs).
     const long long waves4 = (long long)((g.OW + 255) / 256) * ((g.KH + 3) / 4) * g.B;
-    if (N <= 3 && waves4 >= 1024) return launch_q<N, CI, CO, 4, PE>(g, x, w, y, stream);
+    if (N <= 3 && waves4 >= 1024 && !has_epilogue(g.ep)) return launch_q<N, CI, CO, 4, PE>(g, x, w, y, stream);
     return launch_q<N, CI, CO, 2, PE>(g, x, w, y, stream);
 }
 

@@ -37,8 +37,9 @@ __device__ __forceinline__ unsigned fbits(float f) { return __builtin_bit_cast(u
 template <int N, int CO, int QH, bool PE>
 __global__ __launch_bounds__(256) void ukst_thin_kernel(const float* __restrict__ x,
                                                        const float* __restrict__ w,
-                                                       float* __restrict__ y, Geom g, int lwlog,
-                                                       int strips, int bgroups, int nblocks)
+                                                       float* __restrict__ y, GeomBase g, int lwlog,
+                                                       int strips, int bgroups, int nblocks,
+                                                       Epilogue ep)
 {
     constexpr int HI = (N + 1) / 2;  // taps of even parity along one axis, ceil(n/2)
     constexpr int LO = N / 2;        // taps of odd parity, floor(n/2)
@@ -223,6 +224,20 @@ __global__ __launch_bounds__(256) void ukst_thin_kernel(const float* __restrict_
                     }
     }
 
+    if (has_epilogue(ep)) {  // uniform
+#pragma unroll
+        for (int co = 0; co < CO; ++co) {
+            const float bv = ep.bias ? ep.bias[co] : 0.f;
+#pragma unroll
+            for (int qy = 0; qy < QH; ++qy)
+#pragma unroll
+                for (int r = 0; r < 2; ++r)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        acc[co][qy][r][c] = epilogue(acc[co][qy][r][c], bv, ep.act);
+        }
+    }
+
     float* yb = y + (size_t)b * CO * OH * OW;
     const unsigned yrow = (unsigned)OW * 4u, yplane = (unsigned)OH * yrow;
     const __amdgpu_buffer_rsrc_t rs_y = __builtin_amdgcn_make_buffer_rsrc(
@@ -267,7 +282,7 @@ hipError_t launch_q(const Geom& g, const float* x, const float* w, float* y, hip
     if (nblocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     const size_t lds = ((size_t)g.Cin * CO * NNP + 3 * (size_t)(CO * QH * 8) * 64) * sizeof(float);
     hipLaunchKernelGGL((ukst_thin_kernel<N, CO, QH, PE>), dim3((unsigned)nblocks), dim3(256), lds,
-                       stream, x, w, y, g, lwlog, strips, bgroups, (int)nblocks);
+                       stream, x, w, y, (GeomBase)g, lwlog, strips, bgroups, (int)nblocks, g.ep);
     return hipGetLastError();
 }
 

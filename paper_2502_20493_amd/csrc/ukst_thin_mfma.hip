@@ -67,7 +67,7 @@ __device__ __forceinline__ int fdiv(int n, const FastDiv& f)
 }
 
 struct ThinMfmaArgs {
-    Geom g;
+    GeomBase g;
     int Q;      // total quads = B * KH * KW
     int EH;     // input rows one image's quad rows touch = KH + 1
     int ROWS;   // input rows a stage holds
@@ -89,10 +89,12 @@ __device__ __forceinline__ int xcd_contiguous(int bid, int nb)
     return xcd * fl + (xcd < rem ? xcd : rem) + idx;
 }
 
-template <int N, int MT>
+// EPI: the fused epilogue (bias, activation) is compiled into the drain.
+template <int N, int MT, bool EPI>
 __global__ __launch_bounds__(256) void ukst_thin_mfma_kernel(const float* __restrict__ x,
                                                             const float* __restrict__ w,
-                                                            float* __restrict__ y, ThinMfmaArgs a)
+                                                            float* __restrict__ y, ThinMfmaArgs a,
+                                                            Epilogue ep)
 {
     static_assert(N == 3 || N == 4, "2 x 2 window: the four K values of one MFMA");
     constexpr int NN = N * N;
@@ -101,7 +103,7 @@ __global__ __launch_bounds__(256) void ukst_thin_mfma_kernel(const float* __rest
     float* const xl = lds;               // activations [KCH][ROWS][LW]
     float* const wl = lds + KCH * a.XP;  // B slice [KCH][window position][column (co, r, s)]
 
-    const Geom& g = a.g;
+    const GeomBase& g = a.g;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -239,6 +241,9 @@ __global__ __launch_bounds__(256) void ukst_thin_mfma_kernel(const float* __rest
     // ---- drain: lane holds column j = (co, r, s) for quads 4*(lane/16) .. +3 of each tile
     const int co = i16 >> 2, r = (i16 >> 1) & 1;
     const bool s1 = (i16 & 1) != 0;  // class s = 1 is the left column of the pair
+    float bv = 0.f;
+    if constexpr (EPI)
+        if (ep.bias && co < g.Cout) bv = ep.bias[co];
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
         float own[4], par[4];
@@ -252,8 +257,12 @@ __global__ __launch_bounds__(256) void ukst_thin_mfma_kernel(const float* __rest
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             // an s = 1 lane writes quads 0, 1 of its four, its s = 0 neighbour quads 2, 3
-            const float left = s1 ? own[h] : par[2 + h];
-            const float right = s1 ? par[h] : own[2 + h];
+            float left = s1 ? own[h] : par[2 + h];
+            float right = s1 ? par[h] : own[2 + h];
+            if constexpr (EPI) {
+                left = epilogue(left, bv, ep.act);
+                right = epilogue(right, bv, ep.act);
+            }
             const int q = q0 + (wave * MT + t) * 16 + 4 * kk + (s1 ? h : 2 + h);
             const bool ok = q < a.Q && co < g.Cout;
             const int qq = q < a.Q ? q : q_last;
@@ -329,22 +338,27 @@ int pick_mt(const Geom& g, ThinMfmaArgs& a)
 }
 
 template <int N, int MT>
-hipError_t launch_t(const ThinMfmaArgs& a, const float* x, const float* w, float* y, hipStream_t stream)
+hipError_t launch_t(const ThinMfmaArgs& a, const Epilogue& ep, const float* x, const float* w, float* y,
+                    hipStream_t stream)
 {
     const size_t lds = (size_t)(KCH * a.XP + KCH * 64) * 4;
-    hipLaunchKernelGGL((ukst_thin_mfma_kernel<N, MT>), dim3((unsigned)a.nqt), dim3(256), lds, stream,
-                       x, w, y, a);
+    if (has_epilogue(ep))
+        hipLaunchKernelGGL((ukst_thin_mfma_kernel<N, MT, true>), dim3((unsigned)a.nqt), dim3(256), lds,
+                           stream, x, w, y, a, ep);
+    else
+        hipLaunchKernelGGL((ukst_thin_mfma_kernel<N, MT, false>), dim3((unsigned)a.nqt), dim3(256), lds,
+                           stream, x, w, y, a, ep);
     return hipGetLastError();
 }
 
 template <int N>
-hipError_t launch_n(int mt, const ThinMfmaArgs& a, const float* x, const float* w, float* y,
-                    hipStream_t stream)
+hipError_t launch_n(int mt, const ThinMfmaArgs& a, const Epilogue& ep, const float* x, const float* w,
+                    float* y, hipStream_t stream)
 {
     switch (mt) {
-        case 4: return launch_t<N, 4>(a, x, w, y, stream);
-        case 2: return launch_t<N, 2>(a, x, w, y, stream);
-        case 1: return launch_t<N, 1>(a, x, w, y, stream);
+        case 4: return launch_t<N, 4>(a, ep, x, w, y, stream);
+        case 2: return launch_t<N, 2>(a, ep, x, w, y, stream);
+        case 1: return launch_t<N, 1>(a, ep, x, w, y, stream);
         default: return hipErrorInvalidValue;
     }
 }
@@ -364,8 +378,8 @@ hipError_t launch_thin_mfma(const Geom& g, const void* x, const void* w, float* 
     if (!mt) return hipErrorInvalidValue;
     // both operands move in 16-byte pieces
     if ((((uintptr_t)x | (uintptr_t)w) & 15) != 0) return hipErrorInvalidValue;
-    return g.n == 4 ? launch_n<4>(mt, a, (const float*)x, (const float*)w, y, stream)
-                    : launch_n<3>(mt, a, (const float*)x, (const float*)w, y, stream);
+    return g.n == 4 ? launch_n<4>(mt, a, g.ep, (const float*)x, (const float*)w, y, stream)
+                    : launch_n<3>(mt, a, g.ep, (const float*)x, (const float*)w, y, stream);
 }
 
 }  // namespace ukst

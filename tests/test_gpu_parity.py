@@ -304,6 +304,59 @@ def test_non_default_stream(case):
     assert torch.equal(y1, y2)
 
 
+# ------------------------------------------------------------------ fused bias + activation
+EPILOGUE_CASES = [
+    # name, (B, Cin, Cout, H, W, n, P), dtype, path, kernel expected
+    ("narrow", (2, 3, 3, 19, 45, 3, 0), "f32", "auto", "ukst_narrow_kernel"),
+    ("thin", (2, 24, 3, 9, 11, 4, 2), "f32", "auto", "ukst_thin_kernel"),
+    ("general", (2, 8, 8, 9, 11, 5, 1), "f32", "auto", "ukst_direct_kernel"),
+    ("general_bf16", (2, 8, 8, 9, 11, 4, 2), "bf16", "auto", "ukst_direct_kernel"),
+    ("thin_mfma", (2, 32, 3, 9, 12, 4, 2), "f32", "auto", "ukst_thin_mfma_kernel"),
+    ("mfma_f32", (2, 16, 40, 23, 31, 3, 0), "f32", "mfma", "ukst_mfma_f32_kernel"),
+    ("mfma_f32_split_k", (2, 64, 16, 5, 6, 4, 2), "f32", "mfma", "ukst_mfma_f32_kernel"),
+    ("mfma_bf16", (2, 32, 128, 9, 16, 4, 2), "bf16", "auto", "ukst_mfma_bf16_kernel"),
+]
+
+
+@pytest.mark.parametrize("act", ["none", "relu", "tanh"])
+@pytest.mark.parametrize("case", EPILOGUE_CASES, ids=[c[0] for c in EPILOGUE_CASES])
+def test_fused_bias_activation(case, act):
+    """y = act(conv + bias[co]) from the store of every kernel family, against the oracle's fp64
+    sums with the same bias and activation applied in fp64.  tanh and ReLU are 1-Lipschitz, so the
+    convolution's tolerance carries over; tanh adds its own fp32 evaluation error (2e-6)."""
+    import torch
+    from gpu_util import to_device
+    name, shape, dtype, pname, kernel = case
+    B, Cin, Cout, H, W, n, P = shape
+    w = _mk("epi_" + name, 9300 + sum(shape), B, Cin, Cout, H, W, n, P, dtype=dtype)
+    dt = ukst.UKST_F32 if dtype == "f32" else ukst.UKST_BF16_F32
+    assert ukst.ukst_kernel_name(B, Cin, Cout, H, W, n, P, dt, PATHS[pname]) == kernel
+    data = wl.generate(w)
+    rng = np.random.default_rng(9300 + sum(shape))
+    bias = rng.normal(0.0, 1.0, Cout).astype(np.float32)
+    y_ref, S = oracle.naive(data["x"], data["w"], P)
+    z = y_ref + bias.astype(np.float64)[None, :, None, None]
+    code = {"none": ukst.UKST_ACT_NONE, "relu": ukst.UKST_ACT_RELU, "tanh": ukst.UKST_ACT_TANH}[act]
+    ref = {"none": z, "relu": np.maximum(z, 0.0), "tanh": np.tanh(z)}[act]
+    x, k = to_device(data, dtype)
+    y = ukst.ukst_conv_transpose2d_bias_act(x, k, P, bias=torch.from_numpy(bias).cuda(), act=code,
+                                            path=PATHS[pname])
+    torch.cuda.synchronize()
+    got = y.cpu().numpy().astype(np.float64)
+    # the bias is added in fp32 to an fp32 sum: half an ulp of the biased value on top
+    slack = TOL[dtype] * S + 1.2e-7 * np.abs(z) + (2e-6 if act == "tanh" else 0.0)
+    err = np.abs(got - ref)
+    assert np.isfinite(got).all()
+    assert (err <= slack).all(), f"worst excess {np.max(err - slack):.3e}"
+    if act == "none":
+        # no bias and no activation: bit-identical to the plain entry point
+        y0 = ukst.ukst_conv_transpose2d(x, k, P, path=PATHS[pname])
+        y1 = ukst.ukst_conv_transpose2d_bias_act(x, k, P, bias=None, act=ukst.UKST_ACT_NONE,
+                                                 path=PATHS[pname])
+        torch.cuda.synchronize()
+        assert torch.equal(y0, y1)
+
+
 # ------------------------------------------------------------------ buffers with element alignment only
 @pytest.mark.parametrize("dtype,cout", [("f32", 64), ("bf16", 64), ("f32", 3)])
 def test_unaligned_buffers_take_the_vector_alu_kernels(dtype, cout):
