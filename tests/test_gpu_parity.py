@@ -357,6 +357,30 @@ def test_fused_bias_activation(case, act):
         assert torch.equal(y0, y1)
 
 
+@pytest.mark.parametrize("name", ["cfg2a", "cfg3_L1", "cfg3_L4", "cfg4b", "cfg5b"])
+def test_fused_bias_relu_full_size_sampled_planes(name):
+    # the benchmark shapes through the fused entry point (narrow, split-K fp32 MFMA + slice sum,
+    # thin MFMA, fp32 MFMA, bf16 MFMA), on a seeded sample of complete (b, co) planes
+    import torch
+    from gpu_util import to_device
+    w = wl.WORKLOADS[name]
+    planes = _sample_planes(w, 12)
+    data = wl.generate(w)
+    bias = np.random.default_rng(w.index).normal(0.0, 0.5, w.Cout).astype(np.float32)
+    y_ref, S = oracle.naive(data["x"], data["w"], w.P, planes=planes)
+    x, k = to_device(data, w.dtype)
+    y = ukst.ukst_conv_transpose2d_bias_act(x, k, w.P, bias=torch.from_numpy(bias).cuda(),
+                                            act=ukst.UKST_ACT_RELU)
+    torch.cuda.synchronize()
+    OH, OW = y.shape[2:]
+    got = y.view(w.B * w.Cout, OH, OW)[planes].cpu().numpy().astype(np.float64)
+    z = y_ref.reshape(w.B * w.Cout, OH, OW)[planes] + bias.astype(np.float64)[np.array(planes) % w.Cout, None, None]
+    ref = np.maximum(z, 0.0)
+    slack = TOL[w.dtype] * S.reshape(w.B * w.Cout, OH, OW)[planes] + 1.2e-7 * np.abs(z)
+    err = np.abs(got - ref)
+    assert (err <= slack).all(), f"worst excess {np.max(err - slack):.3e}"
+
+
 # ------------------------------------------------------------------ buffers with element alignment only
 @pytest.mark.parametrize("dtype,cout", [("f32", 64), ("bf16", 64), ("f32", 3)])
 def test_unaligned_buffers_take_the_vector_alu_kernels(dtype, cout):
