@@ -48,15 +48,17 @@ def _device_tensors(w, data):
     return x, k
 
 
-def algorithmic_bytes(w, OH, OW):
+def algorithmic_bytes(w, OH, OW, out_bytes=4):
     es = 2 if w.dtype == "bf16" else 4
     return (w.B * w.Cin * w.H * w.W * es + w.Cout * w.Cin * w.n * w.n * es
-            + w.B * w.Cout * OH * OW * 4)
+            + w.B * w.Cout * OH * OW * out_bytes)
 
 
-def measure(w, steps, warmup, rotate_bytes=LLC_BYTES + (64 << 20), warm_seconds=0.0, fused=False):
+def measure(w, steps, warmup, rotate_bytes=LLC_BYTES + (64 << 20), warm_seconds=0.0, fused=False,
+            out_bf16=False):
     """Time `steps` launches of workload w.  Returns a dict of rates.  fused: the same launches
-    through ukst_conv_transpose2d_bias_act with a bias vector and ReLU in the store."""
+    through ukst_conv_transpose2d_bias_act with a bias vector and ReLU in the store.
+    out_bf16 (bf16 workloads): the output is bf16 too (UKST_BF16_BF16)."""
     import torch
     from paper_2502_20493_amd import binding as ukst
     from paper_2502_20493_amd import workloads as wl
@@ -64,12 +66,12 @@ def measure(w, steps, warmup, rotate_bytes=LLC_BYTES + (64 << 20), warm_seconds=
     data = wl.generate(w)
     x0, k = _device_tensors(w, data)
     OH, OW = ukst.ukst_output_shape(w.H, w.W, w.n, w.P)
-    nbytes = algorithmic_bytes(w, OH, OW)
+    nbytes = algorithmic_bytes(w, OH, OW, 2 if out_bf16 else 4)
     nsets = max(1, min(16, -(-rotate_bytes // nbytes)))
     xs = [x0] + [x0.clone() for _ in range(nsets - 1)]
-    ys = [torch.empty((w.B, w.Cout, OH, OW), dtype=torch.float32, device="cuda")
-          for _ in range(nsets)]
-    dt = ukst.UKST_BF16_F32 if w.dtype == "bf16" else ukst.UKST_F32
+    ys = [torch.empty((w.B, w.Cout, OH, OW), dtype=torch.bfloat16 if out_bf16 else torch.float32,
+                      device="cuda") for _ in range(nsets)]
+    dt = (ukst.UKST_BF16_BF16 if out_bf16 else ukst.UKST_BF16_F32) if w.dtype == "bf16" else ukst.UKST_F32
     stream = torch.cuda.current_stream()
 
     # arguments are marshalled once (the binding's checks and pointer lookups stay outside the
@@ -127,14 +129,15 @@ def measure(w, steps, warmup, rotate_bytes=LLC_BYTES + (64 << 20), warm_seconds=
         peak = PEAK_TFLOPS[bound]
         roof = {"bound": "mfma", "achieved": round(gflops / 1e3, 2), "peak": peak,
                 "unit": "TFLOP/s", "frac": round(gflops / 1e3 / peak, 4), "traffic": None}
-    roof["traffic"] = measured_traffic(w.name)
+    roof["traffic"] = None if (fused or out_bf16) else measured_traffic(w.name)
     roof["kernel"] = ukst.ukst_kernel_name(w.B, w.Cin, w.Cout, w.H, w.W, w.n, w.P, dt)
     roof["us_per_launch"] = round(per_launch_s * 1e6, 2)
     roof["algorithmic_bytes"] = nbytes
     return {
-        "workload": w.name + ("+bias+relu" if fused else ""),
+        "workload": w.name + ("+bias+relu" if fused else "") + ("+bf16out" if out_bf16 else ""),
         "shape": f"B{w.B} {w.Cin}->{w.Cout} {w.H}x{w.W} n{w.n} P{w.P} {w.dtype}"
-                 + (", bias and ReLU fused into the store" if fused else ""),
+                 + (", bias and ReLU fused into the store" if fused else "")
+                 + (", bf16 output" if out_bf16 else ""),
         "out": f"{OH}x{OW}", "useful_gflops": round(gflops, 1),
         "nominal_gflops": round(nominal / per_launch_s / 1e9, 1),
         "out_gpixels": round(w.B * w.Cout * OH * OW / per_launch_s / 1e9, 3),
@@ -341,10 +344,15 @@ def main():
             per.append(measure_stack(max(5, min(args.steps, 50))))
             torch.cuda.empty_cache()
             # the fused epilogue on the two ends of the range: HBM-bound images, MFMA-bound layer
-            for name in ("cfg2a", "cfg5a"):
+            # and bf16 output for the bf16 layers, without and with the epilogue
+            for name, kw in (("cfg2a", dict(fused=True)), ("cfg5a", dict(fused=True)),
+                             ("cfg5a", dict(out_bf16=True)), ("cfg5b", dict(out_bf16=True)),
+                             ("cfg5a", dict(out_bf16=True, fused=True))):
                 r = measure(wl.WORKLOADS[name], max(5, min(args.steps, 50)), max(2, min(args.warmup, 5)),
-                            warm_seconds=0.3, fused=True)
+                            warm_seconds=0.3, **kw)
                 r.pop("_data"); r.pop("_exact_flop")
+                if BOUND.get(name, "hbm") != "hbm":
+                    r["roofline"]["measured_ceiling"] = ceilings.get(BOUND[name])
                 per.append(r)
                 torch.cuda.empty_cache()
 

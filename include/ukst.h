@@ -34,7 +34,9 @@ extern "C" {
 /* Element types.  Accumulation is always fp32. */
 typedef enum {
     UKST_F32 = 0,      /* x, w, y are IEEE fp32 */
-    UKST_BF16_F32 = 1  /* x, w are bfloat16 (upper half of an fp32), y is fp32, stored unrounded */
+    UKST_BF16_F32 = 1, /* x, w are bfloat16 (upper half of an fp32), y is fp32, stored unrounded */
+    UKST_BF16_BF16 = 2 /* x, w, y are bfloat16: the fp32 sum (after the fused epilogue, if any) is
+                          rounded once, to nearest even, at the store; halves the output traffic */
 } ukst_dtype;
 
 typedef enum {
@@ -94,14 +96,16 @@ int ukst_select_path(int B, int Cin, int Cout, int H, int W, int n, int P, int d
  *   w       DEVICE pointer, [Cout][Cin][n][n] contiguous, same element type as x, read-only,
  *           used as printed in Eqs. 1-4 (no flip; note torch's ConvTranspose2d weight is
  *           [Cin][Cout][k][k] and flipped relative to this)
- *   y       DEVICE pointer, [B][Cout][OH][OW] contiguous fp32, every element overwritten,
+ *   y       DEVICE pointer, [B][Cout][OH][OW] contiguous fp32 (bf16 for UKST_BF16_BF16), every
+ *           element overwritten,
  *           nothing outside it touched; must not overlap x or w
  *   B..P    sizes as above; 1 <= n <= UKST_MAX_N, P >= 0 (any P, also P > n-1: windows that
  *           meet no input give +0)
  *   dtype   a ukst_dtype
  *   stream  a hipStream_t (as void*), or NULL for the default stream
  *
- * Only element alignment is required (4 bytes fp32, 2 bytes bf16; UKST_ERR_UNSUPPORTED otherwise).
+ * Only element alignment is required (4 bytes fp32, 2 bytes bf16, for y too; UKST_ERR_UNSUPPORTED
+ * otherwise).
  * The matrix-core kernels additionally want w (and x, for bf16 and for fp32 layers with at most 4
  * output channels) aligned to 16 bytes: when they are not, ukst_conv_transpose2d uses the vector-ALU kernels instead.  The caller owns all buffers;
  * the call enqueues work on `stream` and returns without synchronising.  Arguments are validated

@@ -11,7 +11,7 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libukst.so")
 
-UKST_F32, UKST_BF16_F32 = 0, 1
+UKST_F32, UKST_BF16_F32, UKST_BF16_BF16 = 0, 1, 2
 UKST_OK, UKST_ERR_NULL, UKST_ERR_SHAPE, UKST_ERR_DTYPE, UKST_ERR_UNSUPPORTED, UKST_ERR_LAUNCH = range(6)
 UKST_PATH_AUTO, UKST_PATH_DIRECT, UKST_PATH_MFMA = 0, 1, 2
 UKST_MAX_N = 7
@@ -121,7 +121,7 @@ def ukst_conv_transpose2d_raw(x_ptr, w_ptr, y_ptr, B, Cin, Cout, H, W, n, P, dty
 
 
 def ukst_conv_transpose2d_bias_act(x, w, P: int, bias=None, act: int = UKST_ACT_NONE, y=None,
-                                   path: int = UKST_PATH_AUTO, stream=None):
+                                   path: int = UKST_PATH_AUTO, stream=None, out_bf16: bool = False):
     """Marshal torch device tensors into ukst_conv_transpose2d_bias_act:
     y = act(conv_transpose(x, w) + bias[co]); bias: float32 device tensor [Cout] or None."""
     import torch
@@ -130,15 +130,17 @@ def ukst_conv_transpose2d_bias_act(x, w, P: int, bias=None, act: int = UKST_ACT_
         if not (bias.is_cuda and bias.dtype == torch.float32 and bias.is_contiguous()
                 and tuple(bias.shape) == (w.shape[0],)):
             raise ValueError("bias must be a contiguous float32 device tensor [Cout]")
-    return ukst_conv_transpose2d(x, w, P, y=y, path=path, stream=stream, _bias=bias, _act=act)
+    return ukst_conv_transpose2d(x, w, P, y=y, path=path, stream=stream, out_bf16=out_bf16,
+                                 _bias=bias, _act=act)
 
 
 def ukst_conv_transpose2d(x, w, P: int, y=None, path: int = UKST_PATH_AUTO, stream=None,
-                          _bias=None, _act=None):
+                          out_bf16: bool = False, _bias=None, _act=None):
     """Marshal torch device tensors into ukst_conv_transpose2d.
 
     x: [B,Cin,H,W] float32 or bfloat16, w: [Cout,Cin,n,n] same dtype, both contiguous on the GPU.
     y: optional preallocated float32 [B,Cout,OH,OW]; allocated with torch when omitted.
+    out_bf16 (bf16 inputs only), or a bfloat16 y: the output is bfloat16 (UKST_BF16_BF16).
     The call is asynchronous on ``stream`` (default: torch's current stream).
     """
     import torch
@@ -153,13 +155,19 @@ def ukst_conv_transpose2d(x, w, P: int, y=None, path: int = UKST_PATH_AUTO, stre
         raise ValueError("expected x[B,Cin,H,W] and w[Cout,Cin,n,n]")
     B, Cin, H, W = x.shape
     Cout, _, n, _ = w.shape
-    dtype = UKST_F32 if x.dtype == torch.float32 else UKST_BF16_F32
+    if y is not None and y.dtype == torch.bfloat16:
+        out_bf16 = True
+    if out_bf16 and x.dtype != torch.bfloat16:
+        raise ValueError("a bfloat16 output needs bfloat16 inputs")
+    dtype = UKST_F32 if x.dtype == torch.float32 else (UKST_BF16_BF16 if out_bf16 else UKST_BF16_F32)
+    ydt = torch.bfloat16 if out_bf16 else torch.float32
     OH, OW = ukst_output_shape(H, W, n, P)
     if y is None:
-        y = torch.empty((B, Cout, OH, OW), dtype=torch.float32, device=x.device)
-    elif (tuple(y.shape) != (B, Cout, OH, OW) or y.dtype != torch.float32
+        y = torch.empty((B, Cout, OH, OW), dtype=ydt, device=x.device)
+    elif (tuple(y.shape) != (B, Cout, OH, OW) or y.dtype != ydt
           or not y.is_contiguous() or not y.is_cuda):
-        raise ValueError("y must be a contiguous float32 device tensor [B,Cout,OH,OW]")
+        raise ValueError("y must be a contiguous device tensor [B,Cout,OH,OW], float32 or, for a "
+                         "bfloat16 output, bfloat16")
     if stream is None:
         stream = torch.cuda.current_stream(x.device)
     sp = stream.cuda_stream if hasattr(stream, "cuda_stream") else stream

@@ -100,7 +100,7 @@ int ukst_select_path(int B, int Cin, int Cout, int H, int W, int n, int P, int d
 {
     const int st = validate_shape(B, Cin, Cout, H, W, n, P);
     if (st != UKST_OK) return -st;
-    if (dtype != UKST_F32 && dtype != UKST_BF16_F32) return -UKST_ERR_DTYPE;
+    if (dtype != UKST_F32 && dtype != UKST_BF16_F32 && dtype != UKST_BF16_BF16) return -UKST_ERR_DTYPE;
     if (n > UKST_MAX_N) return -UKST_ERR_UNSUPPORTED;
     return resolve_path(ukst::make_geom(B, Cin, Cout, H, W, n, P), dtype, UKST_PATH_AUTO);
 }
@@ -112,7 +112,7 @@ static int run_checked(const void* x, const void* w, const float* bias, int act,
     if (!x || !w || !y) return UKST_ERR_NULL;
     const int st = validate_shape(B, Cin, Cout, H, W, n, P);
     if (st != UKST_OK) return st;
-    if (dtype != UKST_F32 && dtype != UKST_BF16_F32) return UKST_ERR_DTYPE;
+    if (dtype != UKST_F32 && dtype != UKST_BF16_F32 && dtype != UKST_BF16_BF16) return UKST_ERR_DTYPE;
     if (n > UKST_MAX_N) return UKST_ERR_UNSUPPORTED;
     if (path != UKST_PATH_AUTO && path != UKST_PATH_DIRECT && path != UKST_PATH_MFMA)
         return UKST_ERR_UNSUPPORTED;
@@ -123,8 +123,8 @@ static int run_checked(const void* x, const void* w, const float* bias, int act,
     g.ep.act = act;
     // element alignment is required of every buffer; the matrix-core kernels move the weights
     // (and bf16 activations) in 16-byte pieces and need those buffers aligned to that
-    const uintptr_t esz = dtype == UKST_BF16_F32 ? 2 : 4;
-    if (((uintptr_t)x | (uintptr_t)w) & (esz - 1) || ((uintptr_t)y & 3) || ((uintptr_t)bias & 3))
+    const uintptr_t esz = dtype == UKST_F32 ? 4 : 2, osz = dtype == UKST_BF16_BF16 ? 2 : 4;
+    if (((uintptr_t)x | (uintptr_t)w) & (esz - 1) || ((uintptr_t)y & (osz - 1)) || ((uintptr_t)bias & 3))
         return UKST_ERR_UNSUPPORTED;
     int chosen = resolve_path(g, dtype, path);
     const bool x16 = chosen == UKST_PATH_MFMA && ukst::mfma_needs_aligned_x(g, dtype);
@@ -163,7 +163,7 @@ const char* ukst_kernel_name(int B, int Cin, int Cout, int H, int W, int n, int 
                              int path)
 {
     if (validate_shape(B, Cin, Cout, H, W, n, P) != UKST_OK) return "";
-    if ((dtype != UKST_F32 && dtype != UKST_BF16_F32) || n > UKST_MAX_N) return "";
+    if ((dtype != UKST_F32 && dtype != UKST_BF16_F32 && dtype != UKST_BF16_BF16) || n > UKST_MAX_N) return "";
     const ukst::Geom g = ukst::make_geom(B, Cin, Cout, H, W, n, P);
     const int chosen = resolve_path(g, dtype, path);
     if (chosen < 0) return "";

@@ -18,11 +18,14 @@ __device__ __forceinline__ int xcd_contiguous(int bid, int nb)
 
 __device__ __forceinline__ float to_f32(float v) { return v; }
 __device__ __forceinline__ float to_f32(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
+// one rounding to nearest even at the store when the output is bf16
+__device__ __forceinline__ void put(float* p, float v) { *p = v; }
+__device__ __forceinline__ void put(uint16_t* p, float v) { *p = __builtin_bit_cast(uint16_t, (__bf16)v); }
 
-template <int N, int CO_BLK, int TW, int TH, int CI_CHUNK, typename TIn>
+template <int N, int CO_BLK, int TW, int TH, int CI_CHUNK, typename TIn, typename TOut>
 __global__ __launch_bounds__(TW* TH) void ukst_direct_kernel(const TIn* __restrict__ x,
                                                             const TIn* __restrict__ w,
-                                                            float* __restrict__ y, GeomBase g,
+                                                            TOut* __restrict__ y, GeomBase g,
                                                             int tilesX, int tilesY, int coBlocks,
                                                             Epilogue ep)
 {
@@ -98,7 +101,7 @@ __global__ __launch_bounds__(TW* TH) void ukst_direct_kernel(const TIn* __restri
 #pragma unroll
     for (int c = 0; c < CO_BLK; ++c) {
         if (co0 + c >= g.Cout) break;
-        float* yp = y + ((size_t)b * g.Cout + co0 + c) * OH * OW;
+        TOut* yp = y + ((size_t)b * g.Cout + co0 + c) * OH * OW;
         if (has_epilogue(ep)) {  // uniform
             const float bv = ep.bias ? ep.bias[co0 + c] : 0.f;
 #pragma unroll
@@ -107,19 +110,19 @@ __global__ __launch_bounds__(TW* TH) void ukst_direct_kernel(const TIn* __restri
                 for (int sc = 0; sc < 2; ++sc) acc[c][r][sc] = epilogue(acc[c][r][sc], bv, ep.act);
         }
         if (vy1) {
-            float* row = yp + (size_t)oy1 * OW;
-            if (vx1) row[ox1] = acc[c][1][1];
-            if (vx0) row[ox0] = acc[c][1][0];
+            TOut* row = yp + (size_t)oy1 * OW;
+            if (vx1) put(row + ox1, acc[c][1][1]);
+            if (vx0) put(row + ox0, acc[c][1][0]);
         }
         if (vy0) {
-            float* row = yp + (size_t)oy0 * OW;
-            if (vx1) row[ox1] = acc[c][0][1];
-            if (vx0) row[ox0] = acc[c][0][0];
+            TOut* row = yp + (size_t)oy0 * OW;
+            if (vx1) put(row + ox1, acc[c][0][1]);
+            if (vx0) put(row + ox0, acc[c][0][0]);
         }
     }
 }
 
-template <int N, int CO_BLK, typename TIn>
+template <int N, int CO_BLK, typename TIn, typename TOut>
 hipError_t launch_one(const Geom& g, const void* x, const void* w, float* y, hipStream_t stream)
 {
     constexpr int TW = 32, TH = 8, CI_CHUNK = 8;
@@ -127,8 +130,8 @@ hipError_t launch_one(const Geom& g, const void* x, const void* w, float* y, hip
     const int coBlocks = (g.Cout + CO_BLK - 1) / CO_BLK;
     const long long nb = (long long)tilesX * tilesY * coBlocks * g.B;
     if (nb > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL((ukst_direct_kernel<N, CO_BLK, TW, TH, CI_CHUNK, TIn>), dim3((unsigned)nb),
-                       dim3(TW * TH), 0, stream, (const TIn*)x, (const TIn*)w, y, (GeomBase)g, tilesX,
+    hipLaunchKernelGGL((ukst_direct_kernel<N, CO_BLK, TW, TH, CI_CHUNK, TIn, TOut>), dim3((unsigned)nb),
+                       dim3(TW * TH), 0, stream, (const TIn*)x, (const TIn*)w, (TOut*)y, (GeomBase)g, tilesX,
                        tilesY, coBlocks, g.ep);
     return hipGetLastError();
 }
@@ -137,10 +140,11 @@ template <int N>
 hipError_t launch_n(const Geom& g, const void* x, const void* w, float* y, int dtype,
                     hipStream_t stream)
 {
-    if (dtype == 1) return launch_one<N, 4, uint16_t>(g, x, w, y, stream);
-    if (g.Cout == 1) return launch_one<N, 1, float>(g, x, w, y, stream);
-    if (g.Cout == 3) return launch_one<N, 3, float>(g, x, w, y, stream);
-    return launch_one<N, 4, float>(g, x, w, y, stream);
+    if (dtype == 2) return launch_one<N, 4, uint16_t, uint16_t>(g, x, w, y, stream);
+    if (dtype == 1) return launch_one<N, 4, uint16_t, float>(g, x, w, y, stream);
+    if (g.Cout == 1) return launch_one<N, 1, float, float>(g, x, w, y, stream);
+    if (g.Cout == 3) return launch_one<N, 3, float, float>(g, x, w, y, stream);
+    return launch_one<N, 4, float, float>(g, x, w, y, stream);
 }
 
 }  // namespace

@@ -33,6 +33,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef unsigned u2v __attribute__((ext_vector_type(2)));
 typedef unsigned u4v __attribute__((ext_vector_type(4)));
 
@@ -93,11 +94,12 @@ __device__ __forceinline__ u4v transposed_row(const u4v (&in)[8], int k)
 }
 
 // EPI: the fused epilogue (bias, activation) is compiled into the drain; the plain instance keeps
-// the register allocation of its drain to itself.
-template <int N, bool EPI>
+// the register allocation of its drain to itself.  OUT16: y is bf16, each sum rounded once (to
+// nearest even) at the store, the two column classes of a quad packed into one 4-byte store.
+template <int N, bool EPI, bool OUT16>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w,
-                           float* __restrict__ y, MfmaArgs a, Epilogue ep)
+                           void* __restrict__ y, MfmaArgs a, Epilogue ep)
 {
     static_assert(N == 4, "bf16 MFMA path: in-register sub-kernel gather is written for n = 4");
     constexpr int HI = (N + 1) / 2;
@@ -177,9 +179,10 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
     const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc(
         (void*)w, 0, (int)((size_t)g.Cout * g.Cin * NN * 2), kRsrcFlags);
     const __amdgpu_buffer_rsrc_t rs_y = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)y, 0, (int)((size_t)g.B * g.Cout * g.OH * g.OW * 4), kRsrcFlags);
+        y, 0, (int)((size_t)g.B * g.Cout * g.OH * g.OW * (OUT16 ? 2 : 4)), kRsrcFlags);
     const unsigned x_cstride = (unsigned)(g.H * g.W * 2);  // bytes between input channels
-    const unsigned plane = (unsigned)(g.OH * g.OW * 4);
+    constexpr unsigned ES = OUT16 ? 2u : 4u;  // bytes per output element
+    const unsigned plane = (unsigned)(g.OH * g.OW) * ES;
 
     // A (weights): lane = channel cw*32 + l32 of the block tile, k-half gk
     const int a_lds = gk * W_HALF + (cw * 32 + l32) * 16;
@@ -354,14 +357,14 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
             const int oy1 = 2 * k - 1 - g.P, ox1 = 2 * m - 1 - g.P;  // row / column of class 1
             const bool vcol1 = ox1 >= 0 && ox1 < g.OW, vcol0 = ox1 + 1 < g.OW;
             const unsigned y_off =
-                (unsigned)((((b * g.Cout + co0 + cw * 32 + 4 * gk) * g.OH + oy1) * g.OW + ox1) * 4);
+                (unsigned)(((b * g.Cout + co0 + cw * 32 + 4 * gk) * g.OH + oy1) * g.OW + ox1) * ES;
 #pragma unroll
             for (int r = 1; r >= 0; --r) {
                 const bool vrow = qv && (r ? (oy1 >= 0 && oy1 < g.OH) : (oy1 + 1 < g.OH));
-                const unsigned base = y_off + (r ? 0u : (unsigned)(g.OW * 4));
+                const unsigned base = y_off + (r ? 0u : (unsigned)g.OW * ES);
                 off_pair[nt][r] = (vrow && vcol1 && vcol0) ? base : kInvalid;
                 off_s1[nt][r] = (vrow && vcol1 && !vcol0) ? base : kInvalid;
-                off_s0[nt][r] = (vrow && !vcol1 && vcol0) ? base + 4u : kInvalid;
+                off_s0[nt][r] = (vrow && !vcol1 && vcol0) ? base + ES : kInvalid;
                 const bool edge = (off_s1[nt][r] != kInvalid) || (off_s0[nt][r] != kInvalid);
                 any_edge[nt][r] = __builtin_amdgcn_ballot_w64(edge) != 0;  // wave-uniform
             }
@@ -386,12 +389,25 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
                             v1 = epilogue_t<ACT>(v1, bv);
                             v0 = epilogue_t<ACT>(v0, bv);
                         }
-                        d.x = __float_as_uint(v1);
-                        d.y = __float_as_uint(v0);
-                        __builtin_amdgcn_raw_buffer_store_b64(d, rs_y, off_pair[nt][r], soff, 0);
-                        if (any_edge[nt][r]) {
-                            __builtin_amdgcn_raw_buffer_store_b32(d.x, rs_y, off_s1[nt][r], soff, 0);
-                            __builtin_amdgcn_raw_buffer_store_b32(d.y, rs_y, off_s0[nt][r], soff, 0);
+                        if constexpr (OUT16) {
+                            // column ox1 (class s = 1) in the low half: the lower address
+                            const bf16x2 pk = {(__bf16)v1, (__bf16)v0};
+                            const unsigned bits = __builtin_bit_cast(unsigned, pk);
+                            __builtin_amdgcn_raw_buffer_store_b32(bits, rs_y, off_pair[nt][r], soff, 0);
+                            if (any_edge[nt][r]) {
+                                __builtin_amdgcn_raw_buffer_store_b16((short)(bits & 0xFFFFu), rs_y,
+                                                                      off_s1[nt][r], soff, 0);
+                                __builtin_amdgcn_raw_buffer_store_b16((short)(bits >> 16), rs_y,
+                                                                      off_s0[nt][r], soff, 0);
+                            }
+                        } else {
+                            d.x = __float_as_uint(v1);
+                            d.y = __float_as_uint(v0);
+                            __builtin_amdgcn_raw_buffer_store_b64(d, rs_y, off_pair[nt][r], soff, 0);
+                            if (any_edge[nt][r]) {
+                                __builtin_amdgcn_raw_buffer_store_b32(d.x, rs_y, off_s1[nt][r], soff, 0);
+                                __builtin_amdgcn_raw_buffer_store_b32(d.y, rs_y, off_s0[nt][r], soff, 0);
+                            }
                         }
                     }
             }
@@ -404,7 +420,7 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
 
 bool make_args(const Geom& g, int dtype, MfmaArgs& a)
 {
-    if (dtype != 1) return false;                // fp32 operands: see ukst_mfma_f32.hip
+    if (dtype != 1 && dtype != 2) return false;  // fp32 operands: see ukst_mfma_f32.hip
     if (g.n != 4) return false;
     if (g.Cin % KC != 0 || g.Cout % TM != 0) return false;
     if (g.W % 8 != 0) return false;              // 16-byte row chunks
@@ -473,10 +489,11 @@ hipError_t launch_mfma(const Geom& g, const void* x, const void* w, float* y, in
     const size_t lds = 2 * (size_t)(2 * W_HALF) + 2 * (size_t)XS_STAGE_MAX;
     // more than 64 KiB of dynamic LDS has to be allowed per device (a property of the loaded
     // kernel, not library state); cheap enough to repeat on every call
-    const bool epi = has_epilogue(g.ep);
-    const void* kfn = epi ? (const void*)ukst_mfma_bf16_kernel<N, true>
-                          : (const void*)ukst_mfma_bf16_kernel<N, false>;
-    hipError_t e = hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    const bool epi = has_epilogue(g.ep), out16 = dtype == 2;
+    typedef void (*kernel_t)(const uint16_t*, const uint16_t*, void*, MfmaArgs, Epilogue);
+    const kernel_t kfn = out16 ? (epi ? ukst_mfma_bf16_kernel<N, true, true> : ukst_mfma_bf16_kernel<N, false, true>)
+                               : (epi ? ukst_mfma_bf16_kernel<N, true, false> : ukst_mfma_bf16_kernel<N, false, false>);
+    hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     // persistent blocks: one per compute unit (a multiple of the 8 XCDs), never more than tiles
     int dev = 0, cus = 0;
@@ -495,18 +512,14 @@ hipError_t launch_mfma(const Geom& g, const void* x, const void* w, float* y, in
         const int fewer = (((a.ntiles + rounds - 1) / rounds + 7) / 8) * 8;
         if (fewer < grid) grid = fewer;
     }
-    if (epi)
-        hipLaunchKernelGGL((ukst_mfma_bf16_kernel<N, true>), dim3((unsigned)grid), dim3(256), lds,
-                           stream, (const uint16_t*)x, (const uint16_t*)w, y, a, g.ep);
-    else
-        hipLaunchKernelGGL((ukst_mfma_bf16_kernel<N, false>), dim3((unsigned)grid), dim3(256), lds,
-                           stream, (const uint16_t*)x, (const uint16_t*)w, y, a, g.ep);
+    hipLaunchKernelGGL(kfn, dim3((unsigned)grid), dim3(256), lds, stream, (const uint16_t*)x,
+                       (const uint16_t*)w, (void*)y, a, g.ep);
     return hipGetLastError();
 }
 
 const char* mfma_kernel_name(const Geom& g, int dtype)
 {
-    if (dtype != 0) return "ukst_mfma_bf16_kernel";
+    if (dtype != 0) return "ukst_mfma_bf16_kernel";  // bf16 in; fp32 or bf16 out
     return mfma_f32_supported(g) ? "ukst_mfma_f32_kernel" : "ukst_thin_mfma_kernel";
 }
 

@@ -59,12 +59,22 @@ def test_validation_happens_on_the_host():
                 (1, 1, 1, 0, 4, 3, 0), (1, 1, 1, 4, 0, 3, 0), (1, 1, 1, 4, 4, 0, 0),
                 (1, 1, 1, 4, 4, 3, -1), (1, 1, 1, 1, 4, 3, 0), (1, 1, 1, 4, 1, 3, 0)]:
         assert call(X, W, Y, *bad, 0) == ukst.UKST_ERR_SHAPE, bad
-    assert call(X, W, Y, *ok_shape, 2) == ukst.UKST_ERR_DTYPE
+    assert call(X, W, Y, *ok_shape, 3) == ukst.UKST_ERR_DTYPE
     assert call(X, W, Y, *ok_shape, -1) == ukst.UKST_ERR_DTYPE
     assert call(X, W, Y, 1, 1, 1, 8, 8, ukst.UKST_MAX_N + 1, 0, 0) == ukst.UKST_ERR_UNSUPPORTED
     assert call(X, W, Y, *ok_shape, 0, path=7) == ukst.UKST_ERR_UNSUPPORTED
     # MFMA path cannot run a 1-channel problem
     assert call(X, W, Y, *ok_shape, 0, path=ukst.UKST_PATH_MFMA) == ukst.UKST_ERR_UNSUPPORTED
+    # element alignment: fp32 buffers at 4 bytes, a bf16 output at 2
+    assert call(X + 2, W, Y, *ok_shape, 0) == ukst.UKST_ERR_UNSUPPORTED
+    assert call(X, W, Y + 2, *ok_shape, ukst.UKST_BF16_F32) == ukst.UKST_ERR_UNSUPPORTED
+    assert call(X, W, Y + 1, *ok_shape, ukst.UKST_BF16_BF16) == ukst.UKST_ERR_UNSUPPORTED
+    # the fused entry point validates the same way, plus the activation code
+    fused = ukst.lib().ukst_conv_transpose2d_bias_act
+    assert fused(X, W, None, None, *ok_shape, 0, 0, 0, None) == ukst.UKST_ERR_NULL
+    assert fused(X, W, None, Y, 1, 1, 1, 0, 4, 3, 0, 0, 0, 0, None) == ukst.UKST_ERR_SHAPE
+    assert fused(X, W, None, Y, *ok_shape, 0, 9, 0, None) == ukst.UKST_ERR_UNSUPPORTED
+    assert fused(X, W, X + 2, Y, *ok_shape, 0, 1, 0, None) == ukst.UKST_ERR_UNSUPPORTED
 
 
 def _brute_macs(H, W, n, P):

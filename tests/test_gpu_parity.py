@@ -304,6 +304,75 @@ def test_non_default_stream(case):
     assert torch.equal(y1, y2)
 
 
+# ------------------------------------------------------------------ bf16 output (UKST_BF16_BF16)
+def _bf16_out_case(w, path, integer, planes=None, bias=None, act=None):
+    """bf16 in, bf16 out: one rounding (to nearest even) of the fp32 sum at the store.
+    Integer data: the fp32 sum is exact, so the stored bits must equal the rounded exact value.
+    Otherwise |y - y_oracle| <= 1e-2 * sum|x*w| (the fp32-sum tolerance) + 2^-8 |y_oracle|
+    (half an ulp of bf16 is 2^-9 relative)."""
+    import torch
+    from gpu_util import to_device
+    print(f"case {w.name} B={w.B} Cin={w.Cin} Cout={w.Cout} H={w.H} W={w.W} n={w.n} P={w.P} "
+          f"bf16->bf16 path={path} integer={integer}", flush=True)
+    data = wl.generate(w, integer=integer)
+    y_ref, S = oracle.naive(data["x"], data["w"], w.P, planes=planes)
+    x, k = to_device(data, "bf16")
+    OH, OW = ukst.ukst_output_shape(w.H, w.W, w.n, w.P)
+    numel, guard = w.B * w.Cout * OH * OW, 4096
+    buf = torch.full((numel + 2 * guard,), -777.0, dtype=torch.bfloat16, device="cuda")
+    y = buf[guard:guard + numel].view(w.B, w.Cout, OH, OW)
+    if bias is None:
+        ukst.ukst_conv_transpose2d(x, k, w.P, y=y, path=path)
+    else:
+        ukst.ukst_conv_transpose2d_bias_act(x, k, w.P, bias=torch.from_numpy(bias).cuda(), act=act,
+                                            y=y, path=path)
+        y_ref = np.maximum(y_ref + bias.astype(np.float64)[None, :, None, None], 0.0)
+    torch.cuda.synchronize()
+    assert bool((buf[:guard] == -777.0).all()) and bool((buf[guard + numel:] == -777.0).all())
+    bits = y.view(torch.int16).cpu().numpy().view(np.uint16).reshape(w.B * w.Cout, -1)
+    ref = y_ref.reshape(w.B * w.Cout, -1)
+    s = S.reshape(w.B * w.Cout, -1)
+    if planes is not None:
+        bits, ref, s = bits[planes], ref[planes], s[planes]
+    if integer and bias is None:
+        want = wl.round_to_bf16_bits(ref.astype(np.float32))
+        assert np.array_equal(wl.bf16_bits_to_f32(bits), wl.bf16_bits_to_f32(want))
+        return
+    got = wl.bf16_bits_to_f32(bits).astype(np.float64)
+    assert np.isfinite(got).all()
+    err = np.abs(got - ref)
+    assert (err <= TOL["bf16"] * s + 2.0 ** -8 * np.abs(ref) + 1e-30).all()
+
+
+@pytest.mark.parametrize("shape", MFMA_BF16_SHAPES)
+def test_bf16_output_mfma_small_shapes_every_element(shape):
+    B, Cin, Cout, H, W, P = shape
+    w = _mk("mfma_bf16_out", 7500 + sum(shape), B, Cin, Cout, H, W, 4, P, dtype="bf16")
+    assert ukst.ukst_kernel_name(B, Cin, Cout, H, W, 4, P, ukst.UKST_BF16_BF16,
+                                 PATHS["mfma"]) == "ukst_mfma_bf16_kernel"
+    _bf16_out_case(w, PATHS["mfma"], integer=True)
+    _bf16_out_case(w, PATHS["mfma"], integer=False)
+
+
+@pytest.mark.parametrize("shape", [(2, 3, 3, 5, 9, 3, 0), (1, 9, 5, 6, 37, 4, 2), (2, 17, 2, 11, 7, 5, 1),
+                                   (1, 4, 3, 6, 131, 2, 0)])
+def test_bf16_output_general_kernel_every_element(shape):
+    B, Cin, Cout, H, W, n, P = shape
+    w = _mk("direct_bf16_out", 7600 + sum(shape), B, Cin, Cout, H, W, n, P, dtype="bf16")
+    _bf16_out_case(w, PATHS["direct"], integer=True)
+    _bf16_out_case(w, PATHS["direct"], integer=False)
+
+
+@pytest.mark.parametrize("name", ["cfg5a", "cfg5b"])
+def test_bf16_output_full_size_sampled_planes(name):
+    w = wl.WORKLOADS[name]
+    planes = _sample_planes(w, 12)
+    _bf16_out_case(w, PATHS["auto"], integer=False, planes=planes)
+    _bf16_out_case(w, PATHS["auto"], integer=True, planes=planes)
+    bias = np.random.default_rng(w.index).normal(0.0, 0.5, w.Cout).astype(np.float32)
+    _bf16_out_case(w, PATHS["auto"], integer=False, planes=planes, bias=bias, act=ukst.UKST_ACT_RELU)
+
+
 # ------------------------------------------------------------------ fused bias + activation
 EPILOGUE_CASES = [
     # name, (B, Cin, Cout, H, W, n, P), dtype, path, kernel expected
