@@ -7,8 +7,10 @@ gcc, loads it through ctypes and converts numpy arrays.
 
 ``naive`` is the oracle of record (Algorithm 1 of the paper: bed-of-nails upsample, pad by P,
 stride-1 n x n window).  ``scatter`` and ``segregated`` (Algorithm 2 / Eqs. 1-4 / Sec. 3.4) are
-independent formulations used only to pin ``naive``.  Every function is pinned by
-``tests/test_oracle_pins.py``; none is "parity unpinned".
+independent formulations used only to pin ``naive``.  ``grad_input`` and ``grad_weight`` are the
+adjoints of Algorithm 1 (the backward pass of the layer; the paper treats the forward only).
+Every function is pinned by ``tests/test_oracle_pins.py`` / ``tests/test_oracle_backward_pins.py``;
+none is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -43,6 +45,9 @@ def _load():
         lib.ukst_oracle_naive.argtypes = [dp, dp, dp, dp, i, i, i, i, i, i, i, ip, i]
         lib.ukst_oracle_naive.restype = i
         for f in (lib.ukst_oracle_scatter, lib.ukst_oracle_segregated):
+            f.argtypes = [dp, dp, dp, dp, i, i, i, i, i, i, i]
+            f.restype = i
+        for f in (lib.ukst_oracle_grad_input, lib.ukst_oracle_grad_weight):
             f.argtypes = [dp, dp, dp, dp, i, i, i, i, i, i, i]
             f.restype = i
         lib.ukst_oracle_threads.restype = i
@@ -114,3 +119,39 @@ def scatter(x, w, P):
 def segregated(x, w, P):
     """Check-only formulation: four parity sub-kernels selected per output pixel."""
     return _call("segregated", x, w, P)
+
+
+def _f64(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.float64))
+
+
+def grad_input(dy, w, H, W, P):
+    """Adjoint of Algorithm 1 w.r.t. the input.  dy[B,Cout,OH,OW], w[Cout,Cin,n,n] ->
+    (dx[B,Cin,H,W], S) in fp64; S = sum |dy*w| per element (tolerance scale)."""
+    dy, w = _f64(dy), _f64(w)
+    B, Cout, OH, OW = dy.shape
+    Cout2, Cin, n, n2 = w.shape
+    if Cout2 != Cout or n != n2 or (OH, OW) != out_shape(H, W, n, P):
+        raise ValueError("expected dy[B,Cout,2H+2P-n,2W+2P-n] and w[Cout,Cin,n,n]")
+    dx = np.zeros((B, Cin, H, W), dtype=np.float64)
+    S = np.zeros_like(dx)
+    rc = _load().ukst_oracle_grad_input(_dp(dy), _dp(w), _dp(dx), _dp(S), B, Cin, Cout, H, W, n, P)
+    if rc != 0:
+        raise RuntimeError(f"oracle grad_input failed with code {rc}")
+    return dx, S
+
+
+def grad_weight(x, dy, n, P):
+    """Adjoint of Algorithm 1 w.r.t. the kernel.  x[B,Cin,H,W], dy[B,Cout,OH,OW] ->
+    (dw[Cout,Cin,n,n], S) in fp64; S = sum |x*dy| per element (tolerance scale)."""
+    x, dy = _f64(x), _f64(dy)
+    B, Cin, H, W = x.shape
+    B2, Cout, OH, OW = dy.shape
+    if B2 != B or (OH, OW) != out_shape(H, W, n, P):
+        raise ValueError("expected x[B,Cin,H,W] and dy[B,Cout,2H+2P-n,2W+2P-n]")
+    dw = np.zeros((Cout, Cin, n, n), dtype=np.float64)
+    S = np.zeros_like(dw)
+    rc = _load().ukst_oracle_grad_weight(_dp(x), _dp(dy), _dp(dw), _dp(S), B, Cin, Cout, H, W, n, P)
+    if rc != 0:
+        raise RuntimeError(f"oracle grad_weight failed with code {rc}")
+    return dw, S

@@ -188,3 +188,112 @@ int ukst_oracle_segregated(const double *x, const double *w, double *y, double *
         for (int s = 0; s < 2; ++s) free(k[r][s]);
     return 0;
 }
+
+/* ------------------------------------------------------------------------------------------
+ * Backward pass.  The paper evaluates the forward layer only; training a generator also needs
+ * the two gradients of the same linear map.  Both are written here as the adjoint of
+ * Algorithm 1 taken step by step (Algorithm 1: U = bed of nails of the input, padded by P;
+ * y = stride-1 n x n window over U, no flip), for the loss  L = sum(dy * y):
+ *
+ *   ukst_oracle_grad_input   dL/dx: the window step's adjoint spreads every dy over the n x n
+ *                            cells of U its window covered (dU[oy+a][ox+c] += dy * w[a][c]);
+ *                            the bed-of-nails step's adjoint reads dU back at the cells that
+ *                            hold input pixels (dx[i][j] = dU[P+2i][P+2j]) and drops the rest.
+ *   ukst_oracle_grad_weight  dL/dw: U is built exactly as in the forward pass and
+ *                            dw[a][c] = sum over output pixels of dy[oy][ox] * U[oy+a][ox+c].
+ *
+ * Layouts as above; dy [B][Cout][OH][OW], dx [B][Cin][H][W], dw [Cout][Cin][n][n].
+ * S (optional) receives the sum of the absolute values of the same products (tolerance scale).
+ * Pinned in tests/test_oracle_backward_pins.py against the forward oracle (adjoint identity,
+ * element by element through unit vectors), hand-worked values and a library autograd.
+ */
+static int bad_args3(const void *p0, const void *p1, const void *p2, int B, int Cin, int Cout,
+                     int H, int W, int n, int P)
+{
+    if (!p0 || !p1 || !p2) return 1;
+    if (B < 1 || Cin < 1 || Cout < 1 || H < 1 || W < 1 || n < 1 || P < 0) return 1;
+    if (2 * H + 2 * P - n < 1 || 2 * W + 2 * P - n < 1) return 1;
+    return 0;
+}
+
+int ukst_oracle_grad_input(const double *dy, const double *w, double *dx, double *S, int B,
+                           int Cin, int Cout, int H, int W, int n, int P)
+{
+    if (bad_args3(dy, w, dx, B, Cin, Cout, H, W, n, P)) return 1;
+    const int OH = 2 * H + 2 * P - n, OW = 2 * W + 2 * P - n;
+    const int UH = 2 * H - 1 + 2 * P, UW = 2 * W - 1 + 2 * P;
+    int err = 0;
+#pragma omp parallel for schedule(dynamic, 1) reduction(| : err)
+    for (int p = 0; p < B * Cin; ++p) {
+        const int b = p / Cin, ci = p % Cin;
+        double *dU = (double *)calloc((size_t)UH * UW, sizeof(double));
+        double *aU = (double *)calloc((size_t)UH * UW, sizeof(double));
+        if (!dU || !aU) { err |= 2; free(dU); free(aU); continue; }
+        for (int co = 0; co < Cout; ++co) {
+            const double *dyp = dy + ((size_t)b * Cout + co) * OH * OW;
+            const double *wp = w + ((size_t)co * Cin + ci) * n * n;
+            for (int oy = 0; oy < OH; ++oy)
+                for (int ox = 0; ox < OW; ++ox)
+                    for (int a = 0; a < n; ++a)
+                        for (int c = 0; c < n; ++c) {
+                            const double t = dyp[(size_t)oy * OW + ox] * wp[a * n + c];
+                            dU[(size_t)(oy + a) * UW + (ox + c)] += t;
+                            aU[(size_t)(oy + a) * UW + (ox + c)] += fabs(t);
+                        }
+        }
+        for (int i = 0; i < H; ++i)
+            for (int j = 0; j < W; ++j) {
+                dx[(size_t)p * H * W + (size_t)i * W + j] = dU[(size_t)(P + 2 * i) * UW + (P + 2 * j)];
+                if (S) S[(size_t)p * H * W + (size_t)i * W + j] = aU[(size_t)(P + 2 * i) * UW + (P + 2 * j)];
+            }
+        free(dU);
+        free(aU);
+    }
+    return err;
+}
+
+int ukst_oracle_grad_weight(const double *x, const double *dy, double *dw, double *S, int B,
+                            int Cin, int Cout, int H, int W, int n, int P)
+{
+    if (bad_args3(x, dy, dw, B, Cin, Cout, H, W, n, P)) return 1;
+    const int OH = 2 * H + 2 * P - n, OW = 2 * W + 2 * P - n;
+    const int UH = 2 * H - 1 + 2 * P, UW = 2 * W - 1 + 2 * P;
+    int err = 0;
+#pragma omp parallel for schedule(dynamic, 1) reduction(| : err)
+    for (int ci = 0; ci < Cin; ++ci) {
+        double *U = (double *)malloc(sizeof(double) * (size_t)UH * UW);
+        if (!U) { err |= 2; continue; }
+        for (int co = 0; co < Cout; ++co)
+            for (int t = 0; t < n * n; ++t) {
+                dw[((size_t)co * Cin + ci) * n * n + t] = 0.0;
+                if (S) S[((size_t)co * Cin + ci) * n * n + t] = 0.0;
+            }
+        for (int b = 0; b < B; ++b) {
+            const double *xp = x + ((size_t)b * Cin + ci) * H * W;
+            memset(U, 0, sizeof(double) * (size_t)UH * UW);
+            for (int i = 0; i < H; ++i)
+                for (int j = 0; j < W; ++j)
+                    U[(size_t)(P + 2 * i) * UW + (P + 2 * j)] = xp[(size_t)i * W + j];
+            for (int co = 0; co < Cout; ++co) {
+                const double *dyp = dy + ((size_t)b * Cout + co) * OH * OW;
+                double *dwp = dw + ((size_t)co * Cin + ci) * n * n;
+                double *sp = S ? S + ((size_t)co * Cin + ci) * n * n : NULL;
+                for (int a = 0; a < n; ++a)
+                    for (int c = 0; c < n; ++c) {
+                        double acc = 0.0, mag = 0.0;
+                        for (int oy = 0; oy < OH; ++oy)
+                            for (int ox = 0; ox < OW; ++ox) {
+                                const double t = dyp[(size_t)oy * OW + ox] *
+                                                 U[(size_t)(oy + a) * UW + (ox + c)];
+                                acc += t;
+                                mag += fabs(t);
+                            }
+                        dwp[a * n + c] += acc;
+                        if (sp) sp[a * n + c] += mag;
+                    }
+            }
+        }
+        free(U);
+    }
+    return err;
+}
