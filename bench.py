@@ -11,8 +11,8 @@ Prints ONE JSON line.  Besides the contract fields it carries
                 events on the launch stream, against the 8 TB/s HBM peak),
   cpu_baseline  the fp64 CPU oracle timed on this machine's host cores on the same workload,
   per_config    the same measurements for every other benchmark configuration (each against the
-                roofline that bounds it), and for the four cfg3 generator layers chained on one
-                stream (cfg3_stack).
+                roofline that bounds it), for the four cfg3 generator layers chained on one
+                stream (cfg3_stack), and for the two gradients of the backward pass.
 """
 from __future__ import annotations
 
@@ -27,7 +27,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-PEAK_TFLOPS = {"mfma_bf16": 2500.0, "mfma_f32": 157.3, "alu_f32": 78.6}
+PEAK_TFLOPS = {"mfma_bf16": 2500.0, "mfma_f32": 157.3, "alu_f32": 78.6, "alu_f32_published": 157.3}
 LLC_BYTES = 256 << 20
 
 HEADLINE = "cfg2a"
@@ -145,6 +145,87 @@ def measure(w, steps, warmup, rotate_bytes=LLC_BYTES + (64 << 20), warm_seconds=
         "wall_ms_per_step": wall_ms / steps, "buffer_sets": nsets, "roofline": roof,
         "_data": data, "_exact_flop": exact,
     }
+
+
+def measure_backward(w, which, steps, warm_seconds=0.2, rotate_bytes=LLC_BYTES + (64 << 20)):
+    """Time `steps` launches of one gradient of workload w (which = "grad_input" | "grad_weight").
+    The kernels are vector-ALU kernels: the narrow image layers are reported against the HBM peak,
+    everything else against the fp32 vector peak.  Useful flops = 2 x the exact in-range
+    multiply-adds, the same count as the forward pass (every (pixel, tap, output) triple appears
+    once in each of the three products)."""
+    import numpy as np
+    import torch
+    from paper_2502_20493_amd import binding as ukst
+    from paper_2502_20493_amd import workloads as wl
+
+    data = wl.generate(w)
+    OH, OW = ukst.ukst_output_shape(w.H, w.W, w.n, w.P)
+    dyd = wl.generate_dy(w, (OH, OW))
+    x, k = _device_tensors(w, data)
+    if w.dtype == "bf16":
+        dy = torch.from_numpy(dyd["dy_bits"].view(np.int16)).view(torch.bfloat16).cuda()
+    else:
+        dy = torch.from_numpy(dyd["dy"]).cuda()
+    del data, dyd
+    es = 2 if w.dtype == "bf16" else 4
+    nx, nw, ny = w.B * w.Cin * w.H * w.W, w.Cout * w.Cin * w.n * w.n, w.B * w.Cout * OH * OW
+    dt = ukst.UKST_BF16_F32 if w.dtype == "bf16" else ukst.UKST_F32
+    stream = torch.cuda.current_stream()
+    sp = stream.cuda_stream
+    if which == "grad_input":
+        nbytes = ny * es + nw * es + nx * 4
+        nsets = max(1, min(8, -(-rotate_bytes // nbytes)))
+        ins = [dy] + [dy.clone() for _ in range(nsets - 1)]
+        outs = [torch.empty((w.B, w.Cin, w.H, w.W), dtype=torch.float32, device="cuda") for _ in range(nsets)]
+        ukst.ukst_conv_transpose2d_grad_input(ins[0], k, w.H, w.W, w.P, dx=outs[0], stream=stream)
+        fn = ukst.lib().ukst_conv_transpose2d_grad_input
+        calls = [functools.partial(fn, ins[j].data_ptr(), k.data_ptr(), outs[j].data_ptr(), w.B, w.Cin,
+                                   w.Cout, w.H, w.W, w.n, w.P, dt, sp) for j in range(nsets)]
+        kernel = "ukst_grad_input_kernel"
+    else:
+        nbytes = nx * es + ny * es + nw * 4
+        nsets = max(1, min(8, -(-rotate_bytes // nbytes)))
+        ins = [(x, dy)] + [(x.clone(), dy.clone()) for _ in range(nsets - 1)]
+        outs = [torch.empty((w.Cout, w.Cin, w.n, w.n), dtype=torch.float32, device="cuda") for _ in range(nsets)]
+        ukst.ukst_conv_transpose2d_grad_weight(x, dy, w.n, w.P, dw=outs[0], stream=stream)
+        fn = ukst.lib().ukst_conv_transpose2d_grad_weight
+        calls = [functools.partial(fn, ins[j][0].data_ptr(), ins[j][1].data_ptr(), outs[j].data_ptr(), w.B,
+                                   w.Cin, w.Cout, w.H, w.W, w.n, w.P, dt, sp) for j in range(nsets)]
+        kernel = "ukst_grad_weight_kernel"
+
+    def step(i):
+        if calls[i % nsets]() != 0:
+            raise RuntimeError(which + " failed")
+
+    t_w = time.perf_counter()
+    step(0)
+    torch.cuda.synchronize()
+    while time.perf_counter() - t_w < warm_seconds:
+        for i in range(4):
+            step(i)
+        torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for i in range(steps):
+        step(i)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    per_launch_s = e0.elapsed_time(e1) / 1e3 / steps
+    exact = 2 * ukst.ukst_mac_count(w.B, w.Cin, w.Cout, w.H, w.W, w.n, w.P, 0)
+    gflops, gbs = exact / per_launch_s / 1e9, nbytes / per_launch_s / 1e9
+    if BOUND.get(w.name, "hbm") == "hbm":
+        roof = {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None}
+    else:
+        peak = PEAK_TFLOPS["alu_f32_published"]
+        roof = {"bound": "alu", "achieved": round(gflops / 1e3, 2), "peak": peak, "unit": "TFLOP/s",
+                "frac": round(gflops / 1e3 / peak, 4), "traffic": None}
+    roof.update(kernel=kernel, us_per_launch=round(per_launch_s * 1e6, 2), algorithmic_bytes=nbytes)
+    return {"workload": f"{w.name} {which}",
+            "shape": f"B{w.B} {w.Cin}->{w.Cout} {w.H}x{w.W} n{w.n} P{w.P} {w.dtype}, backward pass",
+            "out": f"{w.H}x{w.W}" if which == "grad_input" else f"{w.n}x{w.n}",
+            "useful_gflops": round(gflops, 1), "gbs": round(gbs, 1), "us": round(per_launch_s * 1e6, 2),
+            "buffer_sets": nsets, "roofline": roof}
 
 
 def measure_stack(steps, warm_seconds=0.3, nsets=8):
@@ -354,6 +435,16 @@ def main():
                 if BOUND.get(name, "hbm") != "hbm":
                     r["roofline"]["measured_ceiling"] = ceilings.get(BOUND[name])
                 per.append(r)
+                torch.cuda.empty_cache()
+            # backward pass: both gradients of every configuration
+            for name in names:
+                if name == "cfg1":
+                    continue
+                for which in ("grad_input", "grad_weight"):
+                    per.append(measure_backward(wl.WORKLOADS[name], which, max(5, min(args.steps, 20))))
+                    torch.cuda.empty_cache()
+            for which in ("grad_input", "grad_weight"):
+                per.append(measure_backward(wl.WORKLOADS[HEADLINE], which, max(5, min(args.steps, 200))))
                 torch.cuda.empty_cache()
 
     line = {

@@ -5,7 +5,8 @@
  * by every call) and no call synchronises.  One kernel family takes scratch memory for the
  * duration of a call: the fp32 matrix-core path splits the input channels of layers with very few
  * output tiles over several blocks and keeps their partial outputs in memory obtained with
- * hipMallocAsync / hipFreeAsync on the caller's stream (no other allocation anywhere).
+ * hipMallocAsync / hipFreeAsync on the caller's stream; the kernel-gradient call does the same
+ * for its partial sums (no other allocation anywhere).
  *
  * What is computed (Algorithm 1 of the paper is the definition, Algorithm 2 + Eqs. 1-4 + the
  * padding rule of Sec. 3.4 are how it is evaluated):
@@ -143,6 +144,36 @@ typedef enum { UKST_ACT_NONE = 0, UKST_ACT_RELU = 1, UKST_ACT_TANH = 2 } ukst_ac
 int ukst_conv_transpose2d_bias_act(const void* x, const void* w, const float* bias, void* y, int B,
                                    int Cin, int Cout, int H, int W, int n, int P, int dtype,
                                    int act, int path, void* stream);
+
+/*
+ * Backward pass of the same layer: the gradients of  L = sum(dy * y)  for y = the transpose
+ * convolution above (Algorithm 1 is the definition; these are its adjoints).  The paper measures
+ * the forward layer only; the parity structure of Sec. 3.1 carries over: input pixel (i, j) meets
+ * output pixel (oy, ox) through tap (2i+P-oy, 2j+P-ox), so both gradients run over a stride-2
+ * lattice of dy and never touch an inserted zero:
+ *
+ *   dx[b,ci,i,j]  = sum_co sum_{a,c<n} dy[b,co,2i+P-a,2j+P-c] * w[co,ci,a,c]
+ *   dw[co,ci,a,c] = sum_b  sum_{i,j}   x[b,ci,i,j] * dy[b,co,2i+P-a,2j+P-c]
+ *
+ * with terms whose output pixel lies outside [0,OH) x [0,OW) left out.
+ *
+ *   dy      DEVICE pointer, [B][Cout][OH][OW] contiguous, read-only
+ *   w / x   DEVICE pointers with the layouts of ukst_conv_transpose2d, read-only
+ *   dx      DEVICE pointer, [B][Cin][H][W] contiguous fp32, every element overwritten
+ *   dw      DEVICE pointer, [Cout][Cin][n][n] contiguous fp32, every element overwritten
+ *   dtype   UKST_F32 (all fp32) or UKST_BF16_F32 (the two operands bf16, the gradient fp32,
+ *           fp32 accumulation); UKST_BF16_BF16 gives UKST_ERR_UNSUPPORTED
+ *   B..P, stream, alignment (element alignment only), ownership, asynchrony and error behaviour
+ *   as for ukst_conv_transpose2d; outputs must not overlap inputs.
+ *
+ * ukst_conv_transpose2d_grad_weight sums over batch and space in slices and keeps the slices'
+ * partial results in memory obtained with hipMallocAsync / hipFreeAsync on the caller's stream;
+ * the partial results are added in a fixed order (results are bit-reproducible).
+ */
+int ukst_conv_transpose2d_grad_input(const void* dy, const void* w, void* dx, int B, int Cin,
+                                     int Cout, int H, int W, int n, int P, int dtype, void* stream);
+int ukst_conv_transpose2d_grad_weight(const void* x, const void* dy, void* dw, int B, int Cin,
+                                      int Cout, int H, int W, int n, int P, int dtype, void* stream);
 
 /*
  * Name of the device kernel the given path launches for this problem, as it appears in a

@@ -20,7 +20,8 @@ UKST_ACT_NONE, UKST_ACT_RELU, UKST_ACT_TANH = 0, 1, 2
 # every symbol include/ukst.h declares
 EXPORTS = ["ukst_version", "ukst_status_string", "ukst_output_shape", "ukst_mac_count",
            "ukst_select_path", "ukst_conv_transpose2d", "ukst_conv_transpose2d_path",
-           "ukst_kernel_name", "ukst_bench_mfma_ceiling", "ukst_conv_transpose2d_bias_act"]
+           "ukst_kernel_name", "ukst_bench_mfma_ceiling", "ukst_conv_transpose2d_bias_act",
+           "ukst_conv_transpose2d_grad_input", "ukst_conv_transpose2d_grad_weight"]
 
 _lib = None
 
@@ -62,6 +63,9 @@ def lib():
         L.ukst_conv_transpose2d_bias_act.argtypes = [vp, vp, vp, vp] + [i] * 10 + [vp]
         L.ukst_conv_transpose2d_bias_act.restype = i
         L.ukst_bench_mfma_ceiling.restype = ctypes.c_double
+        for f in (L.ukst_conv_transpose2d_grad_input, L.ukst_conv_transpose2d_grad_weight):
+            f.argtypes = [vp, vp, vp] + [i] * 8 + [vp]
+            f.restype = i
         _lib = L
     return _lib
 
@@ -180,3 +184,65 @@ def ukst_conv_transpose2d(x, w, P: int, y=None, path: int = UKST_PATH_AUTO, stre
                 x.data_ptr(), w.data_ptr(), None if _bias is None else _bias.data_ptr(),
                 y.data_ptr(), B, Cin, Cout, H, W, n, P, dtype, int(_act), path, sp)))
     return y
+
+
+def _backward_operands(p0, p1):
+    import torch
+
+    if not (p0.is_cuda and p1.is_cuda and p0.is_contiguous() and p1.is_contiguous()):
+        raise ValueError("operands must be contiguous device tensors")
+    if p0.dtype != p1.dtype or p0.dtype not in (torch.float32, torch.bfloat16):
+        raise ValueError("operands must both be float32 or both bfloat16")
+    if p0.dim() != 4 or p1.dim() != 4:
+        raise ValueError("operands must be 4-D")
+    return UKST_F32 if p0.dtype == torch.float32 else UKST_BF16_F32
+
+
+def _out(t, shape, device):
+    import torch
+
+    if t is None:
+        return torch.empty(shape, dtype=torch.float32, device=device)
+    if tuple(t.shape) != tuple(shape) or t.dtype != torch.float32 or not t.is_contiguous() or not t.is_cuda:
+        raise ValueError(f"output must be a contiguous float32 device tensor {tuple(shape)}")
+    return t
+
+
+def ukst_conv_transpose2d_grad_input(dy, w, H: int, W: int, P: int, dx=None, stream=None):
+    """Marshal torch device tensors into ukst_conv_transpose2d_grad_input.
+    dy: [B,Cout,OH,OW], w: [Cout,Cin,n,n] (float32 or bfloat16) -> dx float32 [B,Cin,H,W]."""
+    import torch
+
+    dtype = _backward_operands(dy, w)
+    B, Cout = dy.shape[:2]
+    Cout2, Cin, n, n2 = w.shape
+    if Cout2 != Cout or n != n2 or tuple(dy.shape[2:]) != ukst_output_shape(H, W, n, P):
+        raise ValueError("expected dy[B,Cout,2H+2P-n,2W+2P-n] and w[Cout,Cin,n,n]")
+    dx = _out(dx, (B, Cin, H, W), dy.device)
+    if stream is None:
+        stream = torch.cuda.current_stream(dy.device)
+    sp = stream.cuda_stream if hasattr(stream, "cuda_stream") else stream
+    with torch.cuda.device(dy.device):
+        _check(int(lib().ukst_conv_transpose2d_grad_input(dy.data_ptr(), w.data_ptr(), dx.data_ptr(),
+                                                          B, Cin, Cout, H, W, n, P, dtype, sp)))
+    return dx
+
+
+def ukst_conv_transpose2d_grad_weight(x, dy, n: int, P: int, dw=None, stream=None):
+    """Marshal torch device tensors into ukst_conv_transpose2d_grad_weight.
+    x: [B,Cin,H,W], dy: [B,Cout,OH,OW] (float32 or bfloat16) -> dw float32 [Cout,Cin,n,n]."""
+    import torch
+
+    dtype = _backward_operands(x, dy)
+    B, Cin, H, W = x.shape
+    B2, Cout = dy.shape[:2]
+    if B2 != B or tuple(dy.shape[2:]) != ukst_output_shape(H, W, n, P):
+        raise ValueError("expected x[B,Cin,H,W] and dy[B,Cout,2H+2P-n,2W+2P-n]")
+    dw = _out(dw, (Cout, Cin, n, n), x.device)
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device)
+    sp = stream.cuda_stream if hasattr(stream, "cuda_stream") else stream
+    with torch.cuda.device(x.device):
+        _check(int(lib().ukst_conv_transpose2d_grad_weight(x.data_ptr(), dy.data_ptr(), dw.data_ptr(),
+                                                           B, Cin, Cout, H, W, n, P, dtype, sp)))
+    return dw

@@ -159,6 +159,40 @@ int ukst_conv_transpose2d(const void* x, const void* w, void* y, int B, int Cin,
                                       stream);
 }
 
+static int backward_checked(const void* p0, const void* p1, void* out, int B, int Cin, int Cout, int H,
+                            int W, int n, int P, int dtype)
+{
+    if (!p0 || !p1 || !out) return UKST_ERR_NULL;
+    const int st = validate_shape(B, Cin, Cout, H, W, n, P);
+    if (st != UKST_OK) return st;
+    if (dtype != UKST_F32 && dtype != UKST_BF16_F32 && dtype != UKST_BF16_BF16) return UKST_ERR_DTYPE;
+    if (dtype == UKST_BF16_BF16 || n > UKST_MAX_N) return UKST_ERR_UNSUPPORTED;  // gradients are fp32
+    const uintptr_t esz = dtype == UKST_F32 ? 4 : 2;
+    if ((((uintptr_t)p0 | (uintptr_t)p1) & (esz - 1)) || ((uintptr_t)out & 3)) return UKST_ERR_UNSUPPORTED;
+    // the kernels index every tensor with 64-bit offsets; nothing else to bound
+    return UKST_OK;
+}
+
+int ukst_conv_transpose2d_grad_input(const void* dy, const void* w, void* dx, int B, int Cin, int Cout,
+                                     int H, int W, int n, int P, int dtype, void* stream)
+{
+    const int st = backward_checked(dy, w, dx, B, Cin, Cout, H, W, n, P, dtype);
+    if (st != UKST_OK) return st;
+    const ukst::Geom g = ukst::make_geom(B, Cin, Cout, H, W, n, P);
+    return ukst::launch_grad_input(g, dy, w, (float*)dx, dtype, (hipStream_t)stream) == hipSuccess
+               ? UKST_OK : UKST_ERR_LAUNCH;
+}
+
+int ukst_conv_transpose2d_grad_weight(const void* x, const void* dy, void* dw, int B, int Cin, int Cout,
+                                      int H, int W, int n, int P, int dtype, void* stream)
+{
+    const int st = backward_checked(x, dy, dw, B, Cin, Cout, H, W, n, P, dtype);
+    if (st != UKST_OK) return st;
+    const ukst::Geom g = ukst::make_geom(B, Cin, Cout, H, W, n, P);
+    return ukst::launch_grad_weight(g, x, dy, (float*)dw, dtype, (hipStream_t)stream) == hipSuccess
+               ? UKST_OK : UKST_ERR_LAUNCH;
+}
+
 const char* ukst_kernel_name(int B, int Cin, int Cout, int H, int W, int n, int P, int dtype,
                              int path)
 {

@@ -1,0 +1,442 @@
+// Backward pass of the stride-2 transpose convolution: the two gradients of the linear map of
+// Algorithm 1 / Algorithm 2, evaluated like the forward pass without ever touching an inserted
+// zero.  (The paper measures the forward layer only; training a generator needs these too.)
+//
+// The same parity argument as in Sec. 3.1 applies in reverse: input pixel (i, j) meets output
+// pixel (oy, ox) through tap (a, c) = (2i + P - oy, 2j + P - ox), so tap row a only ever pairs an
+// input row with output rows of parity (P - a) & 1.  Hence
+//
+//   dx[b,ci,i,j]  = sum_co sum_{a,c<n} dy[b,co,2i+P-a,2j+P-c] * w[co,ci,a,c]
+//   dw[co,ci,a,c] = sum_b  sum_{i,j}   x[b,ci,i,j] * dy[b,co,2i+P-a,2j+P-c]
+//
+// (terms whose output pixel lies outside [0,OH) x [0,OW) drop out): every input pixel gathers from
+// a stride-2 lattice of dy, each of the n*n taps is used once per pixel, and the number of
+// multiply-adds equals that of the forward pass.  Both kernels stage dy tiles in LDS with rows
+// that fall outside the output filled with zeros, which is the predicate of the formulas above.
+#include "ukst_internal.h"
+
+namespace ukst {
+namespace {
+
+__device__ __forceinline__ float ld_f32(const float* p, size_t i) { return p[i]; }
+__device__ __forceinline__ float ld_f32(const uint16_t* p, size_t i) { return __uint_as_float((uint32_t)p[i] << 16); }
+
+// ------------------------------------------------------------------------------------------
+// Gradient with respect to the input.
+//
+// Block = 256 threads = TJ pixel columns x 256/TJ thread rows; a thread owns PX pixels (thread
+// rows 256/TJ apart) x CI_BLK input channels.  Thread rows enumerate (image, pixel row) pairs of
+// a tile of TB images x TI rows, so that small maps still fill the block.  Per chunk of output
+// channels the dy rows under the tile go to LDS, split by column parity so that the stride-2
+// lattice a wave reads is contiguous: dy column 2*j0 + P - (n-1) + cc sits at [cc & 1][cc >> 1].
+// The weights of the chunk go to LDS as [co][tap][CI_BLK] and are read as 16-byte broadcasts.
+struct GradInArgs {
+    GeomBase g;
+    int TJ, TI, TB;            // tile: pixel columns, pixel rows, images (powers of two)
+    int logTJ, logTI;
+    int LR, HC;                // staged dy rows per image, staged columns per parity
+    int tilesX, tilesY, tilesB, ciBlocks;
+    int coChunk;               // output channels staged per round
+};
+
+template <int N, int CI_BLK, int PX, typename TIn>
+__global__ __launch_bounds__(256) void ukst_grad_input_kernel(const TIn* __restrict__ dy,
+                                                             const TIn* __restrict__ w,
+                                                             float* __restrict__ dx, GradInArgs a)
+{
+    constexpr int NN = N * N;
+    extern __shared__ __align__(16) float lds_f[];
+    const GeomBase& g = a.g;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tileFloats = a.TB * a.LR * 2 * a.HC;  // per output channel
+    float* wl = lds_f;                               // [coChunk][NN][CI_BLK]
+    float* tile = lds_f + a.coChunk * NN * CI_BLK;   // [coChunk][TB][LR][2][HC]
+
+    int bid = blockIdx.x;
+    const int cb = bid % a.ciBlocks; bid /= a.ciBlocks;  // blocks that share a dy tile are neighbours
+    const int tx = bid % a.tilesX; bid /= a.tilesX;
+    const int ty = bid % a.tilesY; bid /= a.tilesY;
+    const int tb = bid;
+    const int ci0 = cb * CI_BLK, i0 = ty * a.TI, j0 = tx * a.TJ, b0 = tb * a.TB;
+    const int oy_base = 2 * i0 + g.P - (N - 1), ox_base = 2 * j0 + g.P - (N - 1);
+
+    const int lj = tid & (a.TJ - 1), trow = tid >> a.logTJ, rowStep = 256 >> a.logTJ;
+    int toff[PX];  // LDS offset of the pixel's (image, 2*row) origin inside a channel's tile
+#pragma unroll
+    for (int p = 0; p < PX; ++p) {
+        const int tr = trow + p * rowStep;
+        const int bl = tr >> a.logTI, li = tr & (a.TI - 1);
+        toff[p] = ((bl * a.LR + 2 * li) * 2) * a.HC + lj;
+    }
+    float acc[PX][CI_BLK];
+#pragma unroll
+    for (int p = 0; p < PX; ++p)
+#pragma unroll
+        for (int q = 0; q < CI_BLK; ++q) acc[p][q] = 0.f;
+
+    const int rowsPerCo = a.TB * a.LR, cols = 2 * a.HC;
+    for (int co0 = 0; co0 < g.Cout; co0 += a.coChunk) {
+        const int nco = g.Cout - co0 < a.coChunk ? g.Cout - co0 : a.coChunk;
+        if (co0) __syncthreads();
+        // weights of the chunk: wl[co][tap][q] = w[co0+co][ci0+q][tap], zero beyond Cin
+        for (int e = tid; e < nco * NN * CI_BLK; e += 256) {
+            const int q = e % CI_BLK, t = (e / CI_BLK) % NN, co = e / (CI_BLK * NN);
+            float v = 0.f;
+            if (ci0 + q < g.Cin) v = ld_f32(w, ((size_t)(co0 + co) * g.Cin + ci0 + q) * NN + t);
+            wl[e] = v;
+        }
+        // dy rows under the tile, one row per wave at a time; rows or columns outside the output
+        // (and images beyond the batch) are zeros
+        for (int row = wave; row < nco * rowsPerCo; row += 4) {
+            const int co = row / rowsPerCo, rem = row - co * rowsPerCo;
+            const int bl = rem / a.LR, rr = rem - bl * a.LR;
+            const int b = b0 + bl, oy = oy_base + rr;
+            const bool rv = b < g.B && oy >= 0 && oy < g.OH;
+            const size_t src = (((size_t)b * g.Cout + co0 + co) * g.OH + oy) * g.OW;
+            float* dst = tile + co * tileFloats + (bl * a.LR + rr) * cols;
+            for (int cc = lane; cc < cols; cc += 64) {
+                const int ox = ox_base + cc;
+                float v = 0.f;
+                if (rv && ox >= 0 && ox < g.OW) v = ld_f32(dy, src + ox);
+                dst[(cc & 1) * a.HC + (cc >> 1)] = v;
+            }
+        }
+        __syncthreads();
+        for (int co = 0; co < nco; ++co) {
+            const float* tc = tile + co * tileFloats;
+            const float* wc = wl + co * NN * CI_BLK;
+#pragma unroll
+            for (int ta = 0; ta < N; ++ta)
+#pragma unroll
+                for (int tcx = 0; tcx < N; ++tcx) {
+                    // tap (ta, tcx): dy row 2*li + (N-1-ta), dy column 2*lj + (N-1-tcx)
+                    const int off = ((N - 1 - ta) * 2 + ((N - 1 - tcx) & 1)) * a.HC + ((N - 1 - tcx) >> 1);
+                    float wv[CI_BLK];
+#pragma unroll
+                    for (int q4 = 0; q4 < CI_BLK; q4 += 4) {
+                        const float4 t4 = *reinterpret_cast<const float4*>(wc + (ta * N + tcx) * CI_BLK + q4);
+                        wv[q4] = t4.x; wv[q4 + 1] = t4.y; wv[q4 + 2] = t4.z; wv[q4 + 3] = t4.w;
+                    }
+#pragma unroll
+                    for (int p = 0; p < PX; ++p) {
+                        const float d = tc[toff[p] + off];
+#pragma unroll
+                        for (int q = 0; q < CI_BLK; ++q) acc[p][q] = fmaf(d, wv[q], acc[p][q]);
+                    }
+                }
+        }
+    }
+
+    const int j = j0 + lj;
+#pragma unroll
+    for (int p = 0; p < PX; ++p) {
+        const int tr = trow + p * rowStep;
+        const int b = b0 + (tr >> a.logTI), i = i0 + (tr & (a.TI - 1));
+        if (b >= g.B || i >= g.H || j >= g.W) continue;
+#pragma unroll
+        for (int q = 0; q < CI_BLK; ++q)
+            if (ci0 + q < g.Cin) dx[(((size_t)b * g.Cin + ci0 + q) * g.H + i) * g.W + j] = acc[p][q];
+    }
+}
+
+int log2_of(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
+int pow2_ceil(int v) { return 1 << log2_of(v); }
+
+template <int N, int CI_BLK, int PX, typename TIn>
+hipError_t launch_gi(const Geom& g, const void* dy, const void* w, float* dx, hipStream_t stream)
+{
+    GradInArgs a;
+    a.g = g;
+    a.TJ = pow2_ceil(g.W < 32 ? g.W : 32);
+    if (a.TJ < 4) a.TJ = 4;
+    const int TR = PX * 256 / a.TJ;
+    a.TI = pow2_ceil(g.H < TR ? g.H : TR);
+    a.TB = TR / a.TI;
+    a.logTJ = log2_of(a.TJ);
+    a.logTI = log2_of(a.TI);
+    a.LR = 2 * a.TI + N - 2 > 1 ? 2 * a.TI + N - 2 : 1;
+    a.HC = a.TJ + N / 2;
+    a.tilesX = (g.W + a.TJ - 1) / a.TJ;
+    a.tilesY = (g.H + a.TI - 1) / a.TI;
+    a.tilesB = (g.B + a.TB - 1) / a.TB;
+    a.ciBlocks = (g.Cin + CI_BLK - 1) / CI_BLK;
+    const size_t tileBytes = (size_t)a.TB * a.LR * 2 * a.HC * 4, wBytes = (size_t)N * N * CI_BLK * 4;
+    const size_t budget = 64 * 1024;
+    int cc = (int)(budget / (tileBytes + wBytes));
+    if (cc < 1) return hipErrorInvalidConfiguration;  // cannot happen for n <= 7 (a channel's tile stays below 51 KiB)
+    if (cc > 8) cc = 8;
+    if (cc > g.Cout) cc = g.Cout;
+    a.coChunk = cc;
+    const long long nb = (long long)a.tilesX * a.tilesY * a.tilesB * a.ciBlocks;
+    if (nb > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    const size_t lds = (size_t)cc * (tileBytes + wBytes);
+    hipLaunchKernelGGL((ukst_grad_input_kernel<N, CI_BLK, PX, TIn>), dim3((unsigned)nb), dim3(256), lds,
+                       stream, (const TIn*)dy, (const TIn*)w, dx, a);
+    return hipGetLastError();
+}
+
+template <int N>
+hipError_t launch_gi_n(const Geom& g, const void* dy, const void* w, float* dx, int dtype,
+                       hipStream_t stream)
+{
+    if (dtype == 1)
+        return g.Cin > 8 ? launch_gi<N, 16, 2, uint16_t>(g, dy, w, dx, stream)
+                         : launch_gi<N, 4, 2, uint16_t>(g, dy, w, dx, stream);
+    return g.Cin > 8 ? launch_gi<N, 16, 2, float>(g, dy, w, dx, stream)
+                     : launch_gi<N, 4, 2, float>(g, dy, w, dx, stream);
+}
+
+// ------------------------------------------------------------------------------------------
+// Gradient with respect to the kernel.
+//
+// A reduction over batch and space with a small result.  Block = TP x TCO x TCI threads: a thread
+// owns CO_R x CI_R (output, input) channel pairs for all n*n taps and every TP-th pixel of the
+// staged tile (TI x TJ input pixels of one image with the dy rows above them); wide layers use
+// TP = 1 and 16 x 16 channel threads, narrow layers put all 256 threads on pixels.  A block walks
+// over a slice of the tiles; lanes that differ only in their pixel share are summed with wave
+// shuffles, and every (slice, wave group) writes its partial result to its own copy of dw, which
+// ukst_sum_partials_kernel adds in a fixed order (bit-reproducible, no atomics).
+struct GradWArgs {
+    GeomBase g;
+    int TCO, TCI, PB, TP;      // threads along co, ci; PB = TCO*TCI; TP = 256 / PB
+    int logTCI, logPB;
+    int TI, TJ, logTJ;         // staged pixel tile
+    int LR, LC;                // staged dy rows / columns
+    int XS;                    // floats per staged pixel (CI_T + pad)
+    int tilesX, tilesY, nStages, stagesPerSlice, nSlices;
+    int coTiles, ciTiles;
+    int SUB;                   // partial copies a block writes (wave groups that share pairs)
+};
+
+template <int N, int CO_R, int CI_R, typename TIn>
+__global__ __launch_bounds__(256) void ukst_grad_weight_kernel(const TIn* __restrict__ x,
+                                                              const TIn* __restrict__ dy,
+                                                              float* __restrict__ part, GradWArgs a)
+{
+    constexpr int NN = N * N;
+    extern __shared__ __align__(16) float lds_f[];
+    const GeomBase& g = a.g;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int CO_T = a.TCO * CO_R, CI_T = a.TCI * CI_R;
+    float* xs = lds_f;                               // [TI*TJ][XS]
+    float* dys = lds_f + a.TI * a.TJ * a.XS;         // [CO_T][LR][LC]
+
+    int bid = blockIdx.x;
+    const int cit = bid % a.ciTiles; bid /= a.ciTiles;
+    const int cot = bid % a.coTiles; bid /= a.coTiles;
+    const int slice = bid;
+    const int co0 = cot * CO_T, ci0 = cit * CI_T;
+
+    const int q = tid & (a.PB - 1), tp = tid >> a.logPB;
+    const int tci = q & (a.TCI - 1), tco = q >> a.logTCI;
+
+    float acc[CO_R][CI_R][NN];
+#pragma unroll
+    for (int c = 0; c < CO_R; ++c)
+#pragma unroll
+        for (int k = 0; k < CI_R; ++k)
+#pragma unroll
+            for (int t = 0; t < NN; ++t) acc[c][k][t] = 0.f;
+
+    const int st_end = (slice + 1) * a.stagesPerSlice < a.nStages ? (slice + 1) * a.stagesPerSlice : a.nStages;
+    const int npix = a.TI * a.TJ, planeLR = a.LR * a.LC;
+    for (int st = slice * a.stagesPerSlice; st < st_end; ++st) {
+        int t = st;
+        const int tx = t % a.tilesX; t /= a.tilesX;
+        const int ty = t % a.tilesY; t /= a.tilesY;
+        const int b = t;
+        const int i0 = ty * a.TI, j0 = tx * a.TJ;
+        const int oy_base = 2 * i0 + g.P - (N - 1), ox_base = 2 * j0 + g.P - (N - 1);
+        __syncthreads();
+        // x tile: xs[pixel][channel], lanes along the pixel row (coalesced reads)
+        for (int e = tid; e < CI_T * npix; e += 256) {
+            const int p = e & (npix - 1), cl = e / npix;
+            const int li = p >> a.logTJ, ljx = p & (a.TJ - 1);
+            const int i = i0 + li, j = j0 + ljx, ci = ci0 + cl;
+            float v = 0.f;
+            if (ci < g.Cin && i < g.H && j < g.W) v = ld_f32(x, (((size_t)b * g.Cin + ci) * g.H + i) * g.W + j);
+            xs[p * a.XS + cl] = v;
+        }
+        // dy rows above the tile, one row per wave at a time, zeros outside the output
+        for (int row = wave; row < CO_T * a.LR; row += 4) {
+            const int col = row / a.LR, rr = row - col * a.LR;
+            const int co = co0 + col, oy = oy_base + rr;
+            const bool rv = co < g.Cout && oy >= 0 && oy < g.OH;
+            const size_t src = (((size_t)b * g.Cout + co) * g.OH + oy) * g.OW;
+            float* dst = dys + row * a.LC;
+            for (int cc = lane; cc < a.LC; cc += 64) {
+                const int ox = ox_base + cc;
+                float v = 0.f;
+                if (rv && ox >= 0 && ox < g.OW) v = ld_f32(dy, src + ox);
+                dst[cc] = v;
+            }
+        }
+        __syncthreads();
+        for (int p = tp; p < npix; p += a.TP) {
+            const int li = p >> a.logTJ, ljx = p & (a.TJ - 1);
+            float xv[CI_R];
+            const float* xp = xs + p * a.XS + tci * CI_R;
+            if constexpr (CI_R % 4 == 0) {
+#pragma unroll
+                for (int k = 0; k < CI_R; k += 4) {
+                    const float4 t4 = *reinterpret_cast<const float4*>(xp + k);
+                    xv[k] = t4.x; xv[k + 1] = t4.y; xv[k + 2] = t4.z; xv[k + 3] = t4.w;
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < CI_R; ++k) xv[k] = xp[k];
+            }
+            const float* dp = dys + (tco * CO_R) * planeLR + (2 * li) * a.LC + 2 * ljx;
+#pragma unroll
+            for (int c = 0; c < CO_R; ++c)
+#pragma unroll
+                for (int ta = 0; ta < N; ++ta)
+#pragma unroll
+                    for (int tcx = 0; tcx < N; ++tcx) {
+                        const float d = dp[c * planeLR + (N - 1 - ta) * a.LC + (N - 1 - tcx)];
+#pragma unroll
+                        for (int k = 0; k < CI_R; ++k)
+                            acc[c][k][ta * N + tcx] = fmaf(d, xv[k], acc[c][k][ta * N + tcx]);
+                    }
+        }
+    }
+
+    // lanes of a wave that hold the same channel pairs (they differ in tp only) are summed
+    for (int m = a.PB; m < 64; m <<= 1)
+#pragma unroll
+        for (int c = 0; c < CO_R; ++c)
+#pragma unroll
+            for (int k = 0; k < CI_R; ++k)
+#pragma unroll
+                for (int t = 0; t < NN; ++t) acc[c][k][t] += __shfl_xor(acc[c][k][t], m, 64);
+    if (a.PB < 64 && lane >= a.PB) return;
+    const int sub = tid >> (a.logPB > 6 ? a.logPB : 6);  // wave group: waves that share pairs differ in it
+    float* out = part + (size_t)(slice * a.SUB + sub) * g.Cout * g.Cin * NN;
+#pragma unroll
+    for (int c = 0; c < CO_R; ++c) {
+        const int co = co0 + tco * CO_R + c;
+        if (co >= g.Cout) continue;
+#pragma unroll
+        for (int k = 0; k < CI_R; ++k) {
+            const int ci = ci0 + tci * CI_R + k;
+            if (ci >= g.Cin) continue;
+#pragma unroll
+            for (int t = 0; t < NN; ++t) out[((size_t)co * g.Cin + ci) * NN + t] = acc[c][k][t];
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void ukst_sum_partials_kernel(const float* __restrict__ part,
+                                                               float* __restrict__ dw, int n, int copies)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    float s = part[i];
+    for (int k = 1; k < copies; ++k) s += part[(size_t)k * n + i];
+    dw[i] = s;
+}
+
+template <int N, int CO_R, int CI_R, typename TIn>
+hipError_t launch_gw(const Geom& g, const void* x, const void* dy, float* dw, hipStream_t stream)
+{
+    GradWArgs a;
+    a.g = g;
+    // channel threads: as many as the layer has pairs for, the rest of the block goes to pixels
+    a.TCI = pow2_ceil((g.Cin + CI_R - 1) / CI_R);
+    if (a.TCI > 16) a.TCI = 16;
+    a.TCO = pow2_ceil((g.Cout + CO_R - 1) / CO_R);
+    if (a.TCO > 16) a.TCO = 16;
+    a.PB = a.TCO * a.TCI;
+    a.TP = 256 / a.PB;
+    a.logTCI = log2_of(a.TCI);
+    a.logPB = log2_of(a.PB);
+    a.SUB = a.PB <= 64 ? 4 : a.PB == 128 ? 2 : 1;
+    const int CO_T = a.TCO * CO_R, CI_T = a.TCI * CI_R;
+    a.TJ = pow2_ceil(g.W < 32 ? g.W : 32);
+    a.logTJ = log2_of(a.TJ);
+    // pixel rows per stage: enough pixels for every pixel thread, within the LDS budget
+    a.XS = CI_T + (CI_T >= 32 ? 4 : 0);
+    a.LC = 2 * a.TJ + N - 2 > 1 ? 2 * a.TJ + N - 2 : 1;
+    const size_t budget = 64 * 1024;
+    int TI = pow2_ceil(g.H < 64 ? g.H : 64);
+    while (TI > 1 && (size_t)4 * (TI * a.TJ * a.XS + CO_T * (2 * TI + N - 2) * a.LC) > budget) TI >>= 1;
+    a.TI = TI;
+    a.LR = 2 * TI + N - 2 > 1 ? 2 * TI + N - 2 : 1;
+    const size_t lds = (size_t)4 * (TI * a.TJ * a.XS + CO_T * a.LR * a.LC);
+    if (lds > budget) return hipErrorInvalidConfiguration;
+    a.tilesX = (g.W + a.TJ - 1) / a.TJ;
+    a.tilesY = (g.H + TI - 1) / TI;
+    const long long stages = (long long)a.tilesX * a.tilesY * g.B;
+    if (stages > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    a.nStages = (int)stages;
+    a.coTiles = (g.Cout + CO_T - 1) / CO_T;
+    a.ciTiles = (g.Cin + CI_T - 1) / CI_T;
+    // slices: enough blocks to cover the chip four times (twice when most of a block's threads
+    // share channel pairs: each block then ends with a shuffle reduction that wants amortising),
+    // never more than stages
+    long long want = (a.PB >= 64 ? 1024 : 512) / ((long long)a.coTiles * a.ciTiles);
+    if (want < 1) want = 1;
+    if (want > stages) want = stages;
+    a.stagesPerSlice = (int)((stages + want - 1) / want);
+    a.nSlices = (int)((stages + a.stagesPerSlice - 1) / a.stagesPerSlice);
+    const long long nb = (long long)a.nSlices * a.coTiles * a.ciTiles;
+    if (nb > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    const int copies = a.nSlices * a.SUB;
+    const size_t elems = (size_t)g.Cout * g.Cin * N * N;
+    if (elems > 0x7fffffffu) return hipErrorInvalidConfiguration;
+    float* part = nullptr;
+    hipError_t e;
+    if ((e = hipMallocAsync((void**)&part, elems * copies * sizeof(float), stream)) != hipSuccess) return e;
+    hipLaunchKernelGGL((ukst_grad_weight_kernel<N, CO_R, CI_R, TIn>), dim3((unsigned)nb), dim3(256), lds,
+                       stream, (const TIn*)x, (const TIn*)dy, part, a);
+    e = hipGetLastError();
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(ukst_sum_partials_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0,
+                           stream, (const float*)part, dw, (int)elems, copies);
+        e = hipGetLastError();
+    }
+    const hipError_t ef = hipFreeAsync(part, stream);
+    return e != hipSuccess ? e : ef;
+}
+
+// register block per kernel side: CO_R x CI_R x n*n accumulators per thread
+template <typename TIn>
+hipError_t launch_gw_t(const Geom& g, const void* x, const void* dy, float* dw, hipStream_t stream)
+{
+    switch (g.n) {
+        case 1: return launch_gw<1, 4, 4, TIn>(g, x, dy, dw, stream);
+        case 2: return launch_gw<2, 4, 4, TIn>(g, x, dy, dw, stream);
+        case 3: return launch_gw<3, 4, 4, TIn>(g, x, dy, dw, stream);
+        case 4: return launch_gw<4, 2, 4, TIn>(g, x, dy, dw, stream);
+        case 5: return launch_gw<5, 2, 4, TIn>(g, x, dy, dw, stream);
+        case 6: return launch_gw<6, 1, 4, TIn>(g, x, dy, dw, stream);
+        case 7: return launch_gw<7, 1, 4, TIn>(g, x, dy, dw, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_grad_input(const Geom& g, const void* dy, const void* w, float* dx, int dtype,
+                             hipStream_t stream)
+{
+    switch (g.n) {
+        case 1: return launch_gi_n<1>(g, dy, w, dx, dtype, stream);
+        case 2: return launch_gi_n<2>(g, dy, w, dx, dtype, stream);
+        case 3: return launch_gi_n<3>(g, dy, w, dx, dtype, stream);
+        case 4: return launch_gi_n<4>(g, dy, w, dx, dtype, stream);
+        case 5: return launch_gi_n<5>(g, dy, w, dx, dtype, stream);
+        case 6: return launch_gi_n<6>(g, dy, w, dx, dtype, stream);
+        case 7: return launch_gi_n<7>(g, dy, w, dx, dtype, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_grad_weight(const Geom& g, const void* x, const void* dy, float* dw, int dtype,
+                              hipStream_t stream)
+{
+    return dtype == 1 ? launch_gw_t<uint16_t>(g, x, dy, dw, stream)
+                      : launch_gw_t<float>(g, x, dy, dw, stream);
+}
+
+}  // namespace ukst

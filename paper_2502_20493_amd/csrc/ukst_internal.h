@@ -113,4 +113,10 @@ hipError_t launch_mfma_f32(const Geom& g, const void* x, const void* w, float* y
 bool thin_mfma_supported(const Geom& g, int dtype);
 hipError_t launch_thin_mfma(const Geom& g, const void* x, const void* w, float* y, hipStream_t stream);
 
+// Backward pass (vector-ALU kernels, any shape; dtype 0: fp32, 1: bf16 operands, fp32 result)
+hipError_t launch_grad_input(const Geom& g, const void* dy, const void* w, float* dx, int dtype,
+                             hipStream_t stream);
+hipError_t launch_grad_weight(const Geom& g, const void* x, const void* dy, float* dw, int dtype,
+                              hipStream_t stream);
+
 }  // namespace ukst

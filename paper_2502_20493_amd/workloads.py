@@ -116,3 +116,16 @@ def generate(wl: Workload, integer: bool = False):
         xb, wb = round_to_bf16_bits(x), round_to_bf16_bits(w)
         out.update(x=bf16_bits_to_f32(xb), w=bf16_bits_to_f32(wb), x_bits=xb, w_bits=wb)
     return out
+
+
+def generate_dy(wl: Workload, out_hw, integer: bool = False):
+    """Upstream gradient for the backward pass of ``wl``: N(0,1) (or integers in {-3..3}) of shape
+    [B, Cout, *out_hw]; the caller supplies the output size.  Returns {"dy": float32 array holding
+    the values both sides consume, "dy_bits": bf16 patterns for bf16 workloads}."""
+    rd = np.random.Generator(np.random.PCG64(SEED_BASE + wl.index + 2000))
+    dy = _draw(rd, "int3" if integer else "normal", (wl.B, wl.Cout, int(out_hw[0]), int(out_hw[1])))
+    out = {"dy": dy}
+    if wl.dtype == "bf16":
+        db = round_to_bf16_bits(dy)
+        out.update(dy=bf16_bits_to_f32(db), dy_bits=db)
+    return out

@@ -58,3 +58,64 @@ def check_against_oracle(y_gpu, y_ref, S, tol, planes=None, exact=False):
     zero = s == 0
     assert (g[zero] == 0).all(), "outputs whose window meets no input must be exactly 0"
     return float(np.max(err / np.maximum(s, 1e-30)))
+
+
+def _dev(a32, bits, dtype):
+    import torch
+    if dtype == "bf16":
+        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda().contiguous()
+    return torch.from_numpy(a32).cuda().contiguous()
+
+
+def _guarded(shape, guard, sentinel):
+    import torch
+    numel = int(np.prod(shape))
+    buf = torch.full((numel + 2 * guard,), sentinel, dtype=torch.float32, device="cuda")
+    return buf, buf[guard:guard + numel].view(*shape)
+
+
+def _read_guarded(buf, shape, guard, sentinel):
+    host = buf.cpu().numpy()
+    numel = int(np.prod(shape))
+    if guard:
+        assert (host[:guard] == sentinel).all(), "wrote before the output tensor"
+        assert (host[guard + numel:] == sentinel).all(), "wrote past the output tensor"
+    return host[guard:guard + numel].reshape(shape)
+
+
+def run_gpu_grad_input(data, dyd, dtype, H, W, P, guard=0, sentinel=-777.0):
+    """dx as a numpy fp32 array, computed by the HIP library; guard bands as in run_gpu."""
+    import torch
+    dy = _dev(dyd["dy"], dyd.get("dy_bits"), dtype)
+    w = _dev(data["w"], data.get("w_bits"), dtype)
+    shape = (dy.shape[0], w.shape[1], H, W)
+    buf, dx = _guarded(shape, guard, sentinel)
+    ukst.ukst_conv_transpose2d_grad_input(dy, w, H, W, P, dx=dx)
+    torch.cuda.synchronize()
+    return _read_guarded(buf, shape, guard, sentinel)
+
+
+def run_gpu_grad_weight(data, dyd, dtype, n, P, guard=0, sentinel=-777.0):
+    """dw as a numpy fp32 array, computed by the HIP library; guard bands as in run_gpu."""
+    import torch
+    x = _dev(data["x"], data.get("x_bits"), dtype)
+    dy = _dev(dyd["dy"], dyd.get("dy_bits"), dtype)
+    shape = (dy.shape[1], x.shape[1], n, n)
+    buf, dw = _guarded(shape, guard, sentinel)
+    ukst.ukst_conv_transpose2d_grad_weight(x, dy, n, P, dw=dw)
+    torch.cuda.synchronize()
+    return _read_guarded(buf, shape, guard, sentinel)
+
+
+def check_elements(g, r, s, tol, exact=False):
+    """Element-by-element check of any gradient tensor against the oracle (same shapes)."""
+    g = np.asarray(g, dtype=np.float64)
+    assert g.shape == r.shape and np.isfinite(g).all()
+    if exact:
+        assert np.array_equal(g, r), f"max abs diff {np.abs(g - r).max()}"
+        return 0.0
+    err = np.abs(g - r)
+    assert (err <= tol * s).all(), (
+        f"worst err/S = {np.max(err / np.maximum(s, 1e-300)):.3e} (tol {tol}), max err {err.max():.3e}")
+    assert (g[s == 0] == 0).all(), "elements that meet no product must be exactly 0"
+    return float(np.max(err / np.maximum(s, 1e-30)))

@@ -75,6 +75,17 @@ def test_validation_happens_on_the_host():
     assert fused(X, W, None, Y, 1, 1, 1, 0, 4, 3, 0, 0, 0, 0, None) == ukst.UKST_ERR_SHAPE
     assert fused(X, W, None, Y, *ok_shape, 0, 9, 0, None) == ukst.UKST_ERR_UNSUPPORTED
     assert fused(X, W, X + 2, Y, *ok_shape, 0, 1, 0, None) == ukst.UKST_ERR_UNSUPPORTED
+    # the backward entry points validate the same way; gradients are fp32 only
+    for back in (ukst.lib().ukst_conv_transpose2d_grad_input, ukst.lib().ukst_conv_transpose2d_grad_weight):
+        assert back(None, W, Y, *ok_shape, 0, None) == ukst.UKST_ERR_NULL
+        assert back(X, None, Y, *ok_shape, 0, None) == ukst.UKST_ERR_NULL
+        assert back(X, W, None, *ok_shape, 0, None) == ukst.UKST_ERR_NULL
+        assert back(X, W, Y, 1, 1, 1, 4, 1, 3, 0, 0, None) == ukst.UKST_ERR_SHAPE
+        assert back(X, W, Y, *ok_shape, 5, None) == ukst.UKST_ERR_DTYPE
+        assert back(X, W, Y, *ok_shape, ukst.UKST_BF16_BF16, None) == ukst.UKST_ERR_UNSUPPORTED
+        assert back(X, W, Y, 1, 1, 1, 8, 8, ukst.UKST_MAX_N + 1, 0, 0, None) == ukst.UKST_ERR_UNSUPPORTED
+        assert back(X + 2, W, Y, *ok_shape, 0, None) == ukst.UKST_ERR_UNSUPPORTED
+        assert back(X, W, Y + 2, *ok_shape, ukst.UKST_BF16_F32, None) == ukst.UKST_ERR_UNSUPPORTED
 
 
 def _brute_macs(H, W, n, P):

@@ -1,0 +1,131 @@
+"""GPU parity of the backward pass: ukst_conv_transpose2d_grad_input / _grad_weight, called through
+the C ABI, against the fp64 CPU oracle on the same seeded inputs.  Tolerances as for the forward
+pass: fp32 max|err| <= 1e-5 * sum|products| per element, bf16 operands <= 1e-2 * sum|products|;
+integer-valued inputs must match exactly."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2502_20493_amd import binding as ukst
+from paper_2502_20493_amd import workloads as wl
+from gpu_util import TOL, check_elements, run_gpu_grad_input, run_gpu_grad_weight
+
+pytestmark = pytest.mark.gpu
+
+
+def _mk(name, idx, B, Cin, Cout, H, W, n, P, dtype="f32"):
+    return wl.Workload(name, idx, B, Cin, Cout, H, W, n, P, dtype, "normal", "normal:0.5")
+
+
+def _both(w, integer=False, guard=4096):
+    """Full-tensor parity of both gradients on workload w."""
+    print(f"case {w.name} B={w.B} Cin={w.Cin} Cout={w.Cout} H={w.H} W={w.W} n={w.n} P={w.P} "
+          f"{w.dtype} integer={integer}", flush=True)
+    data = wl.generate(w, integer=integer)
+    dyd = wl.generate_dy(w, oracle.out_shape(w.H, w.W, w.n, w.P), integer=integer)
+    dx_ref, Sx = oracle.grad_input(dyd["dy"], data["w"], w.H, w.W, w.P)
+    dx = run_gpu_grad_input(data, dyd, w.dtype, w.H, w.W, w.P, guard=guard)
+    check_elements(dx, dx_ref, Sx, TOL[w.dtype], exact=integer)
+    dw_ref, Sw = oracle.grad_weight(data["x"], dyd["dy"], w.n, w.P)
+    dw = run_gpu_grad_weight(data, dyd, w.dtype, w.n, w.P, guard=guard)
+    check_elements(dw, dw_ref, Sw, TOL[w.dtype], exact=integer)
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 5, 6, 7])
+def test_backward_edge_sweep(n):
+    idx = 0
+    for P in range(0, n + 2):
+        for (B, Cin, Cout, H, W) in [(1, 1, 1, 4, 4), (2, 3, 3, 5, 9), (1, 9, 5, 1, 37),
+                                     (1, 17, 2, 11, 1), (2, 2, 4, 33, 70), (3, 5, 3, 2, 3)]:
+            if 2 * H + 2 * P - n < 1 or 2 * W + 2 * P - n < 1:
+                continue
+            idx += 1
+            w = _mk(f"bwd_edge_n{n}", 5000 + 100 * n + idx, B, Cin, Cout, H, W, n, P)
+            _both(w, integer=True)
+            if P in (0, n // 2):
+                _both(w, integer=False)
+                _both(w.with_(dtype="bf16"), integer=False)
+
+
+@pytest.mark.parametrize("shape", [
+    (3, 20, 18, 37, 45, 5, 1), (2, 33, 65, 19, 70, 3, 0), (5, 16, 8, 8, 8, 4, 2),
+    (2, 70, 130, 9, 33, 4, 3), (1, 64, 3, 40, 40, 4, 2), (2, 3, 40, 35, 66, 3, 2),
+    (9, 12, 12, 4, 4, 4, 2), (1, 24, 20, 6, 150, 7, 3), (2, 8, 24, 70, 5, 6, 2)])
+def test_backward_several_tiles_ragged_tails(shape):
+    """Several pixel tiles, channel blocks and reduction slices, with ragged tails in every axis."""
+    B, Cin, Cout, H, W, n, P = shape
+    w = _mk("bwd_mid", 6000 + sum(shape), B, Cin, Cout, H, W, n, P)
+    _both(w, integer=True)
+    _both(w, integer=False)
+    _both(w.with_(dtype="bf16"), integer=False)
+
+
+def test_backward_cfg2_images_full_size():
+    for name in ("cfg2a", "cfg2b"):
+        _both(wl.WORKLOADS[name], guard=1 << 16)
+        _both(wl.WORKLOADS[name].with_(B=2), integer=True)
+
+
+def _sampled(w, n_planes=8, n_co=4, n_ci=4, integer=False):
+    """Full-size launch; the oracle computes a seeded sample: whole (b, ci) planes of dx (those
+    planes only depend on dy[b] and w[:, ci]) and whole (co, ci) kernels of dw (they only depend
+    on x[:, ci] and dy[:, co]), first and last always included."""
+    print(f"case {w.name} full size, sampled; integer={integer}", flush=True)
+    rng = np.random.default_rng(w.index)
+    data = wl.generate(w, integer=integer)
+    dyd = wl.generate_dy(w, oracle.out_shape(w.H, w.W, w.n, w.P), integer=integer)
+    tol = TOL[w.dtype]
+    dx = run_gpu_grad_input(data, dyd, w.dtype, w.H, w.W, w.P, guard=1 << 16)
+    planes = {(0, 0), (w.B - 1, w.Cin - 1)}
+    while len(planes) < min(n_planes, w.B * w.Cin):
+        planes.add((int(rng.integers(w.B)), int(rng.integers(w.Cin))))
+    for b, ci in sorted(planes):
+        ref, S = oracle.grad_input(dyd["dy"][b:b + 1], data["w"][:, ci:ci + 1], w.H, w.W, w.P)
+        check_elements(dx[b:b + 1, ci:ci + 1], ref, S, tol, exact=integer)
+    del dx
+    dw = run_gpu_grad_weight(data, dyd, w.dtype, w.n, w.P, guard=4096)
+    cos = sorted({0, w.Cout - 1} | set(rng.choice(w.Cout, size=min(n_co, w.Cout), replace=False).tolist()))
+    cis = sorted({0, w.Cin - 1} | set(rng.choice(w.Cin, size=min(n_ci, w.Cin), replace=False).tolist()))
+    ref, S = oracle.grad_weight(np.ascontiguousarray(data["x"][:, cis]),
+                                np.ascontiguousarray(dyd["dy"][:, cos]), w.n, w.P)
+    check_elements(dw[np.ix_(cos, cis)], ref, S, tol, exact=integer)
+
+
+@pytest.mark.parametrize("name", ["cfg3_L1", "cfg3_L2", "cfg3_L3", "cfg3_L4"])
+def test_backward_cfg3_dcgan_layers_full_size(name):
+    _sampled(wl.WORKLOADS[name])
+    _sampled(wl.WORKLOADS[name], integer=True)
+
+
+@pytest.mark.parametrize("name", ["cfg4a", "cfg4b"])
+def test_backward_cfg4_odd_output_full_size(name):
+    _sampled(wl.WORKLOADS[name])
+
+
+@pytest.mark.parametrize("name", ["cfg5a", "cfg5b"])
+def test_backward_cfg5_wide_bf16_full_size(name):
+    _sampled(wl.WORKLOADS[name], n_planes=6, n_co=3, n_ci=3)
+
+
+def test_backward_on_a_side_stream_is_bit_reproducible():
+    """Both gradients on a non-default stream, twice: identical bits (the kernel gradient adds its
+    slices in a fixed order)."""
+    import torch
+    w = _mk("bwd_stream", 7001, 4, 24, 40, 30, 30, 4, 2)
+    data = wl.generate(w)
+    OH, OW = oracle.out_shape(w.H, w.W, w.n, w.P)
+    dyd = wl.generate_dy(w, (OH, OW))
+    x, k, dy = (torch.from_numpy(a).cuda() for a in (data["x"], data["w"], dyd["dy"]))
+    st = torch.cuda.Stream()
+    outs = []
+    for _ in range(2):
+        with torch.cuda.stream(st):
+            dx = ukst.ukst_conv_transpose2d_grad_input(dy, k, w.H, w.W, w.P, stream=st)
+            dw = ukst.ukst_conv_transpose2d_grad_weight(x, dy, w.n, w.P, stream=st)
+        st.synchronize()
+        outs.append((dx.cpu().numpy(), dw.cpu().numpy()))
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+    dx_ref, Sx = oracle.grad_input(dyd["dy"], data["w"], w.H, w.W, w.P)
+    dw_ref, Sw = oracle.grad_weight(data["x"], dyd["dy"], w.n, w.P)
+    check_elements(outs[0][0], dx_ref, Sx, TOL["f32"])
+    check_elements(outs[0][1], dw_ref, Sw, TOL["f32"])
