@@ -37,6 +37,7 @@ struct GradInArgs {
     int LR, HC;                // staged dy rows per image, staged columns per parity
     int tilesX, tilesY, tilesB, ciBlocks;
     int coChunk;               // output channels staged per round
+    FastDiv dCols, dRowsPerCo, dLR;
 };
 
 template <int N, int CI_BLK, int PX, typename TIn>
@@ -47,7 +48,7 @@ __global__ __launch_bounds__(256) void ukst_grad_input_kernel(const TIn* __restr
     constexpr int NN = N * N;
     extern __shared__ __align__(16) float lds_f[];
     const GeomBase& g = a.g;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x;
     const int tileFloats = a.TB * a.LR * 2 * a.HC;  // per output channel
     float* wl = lds_f;                               // [coChunk][NN][CI_BLK]
     float* tile = lds_f + a.coChunk * NN * CI_BLK;   // [coChunk][TB][LR][2][HC]
@@ -85,21 +86,17 @@ __global__ __launch_bounds__(256) void ukst_grad_input_kernel(const TIn* __restr
             if (ci0 + q < g.Cin) v = ld_f32(w, ((size_t)(co0 + co) * g.Cin + ci0 + q) * NN + t);
             wl[e] = v;
         }
-        // dy rows under the tile, one row per wave at a time; rows or columns outside the output
-        // (and images beyond the batch) are zeros
-        for (int row = wave; row < nco * rowsPerCo; row += 4) {
-            const int co = row / rowsPerCo, rem = row - co * rowsPerCo;
-            const int bl = rem / a.LR, rr = rem - bl * a.LR;
-            const int b = b0 + bl, oy = oy_base + rr;
-            const bool rv = b < g.B && oy >= 0 && oy < g.OH;
-            const size_t src = (((size_t)b * g.Cout + co0 + co) * g.OH + oy) * g.OW;
-            float* dst = tile + co * tileFloats + (bl * a.LR + rr) * cols;
-            for (int cc = lane; cc < cols; cc += 64) {
-                const int ox = ox_base + cc;
-                float v = 0.f;
-                if (rv && ox >= 0 && ox < g.OW) v = ld_f32(dy, src + ox);
-                dst[(cc & 1) * a.HC + (cc >> 1)] = v;
-            }
+        // dy rows under the tile, lanes along the columns; rows or columns outside the output (and
+        // images beyond the batch) are zeros
+        for (int e = tid; e < nco * rowsPerCo * cols; e += 256) {
+            const int row = fdiv(e, a.dCols), cc = e - row * cols;
+            const int co = fdiv(row, a.dRowsPerCo), rem = row - co * rowsPerCo;
+            const int bl = fdiv(rem, a.dLR), rr = rem - bl * a.LR;
+            const int b = b0 + bl, oy = oy_base + rr, ox = ox_base + cc;
+            float v = 0.f;
+            if (b < g.B && oy >= 0 && oy < g.OH && ox >= 0 && ox < g.OW)
+                v = ld_f32(dy, (((size_t)b * g.Cout + co0 + co) * g.OH + oy) * g.OW + ox);
+            tile[co * tileFloats + rem * cols + (cc & 1) * a.HC + (cc >> 1)] = v;
         }
         __syncthreads();
         for (int co = 0; co < nco; ++co) {
@@ -167,6 +164,9 @@ hipError_t launch_gi(const Geom& g, const void* dy, const void* w, float* dx, hi
     if (cc > 8) cc = 8;
     if (cc > g.Cout) cc = g.Cout;
     a.coChunk = cc;
+    a.dCols = make_fastdiv((unsigned)(2 * a.HC));
+    a.dRowsPerCo = make_fastdiv((unsigned)(a.TB * a.LR));
+    a.dLR = make_fastdiv((unsigned)a.LR);
     const long long nb = (long long)a.tilesX * a.tilesY * a.tilesB * a.ciBlocks;
     if (nb > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     const size_t lds = (size_t)cc * (tileBytes + wBytes);
@@ -175,15 +175,34 @@ hipError_t launch_gi(const Geom& g, const void* dy, const void* w, float* dx, hi
     return hipGetLastError();
 }
 
+// Block count of a (CI_BLK, PX) choice: the widest register block that still gives the chip two
+// blocks per compute unit wins; small maps with many channels fall back to narrower blocks.
+long long gi_blocks(const Geom& g, int ci_blk, int px)
+{
+    int TJ = pow2_ceil(g.W < 32 ? g.W : 32);
+    if (TJ < 4) TJ = 4;
+    const int TR = px * 256 / TJ;
+    const int TI = pow2_ceil(g.H < TR ? g.H : TR), TB = TR / TI;
+    return (long long)((g.W + TJ - 1) / TJ) * ((g.H + TI - 1) / TI) * ((g.B + TB - 1) / TB) *
+           ((g.Cin + ci_blk - 1) / ci_blk);
+}
+
+template <int N, typename TIn>
+hipError_t launch_gi_t(const Geom& g, const void* dy, const void* w, float* dx, hipStream_t stream)
+{
+    if (g.Cin <= 4) return launch_gi<N, 4, 1, TIn>(g, dy, w, dx, stream);
+    if (g.Cin <= 8) return launch_gi<N, 8, 1, TIn>(g, dy, w, dx, stream);
+    if (gi_blocks(g, 16, 2) >= 512) return launch_gi<N, 16, 2, TIn>(g, dy, w, dx, stream);
+    if (gi_blocks(g, 16, 1) >= 512) return launch_gi<N, 16, 1, TIn>(g, dy, w, dx, stream);
+    return launch_gi<N, 8, 1, TIn>(g, dy, w, dx, stream);
+}
+
 template <int N>
 hipError_t launch_gi_n(const Geom& g, const void* dy, const void* w, float* dx, int dtype,
                        hipStream_t stream)
 {
-    if (dtype == 1)
-        return g.Cin > 8 ? launch_gi<N, 16, 2, uint16_t>(g, dy, w, dx, stream)
-                         : launch_gi<N, 4, 2, uint16_t>(g, dy, w, dx, stream);
-    return g.Cin > 8 ? launch_gi<N, 16, 2, float>(g, dy, w, dx, stream)
-                     : launch_gi<N, 4, 2, float>(g, dy, w, dx, stream);
+    return dtype == 1 ? launch_gi_t<N, uint16_t>(g, dy, w, dx, stream)
+                      : launch_gi_t<N, float>(g, dy, w, dx, stream);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -206,6 +225,7 @@ struct GradWArgs {
     int tilesX, tilesY, nStages, stagesPerSlice, nSlices;
     int coTiles, ciTiles;
     int SUB;                   // partial copies a block writes (wave groups that share pairs)
+    FastDiv dLC, dLR;
 };
 
 template <int N, int CO_R, int CI_R, typename TIn>
@@ -216,7 +236,7 @@ __global__ __launch_bounds__(256) void ukst_grad_weight_kernel(const TIn* __rest
     constexpr int NN = N * N;
     extern __shared__ __align__(16) float lds_f[];
     const GeomBase& g = a.g;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
     const int CO_T = a.TCO * CO_R, CI_T = a.TCI * CI_R;
     float* xs = lds_f;                               // [TI*TJ][XS]
     float* dys = lds_f + a.TI * a.TJ * a.XS;         // [CO_T][LR][LC]
@@ -257,19 +277,15 @@ __global__ __launch_bounds__(256) void ukst_grad_weight_kernel(const TIn* __rest
             if (ci < g.Cin && i < g.H && j < g.W) v = ld_f32(x, (((size_t)b * g.Cin + ci) * g.H + i) * g.W + j);
             xs[p * a.XS + cl] = v;
         }
-        // dy rows above the tile, one row per wave at a time, zeros outside the output
-        for (int row = wave; row < CO_T * a.LR; row += 4) {
-            const int col = row / a.LR, rr = row - col * a.LR;
-            const int co = co0 + col, oy = oy_base + rr;
-            const bool rv = co < g.Cout && oy >= 0 && oy < g.OH;
-            const size_t src = (((size_t)b * g.Cout + co) * g.OH + oy) * g.OW;
-            float* dst = dys + row * a.LC;
-            for (int cc = lane; cc < a.LC; cc += 64) {
-                const int ox = ox_base + cc;
-                float v = 0.f;
-                if (rv && ox >= 0 && ox < g.OW) v = ld_f32(dy, src + ox);
-                dst[cc] = v;
-            }
+        // dy rows above the tile, lanes along the columns, zeros outside the output
+        for (int e = tid; e < CO_T * planeLR; e += 256) {
+            const int row = fdiv(e, a.dLC), cc = e - row * a.LC;
+            const int col = fdiv(row, a.dLR), rr = row - col * a.LR;
+            const int co = co0 + col, oy = oy_base + rr, ox = ox_base + cc;
+            float v = 0.f;
+            if (co < g.Cout && oy >= 0 && oy < g.OH && ox >= 0 && ox < g.OW)
+                v = ld_f32(dy, (((size_t)b * g.Cout + co) * g.OH + oy) * g.OW + ox);
+            dys[e] = v;
         }
         __syncthreads();
         for (int p = tp; p < npix; p += a.TP) {
@@ -326,14 +342,27 @@ __global__ __launch_bounds__(256) void ukst_grad_weight_kernel(const TIn* __rest
     }
 }
 
+// dw[i] = sum over the partial copies, in an order that depends on (copies, R) only: the block's
+// 256 threads are 256/R elements x R lanes, lane r adds copies r, r+R, r+2R, ... in sequence, and
+// the R lane sums are added pairwise in a fixed tree.  R > 1 serves layers with few kernel
+// elements and many copies.
 __global__ __launch_bounds__(256) void ukst_sum_partials_kernel(const float* __restrict__ part,
-                                                               float* __restrict__ dw, int n, int copies)
+                                                               float* __restrict__ dw, int n, int copies,
+                                                               int logR)
 {
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= n) return;
-    float s = part[i];
-    for (int k = 1; k < copies; ++k) s += part[(size_t)k * n + i];
-    dw[i] = s;
+    __shared__ float red[256];
+    const int R = 1 << logR;
+    const int r = threadIdx.x & (R - 1);
+    const int i = blockIdx.x * (256 >> logR) + (threadIdx.x >> logR);
+    float s = 0.f;
+    if (i < n)
+        for (int k = r; k < copies; k += R) s += part[(size_t)k * n + i];
+    red[threadIdx.x] = s;
+    for (int m = R >> 1; m > 0; m >>= 1) {
+        __syncthreads();
+        if (r < m) red[threadIdx.x] += red[threadIdx.x + m];
+    }
+    if (r == 0 && i < n) dw[i] = red[threadIdx.x];
 }
 
 template <int N, int CO_R, int CI_R, typename TIn>
@@ -362,6 +391,8 @@ hipError_t launch_gw(const Geom& g, const void* x, const void* dy, float* dw, hi
     while (TI > 1 && (size_t)4 * (TI * a.TJ * a.XS + CO_T * (2 * TI + N - 2) * a.LC) > budget) TI >>= 1;
     a.TI = TI;
     a.LR = 2 * TI + N - 2 > 1 ? 2 * TI + N - 2 : 1;
+    a.dLC = make_fastdiv((unsigned)a.LC);
+    a.dLR = make_fastdiv((unsigned)a.LR);
     const size_t lds = (size_t)4 * (TI * a.TJ * a.XS + CO_T * a.LR * a.LC);
     if (lds > budget) return hipErrorInvalidConfiguration;
     a.tilesX = (g.W + a.TJ - 1) / a.TJ;
@@ -391,26 +422,42 @@ hipError_t launch_gw(const Geom& g, const void* x, const void* dy, float* dw, hi
                        stream, (const TIn*)x, (const TIn*)dy, part, a);
     e = hipGetLastError();
     if (e == hipSuccess) {
-        hipLaunchKernelGGL(ukst_sum_partials_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0,
-                           stream, (const float*)part, dw, (int)elems, copies);
+        int logR = 0;  // lanes per element: until the sum kernel has about 64k threads
+        while (logR < 8 && (elems << logR) < 65536 && (2 << logR) <= copies) ++logR;
+        const unsigned per_block = 256u >> logR;
+        hipLaunchKernelGGL(ukst_sum_partials_kernel, dim3((unsigned)((elems + per_block - 1) / per_block)),
+                           dim3(256), 0, stream, (const float*)part, dw, (int)elems, copies, logR);
         e = hipGetLastError();
     }
     const hipError_t ef = hipFreeAsync(part, stream);
     return e != hipSuccess ? e : ef;
 }
 
-// register block per kernel side: CO_R x CI_R x n*n accumulators per thread
+// register block: CO_R x CI_R channel pairs x n*n taps per thread; layers with at most four
+// channels on a side take one channel per thread there, which leaves the block's threads to the
+// pixels and keeps the closing shuffle reduction short
+template <int N, typename TIn>
+hipError_t launch_gw_n(const Geom& g, const void* x, const void* dy, float* dw, hipStream_t stream)
+{
+    constexpr int CO_W = N <= 3 ? 4 : N <= 5 ? 2 : 1;  // wide register block: CO_W x 4 pairs
+    const bool thin_o = g.Cout <= 4, thin_i = g.Cin <= 4;
+    if (thin_o && thin_i) return launch_gw<N, 1, 1, TIn>(g, x, dy, dw, stream);
+    if (thin_o) return launch_gw<N, 1, 4, TIn>(g, x, dy, dw, stream);
+    if (thin_i) return launch_gw<N, CO_W, 1, TIn>(g, x, dy, dw, stream);
+    return launch_gw<N, CO_W, 4, TIn>(g, x, dy, dw, stream);
+}
+
 template <typename TIn>
 hipError_t launch_gw_t(const Geom& g, const void* x, const void* dy, float* dw, hipStream_t stream)
 {
     switch (g.n) {
-        case 1: return launch_gw<1, 4, 4, TIn>(g, x, dy, dw, stream);
-        case 2: return launch_gw<2, 4, 4, TIn>(g, x, dy, dw, stream);
-        case 3: return launch_gw<3, 4, 4, TIn>(g, x, dy, dw, stream);
-        case 4: return launch_gw<4, 2, 4, TIn>(g, x, dy, dw, stream);
-        case 5: return launch_gw<5, 2, 4, TIn>(g, x, dy, dw, stream);
-        case 6: return launch_gw<6, 1, 4, TIn>(g, x, dy, dw, stream);
-        case 7: return launch_gw<7, 1, 4, TIn>(g, x, dy, dw, stream);
+        case 1: return launch_gw_n<1, TIn>(g, x, dy, dw, stream);
+        case 2: return launch_gw_n<2, TIn>(g, x, dy, dw, stream);
+        case 3: return launch_gw_n<3, TIn>(g, x, dy, dw, stream);
+        case 4: return launch_gw_n<4, TIn>(g, x, dy, dw, stream);
+        case 5: return launch_gw_n<5, TIn>(g, x, dy, dw, stream);
+        case 6: return launch_gw_n<6, TIn>(g, x, dy, dw, stream);
+        case 7: return launch_gw_n<7, TIn>(g, x, dy, dw, stream);
         default: return hipErrorInvalidValue;
     }
 }

@@ -70,6 +70,24 @@ __device__ __forceinline__ void with_activation(int act, F&& f)
     else f(std::integral_constant<int, 0>{});
 }
 
+// Exact division of n < 2^31 by a run-time constant: q = umulhi(n, M) >> sh.
+struct FastDiv { unsigned M; int sh; unsigned d; };
+inline FastDiv make_fastdiv(unsigned d)
+{
+    FastDiv f;
+    f.d = d; f.M = 0; f.sh = 0;
+    if (d <= 1) return f;
+    int l = 0;
+    while ((1ull << l) < d) ++l;
+    f.M = (unsigned)(((1ull << (31 + l)) / d) + 1);
+    f.sh = l - 1;
+    return f;
+}
+__device__ __forceinline__ int fdiv(int n, const FastDiv& f)
+{
+    return f.d == 1 ? n : (int)(__umulhi((unsigned)n, f.M) >> f.sh);
+}
+
 inline Geom make_geom(int B, int Cin, int Cout, int H, int W, int n, int P)
 {
     Geom g;

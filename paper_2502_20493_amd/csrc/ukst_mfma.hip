@@ -47,24 +47,6 @@ constexpr int W_PLANE = (TM + 1) * 16;  // bytes of one tap plane of a k-half (6
 constexpr int W_HALF = 16 * W_PLANE + 64;  // bytes of one k-half (16 tap planes), skewed by 4 slots
 constexpr int XS_STAGE_MAX = 40960;     // bytes reserved per activation stage buffer
 
-// Exact division of n < 2^31 by a run-time constant: q = umulhi(n, M) >> sh.
-struct FastDiv { unsigned M; int sh; unsigned d; };
-inline FastDiv make_fastdiv(unsigned d)
-{
-    FastDiv f;
-    f.d = d; f.M = 0; f.sh = 0;
-    if (d <= 1) return f;
-    int l = 0;
-    while ((1ull << l) < d) ++l;
-    f.M = (unsigned)(((1ull << (31 + l)) / d) + 1);
-    f.sh = l - 1;
-    return f;
-}
-__device__ __forceinline__ int fdiv(int n, const FastDiv& f)
-{
-    return f.d == 1 ? n : (int)(__umulhi((unsigned)n, f.M) >> f.sh);
-}
-
 struct MfmaArgs {
     GeomBase g;
     int Q;        // total quads = B * KH * KW

@@ -36,24 +36,6 @@ constexpr int PW = 65;      // floats per (k, tap) weight row in LDS: 64 channel
 constexpr int nxl_max_for(int n) { return n <= 3 ? 32 : 24; }
 constexpr int LDS_LIMIT = 160 * 1024;
 
-struct FastDiv { unsigned M; int sh; unsigned d; };
-inline FastDiv make_fastdiv(unsigned d)
-{
-    FastDiv f;
-    f.d = d; f.M = 0; f.sh = 0;
-    if (d <= 1) return f;
-    int l = 0;
-    while ((1ull << l) < d) ++l;
-    f.M = (unsigned)(((1ull << (31 + l)) / d) + 1);
-    f.sh = l - 1;
-    return f;
-}
-// exact for 0 <= n < 2^31
-__device__ __forceinline__ int fdiv(int n, const FastDiv& f)
-{
-    return f.d == 1 ? n : (int)(__umulhi((unsigned)n, f.M) >> f.sh);
-}
-
 struct F32Args {
     GeomBase g;
     int Q;       // total quads = B * KH * KW
