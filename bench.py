@@ -181,7 +181,7 @@ def measure_backward(w, which, steps, warm_seconds=0.2, rotate_bytes=LLC_BYTES +
         fn = ukst.lib().ukst_conv_transpose2d_grad_input
         calls = [functools.partial(fn, ins[j].data_ptr(), k.data_ptr(), outs[j].data_ptr(), w.B, w.Cin,
                                    w.Cout, w.H, w.W, w.n, w.P, dt, sp) for j in range(nsets)]
-        kernel = "ukst_grad_input_kernel"
+        kernel = ukst.ukst_grad_kernel_name(0, w.B, w.Cin, w.Cout, w.H, w.W, w.n, w.P, dt)
     else:
         nbytes = nx * es + ny * es + nw * 4
         nsets = max(1, min(8, -(-rotate_bytes // nbytes)))
@@ -191,7 +191,7 @@ def measure_backward(w, which, steps, warm_seconds=0.2, rotate_bytes=LLC_BYTES +
         fn = ukst.lib().ukst_conv_transpose2d_grad_weight
         calls = [functools.partial(fn, ins[j][0].data_ptr(), ins[j][1].data_ptr(), outs[j].data_ptr(), w.B,
                                    w.Cin, w.Cout, w.H, w.W, w.n, w.P, dt, sp) for j in range(nsets)]
-        kernel = "ukst_grad_weight_kernel"
+        kernel = ukst.ukst_grad_kernel_name(1, w.B, w.Cin, w.Cout, w.H, w.W, w.n, w.P, dt)
 
     def step(i):
         if calls[i % nsets]() != 0:
@@ -217,8 +217,9 @@ def measure_backward(w, which, steps, warm_seconds=0.2, rotate_bytes=LLC_BYTES +
         roof = {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None}
     else:
+        # fp32 vector peak and fp32 MFMA peak are the same published number on this chip
         peak = PEAK_TFLOPS["alu_f32_published"]
-        roof = {"bound": "alu", "achieved": round(gflops / 1e3, 2), "peak": peak, "unit": "TFLOP/s",
+        roof = {"bound": "mfma" if "mfma" in kernel else "alu", "achieved": round(gflops / 1e3, 2), "peak": peak, "unit": "TFLOP/s",
                 "frac": round(gflops / 1e3 / peak, 4), "traffic": None}
     roof.update(kernel=kernel, us_per_launch=round(per_launch_s * 1e6, 2), algorithmic_bytes=nbytes)
     return {"workload": f"{w.name} {which}",

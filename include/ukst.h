@@ -168,12 +168,26 @@ int ukst_conv_transpose2d_bias_act(const void* x, const void* w, const float* bi
  *
  * ukst_conv_transpose2d_grad_weight sums over batch and space in slices and keeps the slices'
  * partial results in memory obtained with hipMallocAsync / hipFreeAsync on the caller's stream;
- * the partial results are added in a fixed order (results are bit-reproducible).
+ * the partial results are added in a fixed order (results are bit-reproducible).  The matrix-core
+ * kernel of ukst_conv_transpose2d_grad_input takes its packed weights (and, for layers with few
+ * pixels, slices of the sum over output channels) from the same kind of memory.
  */
 int ukst_conv_transpose2d_grad_input(const void* dy, const void* w, void* dx, int B, int Cin,
                                      int Cout, int H, int W, int n, int P, int dtype, void* stream);
 int ukst_conv_transpose2d_grad_weight(const void* x, const void* dy, void* dw, int B, int Cin,
                                       int Cout, int H, int W, int n, int P, int dtype, void* stream);
+
+/*
+ * Name of the main device kernel a backward call launches for this problem (which = 0:
+ * ukst_conv_transpose2d_grad_input, 1: ukst_conv_transpose2d_grad_weight), as it appears in a
+ * profiler's kernel trace (substring match), or "" on invalid arguments.  Static storage.
+ * Wide layers (Cin >= 32, Cout >= 16) run the input gradient on the matrix cores
+ * ("ukst_grad_input_mfma_kernel", fp32 MFMA for either dtype, weights packed once per call into
+ * stream-ordered scratch, which also holds the copies of dx when the sum over output channels is
+ * split); everything else runs on the vector ALUs.
+ */
+const char* ukst_grad_kernel_name(int which, int B, int Cin, int Cout, int H, int W, int n, int P,
+                                  int dtype);
 
 /*
  * Name of the device kernel the given path launches for this problem, as it appears in a

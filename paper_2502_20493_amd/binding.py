@@ -21,7 +21,8 @@ UKST_ACT_NONE, UKST_ACT_RELU, UKST_ACT_TANH = 0, 1, 2
 EXPORTS = ["ukst_version", "ukst_status_string", "ukst_output_shape", "ukst_mac_count",
            "ukst_select_path", "ukst_conv_transpose2d", "ukst_conv_transpose2d_path",
            "ukst_kernel_name", "ukst_bench_mfma_ceiling", "ukst_conv_transpose2d_bias_act",
-           "ukst_conv_transpose2d_grad_input", "ukst_conv_transpose2d_grad_weight"]
+           "ukst_conv_transpose2d_grad_input", "ukst_conv_transpose2d_grad_weight",
+           "ukst_grad_kernel_name"]
 
 _lib = None
 
@@ -63,6 +64,7 @@ def lib():
         L.ukst_conv_transpose2d_bias_act.argtypes = [vp, vp, vp, vp] + [i] * 10 + [vp]
         L.ukst_conv_transpose2d_bias_act.restype = i
         L.ukst_bench_mfma_ceiling.restype = ctypes.c_double
+        L.ukst_grad_kernel_name.argtypes, L.ukst_grad_kernel_name.restype = [i] * 9, ctypes.c_char_p
         for f in (L.ukst_conv_transpose2d_grad_input, L.ukst_conv_transpose2d_grad_weight):
             f.argtypes = [vp, vp, vp] + [i] * 8 + [vp]
             f.restype = i
@@ -184,6 +186,10 @@ def ukst_conv_transpose2d(x, w, P: int, y=None, path: int = UKST_PATH_AUTO, stre
                 x.data_ptr(), w.data_ptr(), None if _bias is None else _bias.data_ptr(),
                 y.data_ptr(), B, Cin, Cout, H, W, n, P, dtype, int(_act), path, sp)))
     return y
+
+
+def ukst_grad_kernel_name(which: int, B, Cin, Cout, H, W, n, P, dtype) -> str:
+    return lib().ukst_grad_kernel_name(int(which), B, Cin, Cout, H, W, n, P, dtype).decode()
 
 
 def _backward_operands(p0, p1):

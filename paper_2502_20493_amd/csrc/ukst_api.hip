@@ -193,6 +193,15 @@ int ukst_conv_transpose2d_grad_weight(const void* x, const void* dy, void* dw, i
                ? UKST_OK : UKST_ERR_LAUNCH;
 }
 
+const char* ukst_grad_kernel_name(int which, int B, int Cin, int Cout, int H, int W, int n, int P,
+                                  int dtype)
+{
+    if (which != 0 && which != 1) return "";
+    if (validate_shape(B, Cin, Cout, H, W, n, P) != UKST_OK) return "";
+    if ((dtype != UKST_F32 && dtype != UKST_BF16_F32) || n > UKST_MAX_N) return "";
+    return ukst::grad_kernel_name(ukst::make_geom(B, Cin, Cout, H, W, n, P), which);
+}
+
 const char* ukst_kernel_name(int B, int Cin, int Cout, int H, int W, int n, int P, int dtype,
                              int path)
 {

@@ -175,6 +175,261 @@ hipError_t launch_gi(const Geom& g, const void* dy, const void* w, float* dx, hi
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------
+// Gradient with respect to the input on the matrix cores (wide layers, either dtype).
+//
+// The gather above is one dense product per tap: D[ci][pixel] += sum_co W_tap[ci][co] *
+// DY_tap[co][pixel], DY_tap being dy on the tap's stride-2 lattice.  v_mfma_f32_32x32x2_f32 takes
+// 32 input channels x 32 pixels of one tile row x two output channels per instruction; an fp32
+// MFMA lane holds a single K value per operand, so both fragments are plain 4-byte LDS reads of
+// consecutive addresses: the weights from a copy packed once per call as [co][tap][ci] (fp32,
+// zero padded), dy from the same parity-split tile as the vector-ALU kernel.  bf16 operands are
+// widened to fp32 on their way into LDS (exact), so one kernel serves both element types.
+// Block = 4 waves = WM (channel halves) x WP (row groups); wave tile 64 channels x 4 tile rows of
+// 32 pixels = 8 accumulator tiles; two blocks per compute unit cover each other's staging.
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+struct GiMfmaArgs {
+    GeomBase g;
+    int WM, logWM;             // waves along the input channels (1 or 2)
+    int CI_T, logC4, WS;       // channels per block, log2(CI_T / 4), LDS row stride of a tap's channels
+    int CIp, CoutP;            // padded sizes of the packed weights
+    int TJ, logTJ;             // pixel columns per tile (4..32): the 32 MFMA columns hold 32/TJ tile rows
+    int TI, TB, logTI;         // tile rows are (image, pixel row) pairs: TB images x TI rows
+    int LR, HC;
+    int tilesX, tilesY, tilesB, ciTiles;
+    int CC;                    // output channels per LDS round (even)
+    int KS, coPer;             // slices of the output-channel sum (grid.y) and channels per slice
+    FastDiv dCols, dRowsPerCo, dLR;
+};
+
+template <typename TIn>
+__global__ __launch_bounds__(256) void ukst_pack_w_kernel(const TIn* __restrict__ w, float* __restrict__ wp,
+                                                         int Cout, int Cin, int NN, int CoutP, int CIp)
+{
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (size_t)CoutP * NN * CIp) return;
+    const int ci = (int)(idx % CIp);
+    const size_t row = idx / CIp;
+    const int tap = (int)(row % NN), co = (int)(row / NN);
+    float v = 0.f;
+    if (co < Cout && ci < Cin) v = ld_f32(w, ((size_t)co * Cin + ci) * NN + tap);
+    wp[idx] = v;
+}
+
+template <int N, typename TIn>
+__global__ __launch_bounds__(256, 2) void ukst_grad_input_mfma_kernel(const TIn* __restrict__ dy,
+                                                                     const float* __restrict__ wp,
+                                                                     float* __restrict__ dx, GiMfmaArgs a)
+{
+    constexpr int NN = N * N;
+    extern __shared__ __align__(16) float lds_f[];
+    const GeomBase& g = a.g;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, kk = lane >> 5;
+    const int wm = wave & (a.WM - 1), wpx = wave >> a.logWM;
+    const int wlStride = NN * a.WS;                      // floats per output channel
+    const int tileFloats = a.TB * a.LR * 2 * a.HC;
+    float* wl = lds_f;                                   // [CC][NN][WS]
+    float* tile = lds_f + a.CC * wlStride;               // [CC][TB][LR][2][HC]
+
+    int bid = blockIdx.x;
+    const int cit = bid % a.ciTiles; bid /= a.ciTiles;   // blocks that share a dy tile are neighbours
+    const int tx = bid % a.tilesX; bid /= a.tilesX;
+    const int ty = bid % a.tilesY; bid /= a.tilesY;
+    const int tb = bid;
+    const int ci0 = cit * a.CI_T, i0 = ty * a.TI, j0 = tx * a.TJ, b0 = tb * a.TB;
+    const int oy_base = 2 * i0 + g.P - (N - 1), ox_base = 2 * j0 + g.P - (N - 1);
+
+    // MFMA column l32 = (tile row within the group, pixel column): narrow maps put several rows
+    // side by side so that all 32 columns carry pixels
+    const int lj = l32 & (a.TJ - 1), lsub = l32 >> a.logTJ, subRows = 32 >> a.logTJ;
+    int toff[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int tr = (wpx * 4 + t) * subRows + lsub;
+        const int bl = tr >> a.logTI, li = tr & (a.TI - 1);
+        toff[t] = kk * tileFloats + ((bl * a.LR + 2 * li) * 2) * a.HC + lj;
+    }
+    const int a_base = kk * wlStride + wm * 64 + l32;
+    f32x16 acc[2][4];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[mi][t][i] = 0.f;
+
+    const int rowsPerCo = a.TB * a.LR, cols = 2 * a.HC;
+    const int c4n = 1 << a.logC4;  // float4 pieces per weight row
+    const int co_begin = blockIdx.y * a.coPer;
+    const int co_end = co_begin + a.coPer < a.CoutP ? co_begin + a.coPer : a.CoutP;
+    for (int co0 = co_begin; co0 < co_end; co0 += a.CC) {
+        if (co0 != co_begin) __syncthreads();
+        for (int e = tid; e < a.CC * NN * c4n; e += 256) {
+            const int row = e >> a.logC4, c4 = e & (c4n - 1);
+            const float4 v = *reinterpret_cast<const float4*>(
+                wp + ((size_t)co0 * NN + row) * a.CIp + ci0 + 4 * c4);
+            *reinterpret_cast<float4*>(wl + row * a.WS + 4 * c4) = v;
+        }
+        for (int e = tid; e < a.CC * rowsPerCo * cols; e += 256) {
+            const int row = fdiv(e, a.dCols), cc = e - row * cols;
+            const int co = fdiv(row, a.dRowsPerCo), rem = row - co * rowsPerCo;
+            const int bl = fdiv(rem, a.dLR), rr = rem - bl * a.LR;
+            const int b = b0 + bl, oy = oy_base + rr, ox = ox_base + cc;
+            float v = 0.f;
+            if (co0 + co < g.Cout && b < g.B && oy >= 0 && oy < g.OH && ox >= 0 && ox < g.OW)
+                v = ld_f32(dy, (((size_t)b * g.Cout + co0 + co) * g.OH + oy) * g.OW + ox);
+            tile[co * tileFloats + rem * cols + (cc & 1) * a.HC + (cc >> 1)] = v;
+        }
+        __syncthreads();
+        for (int cp = 0; cp < a.CC; cp += 2) {
+            const float* wa = wl + cp * wlStride + a_base;
+            const float* tc = tile + cp * tileFloats;
+#pragma unroll
+            for (int ta = 0; ta < N; ++ta)
+#pragma unroll
+                for (int tcx = 0; tcx < N; ++tcx) {
+                    const int off = ((N - 1 - ta) * 2 + ((N - 1 - tcx) & 1)) * a.HC + ((N - 1 - tcx) >> 1);
+                    const float a0 = wa[(ta * N + tcx) * a.WS], a1 = wa[(ta * N + tcx) * a.WS + 32];
+                    float bv[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) bv[t] = tc[toff[t] + off];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        acc[0][t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, bv[t], acc[0][t], 0, 0, 0);
+                        acc[1][t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, bv[t], acc[1][t], 0, 0, 0);
+                    }
+                }
+        }
+    }
+
+    // accumulator register i of a tile: channel 8*(i/4) + 4*kk + (i%4) of its 32, MFMA column l32;
+    // slice blockIdx.y of the output-channel sum writes the blockIdx.y-th copy of dx
+    const int j = j0 + lj;
+    dx += (size_t)blockIdx.y * g.B * g.Cin * g.H * g.W;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int tr = (wpx * 4 + t) * subRows + lsub;
+        const int b = b0 + (tr >> a.logTI), i = i0 + (tr & (a.TI - 1));
+        if (b >= g.B || i >= g.H || j >= g.W) continue;
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int ci = ci0 + wm * 64 + mi * 32 + 8 * (r / 4) + 4 * kk + (r % 4);
+                if (ci < g.Cin) dx[(((size_t)b * g.Cin + ci) * g.H + i) * g.W + j] = acc[mi][t][r];
+            }
+    }
+}
+
+// dw[i] = sum over the partial copies, in an order that depends on (copies, R) only: the block's
+// 256 threads are 256/R elements x R lanes, lane r adds copies r, r+R, r+2R, ... in sequence, and
+// the R lane sums are added pairwise in a fixed tree.  R > 1 serves layers with few kernel
+// elements and many copies.
+__global__ __launch_bounds__(256) void ukst_sum_partials_kernel(const float* __restrict__ part,
+                                                               float* __restrict__ dw, int n, int copies,
+                                                               int logR)
+{
+    __shared__ float red[256];
+    const int R = 1 << logR;
+    const int r = threadIdx.x & (R - 1);
+    const int i = blockIdx.x * (256 >> logR) + (threadIdx.x >> logR);
+    float s = 0.f;
+    if (i < n)
+        for (int k = r; k < copies; k += R) s += part[(size_t)k * n + i];
+    red[threadIdx.x] = s;
+    for (int m = R >> 1; m > 0; m >>= 1) {
+        __syncthreads();
+        if (r < m) red[threadIdx.x] += red[threadIdx.x + m];
+    }
+    if (r == 0 && i < n) dw[i] = red[threadIdx.x];
+}
+
+// Fills the launch description; false if this shape is better served by the vector-ALU kernel.
+bool gi_mfma_args(const Geom& g, GiMfmaArgs& a)
+{
+    if (g.Cin < 32 || g.Cout < 16) return false;
+    const int N = g.n, NN = N * N;
+    for (int WM = (g.Cin > 64 ? 2 : 1); WM >= 1; --WM) {
+        a.g = g;
+        a.WM = WM; a.logWM = WM == 2 ? 1 : 0;
+        a.CI_T = 64 * WM; a.logC4 = WM == 2 ? 5 : 4; a.WS = a.CI_T + 4;
+        a.TJ = pow2_ceil(g.W < 32 ? g.W : 32);
+        if (a.TJ < 4) a.TJ = 4;
+        a.logTJ = log2_of(a.TJ);
+        const int TR = (16 / WM) * (32 / a.TJ);  // 4 MFMA row groups per wave, 4 / WM waves along them
+        a.TI = pow2_ceil(g.H < TR ? g.H : TR);
+        a.TB = TR / a.TI;
+        a.logTI = log2_of(a.TI);
+        a.LR = 2 * a.TI + N - 2;
+        a.HC = a.TJ + N / 2;
+        const size_t perCo = (size_t)4 * (NN * a.WS + a.TB * a.LR * 2 * a.HC);
+        int cc = (int)((76 * 1024) / perCo) & ~1;
+        if (cc > 8) cc = 8;
+        if (cc < 2) continue;
+        a.CC = cc;
+        a.CoutP = (g.Cout + cc - 1) / cc * cc;
+        a.CIp = (g.Cin + a.CI_T - 1) / a.CI_T * a.CI_T;
+        a.tilesX = (g.W + a.TJ - 1) / a.TJ;
+        a.tilesY = (g.H + a.TI - 1) / a.TI;
+        a.tilesB = (g.B + a.TB - 1) / a.TB;
+        a.ciTiles = a.CIp / a.CI_T;
+        a.dCols = make_fastdiv((unsigned)(2 * a.HC));
+        a.dRowsPerCo = make_fastdiv((unsigned)(a.TB * a.LR));
+        a.dLR = make_fastdiv((unsigned)a.LR);
+        const long long nb = (long long)a.tilesX * a.tilesY * a.tilesB * a.ciTiles;
+        if (nb > 0x7fffffffLL) return false;
+        if ((size_t)a.CoutP * NN * a.CIp > 0x7fffffffu) return false;
+        // few tiles: split the sum over output channels into slices (one copy of dx each, added in
+        // a fixed order afterwards) until the grid has two blocks per compute unit
+        int ks = 1;
+        const int rounds = a.CoutP / cc;
+        while (nb * ks < 512 && ks * 2 <= rounds && ks < 32) ks *= 2;
+        a.coPer = (rounds + ks - 1) / ks * cc;
+        a.KS = (a.CoutP + a.coPer - 1) / a.coPer;
+        if (a.KS > 1 && (size_t)g.B * g.Cin * g.H * g.W > 0x7fffffffu) { a.KS = 1; a.coPer = a.CoutP; }
+        return true;
+    }
+    return false;
+}
+
+template <int N, typename TIn>
+hipError_t launch_gi_mfma(const GiMfmaArgs& a, const void* dy, const void* w, float* dx, hipStream_t stream)
+{
+    const GeomBase& g = a.g;
+    const size_t pelems = (size_t)a.CoutP * N * N * a.CIp;
+    const size_t xelems = (size_t)g.B * g.Cin * g.H * g.W;
+    float* wp = nullptr;  // packed weights, then (split sums) the copies of dx
+    hipError_t e;
+    if ((e = hipMallocAsync((void**)&wp, (pelems + (a.KS > 1 ? xelems * a.KS : 0)) * sizeof(float),
+                            stream)) != hipSuccess)
+        return e;
+    float* part = wp + pelems;
+    hipLaunchKernelGGL((ukst_pack_w_kernel<TIn>), dim3((unsigned)((pelems + 255) / 256)), dim3(256), 0, stream,
+                       (const TIn*)w, wp, g.Cout, g.Cin, N * N, a.CoutP, a.CIp);
+    e = hipGetLastError();
+    if (e == hipSuccess) {
+        const size_t lds = (size_t)4 * a.CC * (N * N * a.WS + a.TB * a.LR * 2 * a.HC);
+        const void* kfn = (const void*)ukst_grad_input_mfma_kernel<N, TIn>;
+        e = hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e == hipSuccess) {
+            const unsigned nb = (unsigned)((long long)a.tilesX * a.tilesY * a.tilesB * a.ciTiles);
+            hipLaunchKernelGGL((ukst_grad_input_mfma_kernel<N, TIn>), dim3(nb, (unsigned)a.KS), dim3(256), lds,
+                               stream, (const TIn*)dy, (const float*)wp, a.KS > 1 ? part : dx, a);
+            e = hipGetLastError();
+        }
+        if (e == hipSuccess && a.KS > 1) {
+            hipLaunchKernelGGL(ukst_sum_partials_kernel, dim3((unsigned)((xelems + 255) / 256)), dim3(256), 0,
+                               stream, (const float*)part, dx, (int)xelems, a.KS, 0);
+            e = hipGetLastError();
+        }
+    }
+    const hipError_t ef = hipFreeAsync(wp, stream);
+    return e != hipSuccess ? e : ef;
+}
+
 // Block count of a (CI_BLK, PX) choice: the widest register block that still gives the chip two
 // blocks per compute unit wins; small maps with many channels fall back to narrower blocks.
 long long gi_blocks(const Geom& g, int ci_blk, int px)
@@ -201,6 +456,10 @@ template <int N>
 hipError_t launch_gi_n(const Geom& g, const void* dy, const void* w, float* dx, int dtype,
                        hipStream_t stream)
 {
+    GiMfmaArgs ma;
+    if (gi_mfma_args(g, ma))
+        return dtype == 1 ? launch_gi_mfma<N, uint16_t>(ma, dy, w, dx, stream)
+                          : launch_gi_mfma<N, float>(ma, dy, w, dx, stream);
     return dtype == 1 ? launch_gi_t<N, uint16_t>(g, dy, w, dx, stream)
                       : launch_gi_t<N, float>(g, dy, w, dx, stream);
 }
@@ -342,29 +601,6 @@ __global__ __launch_bounds__(256) void ukst_grad_weight_kernel(const TIn* __rest
     }
 }
 
-// dw[i] = sum over the partial copies, in an order that depends on (copies, R) only: the block's
-// 256 threads are 256/R elements x R lanes, lane r adds copies r, r+R, r+2R, ... in sequence, and
-// the R lane sums are added pairwise in a fixed tree.  R > 1 serves layers with few kernel
-// elements and many copies.
-__global__ __launch_bounds__(256) void ukst_sum_partials_kernel(const float* __restrict__ part,
-                                                               float* __restrict__ dw, int n, int copies,
-                                                               int logR)
-{
-    __shared__ float red[256];
-    const int R = 1 << logR;
-    const int r = threadIdx.x & (R - 1);
-    const int i = blockIdx.x * (256 >> logR) + (threadIdx.x >> logR);
-    float s = 0.f;
-    if (i < n)
-        for (int k = r; k < copies; k += R) s += part[(size_t)k * n + i];
-    red[threadIdx.x] = s;
-    for (int m = R >> 1; m > 0; m >>= 1) {
-        __syncthreads();
-        if (r < m) red[threadIdx.x] += red[threadIdx.x + m];
-    }
-    if (r == 0 && i < n) dw[i] = red[threadIdx.x];
-}
-
 template <int N, int CO_R, int CI_R, typename TIn>
 hipError_t launch_gw(const Geom& g, const void* x, const void* dy, float* dw, hipStream_t stream)
 {
@@ -463,6 +699,13 @@ hipError_t launch_gw_t(const Geom& g, const void* x, const void* dy, float* dw, 
 }
 
 }  // namespace
+
+const char* grad_kernel_name(const Geom& g, int which)
+{
+    if (which == 1) return "ukst_grad_weight_kernel";
+    GiMfmaArgs ma;
+    return gi_mfma_args(g, ma) ? "ukst_grad_input_mfma_kernel" : "ukst_grad_input_kernel";
+}
 
 hipError_t launch_grad_input(const Geom& g, const void* dy, const void* w, float* dx, int dtype,
                              hipStream_t stream)

@@ -50,7 +50,11 @@ def test_backward_edge_sweep(n):
 @pytest.mark.parametrize("shape", [
     (3, 20, 18, 37, 45, 5, 1), (2, 33, 65, 19, 70, 3, 0), (5, 16, 8, 8, 8, 4, 2),
     (2, 70, 130, 9, 33, 4, 3), (1, 64, 3, 40, 40, 4, 2), (2, 3, 40, 35, 66, 3, 2),
-    (9, 12, 12, 4, 4, 4, 2), (1, 24, 20, 6, 150, 7, 3), (2, 8, 24, 70, 5, 6, 2)])
+    (9, 12, 12, 4, 4, 4, 2), (1, 24, 20, 6, 150, 7, 3), (2, 8, 24, 70, 5, 6, 2),
+    # wide layers (matrix-core input gradient): narrow maps that share the MFMA columns between
+    # rows and images, split sums over the output channels, every kernel side
+    (6, 40, 24, 4, 4, 4, 2), (3, 96, 32, 7, 8, 3, 1), (2, 64, 16, 16, 16, 5, 2), (5, 32, 18, 2, 3, 2, 0),
+    (1, 32, 16, 9, 40, 7, 3), (2, 48, 17, 12, 20, 6, 1), (37, 130, 16, 1, 1, 1, 0), (2, 200, 40, 3, 70, 5, 4)])
 def test_backward_several_tiles_ragged_tails(shape):
     """Several pixel tiles, channel blocks and reduction slices, with ragged tails in every axis."""
     B, Cin, Cout, H, W, n, P = shape
