@@ -21,6 +21,29 @@ namespace {
 __device__ __forceinline__ float ld_f32(const float* p, size_t i) { return p[i]; }
 __device__ __forceinline__ float ld_f32(const uint16_t* p, size_t i) { return __uint_as_float((uint32_t)p[i] << 16); }
 
+// Staging loop of a 256-thread block: element e = tid, tid + 256, ... < total is fetched with
+// fetch(e, dst) -> value (dst = its LDS index) and written to lds[dst].  The loads of U
+// elements are all issued before the first is stored, so their latencies overlap instead of
+// adding up.
+template <int U, class Fetch>
+__device__ __forceinline__ void stage_elements(float* lds, int tid, int total, Fetch fetch)
+{
+    for (int e0 = tid; e0 < total; e0 += 256 * U) {
+        float v[U];
+        int dst[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int e = e0 + 256 * u;
+            dst[u] = -1;
+            v[u] = 0.f;
+            if (e < total) v[u] = fetch(e, dst[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (dst[u] >= 0) lds[dst[u]] = v[u];
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 // Gradient with respect to the input.
 //
@@ -80,24 +103,23 @@ __global__ __launch_bounds__(256) void ukst_grad_input_kernel(const TIn* __restr
         const int nco = g.Cout - co0 < a.coChunk ? g.Cout - co0 : a.coChunk;
         if (co0) __syncthreads();
         // weights of the chunk: wl[co][tap][q] = w[co0+co][ci0+q][tap], zero beyond Cin
-        for (int e = tid; e < nco * NN * CI_BLK; e += 256) {
+        stage_elements<4>(wl, tid, nco * NN * CI_BLK, [&](int e, int& dst) {
             const int q = e % CI_BLK, t = (e / CI_BLK) % NN, co = e / (CI_BLK * NN);
-            float v = 0.f;
-            if (ci0 + q < g.Cin) v = ld_f32(w, ((size_t)(co0 + co) * g.Cin + ci0 + q) * NN + t);
-            wl[e] = v;
-        }
+            dst = e;
+            return (ci0 + q < g.Cin)
+                       ? ld_f32(w, ((size_t)(co0 + co) * g.Cin + ci0 + q) * NN + t) : 0.f;
+        });
         // dy rows under the tile, lanes along the columns; rows or columns outside the output (and
         // images beyond the batch) are zeros
-        for (int e = tid; e < nco * rowsPerCo * cols; e += 256) {
+        stage_elements<8>(tile, tid, nco * rowsPerCo * cols, [&](int e, int& dst) {
             const int row = fdiv(e, a.dCols), cc = e - row * cols;
             const int co = fdiv(row, a.dRowsPerCo), rem = row - co * rowsPerCo;
             const int bl = fdiv(rem, a.dLR), rr = rem - bl * a.LR;
             const int b = b0 + bl, oy = oy_base + rr, ox = ox_base + cc;
-            float v = 0.f;
-            if (b < g.B && oy >= 0 && oy < g.OH && ox >= 0 && ox < g.OW)
-                v = ld_f32(dy, (((size_t)b * g.Cout + co0 + co) * g.OH + oy) * g.OW + ox);
-            tile[co * tileFloats + rem * cols + (cc & 1) * a.HC + (cc >> 1)] = v;
-        }
+            dst = co * tileFloats + rem * cols + (cc & 1) * a.HC + (cc >> 1);
+            return (b < g.B && oy >= 0 && oy < g.OH && ox >= 0 && ox < g.OW)
+                       ? ld_f32(dy, (((size_t)b * g.Cout + co0 + co) * g.OH + oy) * g.OW + ox) : 0.f;
+        });
         __syncthreads();
         for (int co = 0; co < nco; ++co) {
             const float* tc = tile + co * tileFloats;
@@ -273,16 +295,15 @@ __global__ __launch_bounds__(256, 2) void ukst_grad_input_mfma_kernel(const TIn*
                 wp + ((size_t)co0 * NN + row) * a.CIp + ci0 + 4 * c4);
             *reinterpret_cast<float4*>(wl + row * a.WS + 4 * c4) = v;
         }
-        for (int e = tid; e < a.CC * rowsPerCo * cols; e += 256) {
+        stage_elements<8>(tile, tid, a.CC * rowsPerCo * cols, [&](int e, int& dst) {
             const int row = fdiv(e, a.dCols), cc = e - row * cols;
             const int co = fdiv(row, a.dRowsPerCo), rem = row - co * rowsPerCo;
             const int bl = fdiv(rem, a.dLR), rr = rem - bl * a.LR;
             const int b = b0 + bl, oy = oy_base + rr, ox = ox_base + cc;
-            float v = 0.f;
-            if (co0 + co < g.Cout && b < g.B && oy >= 0 && oy < g.OH && ox >= 0 && ox < g.OW)
-                v = ld_f32(dy, (((size_t)b * g.Cout + co0 + co) * g.OH + oy) * g.OW + ox);
-            tile[co * tileFloats + rem * cols + (cc & 1) * a.HC + (cc >> 1)] = v;
-        }
+            dst = co * tileFloats + rem * cols + (cc & 1) * a.HC + (cc >> 1);
+            return (co0 + co < g.Cout && b < g.B && oy >= 0 && oy < g.OH && ox >= 0 && ox < g.OW)
+                       ? ld_f32(dy, (((size_t)b * g.Cout + co0 + co) * g.OH + oy) * g.OW + ox) : 0.f;
+        });
         __syncthreads();
         for (int cp = 0; cp < a.CC; cp += 2) {
             const float* wa = wl + cp * wlStride + a_base;
@@ -528,24 +549,23 @@ __global__ __launch_bounds__(256) void ukst_grad_weight_kernel(const TIn* __rest
         const int oy_base = 2 * i0 + g.P - (N - 1), ox_base = 2 * j0 + g.P - (N - 1);
         __syncthreads();
         // x tile: xs[pixel][channel], lanes along the pixel row (coalesced reads)
-        for (int e = tid; e < CI_T * npix; e += 256) {
+        stage_elements<8>(xs, tid, CI_T * npix, [&](int e, int& dst) {
             const int p = e & (npix - 1), cl = e / npix;
             const int li = p >> a.logTJ, ljx = p & (a.TJ - 1);
             const int i = i0 + li, j = j0 + ljx, ci = ci0 + cl;
-            float v = 0.f;
-            if (ci < g.Cin && i < g.H && j < g.W) v = ld_f32(x, (((size_t)b * g.Cin + ci) * g.H + i) * g.W + j);
-            xs[p * a.XS + cl] = v;
-        }
+            dst = p * a.XS + cl;
+            return (ci < g.Cin && i < g.H && j < g.W)
+                       ? ld_f32(x, (((size_t)b * g.Cin + ci) * g.H + i) * g.W + j) : 0.f;
+        });
         // dy rows above the tile, lanes along the columns, zeros outside the output
-        for (int e = tid; e < CO_T * planeLR; e += 256) {
+        stage_elements<8>(dys, tid, CO_T * planeLR, [&](int e, int& dst) {
             const int row = fdiv(e, a.dLC), cc = e - row * a.LC;
             const int col = fdiv(row, a.dLR), rr = row - col * a.LR;
             const int co = co0 + col, oy = oy_base + rr, ox = ox_base + cc;
-            float v = 0.f;
-            if (co < g.Cout && oy >= 0 && oy < g.OH && ox >= 0 && ox < g.OW)
-                v = ld_f32(dy, (((size_t)b * g.Cout + co) * g.OH + oy) * g.OW + ox);
-            dys[e] = v;
-        }
+            dst = e;
+            return (co < g.Cout && oy >= 0 && oy < g.OH && ox >= 0 && ox < g.OW)
+                       ? ld_f32(dy, (((size_t)b * g.Cout + co) * g.OH + oy) * g.OW + ox) : 0.f;
+        });
         __syncthreads();
         for (int p = tp; p < npix; p += a.TP) {
             const int li = p >> a.logTJ, ljx = p & (a.TJ - 1);
@@ -599,6 +619,222 @@ __global__ __launch_bounds__(256) void ukst_grad_weight_kernel(const TIn* __rest
             for (int t = 0; t < NN; ++t) out[((size_t)co * g.Cin + ci) * NN + t] = acc[c][k][t];
         }
     }
+}
+
+// ------------------------------------------------------------------------------------------
+// Gradient with respect to the kernel on the matrix cores (wide layers, either dtype).
+//
+// Per tap the reduction is a dense product over pixels: DW_tap[co][ci] += sum_pixel
+// DY_tap[co][pixel] * X[ci][pixel].  v_mfma_f32_32x32x2_f32 takes 32 output channels x 32 input
+// channels x two neighbouring pixels per instruction.  The n*n taps of a block's 32 x (32*NC)
+// channel tile are dealt to its four waves (tap t belongs to wave t % 4), so a wave keeps
+// ceil(n*n/4) * NC accumulator tiles and every x fragment it reads feeds all of its taps.  The
+// staged tile is TR (image, pixel row) pairs x TJ pixel columns with the dy rows above them,
+// parity-split as in the other kernels so that a tap's lattice is contiguous; per-channel strides
+// are odd so that the 32 channels of a fragment fall into 32 banks.  Blocks walk over slices of
+// the tiles and write partial results as [slice][co][tap][ci] (lanes along ci);
+// ukst_sum_taps_kernel adds the slices in a fixed order and stores dw[co][ci][tap].
+struct GwMfmaArgs {
+    GeomBase g;
+    int TJ, logTJ, TI, logTI, TB, TR, logPix;  // logPix = log2(TR * TJ)
+    int LR, HC, cols, DP, XP;
+    int tilesX, tilesY, nStages, stagesPerSlice, nSlices;
+    int coTiles, ciTiles;
+    FastDiv dCols, dRows, dLR;
+};
+
+template <int N, int NC, typename TIn>
+__global__ __launch_bounds__(256, 2) void ukst_grad_weight_mfma_kernel(const TIn* __restrict__ x,
+                                                                      const TIn* __restrict__ dy,
+                                                                      float* __restrict__ part, GwMfmaArgs a)
+{
+    constexpr int NN = N * N, TS = (NN + 3) / 4, CI_T = 32 * NC;
+    extern __shared__ __align__(16) float lds_f[];
+    const GeomBase& g = a.g;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, kk = lane >> 5;
+    float* xs = lds_f;                     // [CI_T][XP]
+    float* dys = lds_f + CI_T * a.XP;      // [32][DP]
+
+    int bid = blockIdx.x;
+    const int cit = bid % a.ciTiles; bid /= a.ciTiles;
+    const int cot = bid % a.coTiles; bid /= a.coTiles;
+    const int slice = bid;
+    const int co0 = cot * 32, ci0 = cit * CI_T;
+
+    const int nts = (NN - wave + 3) / 4;   // taps of this wave: wave, wave + 4, ...
+    int tapoff[TS];
+#pragma unroll
+    for (int ts = 0; ts < TS; ++ts) {
+        const int t = wave + 4 * ts < NN ? wave + 4 * ts : 0;
+        const int ta = t / N, tc = t % N;
+        tapoff[ts] = (N - 1 - ta) * a.cols + ((N - 1 - tc) & 1) * a.HC + ((N - 1 - tc) >> 1);
+    }
+    f32x16 acc[TS][NC];
+#pragma unroll
+    for (int ts = 0; ts < TS; ++ts)
+#pragma unroll
+        for (int nc = 0; nc < NC; ++nc)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[ts][nc][i] = 0.f;
+
+    const int npix = 1 << a.logPix, rowsPerCo = a.TB * a.LR;
+    const int a_lane = l32 * a.DP + kk, b_lane = l32 * a.XP + kk;
+    const int st_end = (slice + 1) * a.stagesPerSlice < a.nStages ? (slice + 1) * a.stagesPerSlice : a.nStages;
+    for (int st = slice * a.stagesPerSlice; st < st_end; ++st) {
+        int t = st;
+        const int tx = t % a.tilesX; t /= a.tilesX;
+        const int ty = t % a.tilesY; t /= a.tilesY;
+        const int b0 = t * a.TB, i0 = ty * a.TI, j0 = tx * a.TJ;
+        const int oy_base = 2 * i0 + g.P - (N - 1), ox_base = 2 * j0 + g.P - (N - 1);
+        __syncthreads();
+        stage_elements<8>(xs, tid, CI_T * npix, [&](int e, int& dst) {
+            const int pix = e & (npix - 1), cl = e >> a.logPix;
+            const int tr = pix >> a.logTJ, lj = pix & (a.TJ - 1);
+            const int b = b0 + (tr >> a.logTI), i = i0 + (tr & (a.TI - 1)), j = j0 + lj, ci = ci0 + cl;
+            dst = cl * a.XP + pix;
+            return (ci < g.Cin && b < g.B && i < g.H && j < g.W)
+                       ? ld_f32(x, (((size_t)b * g.Cin + ci) * g.H + i) * g.W + j) : 0.f;
+        });
+        stage_elements<8>(dys, tid, 32 * rowsPerCo * a.cols, [&](int e, int& dst) {
+            const int row = fdiv(e, a.dCols), cc = e - row * a.cols;
+            const int col = fdiv(row, a.dRows), rem = row - col * rowsPerCo;
+            const int bl = fdiv(rem, a.dLR), rr = rem - bl * a.LR;
+            const int b = b0 + bl, co = co0 + col, oy = oy_base + rr, ox = ox_base + cc;
+            dst = col * a.DP + rem * a.cols + (cc & 1) * a.HC + (cc >> 1);
+            return (co < g.Cout && b < g.B && oy >= 0 && oy < g.OH && ox >= 0 && ox < g.OW)
+                       ? ld_f32(dy, (((size_t)b * g.Cout + co) * g.OH + oy) * g.OW + ox) : 0.f;
+        });
+        __syncthreads();
+        const int wj = g.W - j0 < a.TJ ? g.W - j0 : a.TJ;
+        const int steps = (wj + 1) >> 1;
+        for (int tr = 0; tr < a.TR; ++tr) {
+            const int bl = tr >> a.logTI, li = tr & (a.TI - 1);
+            if (b0 + bl >= g.B || i0 + li >= g.H) continue;  // uniform
+            const float* ap = dys + a_lane + (bl * a.LR + 2 * li) * a.cols;
+            const float* bp = xs + b_lane + tr * a.TJ;
+            for (int sp = 0; sp < steps; ++sp) {
+                float bv[NC];
+#pragma unroll
+                for (int nc = 0; nc < NC; ++nc) bv[nc] = bp[nc * 32 * a.XP + 2 * sp];
+#pragma unroll
+                for (int ts = 0; ts < TS; ++ts) {
+                    if (ts < nts) {  // uniform
+                        const float av = ap[2 * sp + tapoff[ts]];
+#pragma unroll
+                        for (int nc = 0; nc < NC; ++nc)
+                            acc[ts][nc] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[nc], acc[ts][nc], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+
+    // accumulator register i: output channel 8*(i/4) + 4*kk + (i%4) of the 32, input channel l32
+    float* out = part + (size_t)slice * g.Cout * g.Cin * NN;
+#pragma unroll
+    for (int ts = 0; ts < TS; ++ts) {
+        if (ts >= nts) continue;
+        const int t = wave + 4 * ts;
+#pragma unroll
+        for (int nc = 0; nc < NC; ++nc) {
+            const int ci = ci0 + nc * 32 + l32;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int co = co0 + 8 * (i / 4) + 4 * kk + (i % 4);
+                if (co < g.Cout && ci < g.Cin) out[((size_t)co * NN + t) * g.Cin + ci] = acc[ts][nc][i];
+            }
+        }
+    }
+}
+
+// dw[co][ci][tap] = sum over the copies of part[copy][co][tap][ci], copies added in sequence;
+// threads run along the copies' layout (coalesced reads), the single write pass is scattered
+__global__ __launch_bounds__(256) void ukst_sum_taps_kernel(const float* __restrict__ part,
+                                                           float* __restrict__ dw, int n, int copies,
+                                                           int NN, int Cin)
+{
+    const int s = blockIdx.x * 256 + threadIdx.x;
+    if (s >= n) return;
+    float v = part[s];
+    for (int k = 1; k < copies; ++k) v += part[(size_t)k * n + s];
+    const int ci = s % Cin, r = s / Cin;
+    const int tap = r % NN, co = r / NN;
+    dw[((size_t)co * Cin + ci) * NN + tap] = v;
+}
+
+template <int NC>
+bool gw_mfma_args(const Geom& g, GwMfmaArgs& a)
+{
+    const int N = g.n, CI_T = 32 * NC;
+    if (g.Cin < 32 || g.Cout < 32 || N < 2) return false;
+    a.g = g;
+    a.TJ = pow2_ceil(g.W < 32 ? g.W : 32);
+    if (a.TJ < 2) a.TJ = 2;
+    a.logTJ = log2_of(a.TJ);
+    a.HC = a.TJ + N / 2;
+    a.cols = 2 * a.HC;
+    const size_t budget = 78 * 1024;
+    int TR = 512 / a.TJ;  // at most 512 pixels per stage
+    for (;; TR >>= 1) {
+        if (TR < 1) return false;
+        a.TI = pow2_ceil(g.H < TR ? g.H : TR);
+        a.TB = TR / a.TI;
+        a.LR = 2 * a.TI + N - 2;
+        a.DP = (a.TB * a.LR * a.cols) | 1;
+        a.XP = (TR * a.TJ) | 1;
+        if ((size_t)4 * (CI_T * a.XP + 32 * a.DP) <= budget) break;
+    }
+    a.TR = TR;
+    a.logTI = log2_of(a.TI);
+    a.logPix = log2_of(TR * a.TJ);
+    a.tilesX = (g.W + a.TJ - 1) / a.TJ;
+    a.tilesY = (g.H + a.TI - 1) / a.TI;
+    const long long stages = (long long)a.tilesX * a.tilesY * ((g.B + a.TB - 1) / a.TB);
+    if (stages > 0x7fffffffLL) return false;
+    a.nStages = (int)stages;
+    a.coTiles = (g.Cout + 31) / 32;
+    a.ciTiles = (g.Cin + CI_T - 1) / CI_T;
+    long long want = 512 / ((long long)a.coTiles * a.ciTiles);
+    if (want < 1) want = 1;
+    if (want > stages) want = stages;
+    a.stagesPerSlice = (int)((stages + want - 1) / want);
+    a.nSlices = (int)((stages + a.stagesPerSlice - 1) / a.stagesPerSlice);
+    a.dCols = make_fastdiv((unsigned)a.cols);
+    a.dRows = make_fastdiv((unsigned)(a.TB * a.LR));
+    a.dLR = make_fastdiv((unsigned)a.LR);
+    if ((size_t)g.Cout * g.Cin * N * N > 0x7fffffffu) return false;
+    return true;
+}
+
+constexpr int gw_nc(int n) { return n <= 4 ? 2 : 1; }  // accumulator tiles per tap by kernel side
+
+template <int N, typename TIn>
+hipError_t launch_gw_mfma(const GwMfmaArgs& a, const void* x, const void* dy, float* dw, hipStream_t stream)
+{
+    constexpr int NC = gw_nc(N);
+    const GeomBase& g = a.g;
+    const size_t elems = (size_t)g.Cout * g.Cin * N * N;
+    float* part = nullptr;
+    hipError_t e;
+    if ((e = hipMallocAsync((void**)&part, elems * a.nSlices * sizeof(float), stream)) != hipSuccess) return e;
+    const size_t lds = (size_t)4 * (32 * NC * a.XP + 32 * a.DP);
+    const void* kfn = (const void*)ukst_grad_weight_mfma_kernel<N, NC, TIn>;
+    e = hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e == hipSuccess) {
+        const unsigned nb = (unsigned)((long long)a.nSlices * a.coTiles * a.ciTiles);
+        hipLaunchKernelGGL((ukst_grad_weight_mfma_kernel<N, NC, TIn>), dim3(nb), dim3(256), lds, stream,
+                           (const TIn*)x, (const TIn*)dy, part, a);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(ukst_sum_taps_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, stream,
+                           (const float*)part, dw, (int)elems, a.nSlices, N * N, g.Cin);
+        e = hipGetLastError();
+    }
+    const hipError_t ef = hipFreeAsync(part, stream);
+    return e != hipSuccess ? e : ef;
 }
 
 template <int N, int CO_R, int CI_R, typename TIn>
@@ -675,6 +911,10 @@ hipError_t launch_gw(const Geom& g, const void* x, const void* dy, float* dw, hi
 template <int N, typename TIn>
 hipError_t launch_gw_n(const Geom& g, const void* x, const void* dy, float* dw, hipStream_t stream)
 {
+    if constexpr (N >= 2) {
+        GwMfmaArgs ma;
+        if (gw_mfma_args<gw_nc(N)>(g, ma)) return launch_gw_mfma<N, TIn>(ma, x, dy, dw, stream);
+    }
     constexpr int CO_W = N <= 3 ? 4 : N <= 5 ? 2 : 1;  // wide register block: CO_W x 4 pairs
     const bool thin_o = g.Cout <= 4, thin_i = g.Cin <= 4;
     if (thin_o && thin_i) return launch_gw<N, 1, 1, TIn>(g, x, dy, dw, stream);
@@ -702,7 +942,11 @@ hipError_t launch_gw_t(const Geom& g, const void* x, const void* dy, float* dw, 
 
 const char* grad_kernel_name(const Geom& g, int which)
 {
-    if (which == 1) return "ukst_grad_weight_kernel";
+    if (which == 1) {
+        GwMfmaArgs wa;
+        const bool m = g.n <= 4 ? gw_mfma_args<gw_nc(4)>(g, wa) : gw_mfma_args<gw_nc(5)>(g, wa);
+        return m ? "ukst_grad_weight_mfma_kernel" : "ukst_grad_weight_kernel";
+    }
     GiMfmaArgs ma;
     return gi_mfma_args(g, ma) ? "ukst_grad_input_mfma_kernel" : "ukst_grad_input_kernel";
 }

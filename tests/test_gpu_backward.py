@@ -54,7 +54,10 @@ def test_backward_edge_sweep(n):
     # wide layers (matrix-core input gradient): narrow maps that share the MFMA columns between
     # rows and images, split sums over the output channels, every kernel side
     (6, 40, 24, 4, 4, 4, 2), (3, 96, 32, 7, 8, 3, 1), (2, 64, 16, 16, 16, 5, 2), (5, 32, 18, 2, 3, 2, 0),
-    (1, 32, 16, 9, 40, 7, 3), (2, 48, 17, 12, 20, 6, 1), (37, 130, 16, 1, 1, 1, 0), (2, 200, 40, 3, 70, 5, 4)])
+    (1, 32, 16, 9, 40, 7, 3), (2, 48, 17, 12, 20, 6, 1), (37, 130, 16, 1, 1, 1, 0), (2, 200, 40, 3, 70, 5, 4),
+    # both channel counts wide (matrix-core kernel gradient): every kernel side it takes, odd widths
+    (2, 40, 33, 5, 6, 2, 1), (1, 33, 40, 9, 12, 7, 3), (2, 64, 32, 4, 4, 6, 2), (1, 32, 32, 3, 7, 4, 2),
+    (3, 36, 70, 1, 1, 3, 1), (2, 32, 32, 40, 45, 5, 0)])
 def test_backward_several_tiles_ragged_tails(shape):
     """Several pixel tiles, channel blocks and reduction slices, with ragged tails in every axis."""
     B, Cin, Cout, H, W, n, P = shape
