@@ -44,6 +44,77 @@ __device__ __forceinline__ void stage_elements(float* lds, int tid, int total, F
     }
 }
 
+// Four consecutive elements starting at element index i (any element alignment).
+struct Quad { float v[4]; };
+__device__ __forceinline__ Quad ld_quad(const float* p, size_t i)
+{
+    typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
+    const f4u t = *reinterpret_cast<const f4u*>(p + i);
+    return Quad{{t[0], t[1], t[2], t[3]}};
+}
+__device__ __forceinline__ Quad ld_quad(const uint16_t* p, size_t i)
+{
+    typedef unsigned u2u __attribute__((ext_vector_type(2), aligned(2)));
+    const u2u t = *reinterpret_cast<const u2u*>(p + i);
+    return Quad{{__uint_as_float(t[0] << 16), __uint_as_float(t[0] & 0xFFFF0000u),
+                 __uint_as_float(t[1] << 16), __uint_as_float(t[1] & 0xFFFF0000u)}};
+}
+
+// Stages the parity-split dy tile of a block: `nrows` rows (row = (channel, image, dy row), the
+// last two as rowsPerCo = TB * LR per channel), `cols` columns each.  A thread moves four
+// consecutive columns with one vector load (scalar loads where the four straddle the edge of the
+// tensor), columns or rows outside the output become zeros; the loads of U quads are issued
+// before the first is stored.  LDS position of column cc of a row: (cc & 1) * HC + (cc >> 1).
+struct DyTile {
+    int nrows, rowsPerCo, coStride, cols, cols4, HC, LR;
+    int co_first, co_end, b0, oy_base, ox_base;
+    FastDiv dC4, dRowsPerCo, dLR;
+};
+template <int U, typename TIn>
+__device__ __forceinline__ void stage_dy_tile(float* lds, const TIn* __restrict__ dy, const GeomBase& g,
+                                              const DyTile& t, int tid)
+{
+    const int n = t.nrows * t.cols4;
+    for (int e0 = tid; e0 < n; e0 += 256 * U) {
+        Quad q[U];
+        int dst[U], ncol[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int e = e0 + 256 * u;
+            dst[u] = -1;
+            q[u] = Quad{{0.f, 0.f, 0.f, 0.f}};
+            if (e < n) {
+                const int row = fdiv(e, t.dC4), cc = 4 * (e - row * t.cols4);
+                const int col = fdiv(row, t.dRowsPerCo), rem = row - col * t.rowsPerCo;
+                const int bl = fdiv(rem, t.dLR), rr = rem - bl * t.LR;
+                const int b = t.b0 + bl, co = t.co_first + col, oy = t.oy_base + rr, ox = t.ox_base + cc;
+                dst[u] = col * t.coStride + rem * t.cols + (cc >> 1);
+                ncol[u] = t.cols - cc;  // columns of this quad that belong to the row (2 or >= 4)
+                if (co < t.co_end && b < g.B && oy >= 0 && oy < g.OH && ox + 3 >= 0 && ox < g.OW) {
+                    const size_t src = (((size_t)b * g.Cout + co) * g.OH + oy) * g.OW;
+                    if (ox >= 0 && ox + 3 < g.OW) {
+                        q[u] = ld_quad(dy, src + ox);
+                    } else {
+#pragma unroll
+                        for (int k = 0; k < 4; ++k)
+                            if (ox + k >= 0 && ox + k < g.OW) q[u].v[k] = ld_f32(dy, src + ox + k);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (dst[u] >= 0) {
+                lds[dst[u]] = q[u].v[0];
+                lds[dst[u] + t.HC] = q[u].v[1];
+                if (ncol[u] > 2) {
+                    lds[dst[u] + 1] = q[u].v[2];
+                    lds[dst[u] + t.HC + 1] = q[u].v[3];
+                }
+            }
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 // Gradient with respect to the input.
 //
@@ -222,7 +293,8 @@ struct GiMfmaArgs {
     int tilesX, tilesY, tilesB, ciTiles;
     int CC;                    // output channels per LDS round (even)
     int KS, coPer;             // slices of the output-channel sum (grid.y) and channels per slice
-    FastDiv dCols, dRowsPerCo, dLR;
+    int cols4;                 // four-column pieces per staged dy row
+    FastDiv dC4, dRowsPerCo, dLR;
 };
 
 template <typename TIn>
@@ -295,15 +367,13 @@ __global__ __launch_bounds__(256, 2) void ukst_grad_input_mfma_kernel(const TIn*
                 wp + ((size_t)co0 * NN + row) * a.CIp + ci0 + 4 * c4);
             *reinterpret_cast<float4*>(wl + row * a.WS + 4 * c4) = v;
         }
-        stage_elements<8>(tile, tid, a.CC * rowsPerCo * cols, [&](int e, int& dst) {
-            const int row = fdiv(e, a.dCols), cc = e - row * cols;
-            const int co = fdiv(row, a.dRowsPerCo), rem = row - co * rowsPerCo;
-            const int bl = fdiv(rem, a.dLR), rr = rem - bl * a.LR;
-            const int b = b0 + bl, oy = oy_base + rr, ox = ox_base + cc;
-            dst = co * tileFloats + rem * cols + (cc & 1) * a.HC + (cc >> 1);
-            return (co0 + co < g.Cout && b < g.B && oy >= 0 && oy < g.OH && ox >= 0 && ox < g.OW)
-                       ? ld_f32(dy, (((size_t)b * g.Cout + co0 + co) * g.OH + oy) * g.OW + ox) : 0.f;
-        });
+        {
+            DyTile t;
+            t.nrows = a.CC * rowsPerCo; t.rowsPerCo = rowsPerCo; t.coStride = tileFloats; t.cols = cols;
+            t.cols4 = a.cols4; t.HC = a.HC; t.LR = a.LR; t.co_first = co0; t.co_end = g.Cout; t.b0 = b0;
+            t.oy_base = oy_base; t.ox_base = ox_base; t.dC4 = a.dC4; t.dRowsPerCo = a.dRowsPerCo; t.dLR = a.dLR;
+            stage_dy_tile<4>(tile, dy, g, t, tid);
+        }
         __syncthreads();
         for (int cp = 0; cp < a.CC; cp += 2) {
             const float* wa = wl + cp * wlStride + a_base;
@@ -397,7 +467,8 @@ bool gi_mfma_args(const Geom& g, GiMfmaArgs& a)
         a.tilesY = (g.H + a.TI - 1) / a.TI;
         a.tilesB = (g.B + a.TB - 1) / a.TB;
         a.ciTiles = a.CIp / a.CI_T;
-        a.dCols = make_fastdiv((unsigned)(2 * a.HC));
+        a.cols4 = (2 * a.HC + 3) / 4;
+        a.dC4 = make_fastdiv((unsigned)a.cols4);
         a.dRowsPerCo = make_fastdiv((unsigned)(a.TB * a.LR));
         a.dLR = make_fastdiv((unsigned)a.LR);
         const long long nb = (long long)a.tilesX * a.tilesY * a.tilesB * a.ciTiles;
@@ -640,7 +711,8 @@ struct GwMfmaArgs {
     int LR, HC, cols, DP, XP;
     int tilesX, tilesY, nStages, stagesPerSlice, nSlices;
     int coTiles, ciTiles;
-    FastDiv dCols, dRows, dLR;
+    int cols4;                 // four-column pieces per staged dy row
+    FastDiv dC4, dRows, dLR;
 };
 
 template <int N, int NC, typename TIn>
@@ -689,6 +761,42 @@ __global__ __launch_bounds__(256, 2) void ukst_grad_weight_mfma_kernel(const TIn
         const int b0 = t * a.TB, i0 = ty * a.TI, j0 = tx * a.TJ;
         const int oy_base = 2 * i0 + g.P - (N - 1), ox_base = 2 * j0 + g.P - (N - 1);
         __syncthreads();
+        if (a.logTJ >= 2) {
+            // x tile, four pixels of a row per thread (one vector load unless they straddle the row end)
+            const int nq = (CI_T * npix) >> 2;
+            for (int e0 = tid; e0 < nq; e0 += 256 * 4) {
+                Quad q[4];
+                int dst[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int e = e0 + 256 * u;
+                    dst[u] = -1;
+                    q[u] = Quad{{0.f, 0.f, 0.f, 0.f}};
+                    if (e < nq) {
+                        const int pix = (e << 2) & (npix - 1), cl = (e << 2) >> a.logPix;
+                        const int tr = pix >> a.logTJ, lj = pix & (a.TJ - 1);
+                        const int b = b0 + (tr >> a.logTI), i = i0 + (tr & (a.TI - 1)), j = j0 + lj, ci = ci0 + cl;
+                        dst[u] = cl * a.XP + pix;
+                        if (ci < g.Cin && b < g.B && i < g.H && j < g.W) {
+                            const size_t src = (((size_t)b * g.Cin + ci) * g.H + i) * g.W;
+                            if (j + 3 < g.W) {
+                                q[u] = ld_quad(x, src + j);
+                            } else {
+#pragma unroll
+                                for (int k = 0; k < 4; ++k)
+                                    if (j + k < g.W) q[u].v[k] = ld_f32(x, src + j + k);
+                            }
+                        }
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (dst[u] >= 0) {
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) xs[dst[u] + k] = q[u].v[k];
+                    }
+            }
+        } else
         stage_elements<8>(xs, tid, CI_T * npix, [&](int e, int& dst) {
             const int pix = e & (npix - 1), cl = e >> a.logPix;
             const int tr = pix >> a.logTJ, lj = pix & (a.TJ - 1);
@@ -697,38 +805,44 @@ __global__ __launch_bounds__(256, 2) void ukst_grad_weight_mfma_kernel(const TIn
             return (ci < g.Cin && b < g.B && i < g.H && j < g.W)
                        ? ld_f32(x, (((size_t)b * g.Cin + ci) * g.H + i) * g.W + j) : 0.f;
         });
-        stage_elements<8>(dys, tid, 32 * rowsPerCo * a.cols, [&](int e, int& dst) {
-            const int row = fdiv(e, a.dCols), cc = e - row * a.cols;
-            const int col = fdiv(row, a.dRows), rem = row - col * rowsPerCo;
-            const int bl = fdiv(rem, a.dLR), rr = rem - bl * a.LR;
-            const int b = b0 + bl, co = co0 + col, oy = oy_base + rr, ox = ox_base + cc;
-            dst = col * a.DP + rem * a.cols + (cc & 1) * a.HC + (cc >> 1);
-            return (co < g.Cout && b < g.B && oy >= 0 && oy < g.OH && ox >= 0 && ox < g.OW)
-                       ? ld_f32(dy, (((size_t)b * g.Cout + co) * g.OH + oy) * g.OW + ox) : 0.f;
-        });
+        {
+            DyTile t;
+            t.nrows = 32 * rowsPerCo; t.rowsPerCo = rowsPerCo; t.coStride = a.DP; t.cols = a.cols;
+            t.cols4 = a.cols4; t.HC = a.HC; t.LR = a.LR; t.co_first = co0; t.co_end = g.Cout; t.b0 = b0;
+            t.oy_base = oy_base; t.ox_base = ox_base; t.dC4 = a.dC4; t.dRowsPerCo = a.dRows; t.dLR = a.dLR;
+            stage_dy_tile<8>(dys, dy, g, t, tid);
+        }
         __syncthreads();
         const int wj = g.W - j0 < a.TJ ? g.W - j0 : a.TJ;
         const int steps = (wj + 1) >> 1;
-        for (int tr = 0; tr < a.TR; ++tr) {
-            const int bl = tr >> a.logTI, li = tr & (a.TI - 1);
-            if (b0 + bl >= g.B || i0 + li >= g.H) continue;  // uniform
-            const float* ap = dys + a_lane + (bl * a.LR + 2 * li) * a.cols;
-            const float* bp = xs + b_lane + tr * a.TJ;
-            for (int sp = 0; sp < steps; ++sp) {
-                float bv[NC];
+        // the tap count of a wave is TS or TS - 1: one branch per stage picks a loop body whose
+        // taps are unrolled, so that all fragment reads of a step are in flight before its MFMAs
+        auto rows = [&](auto nts_tag) {
+            constexpr int NTS = decltype(nts_tag)::value;
+            for (int tr = 0; tr < a.TR; ++tr) {
+                const int bl = tr >> a.logTI, li = tr & (a.TI - 1);
+                if (b0 + bl >= g.B || i0 + li >= g.H) continue;  // uniform
+                const float* ap = dys + a_lane + (bl * a.LR + 2 * li) * a.cols;
+                const float* bp = xs + b_lane + tr * a.TJ;
+                auto step = [&](int sp) {
+                    float bv[NC], av[NTS > 0 ? NTS : 1];
 #pragma unroll
-                for (int nc = 0; nc < NC; ++nc) bv[nc] = bp[nc * 32 * a.XP + 2 * sp];
+                    for (int nc = 0; nc < NC; ++nc) bv[nc] = bp[nc * 32 * a.XP + 2 * sp];
 #pragma unroll
-                for (int ts = 0; ts < TS; ++ts) {
-                    if (ts < nts) {  // uniform
-                        const float av = ap[2 * sp + tapoff[ts]];
+                    for (int ts = 0; ts < NTS; ++ts) av[ts] = ap[2 * sp + tapoff[ts]];
+#pragma unroll
+                    for (int ts = 0; ts < NTS; ++ts)
 #pragma unroll
                         for (int nc = 0; nc < NC; ++nc)
-                            acc[ts][nc] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[nc], acc[ts][nc], 0, 0, 0);
-                    }
-                }
+                            acc[ts][nc] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[ts], bv[nc], acc[ts][nc], 0, 0, 0);
+                };
+                int sp = 0;
+                for (; sp + 2 <= steps; sp += 2) { step(sp); step(sp + 1); }
+                if (sp < steps) step(sp);
             }
-        }
+        };
+        if (nts == TS) rows(std::integral_constant<int, TS>{});
+        else rows(std::integral_constant<int, TS - 1>{});
     }
 
     // accumulator register i: output channel 8*(i/4) + 4*kk + (i%4) of the 32, input channel l32
@@ -801,7 +915,8 @@ bool gw_mfma_args(const Geom& g, GwMfmaArgs& a)
     if (want > stages) want = stages;
     a.stagesPerSlice = (int)((stages + want - 1) / want);
     a.nSlices = (int)((stages + a.stagesPerSlice - 1) / a.stagesPerSlice);
-    a.dCols = make_fastdiv((unsigned)a.cols);
+    a.cols4 = (a.cols + 3) / 4;
+    a.dC4 = make_fastdiv((unsigned)a.cols4);
     a.dRows = make_fastdiv((unsigned)(a.TB * a.LR));
     a.dLR = make_fastdiv((unsigned)a.LR);
     if ((size_t)g.Cout * g.Cin * N * N > 0x7fffffffu) return false;
