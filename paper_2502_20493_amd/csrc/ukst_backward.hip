@@ -131,7 +131,8 @@ struct GradInArgs {
     int LR, HC;                // staged dy rows per image, staged columns per parity
     int tilesX, tilesY, tilesB, ciBlocks;
     int coChunk;               // output channels staged per round
-    FastDiv dCols, dRowsPerCo, dLR;
+    int cols4;                 // four-column pieces per staged dy row
+    FastDiv dC4, dRowsPerCo, dLR;
 };
 
 template <int N, int CI_BLK, int PX, typename TIn>
@@ -182,15 +183,13 @@ __global__ __launch_bounds__(256) void ukst_grad_input_kernel(const TIn* __restr
         });
         // dy rows under the tile, lanes along the columns; rows or columns outside the output (and
         // images beyond the batch) are zeros
-        stage_elements<8>(tile, tid, nco * rowsPerCo * cols, [&](int e, int& dst) {
-            const int row = fdiv(e, a.dCols), cc = e - row * cols;
-            const int co = fdiv(row, a.dRowsPerCo), rem = row - co * rowsPerCo;
-            const int bl = fdiv(rem, a.dLR), rr = rem - bl * a.LR;
-            const int b = b0 + bl, oy = oy_base + rr, ox = ox_base + cc;
-            dst = co * tileFloats + rem * cols + (cc & 1) * a.HC + (cc >> 1);
-            return (b < g.B && oy >= 0 && oy < g.OH && ox >= 0 && ox < g.OW)
-                       ? ld_f32(dy, (((size_t)b * g.Cout + co0 + co) * g.OH + oy) * g.OW + ox) : 0.f;
-        });
+        {
+            DyTile t;
+            t.nrows = nco * rowsPerCo; t.rowsPerCo = rowsPerCo; t.coStride = tileFloats; t.cols = cols;
+            t.cols4 = a.cols4; t.HC = a.HC; t.LR = a.LR; t.co_first = co0; t.co_end = g.Cout; t.b0 = b0;
+            t.oy_base = oy_base; t.ox_base = ox_base; t.dC4 = a.dC4; t.dRowsPerCo = a.dRowsPerCo; t.dLR = a.dLR;
+            stage_dy_tile<4>(tile, dy, g, t, tid);
+        }
         __syncthreads();
         for (int co = 0; co < nco; ++co) {
             const float* tc = tile + co * tileFloats;
@@ -257,7 +256,8 @@ hipError_t launch_gi(const Geom& g, const void* dy, const void* w, float* dx, hi
     if (cc > 8) cc = 8;
     if (cc > g.Cout) cc = g.Cout;
     a.coChunk = cc;
-    a.dCols = make_fastdiv((unsigned)(2 * a.HC));
+    a.cols4 = (2 * a.HC + 3) / 4;
+    a.dC4 = make_fastdiv((unsigned)a.cols4);
     a.dRowsPerCo = make_fastdiv((unsigned)(a.TB * a.LR));
     a.dLR = make_fastdiv((unsigned)a.LR);
     const long long nb = (long long)a.tilesX * a.tilesY * a.tilesB * a.ciBlocks;
@@ -576,7 +576,8 @@ struct GradWArgs {
     int tilesX, tilesY, nStages, stagesPerSlice, nSlices;
     int coTiles, ciTiles;
     int SUB;                   // partial copies a block writes (wave groups that share pairs)
-    FastDiv dLC, dLR;
+    int LC4;                   // four-column pieces per staged dy row
+    FastDiv dLC4, dLR;
 };
 
 template <int N, int CO_R, int CI_R, typename TIn>
@@ -620,23 +621,88 @@ __global__ __launch_bounds__(256) void ukst_grad_weight_kernel(const TIn* __rest
         const int oy_base = 2 * i0 + g.P - (N - 1), ox_base = 2 * j0 + g.P - (N - 1);
         __syncthreads();
         // x tile: xs[pixel][channel], lanes along the pixel row (coalesced reads)
-        stage_elements<8>(xs, tid, CI_T * npix, [&](int e, int& dst) {
-            const int p = e & (npix - 1), cl = e / npix;
-            const int li = p >> a.logTJ, ljx = p & (a.TJ - 1);
-            const int i = i0 + li, j = j0 + ljx, ci = ci0 + cl;
-            dst = p * a.XS + cl;
-            return (ci < g.Cin && i < g.H && j < g.W)
-                       ? ld_f32(x, (((size_t)b * g.Cin + ci) * g.H + i) * g.W + j) : 0.f;
-        });
-        // dy rows above the tile, lanes along the columns, zeros outside the output
-        stage_elements<8>(dys, tid, CO_T * planeLR, [&](int e, int& dst) {
-            const int row = fdiv(e, a.dLC), cc = e - row * a.LC;
-            const int col = fdiv(row, a.dLR), rr = row - col * a.LR;
-            const int co = co0 + col, oy = oy_base + rr, ox = ox_base + cc;
-            dst = e;
-            return (co < g.Cout && oy >= 0 && oy < g.OH && ox >= 0 && ox < g.OW)
-                       ? ld_f32(dy, (((size_t)b * g.Cout + co) * g.OH + oy) * g.OW + ox) : 0.f;
-        });
+        // x tile as xs[pixel][channel] and the dy rows above it as dys[channel][row][column]; a
+        // thread moves four consecutive pixels / columns with one vector load (scalar loads where
+        // they straddle the end of a row), everything outside the tensors becomes zeros
+        {
+            const int nq = a.TJ >= 4 ? (CI_T * npix) >> 2 : 0;
+            for (int e0 = tid; e0 < nq; e0 += 256 * 4) {
+                Quad q[4];
+                int dst[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int e = e0 + 256 * u;
+                    dst[u] = -1;
+                    q[u] = Quad{{0.f, 0.f, 0.f, 0.f}};
+                    if (e < nq) {
+                        const int p = (e << 2) & (npix - 1), cl = (e << 2) / npix;
+                        const int li = p >> a.logTJ, ljx = p & (a.TJ - 1);
+                        const int i = i0 + li, j = j0 + ljx, ci = ci0 + cl;
+                        dst[u] = p * a.XS + cl;
+                        if (ci < g.Cin && i < g.H && j < g.W) {
+                            const size_t src = (((size_t)b * g.Cin + ci) * g.H + i) * g.W;
+                            if (j + 3 < g.W) {
+                                q[u] = ld_quad(x, src + j);
+                            } else {
+#pragma unroll
+                                for (int k = 0; k < 4; ++k)
+                                    if (j + k < g.W) q[u].v[k] = ld_f32(x, src + j + k);
+                            }
+                        }
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (dst[u] >= 0) {
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) xs[dst[u] + k * a.XS] = q[u].v[k];
+                    }
+            }
+            if (a.TJ < 4)
+                stage_elements<8>(xs, tid, CI_T * npix, [&](int e, int& dst) {
+                    const int p = e & (npix - 1), cl = e / npix;
+                    const int li = p >> a.logTJ, ljx = p & (a.TJ - 1);
+                    const int i = i0 + li, j = j0 + ljx, ci = ci0 + cl;
+                    dst = p * a.XS + cl;
+                    return (ci < g.Cin && i < g.H && j < g.W)
+                               ? ld_f32(x, (((size_t)b * g.Cin + ci) * g.H + i) * g.W + j) : 0.f;
+                });
+            const int nd = CO_T * a.LR * a.LC4;
+            for (int e0 = tid; e0 < nd; e0 += 256 * 4) {
+                Quad q[4];
+                int dst[4], ncol[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int e = e0 + 256 * u;
+                    dst[u] = -1;
+                    q[u] = Quad{{0.f, 0.f, 0.f, 0.f}};
+                    if (e < nd) {
+                        const int row = fdiv(e, a.dLC4), cc = 4 * (e - row * a.LC4);
+                        const int col = fdiv(row, a.dLR), rr = row - col * a.LR;
+                        const int co = co0 + col, oy = oy_base + rr, ox = ox_base + cc;
+                        dst[u] = row * a.LC + cc;
+                        ncol[u] = a.LC - cc;
+                        if (co < g.Cout && oy >= 0 && oy < g.OH && ox + 3 >= 0 && ox < g.OW) {
+                            const size_t src = (((size_t)b * g.Cout + co) * g.OH + oy) * g.OW;
+                            if (ox >= 0 && ox + 3 < g.OW) {
+                                q[u] = ld_quad(dy, src + ox);
+                            } else {
+#pragma unroll
+                                for (int k = 0; k < 4; ++k)
+                                    if (ox + k >= 0 && ox + k < g.OW) q[u].v[k] = ld_f32(dy, src + ox + k);
+                            }
+                        }
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (dst[u] >= 0) {
+#pragma unroll
+                        for (int k = 0; k < 4; ++k)
+                            if (k < ncol[u]) dys[dst[u] + k] = q[u].v[k];
+                    }
+            }
+        }
         __syncthreads();
         for (int p = tp; p < npix; p += a.TP) {
             const int li = p >> a.logTJ, ljx = p & (a.TJ - 1);
@@ -978,7 +1044,8 @@ hipError_t launch_gw(const Geom& g, const void* x, const void* dy, float* dw, hi
     while (TI > 1 && (size_t)4 * (TI * a.TJ * a.XS + CO_T * (2 * TI + N - 2) * a.LC) > budget) TI >>= 1;
     a.TI = TI;
     a.LR = 2 * TI + N - 2 > 1 ? 2 * TI + N - 2 : 1;
-    a.dLC = make_fastdiv((unsigned)a.LC);
+    a.LC4 = (a.LC + 3) / 4;
+    a.dLC4 = make_fastdiv((unsigned)a.LC4);
     a.dLR = make_fastdiv((unsigned)a.LR);
     const size_t lds = (size_t)4 * (TI * a.TJ * a.XS + CO_T * a.LR * a.LC);
     if (lds > budget) return hipErrorInvalidConfiguration;
