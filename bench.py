@@ -385,6 +385,9 @@ def main():
                     help="'all', 'none' or comma-separated extra configs for per_config")
     ap.add_argument("--only", default=None, help="time just this workload as the headline")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--grad", default=None, choices=["grad_input", "grad_weight"],
+                    help="with --only: time this gradient of the workload instead of the forward "
+                         "pass (used for the per-kernel counter runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path shards by batch with no "
@@ -399,6 +402,17 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
 
     head = wl.WORKLOADS[args.only or HEADLINE]
+    if args.grad:
+        if not args.only:
+            ap.error("--grad needs --only <workload>")
+        r = measure_backward(head, args.grad, args.steps, warm_seconds=0.0)
+        print(json.dumps({"metric": "useful (zero-free) GFLOP/s", "value": r["useful_gflops"],
+                          "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+                          "ms_per_step": r["us"] / 1e3, "higher_is_better": True, "scaling": "weak",
+                          "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+                          "config": {"workload": r["workload"] + ": " + r["shape"]},
+                          "roofline": r["roofline"], "cpu_baseline": None}))
+        return
     m = measure(head, args.steps, args.warmup)
     data = m.pop("_data")
     m.pop("_exact_flop")

@@ -148,7 +148,7 @@ __global__ __launch_bounds__(256) void ukst_grad_input_kernel(const TIn* __restr
     float* wl = lds_f;                               // [coChunk][NN][CI_BLK]
     float* tile = lds_f + a.coChunk * NN * CI_BLK;   // [coChunk][TB][LR][2][HC]
 
-    int bid = blockIdx.x;
+    int bid = xcd_contiguous(blockIdx.x, gridDim.x);     // neighbours in this numbering share an L2
     const int cb = bid % a.ciBlocks; bid /= a.ciBlocks;  // blocks that share a dy tile are neighbours
     const int tx = bid % a.tilesX; bid /= a.tilesX;
     const int ty = bid % a.tilesY; bid /= a.tilesY;
@@ -328,7 +328,10 @@ __global__ __launch_bounds__(256, 2) void ukst_grad_input_mfma_kernel(const TIn*
     float* wl = lds_f;                                   // [CC][NN][WS]
     float* tile = lds_f + a.CC * wlStride;               // [CC][TB][LR][2][HC]
 
-    int bid = blockIdx.x;
+    // neighbours in this numbering share an L2; the slices of a split sum (grid.y) come last
+    const int lin = xcd_contiguous(blockIdx.y * gridDim.x + blockIdx.x, gridDim.x * gridDim.y);
+    const int ks = lin / gridDim.x;
+    int bid = lin - ks * gridDim.x;
     const int cit = bid % a.ciTiles; bid /= a.ciTiles;   // blocks that share a dy tile are neighbours
     const int tx = bid % a.tilesX; bid /= a.tilesX;
     const int ty = bid % a.tilesY; bid /= a.tilesY;
@@ -357,7 +360,7 @@ __global__ __launch_bounds__(256, 2) void ukst_grad_input_mfma_kernel(const TIn*
 
     const int rowsPerCo = a.TB * a.LR, cols = 2 * a.HC;
     const int c4n = 1 << a.logC4;  // float4 pieces per weight row
-    const int co_begin = blockIdx.y * a.coPer;
+    const int co_begin = ks * a.coPer;
     const int co_end = co_begin + a.coPer < a.CoutP ? co_begin + a.coPer : a.CoutP;
     for (int co0 = co_begin; co0 < co_end; co0 += a.CC) {
         if (co0 != co_begin) __syncthreads();
@@ -397,9 +400,9 @@ __global__ __launch_bounds__(256, 2) void ukst_grad_input_mfma_kernel(const TIn*
     }
 
     // accumulator register i of a tile: channel 8*(i/4) + 4*kk + (i%4) of its 32, MFMA column l32;
-    // slice blockIdx.y of the output-channel sum writes the blockIdx.y-th copy of dx
+    // slice ks of the output-channel sum writes the ks-th copy of dx
     const int j = j0 + lj;
-    dx += (size_t)blockIdx.y * g.B * g.Cin * g.H * g.W;
+    dx += (size_t)ks * g.B * g.Cin * g.H * g.W;
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
         const int tr = (wpx * 4 + t) * subRows + lsub;
@@ -593,7 +596,7 @@ __global__ __launch_bounds__(256) void ukst_grad_weight_kernel(const TIn* __rest
     float* xs = lds_f;                               // [TI*TJ][XS]
     float* dys = lds_f + a.TI * a.TJ * a.XS;         // [CO_T][LR][LC]
 
-    int bid = blockIdx.x;
+    int bid = xcd_contiguous(blockIdx.x, gridDim.x);  // neighbours in this numbering share an L2
     const int cit = bid % a.ciTiles; bid /= a.ciTiles;
     const int cot = bid % a.coTiles; bid /= a.coTiles;
     const int slice = bid;
@@ -795,7 +798,7 @@ __global__ __launch_bounds__(256, 2) void ukst_grad_weight_mfma_kernel(const TIn
     float* xs = lds_f;                     // [CI_T][XP]
     float* dys = lds_f + CI_T * a.XP;      // [32][DP]
 
-    int bid = blockIdx.x;
+    int bid = xcd_contiguous(blockIdx.x, gridDim.x);  // neighbours in this numbering share an L2
     const int cit = bid % a.ciTiles; bid /= a.ciTiles;
     const int cot = bid % a.coTiles; bid /= a.coTiles;
     const int slice = bid;

@@ -6,16 +6,6 @@
 namespace ukst {
 namespace {
 
-// Workgroups are handed to the 8 XCDs round-robin.  Renumber them so that each XCD (one L2)
-// works on a contiguous run of tiles and neighbouring tiles' halos hit the same L2.
-__device__ __forceinline__ int xcd_contiguous(int bid, int nb)
-{
-    constexpr int X = 8;
-    const int xcd = bid % X, idx = bid / X;
-    const int fl = nb / X, rem = nb % X;
-    return xcd * fl + (xcd < rem ? xcd : rem) + idx;
-}
-
 __device__ __forceinline__ float to_f32(float v) { return v; }
 __device__ __forceinline__ float to_f32(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
 // one rounding to nearest even at the store when the output is bf16

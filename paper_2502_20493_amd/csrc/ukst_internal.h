@@ -88,6 +88,16 @@ __device__ __forceinline__ int fdiv(int n, const FastDiv& f)
     return f.d == 1 ? n : (int)(__umulhi((unsigned)n, f.M) >> f.sh);
 }
 
+// Workgroups are handed to the 8 XCDs round-robin.  Renumber them so that each XCD (one L2)
+// works on a contiguous run of tiles and neighbouring tiles' halos hit the same L2.
+__device__ __forceinline__ int xcd_contiguous(int bid, int nb)
+{
+    constexpr int X = 8;
+    const int xcd = bid % X, idx = bid / X;
+    const int fl = nb / X, rem = nb % X;
+    return xcd * fl + (xcd < rem ? xcd : rem) + idx;
+}
+
 inline Geom make_geom(int B, int Cin, int Cout, int H, int W, int n, int P)
 {
     Geom g;

@@ -52,14 +52,6 @@ struct F32Args {
     FastDiv dKHW, dKW, dEH, dRW, dW;
 };
 
-__device__ __forceinline__ int xcd_contiguous(int bid, int nb)
-{
-    constexpr int X = 8;
-    const int xcd = bid % X, idx = bid / X;
-    const int fl = nb / X, rem = nb % X;
-    return xcd * fl + (xcd < rem ? xcd : rem) + idx;
-}
-
 // Narrow tiles (NW < 4) keep few accumulators, so two blocks may share a compute unit and cover
 // each other's staging latency; the widest tile needs the whole register file.
 // EPI: the fused epilogue (bias, activation) is compiled into the drain; the plain instance keeps

@@ -29,14 +29,6 @@ typedef unsigned u4v __attribute__((ext_vector_type(4)));
 constexpr int kRsrcFlags = 0x00020000;  // raw 32-bit buffer, gfx9 family
 constexpr int kFarBand = 0x20000000;         // a quad row whose input and output rows do not exist
 
-__device__ __forceinline__ int xcd_contiguous(int bid, int nb)
-{
-    constexpr int X = 8;
-    const int xcd = bid % X, idx = bid / X;
-    const int fl = nb / X, rem = nb % X;
-    return xcd * fl + (xcd < rem ? xcd : rem) + idx;
-}
-
 __device__ __forceinline__ unsigned fbits(float f) { return __builtin_bit_cast(unsigned, f); }
 
 // EPI: the fused epilogue (bias, activation) is compiled in between the sums and the stores; the

@@ -79,16 +79,6 @@ struct ThinMfmaArgs {
     FastDiv dKHW, dKW, dEH, dW4, dROWS;
 };
 
-// Blocks are dealt to the 8 XCDs round-robin; give each XCD a contiguous range of tiles so that
-// the rows neighbouring tiles share are fetched into one L2.
-__device__ __forceinline__ int xcd_contiguous(int bid, int nb)
-{
-    constexpr int X = 8;
-    const int xcd = bid % X, idx = bid / X;
-    const int fl = nb / X, rem = nb % X;
-    return xcd * fl + (xcd < rem ? xcd : rem) + idx;
-}
-
 // EPI: the fused epilogue (bias, activation) is compiled into the drain.
 template <int N, int MT, bool EPI>
 __global__ __launch_bounds__(256) void ukst_thin_mfma_kernel(const float* __restrict__ x,
