@@ -540,7 +540,7 @@ long long gi_blocks(const Geom& g, int ci_blk, int px)
 template <int N, typename TIn>
 hipError_t launch_gi_t(const Geom& g, const void* dy, const void* w, float* dx, hipStream_t stream)
 {
-    if (g.Cin <= 4) return launch_gi<N, 4, 1, TIn>(g, dy, w, dx, stream);
+    if (g.Cin <= 4) return launch_gi<N, 4, 2, TIn>(g, dy, w, dx, stream);
     if (g.Cin <= 8) return launch_gi<N, 8, 1, TIn>(g, dy, w, dx, stream);
     if (gi_blocks(g, 16, 2) >= 512) return launch_gi<N, 16, 2, TIn>(g, dy, w, dx, stream);
     if (gi_blocks(g, 16, 1) >= 512) return launch_gi<N, 16, 1, TIn>(g, dy, w, dx, stream);
@@ -671,11 +671,11 @@ __global__ __launch_bounds__(256) void ukst_grad_weight_kernel(const TIn* __rest
                                ? ld_f32(x, (((size_t)b * g.Cin + ci) * g.H + i) * g.W + j) : 0.f;
                 });
             const int nd = CO_T * a.LR * a.LC4;
-            for (int e0 = tid; e0 < nd; e0 += 256 * 4) {
-                Quad q[4];
-                int dst[4], ncol[4];
+            for (int e0 = tid; e0 < nd; e0 += 256 * 10) {
+                Quad q[10];
+                int dst[10], ncol[10];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < 10; ++u) {
                     const int e = e0 + 256 * u;
                     dst[u] = -1;
                     q[u] = Quad{{0.f, 0.f, 0.f, 0.f}};
@@ -698,7 +698,7 @@ __global__ __launch_bounds__(256) void ukst_grad_weight_kernel(const TIn* __rest
                     }
                 }
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
+                for (int u = 0; u < 10; ++u)
                     if (dst[u] >= 0) {
 #pragma unroll
                         for (int k = 0; k < 4; ++k)
@@ -1062,7 +1062,7 @@ hipError_t launch_gw(const Geom& g, const void* x, const void* dy, float* dw, hi
     // slices: enough blocks to cover the chip four times (twice when most of a block's threads
     // share channel pairs: each block then ends with a shuffle reduction that wants amortising),
     // never more than stages
-    long long want = (a.PB >= 64 ? 1024 : 512) / ((long long)a.coTiles * a.ciTiles);
+    long long want = (a.PB >= 64 ? 1024 : 1024) / ((long long)a.coTiles * a.ciTiles);
     if (want < 1) want = 1;
     if (want > stages) want = stages;
     a.stagesPerSlice = (int)((stages + want - 1) / want);
