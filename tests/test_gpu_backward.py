@@ -136,3 +136,64 @@ def test_backward_on_a_side_stream_is_bit_reproducible():
     dw_ref, Sw = oracle.grad_weight(data["x"], dyd["dy"], w.n, w.P)
     check_elements(outs[0][0], dx_ref, Sx, TOL["f32"])
     check_elements(outs[0][1], dw_ref, Sw, TOL["f32"])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(2, 3, 3, 9, 21, 3, 0), (2, 40, 36, 6, 18, 4, 2)])
+def test_backward_operands_with_element_alignment_only(dtype, shape):
+    """x, w, dy one element past an aligned address (narrow layer: vector-ALU kernels, wide layer:
+    matrix-core kernels): the four-element vector loads of the staging code may assume nothing
+    beyond element alignment."""
+    import torch
+    B, Cin, Cout, H, W, n, P = shape
+    w = _mk("bwd_unaligned", 7100 + Cin, B, Cin, Cout, H, W, n, P, dtype=dtype)
+    data = wl.generate(w)
+    dyd = wl.generate_dy(w, oracle.out_shape(H, W, n, P))
+
+    def shifted(a32, bits):  # same values, storage starting one element after an aligned address
+        t = (torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16) if dtype == "bf16"
+             else torch.from_numpy(a32))
+        buf = torch.empty(t.numel() + 1, dtype=t.dtype, device="cuda")
+        v = buf[1:].view(t.shape)
+        v.copy_(t)
+        assert v.data_ptr() % 16 != 0
+        return v
+
+    x = shifted(data["x"], data.get("x_bits"))
+    k = shifted(data["w"], data.get("w_bits"))
+    dy = shifted(dyd["dy"], dyd.get("dy_bits"))
+    dx = ukst.ukst_conv_transpose2d_grad_input(dy, k, H, W, P)
+    dw = ukst.ukst_conv_transpose2d_grad_weight(x, dy, n, P)
+    torch.cuda.synchronize()
+    ref, S = oracle.grad_input(dyd["dy"], data["w"], H, W, P)
+    check_elements(dx.cpu().numpy(), ref, S, TOL[dtype])
+    ref, S = oracle.grad_weight(data["x"], dyd["dy"], n, P)
+    check_elements(dw.cpu().numpy(), ref, S, TOL[dtype])
+
+
+def test_backward_beyond_32bit_byte_offsets():
+    """dy of 4.6 GB: its last planes start past 2^32 bytes.  Integer data, exact comparison of
+    sampled dx planes and of all of dw (the oracle sees one image at a time)."""
+    import torch
+    B, Cin, Cout, H, W, n, P = 2, 2, 3, 6900, 6900, 3, 0
+    OH, OW = oracle.out_shape(H, W, n, P)
+    assert B * Cout * OH * OW * 4 > 1 << 32
+    print(f"case bwd_big B={B} Cin={Cin} Cout={Cout} H={H} W={W} n={n} P={P}", flush=True)
+    g = torch.Generator(device="cuda").manual_seed(20493)
+    x = torch.randint(-3, 4, (B, Cin, H, W), generator=g, device="cuda").float()
+    k = torch.randint(-3, 4, (Cout, Cin, n, n), generator=g, device="cuda").float()
+    dy = torch.randint(-3, 4, (B, Cout, OH, OW), generator=g, device="cuda").float()
+    dx = ukst.ukst_conv_transpose2d_grad_input(dy, k, H, W, P)
+    dw = ukst.ukst_conv_transpose2d_grad_weight(x, dy, n, P)
+    torch.cuda.synchronize()
+    kh = k.cpu().numpy()
+    for b, ci in ((0, 0), (B - 1, Cin - 1)):
+        ref, _ = oracle.grad_input(dy[b:b + 1].cpu().numpy(), kh[:, ci:ci + 1], H, W, P)
+        assert np.array_equal(dx[b, ci].cpu().numpy().astype(np.float64), ref[0, 0]), (b, ci)
+    ref = np.zeros((Cout, Cin, n, n))
+    for b in range(B):
+        ref += oracle.grad_weight(x[b:b + 1].cpu().numpy(), dy[b:b + 1].cpu().numpy(), n, P)[0]
+    # |sums| stay below 2^24 (at most 9 * 2 * 6900^2 terms of magnitude <= 9 would not: compare in
+    # the tolerance of the fp32 slices instead of bit for bit)
+    Sw = 9.0 * B * H * W
+    assert np.abs(dw.cpu().numpy().astype(np.float64) - ref).max() <= 1e-5 * Sw
