@@ -221,7 +221,8 @@ def measure_backward(w, which, steps, warm_seconds=0.2, rotate_bytes=LLC_BYTES +
         peak = PEAK_TFLOPS["alu_f32_published"]
         roof = {"bound": "mfma" if "mfma" in kernel else "alu", "achieved": round(gflops / 1e3, 2), "peak": peak, "unit": "TFLOP/s",
                 "frac": round(gflops / 1e3 / peak, 4), "traffic": None}
-    roof.update(kernel=kernel, us_per_launch=round(per_launch_s * 1e6, 2), algorithmic_bytes=nbytes)
+    roof.update(kernel=kernel, us_per_launch=round(per_launch_s * 1e6, 2), algorithmic_bytes=nbytes,
+                traffic=measured_traffic(f"{w.name} {which}"))
     return {"workload": f"{w.name} {which}",
             "shape": f"B{w.B} {w.Cin}->{w.Cout} {w.H}x{w.W} n{w.n} P{w.P} {w.dtype}, backward pass",
             "out": f"{w.H}x{w.W}" if which == "grad_input" else f"{w.n}x{w.n}",
