@@ -217,10 +217,11 @@ def measure_backward(w, which, steps, warm_seconds=0.2, rotate_bytes=LLC_BYTES +
         roof = {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None}
     else:
-        # fp32 vector peak and fp32 MFMA peak are the same published number on this chip
-        peak = PEAK_TFLOPS["alu_f32_published"]
-        roof = {"bound": "mfma" if "mfma" in kernel else "alu", "achieved": round(gflops / 1e3, 2), "peak": peak, "unit": "TFLOP/s",
-                "frac": round(gflops / 1e3 / peak, 4), "traffic": None}
+        # fp32 vector peak and fp32 MFMA peak are the same published number on this chip; the bf16
+        # input gradient multiplies on the bf16 matrix pipe
+        peak = PEAK_TFLOPS["mfma_bf16" if "mfma_bf16" in kernel else "alu_f32_published"]
+        roof = {"bound": "mfma" if "mfma" in kernel else "alu", "achieved": round(gflops / 1e3, 2),
+                "peak": peak, "unit": "TFLOP/s", "frac": round(gflops / 1e3 / peak, 4), "traffic": None}
     roof.update(kernel=kernel, us_per_launch=round(per_launch_s * 1e6, 2), algorithmic_bytes=nbytes,
                 traffic=measured_traffic(f"{w.name} {which}"))
     return {"workload": f"{w.name} {which}",

@@ -199,7 +199,7 @@ const char* ukst_grad_kernel_name(int which, int B, int Cin, int Cout, int H, in
     if (which != 0 && which != 1) return "";
     if (validate_shape(B, Cin, Cout, H, W, n, P) != UKST_OK) return "";
     if ((dtype != UKST_F32 && dtype != UKST_BF16_F32) || n > UKST_MAX_N) return "";
-    return ukst::grad_kernel_name(ukst::make_geom(B, Cin, Cout, H, W, n, P), which);
+    return ukst::grad_kernel_name(ukst::make_geom(B, Cin, Cout, H, W, n, P), which, dtype);
 }
 
 const char* ukst_kernel_name(int B, int Cin, int Cout, int H, int W, int n, int P, int dtype,

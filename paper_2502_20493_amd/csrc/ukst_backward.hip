@@ -441,15 +441,192 @@ __global__ __launch_bounds__(256) void ukst_sum_partials_kernel(const float* __r
     if (r == 0 && i < n) dw[i] = red[threadIdx.x];
 }
 
+// ------------------------------------------------------------------------------------------
+// The same input gradient for bf16 operands on the bf16 matrix pipe: v_mfma_f32_32x32x8_bf16_1k
+// takes 8 output channels per instruction, a lane holding four consecutive ones of its row or
+// column.  LDS therefore keeps 8-byte elements of four output channels: weights packed once per
+// call as [co/8][co%8/4][tap][ci][co%4], the dy tile transposed on its way in (a thread loads four
+// columns of four channels and writes four elements), parity-split as before.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+
+__global__ __launch_bounds__(256) void ukst_pack_w_bf16_kernel(const uint16_t* __restrict__ w,
+                                                              uint16_t* __restrict__ wp, int Cout, int Cin,
+                                                              int NN, int CoutP, int CIp)
+{
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;  // over [CoutP/4][NN][CIp][4]
+    if (idx >= (size_t)CoutP * NN * CIp) return;
+    const int q = (int)(idx & 3);
+    const size_t r1 = idx >> 2;
+    const int ci = (int)(r1 % CIp);
+    const size_t r2 = r1 / CIp;
+    const int tap = (int)(r2 % NN), co = (int)(r2 / NN) * 4 + q;
+    wp[idx] = (co < Cout && ci < Cin) ? w[((size_t)co * Cin + ci) * NN + tap] : (uint16_t)0;
+}
+
+template <int N>
+__global__ __launch_bounds__(256, 2) void ukst_grad_input_mfma_bf16_kernel(const uint16_t* __restrict__ dy,
+                                                                          const uint16_t* __restrict__ wp,
+                                                                          float* __restrict__ dx, GiMfmaArgs a)
+{
+    constexpr int NN = N * N;
+    extern __shared__ __align__(16) u32x2 lds8[];
+    const GeomBase& g = a.g;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, kk = lane >> 5;
+    const int wm = wave & (a.WM - 1), wpx = wave >> a.logWM;
+    const int wlEls = NN * a.WS;                         // 8-byte elements per group of 4 channels
+    const int tileEls = a.TB * a.LR * 2 * a.HC;
+    u32x2* wl = lds8;                                    // [2][NN][WS]
+    u32x2* tile = lds8 + 2 * wlEls;                      // [2][TB][LR][2][HC]
+
+    const int lin = xcd_contiguous(blockIdx.y * gridDim.x + blockIdx.x, gridDim.x * gridDim.y);
+    const int ks = lin / gridDim.x;
+    int bid = lin - ks * gridDim.x;
+    const int cit = bid % a.ciTiles; bid /= a.ciTiles;
+    const int tx = bid % a.tilesX; bid /= a.tilesX;
+    const int ty = bid % a.tilesY; bid /= a.tilesY;
+    const int tb = bid;
+    const int ci0 = cit * a.CI_T, i0 = ty * a.TI, j0 = tx * a.TJ, b0 = tb * a.TB;
+    const int oy_base = 2 * i0 + g.P - (N - 1), ox_base = 2 * j0 + g.P - (N - 1);
+
+    const int lj = l32 & (a.TJ - 1), lsub = l32 >> a.logTJ, subRows = 32 >> a.logTJ;
+    int toff[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int tr = (wpx * 4 + t) * subRows + lsub;
+        const int bl = tr >> a.logTI, li = tr & (a.TI - 1);
+        toff[t] = kk * tileEls + ((bl * a.LR + 2 * li) * 2) * a.HC + lj;
+    }
+    const int a_base = kk * wlEls + wm * 64 + l32;
+    f32x16 acc[2][4];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[mi][t][i] = 0.f;
+
+    const int rowsPerCo = a.TB * a.LR, cols = 2 * a.HC;
+    const int c2n = 1 << a.logC4;  // 16-byte pieces per weight row (two elements each)
+    const size_t plane = (size_t)g.OH * g.OW;
+    const int co_begin = ks * a.coPer;
+    const int co_end = co_begin + a.coPer < a.CoutP ? co_begin + a.coPer : a.CoutP;
+    for (int co0 = co_begin; co0 < co_end; co0 += 8) {
+        if (co0 != co_begin) __syncthreads();
+        for (int e = tid; e < 2 * NN * c2n; e += 256) {
+            const int row = e >> a.logC4, c2 = e & (c2n - 1);
+            const uint4 v = *reinterpret_cast<const uint4*>(
+                wp + (((size_t)(co0 >> 2) * NN + row) * a.CIp + ci0 + 2 * c2) * 4);
+            *reinterpret_cast<uint4*>(wl + row * a.WS + 2 * c2) = v;
+        }
+        // dy: task = (channel group of four, tile row, four columns)
+        const int ntask = 2 * rowsPerCo * a.cols4;
+        for (int e0 = tid; e0 < ntask; e0 += 256 * 4) {
+            u32x2 q[4][4];
+            int dst[4], ncol[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int e = e0 + 256 * u;
+                dst[u] = -1;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) q[u][c] = u32x2{0u, 0u};
+                if (e < ntask) {
+                    const int row = fdiv(e, a.dC4), cc = 4 * (e - row * a.cols4);
+                    const int kg = fdiv(row, a.dRowsPerCo), rem = row - kg * rowsPerCo;
+                    const int bl = fdiv(rem, a.dLR), rr = rem - bl * a.LR;
+                    const int b = b0 + bl, oy = oy_base + rr, ox = ox_base + cc;
+                    dst[u] = kg * tileEls + rem * cols + (cc >> 1);
+                    ncol[u] = cols - cc;
+                    if (b < g.B && oy >= 0 && oy < g.OH && ox + 3 >= 0 && ox < g.OW) {
+                        const int cbase = co0 + 4 * kg;
+                        const size_t src = (((size_t)b * g.Cout + cbase) * g.OH + oy) * g.OW;
+                        const bool whole = ox >= 0 && ox + 3 < g.OW;
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) {
+                            if (cbase + c >= g.Cout) continue;
+                            const uint16_t* pc = dy + src + c * plane;
+                            if (whole) {
+                                typedef unsigned u2u __attribute__((ext_vector_type(2), aligned(2)));
+                                const u2u t2 = *reinterpret_cast<const u2u*>(pc + ox);
+                                q[u][c] = u32x2{t2[0], t2[1]};
+                            } else {
+                                unsigned h[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+                                for (int k = 0; k < 4; ++k)
+                                    if (ox + k >= 0 && ox + k < g.OW) h[k] = pc[ox + k];
+                                q[u][c] = u32x2{h[0] | (h[1] << 16), h[2] | (h[3] << 16)};
+                            }
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (dst[u] >= 0) {
+                    // element of column k: that column of channels 0..3
+                    const unsigned lo = 0x05040100u, hi = 0x07060302u;
+                    tile[dst[u]] = u32x2{__builtin_amdgcn_perm(q[u][1][0], q[u][0][0], lo),
+                                         __builtin_amdgcn_perm(q[u][3][0], q[u][2][0], lo)};
+                    tile[dst[u] + a.HC] = u32x2{__builtin_amdgcn_perm(q[u][1][0], q[u][0][0], hi),
+                                                __builtin_amdgcn_perm(q[u][3][0], q[u][2][0], hi)};
+                    if (ncol[u] > 2) {
+                        tile[dst[u] + 1] = u32x2{__builtin_amdgcn_perm(q[u][1][1], q[u][0][1], lo),
+                                                 __builtin_amdgcn_perm(q[u][3][1], q[u][2][1], lo)};
+                        tile[dst[u] + a.HC + 1] = u32x2{__builtin_amdgcn_perm(q[u][1][1], q[u][0][1], hi),
+                                                        __builtin_amdgcn_perm(q[u][3][1], q[u][2][1], hi)};
+                    }
+                }
+        }
+        __syncthreads();
+        const u32x2* wa = wl + a_base;
+#pragma unroll
+        for (int ta = 0; ta < N; ++ta)
+#pragma unroll
+            for (int tcx = 0; tcx < N; ++tcx) {
+                const int off = ((N - 1 - ta) * 2 + ((N - 1 - tcx) & 1)) * a.HC + ((N - 1 - tcx) >> 1);
+                const s16x4 a0 = __builtin_bit_cast(s16x4, wa[(ta * N + tcx) * a.WS]);
+                const s16x4 a1 = __builtin_bit_cast(s16x4, wa[(ta * N + tcx) * a.WS + 32]);
+                s16x4 bv[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) bv[t] = __builtin_bit_cast(s16x4, tile[toff[t] + off]);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    acc[0][t] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(a0, bv[t], acc[0][t], 0, 0, 0);
+                    acc[1][t] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(a1, bv[t], acc[1][t], 0, 0, 0);
+                }
+            }
+    }
+
+    const int j = j0 + lj;
+    dx += (size_t)ks * g.B * g.Cin * g.H * g.W;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int tr = (wpx * 4 + t) * subRows + lsub;
+        const int b = b0 + (tr >> a.logTI), i = i0 + (tr & (a.TI - 1));
+        if (b >= g.B || i >= g.H || j >= g.W) continue;
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int ci = ci0 + wm * 64 + mi * 32 + 8 * (r / 4) + 4 * kk + (r % 4);
+                if (ci < g.Cin) dx[(((size_t)b * g.Cin + ci) * g.H + i) * g.W + j] = acc[mi][t][r];
+            }
+    }
+}
+
 // Fills the launch description; false if this shape is better served by the vector-ALU kernel.
-bool gi_mfma_args(const Geom& g, GiMfmaArgs& a)
+// packed16: the description of the bf16 kernel (8-byte LDS elements of four channels, rounds of 8)
+bool gi_mfma_args(const Geom& g, GiMfmaArgs& a, bool packed16 = false)
 {
     if (g.Cin < 32 || g.Cout < 16) return false;
     const int N = g.n, NN = N * N;
     for (int WM = (g.Cin > 64 ? 2 : 1); WM >= 1; --WM) {
         a.g = g;
         a.WM = WM; a.logWM = WM == 2 ? 1 : 0;
-        a.CI_T = 64 * WM; a.logC4 = WM == 2 ? 5 : 4; a.WS = a.CI_T + 4;
+        a.CI_T = 64 * WM; a.logC4 = (WM == 2 ? 5 : 4) + (packed16 ? 1 : 0);
+        a.WS = a.CI_T + (packed16 ? 2 : 4);
         a.TJ = pow2_ceil(g.W < 32 ? g.W : 32);
         if (a.TJ < 4) a.TJ = 4;
         a.logTJ = log2_of(a.TJ);
@@ -462,6 +639,7 @@ bool gi_mfma_args(const Geom& g, GiMfmaArgs& a)
         const size_t perCo = (size_t)4 * (NN * a.WS + a.TB * a.LR * 2 * a.HC);
         int cc = (int)((76 * 1024) / perCo) & ~1;
         if (cc > 8) cc = 8;
+        if (packed16) cc = (size_t)16 * (NN * a.WS + a.TB * a.LR * 2 * a.HC) <= 76 * 1024 ? 8 : 0;
         if (cc < 2) continue;
         a.CC = cc;
         a.CoutP = (g.Cout + cc - 1) / cc * cc;
@@ -488,6 +666,42 @@ bool gi_mfma_args(const Geom& g, GiMfmaArgs& a)
         return true;
     }
     return false;
+}
+
+template <int N>
+hipError_t launch_gi_mfma_bf16(const GiMfmaArgs& a, const void* dy, const void* w, float* dx, hipStream_t stream)
+{
+    const GeomBase& g = a.g;
+    const size_t pelems = (size_t)a.CoutP * N * N * a.CIp;           // bf16 elements
+    const size_t pbytes = (pelems * 2 + 255) & ~(size_t)255;
+    const size_t xelems = (size_t)g.B * g.Cin * g.H * g.W;
+    unsigned char* scratch = nullptr;  // packed weights, then (split sums) the copies of dx
+    hipError_t e;
+    if ((e = hipMallocAsync((void**)&scratch, pbytes + (a.KS > 1 ? xelems * a.KS * 4 : 0), stream)) != hipSuccess)
+        return e;
+    uint16_t* wp = (uint16_t*)scratch;
+    float* part = (float*)(scratch + pbytes);
+    hipLaunchKernelGGL(ukst_pack_w_bf16_kernel, dim3((unsigned)((pelems + 255) / 256)), dim3(256), 0, stream,
+                       (const uint16_t*)w, wp, g.Cout, g.Cin, N * N, a.CoutP, a.CIp);
+    e = hipGetLastError();
+    if (e == hipSuccess) {
+        const size_t lds = (size_t)16 * (N * N * a.WS + a.TB * a.LR * 2 * a.HC);
+        const void* kfn = (const void*)ukst_grad_input_mfma_bf16_kernel<N>;
+        e = hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e == hipSuccess) {
+            const unsigned nb = (unsigned)((long long)a.tilesX * a.tilesY * a.tilesB * a.ciTiles);
+            hipLaunchKernelGGL((ukst_grad_input_mfma_bf16_kernel<N>), dim3(nb, (unsigned)a.KS), dim3(256), lds,
+                               stream, (const uint16_t*)dy, (const uint16_t*)wp, a.KS > 1 ? part : dx, a);
+            e = hipGetLastError();
+        }
+        if (e == hipSuccess && a.KS > 1) {
+            hipLaunchKernelGGL(ukst_sum_partials_kernel, dim3((unsigned)((xelems + 255) / 256)), dim3(256), 0,
+                               stream, (const float*)part, dx, (int)xelems, a.KS, 0);
+            e = hipGetLastError();
+        }
+    }
+    const hipError_t ef = hipFreeAsync(scratch, stream);
+    return e != hipSuccess ? e : ef;
 }
 
 template <int N, typename TIn>
@@ -552,6 +766,7 @@ hipError_t launch_gi_n(const Geom& g, const void* dy, const void* w, float* dx, 
                        hipStream_t stream)
 {
     GiMfmaArgs ma;
+    if (dtype == 1 && gi_mfma_args(g, ma, true)) return launch_gi_mfma_bf16<N>(ma, dy, w, dx, stream);
     if (gi_mfma_args(g, ma))
         return dtype == 1 ? launch_gi_mfma<N, uint16_t>(ma, dy, w, dx, stream)
                           : launch_gi_mfma<N, float>(ma, dy, w, dx, stream);
@@ -1125,7 +1340,7 @@ hipError_t launch_gw_t(const Geom& g, const void* x, const void* dy, float* dw, 
 
 }  // namespace
 
-const char* grad_kernel_name(const Geom& g, int which)
+const char* grad_kernel_name(const Geom& g, int which, int dtype)
 {
     if (which == 1) {
         GwMfmaArgs wa;
@@ -1133,6 +1348,7 @@ const char* grad_kernel_name(const Geom& g, int which)
         return m ? "ukst_grad_weight_mfma_kernel" : "ukst_grad_weight_kernel";
     }
     GiMfmaArgs ma;
+    if (dtype == 1 && gi_mfma_args(g, ma, true)) return "ukst_grad_input_mfma_bf16_kernel";
     return gi_mfma_args(g, ma) ? "ukst_grad_input_mfma_kernel" : "ukst_grad_input_kernel";
 }
 

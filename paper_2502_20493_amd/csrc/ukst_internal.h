@@ -147,6 +147,6 @@ hipError_t launch_grad_input(const Geom& g, const void* dy, const void* w, float
 hipError_t launch_grad_weight(const Geom& g, const void* x, const void* dy, float* dw, int dtype,
                               hipStream_t stream);
 // which: 0 gradient w.r.t. the input, 1 w.r.t. the kernel
-const char* grad_kernel_name(const Geom& g, int which);
+const char* grad_kernel_name(const Geom& g, int which, int dtype);
 
 }  // namespace ukst
