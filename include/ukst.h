@@ -182,7 +182,8 @@ int ukst_conv_transpose2d_grad_weight(const void* x, const void* dy, void* dw, i
  * ukst_conv_transpose2d_grad_input, 1: ukst_conv_transpose2d_grad_weight), as it appears in a
  * profiler's kernel trace (substring match), or "" on invalid arguments.  Static storage.
  * Wide layers (Cin >= 32, Cout >= 16) run the input gradient on the matrix cores
- * ("ukst_grad_input_mfma_bf16_kernel": bf16 MFMA for bf16 operands, kernel side up to 5;
+ * ("ukst_grad_input_mfma_bf16_kernel": bf16 MFMA for bf16 operands where its LDS tile fits, i.e.
+ * kernel sides up to about 5;
  * "ukst_grad_input_mfma_kernel": fp32 MFMA otherwise; weights packed once per call into
  * stream-ordered scratch, which also holds the copies of dx when the sum over output channels is
  * split), layers with Cin, Cout >= 32 run the kernel gradient there ("ukst_grad_weight_mfma_kernel",
