@@ -364,11 +364,24 @@ __global__ __launch_bounds__(256, 2) void ukst_grad_input_mfma_kernel(const TIn*
     const int co_end = co_begin + a.coPer < a.CoutP ? co_begin + a.coPer : a.CoutP;
     for (int co0 = co_begin; co0 < co_end; co0 += a.CC) {
         if (co0 != co_begin) __syncthreads();
-        for (int e = tid; e < a.CC * NN * c4n; e += 256) {
-            const int row = e >> a.logC4, c4 = e & (c4n - 1);
-            const float4 v = *reinterpret_cast<const float4*>(
-                wp + ((size_t)co0 * NN + row) * a.CIp + ci0 + 4 * c4);
-            *reinterpret_cast<float4*>(wl + row * a.WS + 4 * c4) = v;
+        // packed weights of the round: eight 16-byte pieces in flight per thread; no predicates
+        // (a written-out loop waits for every load): indices past the end repeat the last piece
+        {
+            const int npc = a.CC * NN * c4n;
+            for (int e0 = tid; e0 < npc; e0 += 256 * 8) {
+                float4 v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int e = e0 + 256 * u < npc ? e0 + 256 * u : npc - 1;
+                    v[u] = *reinterpret_cast<const float4*>(
+                        wp + ((size_t)co0 * NN + (e >> a.logC4)) * a.CIp + ci0 + 4 * (e & (c4n - 1)));
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int e = e0 + 256 * u < npc ? e0 + 256 * u : npc - 1;
+                    *reinterpret_cast<float4*>(wl + (e >> a.logC4) * a.WS + 4 * (e & (c4n - 1))) = v[u];
+                }
+            }
         }
         {
             DyTile t;
@@ -515,11 +528,24 @@ __global__ __launch_bounds__(256, 2) void ukst_grad_input_mfma_bf16_kernel(const
     const int co_end = co_begin + a.coPer < a.CoutP ? co_begin + a.coPer : a.CoutP;
     for (int co0 = co_begin; co0 < co_end; co0 += 8) {
         if (co0 != co_begin) __syncthreads();
-        for (int e = tid; e < 2 * NN * c2n; e += 256) {
-            const int row = e >> a.logC4, c2 = e & (c2n - 1);
-            const uint4 v = *reinterpret_cast<const uint4*>(
-                wp + (((size_t)(co0 >> 2) * NN + row) * a.CIp + ci0 + 2 * c2) * 4);
-            *reinterpret_cast<uint4*>(wl + row * a.WS + 2 * c2) = v;
+        // packed weights of the round: eight 16-byte pieces in flight per thread; no predicates
+        // (a written-out loop waits for every load): indices past the end repeat the last piece
+        {
+            const int npc = 2 * NN * c2n;
+            for (int e0 = tid; e0 < npc; e0 += 256 * 8) {
+                uint4 v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int e = e0 + 256 * u < npc ? e0 + 256 * u : npc - 1;
+                    v[u] = *reinterpret_cast<const uint4*>(
+                        wp + (((size_t)(co0 >> 2) * NN + (e >> a.logC4)) * a.CIp + ci0 + 2 * (e & (c2n - 1))) * 4);
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int e = e0 + 256 * u < npc ? e0 + 256 * u : npc - 1;
+                    *reinterpret_cast<uint4*>(wl + (e >> a.logC4) * a.WS + 2 * (e & (c2n - 1))) = v[u];
+                }
+            }
         }
         // dy: task = (channel group of four, tile row, four columns)
         const int ntask = 2 * rowsPerCo * a.cols4;
