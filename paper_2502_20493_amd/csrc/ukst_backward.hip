@@ -821,6 +821,7 @@ struct GradWArgs {
     int coTiles, ciTiles;
     int SUB;                   // partial copies a block writes (wave groups that share pairs)
     int LC4;                   // four-column pieces per staged dy row
+    int foldWaves;             // 1: the block adds its four waves' sums in LDS and writes one copy
     FastDiv dLC4, dLR;
 };
 
@@ -985,8 +986,37 @@ __global__ __launch_bounds__(256) void ukst_grad_weight_kernel(const TIn* __rest
             for (int k = 0; k < CI_R; ++k)
 #pragma unroll
                 for (int t = 0; t < NN; ++t) acc[c][k][t] += __shfl_xor(acc[c][k][t], m, 64);
-    if (a.PB < 64 && lane >= a.PB) return;
-    const int sub = tid >> (a.logPB > 6 ? a.logPB : 6);  // wave group: waves that share pairs differ in it
+    int sub = tid >> (a.logPB > 6 ? a.logPB : 6);  // wave group: waves that share pairs differ in it
+    if (a.foldWaves) {
+        // few pairs and few taps: the four waves' sums meet in LDS (fixed order) and the block
+        // writes one copy instead of four
+        constexpr int R = CO_R * CI_R * NN;
+        __syncthreads();  // the staged tiles are no longer read
+        if (lane < a.PB) {
+            float* r = lds_f + ((tid >> 6) * a.PB + lane) * R;
+#pragma unroll
+            for (int c = 0; c < CO_R; ++c)
+#pragma unroll
+                for (int k = 0; k < CI_R; ++k)
+#pragma unroll
+                    for (int t = 0; t < NN; ++t) r[(c * CI_R + k) * NN + t] = acc[c][k][t];
+        }
+        __syncthreads();
+        if (tid >= a.PB) return;
+#pragma unroll
+        for (int c = 0; c < CO_R; ++c)
+#pragma unroll
+            for (int k = 0; k < CI_R; ++k)
+#pragma unroll
+                for (int t = 0; t < NN; ++t) {
+                    const int i = (c * CI_R + k) * NN + t;
+                    acc[c][k][t] = ((lds_f[tid * R + i] + lds_f[(a.PB + tid) * R + i]) +
+                                    lds_f[(2 * a.PB + tid) * R + i]) + lds_f[(3 * a.PB + tid) * R + i];
+                }
+        sub = 0;
+    } else if (a.PB < 64 && lane >= a.PB) {
+        return;
+    }
     float* out = part + (size_t)(slice * a.SUB + sub) * g.Cout * g.Cin * NN;
 #pragma unroll
     for (int c = 0; c < CO_R; ++c) {
@@ -1277,6 +1307,8 @@ hipError_t launch_gw(const Geom& g, const void* x, const void* dy, float* dw, hi
     a.logTCI = log2_of(a.TCI);
     a.logPB = log2_of(a.PB);
     a.SUB = a.PB <= 64 ? 4 : a.PB == 128 ? 2 : 1;
+    a.foldWaves = (a.PB <= 64 && 4 * a.PB * CO_R * CI_R * N * N * 4 <= 16 * 1024) ? 1 : 0;
+    if (a.foldWaves) a.SUB = 1;
     const int CO_T = a.TCO * CO_R, CI_T = a.TCI * CI_R;
     a.TJ = pow2_ceil(g.W < 32 ? g.W : 32);
     a.logTJ = log2_of(a.TJ);
@@ -1291,8 +1323,9 @@ hipError_t launch_gw(const Geom& g, const void* x, const void* dy, float* dw, hi
     a.LC4 = (a.LC + 3) / 4;
     a.dLC4 = make_fastdiv((unsigned)a.LC4);
     a.dLR = make_fastdiv((unsigned)a.LR);
-    const size_t lds = (size_t)4 * (TI * a.TJ * a.XS + CO_T * a.LR * a.LC);
+    size_t lds = (size_t)4 * (TI * a.TJ * a.XS + CO_T * a.LR * a.LC);
     if (lds > budget) return hipErrorInvalidConfiguration;
+    if (a.foldWaves && lds < 16 * 1024) lds = 16 * 1024;  // room for the four waves' sums
     a.tilesX = (g.W + a.TJ - 1) / a.TJ;
     a.tilesY = (g.H + TI - 1) / TI;
     const long long stages = (long long)a.tilesX * a.tilesY * g.B;
