@@ -8,6 +8,7 @@ import numpy as np
 import pytest
 
 from paper_2502_20493_amd import binding as ukst
+from paper_2502_20493_amd import workloads as wl
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -145,3 +146,27 @@ def test_workloads_are_seeded_and_shaped():
     assert np.array_equal(wl.round_to_bf16_bits(d["x"]), d["x_bits"])
     t = np.array([1.0, 1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8, 1.0 + 2 ** -7], dtype=np.float32)
     assert wl.bf16_bits_to_f32(wl.round_to_bf16_bits(t)).tolist() == [1.0, 1.0, 1.0 + 2 ** -6, 1.0 + 2 ** -7]
+
+
+def test_backward_kernel_selection_is_host_arithmetic():
+    """ukst_grad_kernel_name needs no GPU: wide layers go to the matrix cores (bf16 operands to the
+    bf16 pipe for the input gradient), narrow ones to the vector ALUs."""
+    name = ukst.ukst_grad_kernel_name
+    w = wl.WORKLOADS
+    def shape(k):
+        return (w[k].B, w[k].Cin, w[k].Cout, w[k].H, w[k].W, w[k].n, w[k].P)
+    assert name(0, *shape("cfg2a"), ukst.UKST_F32) == "ukst_grad_input_kernel"
+    assert name(1, *shape("cfg2a"), ukst.UKST_F32) == "ukst_grad_weight_kernel"
+    assert name(0, *shape("cfg3_L4"), ukst.UKST_F32) == "ukst_grad_input_kernel"      # Cout = 3
+    assert name(1, *shape("cfg3_L4"), ukst.UKST_F32) == "ukst_grad_weight_kernel"
+    for k in ("cfg3_L1", "cfg3_L2", "cfg3_L3", "cfg4a", "cfg4b"):
+        assert name(0, *shape(k), ukst.UKST_F32) == "ukst_grad_input_mfma_kernel", k
+        assert name(1, *shape(k), ukst.UKST_F32) == "ukst_grad_weight_mfma_kernel", k
+    for k in ("cfg5a", "cfg5b"):
+        assert name(0, *shape(k), ukst.UKST_BF16_F32) == "ukst_grad_input_mfma_bf16_kernel", k
+        assert name(1, *shape(k), ukst.UKST_BF16_F32) == "ukst_grad_weight_mfma_kernel", k
+    # kernel sides whose tile does not fit the bf16 kernel's LDS budget fall back to the fp32 pipe
+    assert name(0, 2, 64, 32, 40, 40, 7, 3, ukst.UKST_BF16_F32) == "ukst_grad_input_mfma_kernel"
+    assert name(0, 1, 1, 1, 4, 4, 3, 0, ukst.UKST_BF16_BF16) == ""
+    assert name(2, 1, 1, 1, 4, 4, 3, 0, ukst.UKST_F32) == ""
+    assert name(0, 1, 1, 1, 1, 4, 3, 0, ukst.UKST_F32) == ""
