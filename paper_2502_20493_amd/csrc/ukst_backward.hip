@@ -477,7 +477,11 @@ __global__ __launch_bounds__(256) void ukst_pack_w_bf16_kernel(const uint16_t* _
     wp[idx] = (co < Cout && ci < Cin) ? w[((size_t)co * Cin + ci) * NN + tap] : (uint16_t)0;
 }
 
-template <int N>
+// SHIFT: how quads that straddle an end of their dy row are fetched.  false: element by element
+// (best when most tiles lie inside the rows); true: one vector load from the nearest position
+// inside the row, shifted into place (best for narrow maps, where every tile touches both ends:
+// the batch then holds a single kind of load and waits once).
+template <int N, bool SHIFT>
 __global__ __launch_bounds__(256, 2) void ukst_grad_input_mfma_bf16_kernel(const uint16_t* __restrict__ dy,
                                                                           const uint16_t* __restrict__ wp,
                                                                           float* __restrict__ dx, GiMfmaArgs a)
@@ -565,7 +569,23 @@ __global__ __launch_bounds__(256, 2) void ukst_grad_input_mfma_bf16_kernel(const
                     const int b = b0 + bl, oy = oy_base + rr, ox = ox_base + cc;
                     dst[u] = kg * tileEls + rem * cols + (cc >> 1);
                     ncol[u] = cols - cc;
-                    if (b < g.B && oy >= 0 && oy < g.OH && ox + 3 >= 0 && ox < g.OW) {
+                    if constexpr (SHIFT) {
+                        if (b < g.B && oy >= 0 && oy < g.OH && ox + 3 >= 0 && ox < g.OW) {
+                            const int cbase = co0 + 4 * kg;
+                            const int start = ox < 0 ? 0 : (ox + 4 > g.OW ? g.OW - 4 : ox);
+                            const int sh = 16 * (ox - start);  // > 0: drop leading elements
+                            const size_t src = (((size_t)b * g.Cout + cbase) * g.OH + oy) * g.OW + start;
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) {
+                                if (cbase + c >= g.Cout) continue;
+                                typedef unsigned u2u __attribute__((ext_vector_type(2), aligned(2)));
+                                const u2u t2 = *reinterpret_cast<const u2u*>(dy + src + c * plane);
+                                unsigned long long v = ((unsigned long long)t2[1] << 32) | t2[0];
+                                v = sh >= 0 ? v >> sh : v << -sh;  // whole elements, zeros moving in
+                                q[u][c] = u32x2{(unsigned)v, (unsigned)(v >> 32)};
+                            }
+                        }
+                    } else if (b < g.B && oy >= 0 && oy < g.OH && ox + 3 >= 0 && ox < g.OW) {
                         const int cbase = co0 + 4 * kg;
                         const size_t src = (((size_t)b * g.Cout + cbase) * g.OH + oy) * g.OW;
                         const bool whole = ox >= 0 && ox + 3 < g.OW;
@@ -712,12 +732,17 @@ hipError_t launch_gi_mfma_bf16(const GiMfmaArgs& a, const void* dy, const void* 
     e = hipGetLastError();
     if (e == hipSuccess) {
         const size_t lds = (size_t)16 * (N * N * a.WS + a.TB * a.LR * 2 * a.HC);
-        const void* kfn = (const void*)ukst_grad_input_mfma_bf16_kernel<N>;
-        e = hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        // maps of at most 16 columns (every tile touches both ends of the dy rows, which must hold
+        // a whole quad) take the shifting variant
+        const bool shift = g.W <= 16 && g.OW >= 4;
+        typedef void (*kernel_t)(const uint16_t*, const uint16_t*, float*, GiMfmaArgs);
+        const kernel_t kfn = shift ? ukst_grad_input_mfma_bf16_kernel<N, true>
+                                   : ukst_grad_input_mfma_bf16_kernel<N, false>;
+        e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e == hipSuccess) {
             const unsigned nb = (unsigned)((long long)a.tilesX * a.tilesY * a.tilesB * a.ciTiles);
-            hipLaunchKernelGGL((ukst_grad_input_mfma_bf16_kernel<N>), dim3(nb, (unsigned)a.KS), dim3(256), lds,
-                               stream, (const uint16_t*)dy, (const uint16_t*)wp, a.KS > 1 ? part : dx, a);
+            hipLaunchKernelGGL(kfn, dim3(nb, (unsigned)a.KS), dim3(256), lds, stream, (const uint16_t*)dy,
+                               (const uint16_t*)wp, a.KS > 1 ? part : dx, a);
             e = hipGetLastError();
         }
         if (e == hipSuccess && a.KS > 1) {
