@@ -432,8 +432,8 @@ __global__ __launch_bounds__(256, 2) void ukst_grad_input_mfma_kernel(const TIn*
 }
 
 // dw[i] = sum over the partial copies, in an order that depends on (copies, R) only: the block's
-// 256 threads are 256/R elements x R lanes, lane r adds copies r, r+R, r+2R, ... in sequence, and
-// the R lane sums are added pairwise in a fixed tree.  R > 1 serves layers with few kernel
+// 256 threads are 256/R elements x R lanes, lane r adds copies r, r+R, r+2R, ... into four running
+// sums taken in turn, and the R lane sums are added pairwise in a fixed tree.  R > 1 serves layers with few kernel
 // elements and many copies.
 __global__ __launch_bounds__(256) void ukst_sum_partials_kernel(const float* __restrict__ part,
                                                                float* __restrict__ dw, int n, int copies,
@@ -443,9 +443,18 @@ __global__ __launch_bounds__(256) void ukst_sum_partials_kernel(const float* __r
     const int R = 1 << logR;
     const int r = threadIdx.x & (R - 1);
     const int i = blockIdx.x * (256 >> logR) + (threadIdx.x >> logR);
+    // four running sums per lane (copies k, k+R, k+2R, k+3R in turn): four loads in flight
     float s = 0.f;
-    if (i < n)
-        for (int k = r; k < copies; k += R) s += part[(size_t)k * n + i];
+    if (i < n) {
+        float s4[4] = {0.f, 0.f, 0.f, 0.f};
+        int k = r;
+        for (; k + 3 * R < copies; k += 4 * R) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) s4[u] += part[(size_t)(k + u * R) * n + i];
+        }
+        for (int u = 0; k < copies; k += R, ++u) s4[u] += part[(size_t)k * n + i];
+        s = (s4[0] + s4[1]) + (s4[2] + s4[3]);
+    }
     red[threadIdx.x] = s;
     for (int m = R >> 1; m > 0; m >>= 1) {
         __syncthreads();
@@ -1228,7 +1237,7 @@ __global__ __launch_bounds__(256, 2) void ukst_grad_weight_mfma_kernel(const TIn
     }
 }
 
-// dw[co][ci][tap] = sum over the copies of part[copy][co][tap][ci], copies added in sequence;
+// dw[co][ci][tap] = sum over the copies of part[copy][co][tap][ci], copies added in a fixed order;
 // threads run along the copies' layout (coalesced reads), the single write pass is scattered
 __global__ __launch_bounds__(256) void ukst_sum_taps_kernel(const float* __restrict__ part,
                                                            float* __restrict__ dw, int n, int copies,
@@ -1236,8 +1245,15 @@ __global__ __launch_bounds__(256) void ukst_sum_taps_kernel(const float* __restr
 {
     const int s = blockIdx.x * 256 + threadIdx.x;
     if (s >= n) return;
-    float v = part[s];
-    for (int k = 1; k < copies; ++k) v += part[(size_t)k * n + s];
+    // four running sums (copies k, k+1, k+2, k+3 in turn): four loads in flight
+    float v4[4] = {0.f, 0.f, 0.f, 0.f};
+    int k = 0;
+    for (; k + 3 < copies; k += 4) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v4[u] += part[(size_t)(k + u) * n + s];
+    }
+    for (int u = 0; k < copies; ++k, ++u) v4[u] += part[(size_t)k * n + s];
+    const float v = (v4[0] + v4[1]) + (v4[2] + v4[3]);
     const int ci = s % Cin, r = s / Cin;
     const int tap = r % NN, co = r / NN;
     dw[((size_t)co * Cin + ci) * NN + tap] = v;
