@@ -2,11 +2,11 @@
  * ukst -- unified kernel-segregated stride-2 2-D transpose convolution for AMD MI355X (gfx950).
  *
  * C ABI, stateless: nothing is cached or kept between calls (weights are re-read and re-gathered
- * by every call) and no call synchronises.  One kernel family takes scratch memory for the
- * duration of a call: the fp32 matrix-core path splits the input channels of layers with very few
- * output tiles over several blocks and keeps their partial outputs in memory obtained with
- * hipMallocAsync / hipFreeAsync on the caller's stream; the kernel-gradient call does the same
- * for its partial sums (no other allocation anywhere).
+ * by every call), no call synchronises, and no call allocates or frees memory.  Kernels that need
+ * scratch memory for the duration of a call (partial sums of a split reduction, re-packed
+ * weights) take it from a workspace the caller owns: ukst_workspace_bytes() gives its size from
+ * the shape alone, the entry points that can use one have `workspace` / `workspace_bytes`
+ * arguments.
  *
  * What is computed (Algorithm 1 of the paper is the definition, Algorithm 2 + Eqs. 1-4 + the
  * padding rule of Sec. 3.4 are how it is evaluated):
@@ -28,6 +28,8 @@
 #ifndef UKST_H
 #define UKST_H
 
+#include <stddef.h>
+
 #ifdef __cplusplus
 extern "C" {
 #endif
@@ -46,7 +48,9 @@ typedef enum {
     UKST_ERR_SHAPE = 2,       /* a dimension < 1, P < 0, or an empty output (2H+2P-n < 1 ...) */
     UKST_ERR_DTYPE = 3,       /* dtype is not a ukst_dtype */
     UKST_ERR_UNSUPPORTED = 4, /* n > UKST_MAX_N, unknown path id, or path cannot run this shape */
-    UKST_ERR_LAUNCH = 5       /* the HIP runtime reported an error at launch */
+    UKST_ERR_LAUNCH = 5,      /* the HIP runtime reported an error at launch */
+    UKST_ERR_WORKSPACE = 6    /* workspace NULL with a non-zero size, not 256-byte aligned, or smaller
+                                 than ukst_workspace_bytes() for this call */
 } ukst_status;
 
 /* Kernel families ("paths").  UKST_PATH_AUTO picks by channel width. */
@@ -111,7 +115,8 @@ int ukst_select_path(int B, int Cin, int Cout, int H, int W, int n, int P, int d
  * output channels) aligned to 16 bytes: when they are not, ukst_conv_transpose2d uses the vector-ALU kernels instead.  The caller owns all buffers;
  * the call enqueues work on `stream` and returns without synchronising.  Arguments are validated
  * on the host before anything touches the GPU; on a validation error nothing is launched.  A
- * failing scratch allocation or launch is reported as UKST_ERR_LAUNCH.
+ * failing launch is reported as UKST_ERR_LAUNCH.  This entry point (like the two below it) takes
+ * no workspace and uses only kernels that need none; see ukst_conv_transpose2d_ws.
  * Returns a ukst_status.
  */
 int ukst_conv_transpose2d(const void* x, const void* w, void* y, int B, int Cin, int Cout, int H,
@@ -145,6 +150,42 @@ int ukst_conv_transpose2d_bias_act(const void* x, const void* w, const float* bi
                                    int Cin, int Cout, int H, int W, int n, int P, int dtype,
                                    int act, int path, void* stream);
 
+/* The operations that may want a workspace (argument `op` of ukst_workspace_bytes). */
+typedef enum { UKST_OP_FORWARD = 0, UKST_OP_GRAD_INPUT = 1, UKST_OP_GRAD_WEIGHT = 2 } ukst_op;
+
+/*
+ * Bytes of scratch memory the given operation uses on this problem (host arithmetic only, a
+ * function of the arguments alone; 0 if the operation needs none, or on invalid arguments).
+ *   UKST_OP_FORWARD      layers with fewer output tiles than compute units on the fp32
+ *                        matrix-core path divide the input channels of a tile among 2, 4 or 8
+ *                        blocks; each slice writes its partial sums to its own copy of y in the
+ *                        workspace and a second kernel adds the copies in slice order.
+ *   UKST_OP_GRAD_INPUT   matrix-core kernels (Cin >= 32, Cout >= 16): the weights re-packed once
+ *                        per call, plus, for layers with few pixels, one copy of dx per slice of
+ *                        the sum over output channels (added in slice order).
+ *   UKST_OP_GRAD_WEIGHT  one copy of dw per slice of the sum over batch and space (added in a
+ *                        fixed order); every kernel of this operation needs it.
+ * The workspace is caller-owned DEVICE memory, 256-byte aligned, needs no initialisation, holds
+ * nothing of value after the call's work has finished on its stream, and must not be used by
+ * another call that may run concurrently.
+ */
+size_t ukst_workspace_bytes(int op, int B, int Cin, int Cout, int H, int W, int n, int P, int dtype);
+
+/*
+ * ukst_conv_transpose2d_bias_act with a workspace (Algorithm 2, as above; bias == NULL and
+ * act == UKST_ACT_NONE give the plain transpose convolution).
+ *   workspace        DEVICE pointer as described at ukst_workspace_bytes, or NULL
+ *   workspace_bytes  its size
+ * With workspace == NULL (and workspace_bytes == 0) the call behaves like
+ * ukst_conv_transpose2d_bias_act: layers that would split their input channels keep the whole sum
+ * in one block per tile instead (same result up to fp32 summation order, fewer blocks).  With a
+ * workspace smaller than ukst_workspace_bytes(UKST_OP_FORWARD, ...) for a layer that uses one the
+ * call returns UKST_ERR_WORKSPACE and launches nothing.  Results are bit-reproducible either way.
+ */
+int ukst_conv_transpose2d_ws(const void* x, const void* w, const float* bias, void* y, int B, int Cin,
+                             int Cout, int H, int W, int n, int P, int dtype, int act, int path,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
 /*
  * Backward pass of the same layer: the gradients of  L = sum(dy * y)  for y = the transpose
  * convolution above (Algorithm 1 is the definition; these are its adjoints).  The paper measures
@@ -163,19 +204,20 @@ int ukst_conv_transpose2d_bias_act(const void* x, const void* w, const float* bi
  *   dw      DEVICE pointer, [Cout][Cin][n][n] contiguous fp32, every element overwritten
  *   dtype   UKST_F32 (all fp32) or UKST_BF16_F32 (the two operands bf16, the gradient fp32,
  *           fp32 accumulation); UKST_BF16_BF16 gives UKST_ERR_UNSUPPORTED
+ *   workspace, workspace_bytes   caller-owned scratch of at least
+ *           ukst_workspace_bytes(UKST_OP_GRAD_INPUT / UKST_OP_GRAD_WEIGHT, ...) bytes (NULL and 0
+ *           where that is 0); UKST_ERR_WORKSPACE otherwise, with nothing launched
  *   B..P, stream, alignment (element alignment only), ownership, asynchrony and error behaviour
  *   as for ukst_conv_transpose2d; outputs must not overlap inputs.
  *
- * ukst_conv_transpose2d_grad_weight sums over batch and space in slices and keeps the slices'
- * partial results in memory obtained with hipMallocAsync / hipFreeAsync on the caller's stream;
- * the partial results are added in a fixed order (results are bit-reproducible).  The matrix-core
- * kernel of ukst_conv_transpose2d_grad_input takes its packed weights (and, for layers with few
- * pixels, slices of the sum over output channels) from the same kind of memory.
+ * Partial results are added in a fixed order: both gradients are bit-reproducible.
  */
 int ukst_conv_transpose2d_grad_input(const void* dy, const void* w, void* dx, int B, int Cin,
-                                     int Cout, int H, int W, int n, int P, int dtype, void* stream);
+                                     int Cout, int H, int W, int n, int P, int dtype,
+                                     void* workspace, size_t workspace_bytes, void* stream);
 int ukst_conv_transpose2d_grad_weight(const void* x, const void* dy, void* dw, int B, int Cin,
-                                      int Cout, int H, int W, int n, int P, int dtype, void* stream);
+                                      int Cout, int H, int W, int n, int P, int dtype,
+                                      void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Name of the main device kernel a backward call launches for this problem (which = 0:
@@ -184,10 +226,10 @@ int ukst_conv_transpose2d_grad_weight(const void* x, const void* dy, void* dw, i
  * Wide layers (Cin >= 32, Cout >= 16) run the input gradient on the matrix cores
  * ("ukst_grad_input_mfma_bf16_kernel": bf16 MFMA for bf16 operands where its LDS tile fits, i.e.
  * kernel sides up to about 5;
- * "ukst_grad_input_mfma_kernel": fp32 MFMA otherwise; weights packed once per call into
- * stream-ordered scratch, which also holds the copies of dx when the sum over output channels is
- * split), layers with Cin, Cout >= 32 run the kernel gradient there ("ukst_grad_weight_mfma_kernel",
- * fp32 MFMA for either dtype); everything else runs on the vector ALUs.
+ * "ukst_grad_input_mfma_kernel": fp32 MFMA otherwise; weights packed once per call into the
+ * workspace, which also holds the copies of dx when the sum over output channels is split),
+ * layers with Cin, Cout >= 32 run the kernel gradient there ("ukst_grad_weight_mfma_kernel", fp32
+ * MFMA for either dtype); everything else runs on the vector ALUs.
  */
 const char* ukst_grad_kernel_name(int which, int B, int Cin, int Cout, int H, int W, int n, int P,
                                   int dtype);
@@ -198,17 +240,6 @@ const char* ukst_grad_kernel_name(int which, int B, int Cin, int Cout, int H, in
  */
 const char* ukst_kernel_name(int B, int Cin, int Cout, int H, int W, int n, int P, int dtype,
                              int path);
-
-/*
- * Benchmark helper, not part of the operation: enqueues on `stream` one launch of a
- * register-resident loop of independent MFMAs (dtype UKST_BF16_F32: 32x32x16 bf16, UKST_F32:
- * 32x32x2 fp32; `iters` rounds of 4 per wave, two blocks of four waves per compute unit) and
- * returns the floating-point operations that launch performs, or 0 on a bad argument or a failed
- * launch.  The caller times the launch: the rate is the ceiling the matrix pipes sustain at the
- * clock the chip settles on, to be printed next to the published peak.  `sink` is a DEVICE
- * buffer of at least 64 floats that is practically never written.
- */
-double ukst_bench_mfma_ceiling(int dtype, int iters, void* sink, void* stream);
 
 #ifdef __cplusplus
 }

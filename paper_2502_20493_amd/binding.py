@@ -10,9 +10,12 @@ import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libukst.so")
+BENCH_LIB_PATH = os.path.join(_HERE, "libukst_bench.so")
 
 UKST_F32, UKST_BF16_F32, UKST_BF16_BF16 = 0, 1, 2
-UKST_OK, UKST_ERR_NULL, UKST_ERR_SHAPE, UKST_ERR_DTYPE, UKST_ERR_UNSUPPORTED, UKST_ERR_LAUNCH = range(6)
+(UKST_OK, UKST_ERR_NULL, UKST_ERR_SHAPE, UKST_ERR_DTYPE, UKST_ERR_UNSUPPORTED, UKST_ERR_LAUNCH,
+ UKST_ERR_WORKSPACE) = range(7)
+UKST_OP_FORWARD, UKST_OP_GRAD_INPUT, UKST_OP_GRAD_WEIGHT = 0, 1, 2
 UKST_PATH_AUTO, UKST_PATH_DIRECT, UKST_PATH_MFMA = 0, 1, 2
 UKST_MAX_N = 7
 UKST_ACT_NONE, UKST_ACT_RELU, UKST_ACT_TANH = 0, 1, 2
@@ -20,11 +23,14 @@ UKST_ACT_NONE, UKST_ACT_RELU, UKST_ACT_TANH = 0, 1, 2
 # every symbol include/ukst.h declares
 EXPORTS = ["ukst_version", "ukst_status_string", "ukst_output_shape", "ukst_mac_count",
            "ukst_select_path", "ukst_conv_transpose2d", "ukst_conv_transpose2d_path",
-           "ukst_kernel_name", "ukst_bench_mfma_ceiling", "ukst_conv_transpose2d_bias_act",
-           "ukst_conv_transpose2d_grad_input", "ukst_conv_transpose2d_grad_weight",
-           "ukst_grad_kernel_name"]
+           "ukst_kernel_name", "ukst_conv_transpose2d_bias_act", "ukst_workspace_bytes",
+           "ukst_conv_transpose2d_ws", "ukst_conv_transpose2d_grad_input",
+           "ukst_conv_transpose2d_grad_weight", "ukst_grad_kernel_name"]
+# every symbol include/ukst_bench.h declares (libukst_bench.so: measurement helpers)
+BENCH_EXPORTS = ["ukst_bench_mfma_ceiling", "ukst_bench_stream_ceiling"]
 
 _lib = None
+_bench_lib = None
 
 
 class UkstError(RuntimeError):
@@ -60,16 +66,34 @@ def lib():
         L.ukst_conv_transpose2d_path.argtypes = [vp, vp, vp] + [i] * 9 + [vp]
         L.ukst_conv_transpose2d_path.restype = i
         L.ukst_kernel_name.argtypes, L.ukst_kernel_name.restype = [i] * 9, ctypes.c_char_p
-        L.ukst_bench_mfma_ceiling.argtypes = [i, i, vp, vp]
         L.ukst_conv_transpose2d_bias_act.argtypes = [vp, vp, vp, vp] + [i] * 10 + [vp]
         L.ukst_conv_transpose2d_bias_act.restype = i
-        L.ukst_bench_mfma_ceiling.restype = ctypes.c_double
+        L.ukst_workspace_bytes.argtypes, L.ukst_workspace_bytes.restype = [i] * 9, ctypes.c_size_t
+        L.ukst_conv_transpose2d_ws.argtypes = [vp, vp, vp, vp] + [i] * 10 + [vp, ctypes.c_size_t, vp]
+        L.ukst_conv_transpose2d_ws.restype = i
         L.ukst_grad_kernel_name.argtypes, L.ukst_grad_kernel_name.restype = [i] * 9, ctypes.c_char_p
         for f in (L.ukst_conv_transpose2d_grad_input, L.ukst_conv_transpose2d_grad_weight):
-            f.argtypes = [vp, vp, vp] + [i] * 8 + [vp]
+            f.argtypes = [vp, vp, vp] + [i] * 8 + [vp, ctypes.c_size_t, vp]
             f.restype = i
         _lib = L
     return _lib
+
+
+def bench_lib():
+    """Load libukst_bench.so (once): the measured ceilings of include/ukst_bench.h."""
+    global _bench_lib
+    if _bench_lib is None:
+        if not os.path.exists(BENCH_LIB_PATH):
+            raise RuntimeError(f"{BENCH_LIB_PATH} is missing: python -m paper_2502_20493_amd.build")
+        import torch  # noqa: F401  (same load-order requirement as lib())
+        L = ctypes.CDLL(BENCH_LIB_PATH)
+        i, vp = ctypes.c_int, ctypes.c_void_p
+        L.ukst_bench_mfma_ceiling.argtypes = [i, i, vp, vp]
+        L.ukst_bench_mfma_ceiling.restype = ctypes.c_double
+        L.ukst_bench_stream_ceiling.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_size_t, vp]
+        L.ukst_bench_stream_ceiling.restype = i
+        _bench_lib = L
+    return _bench_lib
 
 
 def _check(status: int):
@@ -115,8 +139,43 @@ def ukst_bench_mfma_ceiling(dtype: int, iters: int, sink, stream=None) -> float:
         raise ValueError("sink must be a float32 device tensor with at least 64 elements")
     if stream is None:
         stream = torch.cuda.current_stream(sink.device)
-    return float(lib().ukst_bench_mfma_ceiling(int(dtype), int(iters), sink.data_ptr(),
-                                               stream.cuda_stream))
+    return float(bench_lib().ukst_bench_mfma_ceiling(int(dtype), int(iters), sink.data_ptr(),
+                                                     stream.cuda_stream))
+
+
+def ukst_bench_stream_ceiling(src, dst, stream=None) -> None:
+    """Enqueue the streaming kernel: reads all of src, writes all of dst (device tensors whose
+    byte sizes are multiples of 16)."""
+    import torch
+
+    if stream is None:
+        stream = torch.cuda.current_stream(src.device)
+    rc = bench_lib().ukst_bench_stream_ceiling(src.data_ptr(), src.numel() * src.element_size(),
+                                               dst.data_ptr(), dst.numel() * dst.element_size(),
+                                               stream.cuda_stream)
+    if rc != 0:
+        raise RuntimeError("ukst_bench_stream_ceiling failed")
+
+
+def ukst_workspace_bytes(op: int, B, Cin, Cout, H, W, n, P, dtype) -> int:
+    return int(lib().ukst_workspace_bytes(int(op), B, Cin, Cout, H, W, n, P, dtype))
+
+
+def _workspace(workspace, need: int, device, stream):
+    """The (pointer, size) pair of a call.  workspace: None = allocate `need` bytes with torch for
+    this call (torch supplies device memory; the library itself never allocates), False = pass
+    none, or a caller-provided uint8 device tensor."""
+    import torch
+
+    if workspace is False or (workspace is None and need == 0):
+        return None, 0, None
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=device)
+        if hasattr(stream, "cuda_stream"):
+            workspace.record_stream(stream)  # the block must outlive the work enqueued on `stream`
+    if not (workspace.is_cuda and workspace.dtype == torch.uint8 and workspace.is_contiguous()):
+        raise ValueError("workspace must be a contiguous uint8 device tensor")
+    return workspace.data_ptr(), workspace.numel(), workspace
 
 
 def ukst_conv_transpose2d_raw(x_ptr, w_ptr, y_ptr, B, Cin, Cout, H, W, n, P, dtype,
@@ -127,7 +186,8 @@ def ukst_conv_transpose2d_raw(x_ptr, w_ptr, y_ptr, B, Cin, Cout, H, W, n, P, dty
 
 
 def ukst_conv_transpose2d_bias_act(x, w, P: int, bias=None, act: int = UKST_ACT_NONE, y=None,
-                                   path: int = UKST_PATH_AUTO, stream=None, out_bf16: bool = False):
+                                   path: int = UKST_PATH_AUTO, stream=None, out_bf16: bool = False,
+                                   workspace=False):
     """Marshal torch device tensors into ukst_conv_transpose2d_bias_act:
     y = act(conv_transpose(x, w) + bias[co]); bias: float32 device tensor [Cout] or None."""
     import torch
@@ -137,12 +197,24 @@ def ukst_conv_transpose2d_bias_act(x, w, P: int, bias=None, act: int = UKST_ACT_
                 and tuple(bias.shape) == (w.shape[0],)):
             raise ValueError("bias must be a contiguous float32 device tensor [Cout]")
     return ukst_conv_transpose2d(x, w, P, y=y, path=path, stream=stream, out_bf16=out_bf16,
-                                 _bias=bias, _act=act)
+                                 workspace=workspace, _bias=bias, _act=act)
+
+
+def ukst_conv_transpose2d_ws(x, w, P: int, bias=None, act: int = UKST_ACT_NONE, y=None,
+                             path: int = UKST_PATH_AUTO, stream=None, out_bf16: bool = False,
+                             workspace=None):
+    """Marshal torch device tensors into ukst_conv_transpose2d_ws.  workspace: a uint8 device
+    tensor of at least ukst_workspace_bytes(UKST_OP_FORWARD, ...) bytes, or None to have one
+    allocated with torch for this call."""
+    return ukst_conv_transpose2d_bias_act(x, w, P, bias=bias, act=act, y=y, path=path, stream=stream,
+                                          out_bf16=out_bf16, workspace=workspace)
 
 
 def ukst_conv_transpose2d(x, w, P: int, y=None, path: int = UKST_PATH_AUTO, stream=None,
-                          out_bf16: bool = False, _bias=None, _act=None):
-    """Marshal torch device tensors into ukst_conv_transpose2d.
+                          out_bf16: bool = False, workspace=False, _bias=None, _act=None):
+    """Marshal torch device tensors into ukst_conv_transpose2d (workspace=False, the default: the
+    entry points that take no workspace) or ukst_conv_transpose2d_ws (workspace=None: allocated
+    with torch for this call; or a uint8 device tensor).
 
     x: [B,Cin,H,W] float32 or bfloat16, w: [Cout,Cin,n,n] same dtype, both contiguous on the GPU.
     y: optional preallocated float32 [B,Cout,OH,OW]; allocated with torch when omitted.
@@ -178,7 +250,14 @@ def ukst_conv_transpose2d(x, w, P: int, y=None, path: int = UKST_PATH_AUTO, stre
         stream = torch.cuda.current_stream(x.device)
     sp = stream.cuda_stream if hasattr(stream, "cuda_stream") else stream
     with torch.cuda.device(x.device):
-        if _act is None:
+        if workspace is not False:
+            need = ukst_workspace_bytes(UKST_OP_FORWARD, B, Cin, Cout, H, W, n, P, dtype)
+            wp, wb, _keep = _workspace(workspace, need, x.device, stream)
+            _check(int(lib().ukst_conv_transpose2d_ws(
+                x.data_ptr(), w.data_ptr(), None if _bias is None else _bias.data_ptr(),
+                y.data_ptr(), B, Cin, Cout, H, W, n, P, dtype,
+                UKST_ACT_NONE if _act is None else int(_act), path, wp, wb, sp)))
+        elif _act is None:
             _check(ukst_conv_transpose2d_raw(x.data_ptr(), w.data_ptr(), y.data_ptr(), B, Cin, Cout,
                                              H, W, n, P, dtype, path, sp))
         else:
@@ -214,9 +293,12 @@ def _out(t, shape, device):
     return t
 
 
-def ukst_conv_transpose2d_grad_input(dy, w, H: int, W: int, P: int, dx=None, stream=None):
+def ukst_conv_transpose2d_grad_input(dy, w, H: int, W: int, P: int, dx=None, stream=None,
+                                     workspace=None):
     """Marshal torch device tensors into ukst_conv_transpose2d_grad_input.
-    dy: [B,Cout,OH,OW], w: [Cout,Cin,n,n] (float32 or bfloat16) -> dx float32 [B,Cin,H,W]."""
+    dy: [B,Cout,OH,OW], w: [Cout,Cin,n,n] (float32 or bfloat16) -> dx float32 [B,Cin,H,W].
+    workspace: uint8 device tensor (>= ukst_workspace_bytes(UKST_OP_GRAD_INPUT, ...)), or None to
+    have it allocated with torch for this call."""
     import torch
 
     dtype = _backward_operands(dy, w)
@@ -229,14 +311,18 @@ def ukst_conv_transpose2d_grad_input(dy, w, H: int, W: int, P: int, dx=None, str
         stream = torch.cuda.current_stream(dy.device)
     sp = stream.cuda_stream if hasattr(stream, "cuda_stream") else stream
     with torch.cuda.device(dy.device):
+        need = ukst_workspace_bytes(UKST_OP_GRAD_INPUT, B, Cin, Cout, H, W, n, P, dtype)
+        wp, wb, _keep = _workspace(workspace, need, dy.device, stream)
         _check(int(lib().ukst_conv_transpose2d_grad_input(dy.data_ptr(), w.data_ptr(), dx.data_ptr(),
-                                                          B, Cin, Cout, H, W, n, P, dtype, sp)))
+                                                          B, Cin, Cout, H, W, n, P, dtype, wp, wb, sp)))
     return dx
 
 
-def ukst_conv_transpose2d_grad_weight(x, dy, n: int, P: int, dw=None, stream=None):
+def ukst_conv_transpose2d_grad_weight(x, dy, n: int, P: int, dw=None, stream=None, workspace=None):
     """Marshal torch device tensors into ukst_conv_transpose2d_grad_weight.
-    x: [B,Cin,H,W], dy: [B,Cout,OH,OW] (float32 or bfloat16) -> dw float32 [Cout,Cin,n,n]."""
+    x: [B,Cin,H,W], dy: [B,Cout,OH,OW] (float32 or bfloat16) -> dw float32 [Cout,Cin,n,n].
+    workspace: uint8 device tensor (>= ukst_workspace_bytes(UKST_OP_GRAD_WEIGHT, ...)), or None to
+    have it allocated with torch for this call."""
     import torch
 
     dtype = _backward_operands(x, dy)
@@ -249,6 +335,8 @@ def ukst_conv_transpose2d_grad_weight(x, dy, n: int, P: int, dw=None, stream=Non
         stream = torch.cuda.current_stream(x.device)
     sp = stream.cuda_stream if hasattr(stream, "cuda_stream") else stream
     with torch.cuda.device(x.device):
+        need = ukst_workspace_bytes(UKST_OP_GRAD_WEIGHT, B, Cin, Cout, H, W, n, P, dtype)
+        wp, wb, _keep = _workspace(workspace, need, x.device, stream)
         _check(int(lib().ukst_conv_transpose2d_grad_weight(x.data_ptr(), dy.data_ptr(), dw.data_ptr(),
-                                                           B, Cin, Cout, H, W, n, P, dtype, sp)))
+                                                           B, Cin, Cout, H, W, n, P, dtype, wp, wb, sp)))
     return dw

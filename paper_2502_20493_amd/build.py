@@ -10,6 +10,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libukst.so")
+BENCH_LIB = os.path.join(HERE, "libukst_bench.so")  # measurement helpers, not part of the product
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -21,6 +22,10 @@ OBJDIR = os.path.join(HERE, "_build")
 
 def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
+
+
+def bench_sources():
+    return sorted(glob.glob(os.path.join(CSRC, "bench", "*.hip")))
 
 
 def _run(cmd, verbose):
@@ -36,26 +41,29 @@ def _run(cmd, verbose):
 
 
 def build_library(verbose: bool = False, jobs: int | None = None) -> str:
-    """Compile every csrc/*.hip to an object (in parallel) and link libukst.so."""
+    """Compile every csrc/*.hip to an object (in parallel) and link libukst.so; csrc/bench/*.hip
+    become libukst_bench.so (the benchmark's measured ceilings)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     os.makedirs(OBJDIR, exist_ok=True)
-    srcs = sources()
+    srcs, bsrcs = sources(), bench_sources()
     objs = [os.path.join(OBJDIR, os.path.basename(s)[:-4] + ".o") for s in srcs]
+    bobjs = [os.path.join(OBJDIR, "bench_" + os.path.basename(s)[:-4] + ".o") for s in bsrcs]
     jobs = jobs or max(1, min(len(srcs), int(os.environ.get("MAX_JOBS", os.cpu_count() or 1)), 16))
     with ThreadPoolExecutor(max_workers=jobs) as pool:
         futs = [pool.submit(_run, [hipcc] + HIPCC_FLAGS + ["-c", s, "-o", o], verbose)
-                for s, o in zip(srcs, objs)]
+                for s, o in zip(srcs + bsrcs, objs + bobjs)]
         for f in futs:
             f.result()
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB], verbose)
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + bobjs + ["-o", BENCH_LIB], verbose)
     return LIB
 
 
 def is_stale() -> bool:
-    if not os.path.exists(LIB):
+    if not os.path.exists(LIB) or not os.path.exists(BENCH_LIB):
         return True
-    t = os.path.getmtime(LIB)
-    deps = sources() + glob.glob(os.path.join(CSRC, "*.h")) + \
+    t = min(os.path.getmtime(LIB), os.path.getmtime(BENCH_LIB))
+    deps = sources() + bench_sources() + glob.glob(os.path.join(CSRC, "*.h")) + \
         glob.glob(os.path.join(HERE, "..", "include", "*.h"))
     return any(os.path.getmtime(d) > t for d in deps)
 

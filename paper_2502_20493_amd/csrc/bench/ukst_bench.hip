@@ -1,9 +1,13 @@
-// Measured ceiling of the matrix pipes, printed by the benchmark next to the published peak: a
-// register-resident loop of independent MFMAs, no memory traffic at all.  What it reaches is the
-// rate the chip sustains at the clock its power management settles on under matrix load; a real
-// kernel cannot beat it.  Not part of the transpose convolution.
-#include "../../include/ukst.h"
+// Measured ceilings printed by the benchmark next to the published peaks (libukst_bench.so; not
+// part of the transpose convolution).
+// Matrix pipes: a register-resident loop of independent MFMAs, no memory traffic at all.  What it
+// reaches is the rate the chip sustains at the clock its power management settles on under matrix
+// load; a real kernel cannot beat it.
+// Memory: a streaming kernel that reads R bytes and writes W bytes, the traffic of a layer with
+// that much input and output.
+#include "../../../include/ukst_bench.h"
 #include <hip/hip_runtime.h>
+#include <stdint.h>
 
 namespace {
 
@@ -54,10 +58,42 @@ __global__ __launch_bounds__(256) void ukst_mfma_ceiling_kernel(float* sink, int
     if (s == 123456.789f) sink[lane] = s;  // keeps the loop alive; practically never taken
 }
 
+// Thread t of the grid reads the 16-byte pieces t, t + T, t + 2T, ... of src (T = threads of the
+// grid) and then writes the pieces t, t + T, ... of dst: the launch reads all of src once and
+// writes all of dst once, a wave's accesses are consecutive.
+__global__ __launch_bounds__(256) void ukst_stream_ceiling_kernel(const uint4* __restrict__ src,
+                                                                 size_t nread, uint4* __restrict__ dst,
+                                                                 size_t nwrite)
+{
+    const size_t T = (size_t)gridDim.x * 256, t = (size_t)blockIdx.x * 256 + threadIdx.x;
+    uint4 acc = make_uint4(0u, 0u, 0u, 0u);
+    for (size_t i = t; i < nread; i += T) {
+        const uint4 v = src[i];
+        acc.x ^= v.x; acc.y ^= v.y; acc.z ^= v.z; acc.w ^= v.w;
+    }
+    for (size_t i = t; i < nwrite; i += T) dst[i] = acc;
+}
+
 }  // namespace
+
+extern "C" int ukst_bench_stream_ceiling(const void* src, size_t read_bytes, void* dst,
+                                         size_t write_bytes, void* stream)
+{
+    if (!src || !dst || (read_bytes & 15) || (write_bytes & 15) || (((uintptr_t)src | (uintptr_t)dst) & 15))
+        return -1;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return -1;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return -1;
+    // 8 blocks per compute unit: every SIMD holds two waves per block slot, pieces are strided so
+    // that a wave's accesses are consecutive
+    hipLaunchKernelGGL(ukst_stream_ceiling_kernel, dim3(8 * cus), dim3(256), 0, (hipStream_t)stream,
+                       (const uint4*)src, read_bytes / 16, (uint4*)dst, write_bytes / 16);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
 
 extern "C" double ukst_bench_mfma_ceiling(int dtype, int iters, void* sink, void* stream)
 {
+    constexpr int UKST_F32 = 0, UKST_BF16_F32 = 1;
     if (!sink || iters < 1 || (dtype != UKST_F32 && dtype != UKST_BF16_F32)) return 0.0;
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0.0;

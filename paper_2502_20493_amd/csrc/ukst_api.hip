@@ -50,7 +50,7 @@ int resolve_path(const ukst::Geom& g, int dtype, int path)
 
 extern "C" {
 
-int ukst_version(void) { return 100; }
+int ukst_version(void) { return 200; }
 
 const char* ukst_status_string(int status)
 {
@@ -61,6 +61,7 @@ const char* ukst_status_string(int status)
         case UKST_ERR_DTYPE: return "unknown dtype";
         case UKST_ERR_UNSUPPORTED: return "unsupported: kernel side above UKST_MAX_N or path cannot run this shape";
         case UKST_ERR_LAUNCH: return "HIP launch error";
+        case UKST_ERR_WORKSPACE: return "workspace missing, misaligned or smaller than ukst_workspace_bytes";
         default: return "unknown status";
     }
 }
@@ -105,9 +106,11 @@ int ukst_select_path(int B, int Cin, int Cout, int H, int W, int n, int P, int d
     return resolve_path(ukst::make_geom(B, Cin, Cout, H, W, n, P), dtype, UKST_PATH_AUTO);
 }
 
-static int run_checked(const void* x, const void* w, const float* bias, int act, void* y, int B,
-                       int Cin, int Cout, int H, int W, int n, int P, int dtype, int path,
-                       void* stream)
+// Validation shared by the forward entry points and the workspace query; on UKST_OK `g` holds the
+// geometry with the epilogue and `chosen` the kernel family.
+static int forward_checked(const void* x, const void* w, const float* bias, int act, const void* y,
+                           int B, int Cin, int Cout, int H, int W, int n, int P, int dtype, int path,
+                           ukst::Geom& g, int& chosen)
 {
     if (!x || !w || !y) return UKST_ERR_NULL;
     const int st = validate_shape(B, Cin, Cout, H, W, n, P);
@@ -118,7 +121,7 @@ static int run_checked(const void* x, const void* w, const float* bias, int act,
         return UKST_ERR_UNSUPPORTED;
     if (act != UKST_ACT_NONE && act != UKST_ACT_RELU && act != UKST_ACT_TANH)
         return UKST_ERR_UNSUPPORTED;
-    ukst::Geom g = ukst::make_geom(B, Cin, Cout, H, W, n, P);
+    g = ukst::make_geom(B, Cin, Cout, H, W, n, P);
     g.ep.bias = bias;
     g.ep.act = act;
     // element alignment is required of every buffer; the matrix-core kernels move the weights
@@ -126,30 +129,84 @@ static int run_checked(const void* x, const void* w, const float* bias, int act,
     const uintptr_t esz = dtype == UKST_F32 ? 4 : 2, osz = dtype == UKST_BF16_BF16 ? 2 : 4;
     if (((uintptr_t)x | (uintptr_t)w) & (esz - 1) || ((uintptr_t)y & (osz - 1)) || ((uintptr_t)bias & 3))
         return UKST_ERR_UNSUPPORTED;
-    int chosen = resolve_path(g, dtype, path);
+    chosen = resolve_path(g, dtype, path);
     const bool x16 = chosen == UKST_PATH_MFMA && ukst::mfma_needs_aligned_x(g, dtype);
     const bool wide_ok = (((uintptr_t)w | (x16 ? (uintptr_t)x : 0)) & 15) == 0;
     if (chosen == UKST_PATH_MFMA && !wide_ok) chosen = (path == UKST_PATH_AUTO) ? UKST_PATH_DIRECT : -1;
-    if (chosen < 0) return UKST_ERR_UNSUPPORTED;
+    return chosen < 0 ? UKST_ERR_UNSUPPORTED : UKST_OK;
+}
+
+static int status_of(hipError_t e)
+{
+    return e == hipSuccess ? UKST_OK : e == ukst::kWorkspaceTooSmall ? UKST_ERR_WORKSPACE : UKST_ERR_LAUNCH;
+}
+
+static int workspace_checked(const void* workspace, size_t bytes)
+{
+    if (workspace == nullptr) return bytes == 0 ? UKST_OK : UKST_ERR_WORKSPACE;
+    return ((uintptr_t)workspace & 255) == 0 ? UKST_OK : UKST_ERR_WORKSPACE;
+}
+
+static int run_checked(const void* x, const void* w, const float* bias, int act, void* y, int B,
+                       int Cin, int Cout, int H, int W, int n, int P, int dtype, int path,
+                       void* workspace, size_t workspace_bytes, void* stream)
+{
+    ukst::Geom g;
+    int chosen = -1;
+    const int st = forward_checked(x, w, bias, act, y, B, Cin, Cout, H, W, n, P, dtype, path, g, chosen);
+    if (st != UKST_OK) return st;
+    ukst::Workspace ws;
+    ws.ptr = workspace;
+    ws.bytes = workspace_bytes;
     hipError_t e;
     if (chosen == UKST_PATH_MFMA)
-        e = ukst::launch_mfma(g, x, w, (float*)y, dtype, (hipStream_t)stream);
+        e = ukst::launch_mfma(g, x, w, (float*)y, dtype, ws, (hipStream_t)stream);
     else
         e = ukst::launch_direct(g, x, w, (float*)y, dtype, (hipStream_t)stream);
-    return e == hipSuccess ? UKST_OK : UKST_ERR_LAUNCH;
+    return status_of(e);
 }
 
 int ukst_conv_transpose2d_path(const void* x, const void* w, void* y, int B, int Cin, int Cout,
                                int H, int W, int n, int P, int dtype, int path, void* stream)
 {
-    return run_checked(x, w, nullptr, UKST_ACT_NONE, y, B, Cin, Cout, H, W, n, P, dtype, path, stream);
+    return run_checked(x, w, nullptr, UKST_ACT_NONE, y, B, Cin, Cout, H, W, n, P, dtype, path, nullptr,
+                       0, stream);
 }
 
 int ukst_conv_transpose2d_bias_act(const void* x, const void* w, const float* bias, void* y, int B,
                                    int Cin, int Cout, int H, int W, int n, int P, int dtype,
                                    int act, int path, void* stream)
 {
-    return run_checked(x, w, bias, act, y, B, Cin, Cout, H, W, n, P, dtype, path, stream);
+    return run_checked(x, w, bias, act, y, B, Cin, Cout, H, W, n, P, dtype, path, nullptr, 0, stream);
+}
+
+int ukst_conv_transpose2d_ws(const void* x, const void* w, const float* bias, void* y, int B, int Cin,
+                             int Cout, int H, int W, int n, int P, int dtype, int act, int path,
+                             void* workspace, size_t workspace_bytes, void* stream)
+{
+    const int st = workspace_checked(workspace, workspace_bytes);
+    if (st != UKST_OK) return st;
+    return run_checked(x, w, bias, act, y, B, Cin, Cout, H, W, n, P, dtype, path, workspace,
+                       workspace_bytes, stream);
+}
+
+size_t ukst_workspace_bytes(int op, int B, int Cin, int Cout, int H, int W, int n, int P, int dtype)
+{
+    if (validate_shape(B, Cin, Cout, H, W, n, P) != UKST_OK || n > UKST_MAX_N) return 0;
+    if (dtype != UKST_F32 && dtype != UKST_BF16_F32 && dtype != UKST_BF16_BF16) return 0;
+    ukst::Geom g = ukst::make_geom(B, Cin, Cout, H, W, n, P);
+    ukst::Workspace ws;
+    ws.query = true;
+    hipError_t e = hipErrorInvalidValue;
+    if (op == UKST_OP_FORWARD) {
+        if (resolve_path(g, dtype, UKST_PATH_AUTO) != UKST_PATH_MFMA) return 0;
+        e = ukst::launch_mfma(g, nullptr, nullptr, nullptr, dtype, ws, nullptr);
+    } else if (dtype != UKST_BF16_BF16 && op == UKST_OP_GRAD_INPUT) {
+        e = ukst::launch_grad_input(g, nullptr, nullptr, nullptr, dtype, ws, nullptr);
+    } else if (dtype != UKST_BF16_BF16 && op == UKST_OP_GRAD_WEIGHT) {
+        e = ukst::launch_grad_weight(g, nullptr, nullptr, nullptr, dtype, ws, nullptr);
+    }
+    return e == hipSuccess ? ws.need : 0;
 }
 
 int ukst_conv_transpose2d(const void* x, const void* w, void* y, int B, int Cin, int Cout, int H,
@@ -174,23 +231,31 @@ static int backward_checked(const void* p0, const void* p1, void* out, int B, in
 }
 
 int ukst_conv_transpose2d_grad_input(const void* dy, const void* w, void* dx, int B, int Cin, int Cout,
-                                     int H, int W, int n, int P, int dtype, void* stream)
+                                     int H, int W, int n, int P, int dtype, void* workspace,
+                                     size_t workspace_bytes, void* stream)
 {
-    const int st = backward_checked(dy, w, dx, B, Cin, Cout, H, W, n, P, dtype);
+    int st = backward_checked(dy, w, dx, B, Cin, Cout, H, W, n, P, dtype);
     if (st != UKST_OK) return st;
+    if ((st = workspace_checked(workspace, workspace_bytes)) != UKST_OK) return st;
     const ukst::Geom g = ukst::make_geom(B, Cin, Cout, H, W, n, P);
-    return ukst::launch_grad_input(g, dy, w, (float*)dx, dtype, (hipStream_t)stream) == hipSuccess
-               ? UKST_OK : UKST_ERR_LAUNCH;
+    ukst::Workspace ws;
+    ws.ptr = workspace;
+    ws.bytes = workspace_bytes;
+    return status_of(ukst::launch_grad_input(g, dy, w, (float*)dx, dtype, ws, (hipStream_t)stream));
 }
 
 int ukst_conv_transpose2d_grad_weight(const void* x, const void* dy, void* dw, int B, int Cin, int Cout,
-                                      int H, int W, int n, int P, int dtype, void* stream)
+                                      int H, int W, int n, int P, int dtype, void* workspace,
+                                      size_t workspace_bytes, void* stream)
 {
-    const int st = backward_checked(x, dy, dw, B, Cin, Cout, H, W, n, P, dtype);
+    int st = backward_checked(x, dy, dw, B, Cin, Cout, H, W, n, P, dtype);
     if (st != UKST_OK) return st;
+    if ((st = workspace_checked(workspace, workspace_bytes)) != UKST_OK) return st;
     const ukst::Geom g = ukst::make_geom(B, Cin, Cout, H, W, n, P);
-    return ukst::launch_grad_weight(g, x, dy, (float*)dw, dtype, (hipStream_t)stream) == hipSuccess
-               ? UKST_OK : UKST_ERR_LAUNCH;
+    ukst::Workspace ws;
+    ws.ptr = workspace;
+    ws.bytes = workspace_bytes;
+    return status_of(ukst::launch_grad_weight(g, x, dy, (float*)dw, dtype, ws, (hipStream_t)stream));
 }
 
 const char* ukst_grad_kernel_name(int which, int B, int Cin, int Cout, int H, int W, int n, int P,

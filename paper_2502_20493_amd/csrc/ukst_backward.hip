@@ -724,16 +724,19 @@ bool gi_mfma_args(const Geom& g, GiMfmaArgs& a, bool packed16 = false)
 }
 
 template <int N>
-hipError_t launch_gi_mfma_bf16(const GiMfmaArgs& a, const void* dy, const void* w, float* dx, hipStream_t stream)
+hipError_t launch_gi_mfma_bf16(const GiMfmaArgs& a, const void* dy, const void* w, float* dx, Workspace& ws,
+                               hipStream_t stream)
 {
     const GeomBase& g = a.g;
     const size_t pelems = (size_t)a.CoutP * N * N * a.CIp;           // bf16 elements
-    const size_t pbytes = (pelems * 2 + 255) & ~(size_t)255;
+    const size_t pbytes = ws_align(pelems * 2);
     const size_t xelems = (size_t)g.B * g.Cin * g.H * g.W;
-    unsigned char* scratch = nullptr;  // packed weights, then (split sums) the copies of dx
+    // workspace: packed weights, then (split sums) the copies of dx
+    const size_t need = pbytes + (a.KS > 1 ? xelems * a.KS * 4 : 0);
+    if (ws.query) { ws.need = need; return hipSuccess; }
+    if (ws.bytes < need) return kWorkspaceTooSmall;
+    unsigned char* scratch = (unsigned char*)ws.ptr;
     hipError_t e;
-    if ((e = hipMallocAsync((void**)&scratch, pbytes + (a.KS > 1 ? xelems * a.KS * 4 : 0), stream)) != hipSuccess)
-        return e;
     uint16_t* wp = (uint16_t*)scratch;
     float* part = (float*)(scratch + pbytes);
     hipLaunchKernelGGL(ukst_pack_w_bf16_kernel, dim3((unsigned)((pelems + 255) / 256)), dim3(256), 0, stream,
@@ -760,21 +763,22 @@ hipError_t launch_gi_mfma_bf16(const GiMfmaArgs& a, const void* dy, const void* 
             e = hipGetLastError();
         }
     }
-    const hipError_t ef = hipFreeAsync(scratch, stream);
-    return e != hipSuccess ? e : ef;
+    return e;
 }
 
 template <int N, typename TIn>
-hipError_t launch_gi_mfma(const GiMfmaArgs& a, const void* dy, const void* w, float* dx, hipStream_t stream)
+hipError_t launch_gi_mfma(const GiMfmaArgs& a, const void* dy, const void* w, float* dx, Workspace& ws,
+                          hipStream_t stream)
 {
     const GeomBase& g = a.g;
     const size_t pelems = (size_t)a.CoutP * N * N * a.CIp;
     const size_t xelems = (size_t)g.B * g.Cin * g.H * g.W;
-    float* wp = nullptr;  // packed weights, then (split sums) the copies of dx
+    // workspace: packed weights, then (split sums) the copies of dx
+    const size_t need = (pelems + (a.KS > 1 ? xelems * a.KS : 0)) * sizeof(float);
+    if (ws.query) { ws.need = need; return hipSuccess; }
+    if (ws.bytes < need) return kWorkspaceTooSmall;
+    float* wp = (float*)ws.ptr;
     hipError_t e;
-    if ((e = hipMallocAsync((void**)&wp, (pelems + (a.KS > 1 ? xelems * a.KS : 0)) * sizeof(float),
-                            stream)) != hipSuccess)
-        return e;
     float* part = wp + pelems;
     hipLaunchKernelGGL((ukst_pack_w_kernel<TIn>), dim3((unsigned)((pelems + 255) / 256)), dim3(256), 0, stream,
                        (const TIn*)w, wp, g.Cout, g.Cin, N * N, a.CoutP, a.CIp);
@@ -795,8 +799,7 @@ hipError_t launch_gi_mfma(const GiMfmaArgs& a, const void* dy, const void* w, fl
             e = hipGetLastError();
         }
     }
-    const hipError_t ef = hipFreeAsync(wp, stream);
-    return e != hipSuccess ? e : ef;
+    return e;
 }
 
 // Block count of a (CI_BLK, PX) choice: the widest register block that still gives the chip two
@@ -823,13 +826,14 @@ hipError_t launch_gi_t(const Geom& g, const void* dy, const void* w, float* dx, 
 
 template <int N>
 hipError_t launch_gi_n(const Geom& g, const void* dy, const void* w, float* dx, int dtype,
-                       hipStream_t stream)
+                       Workspace& ws, hipStream_t stream)
 {
     GiMfmaArgs ma;
-    if (dtype == 1 && gi_mfma_args(g, ma, true)) return launch_gi_mfma_bf16<N>(ma, dy, w, dx, stream);
+    if (dtype == 1 && gi_mfma_args(g, ma, true)) return launch_gi_mfma_bf16<N>(ma, dy, w, dx, ws, stream);
     if (gi_mfma_args(g, ma))
-        return dtype == 1 ? launch_gi_mfma<N, uint16_t>(ma, dy, w, dx, stream)
-                          : launch_gi_mfma<N, float>(ma, dy, w, dx, stream);
+        return dtype == 1 ? launch_gi_mfma<N, uint16_t>(ma, dy, w, dx, ws, stream)
+                          : launch_gi_mfma<N, float>(ma, dy, w, dx, ws, stream);
+    if (ws.query) return hipSuccess;  // the vector-ALU kernel uses no scratch
     return dtype == 1 ? launch_gi_t<N, uint16_t>(g, dy, w, dx, stream)
                       : launch_gi_t<N, float>(g, dy, w, dx, stream);
 }
@@ -1307,14 +1311,17 @@ bool gw_mfma_args(const Geom& g, GwMfmaArgs& a)
 constexpr int gw_nc(int n) { return n <= 4 ? 2 : 1; }  // accumulator tiles per tap by kernel side
 
 template <int N, typename TIn>
-hipError_t launch_gw_mfma(const GwMfmaArgs& a, const void* x, const void* dy, float* dw, hipStream_t stream)
+hipError_t launch_gw_mfma(const GwMfmaArgs& a, const void* x, const void* dy, float* dw, Workspace& ws,
+                          hipStream_t stream)
 {
     constexpr int NC = gw_nc(N);
     const GeomBase& g = a.g;
     const size_t elems = (size_t)g.Cout * g.Cin * N * N;
-    float* part = nullptr;
+    const size_t need = elems * a.nSlices * sizeof(float);  // one copy of dw per slice
+    if (ws.query) { ws.need = need; return hipSuccess; }
+    if (ws.bytes < need) return kWorkspaceTooSmall;
+    float* part = (float*)ws.ptr;
     hipError_t e;
-    if ((e = hipMallocAsync((void**)&part, elems * a.nSlices * sizeof(float), stream)) != hipSuccess) return e;
     const size_t lds = (size_t)4 * (32 * NC * a.XP + 32 * a.DP);
     const void* kfn = (const void*)ukst_grad_weight_mfma_kernel<N, NC, TIn>;
     e = hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -1329,12 +1336,12 @@ hipError_t launch_gw_mfma(const GwMfmaArgs& a, const void* x, const void* dy, fl
                            (const float*)part, dw, (int)elems, a.nSlices, N * N, g.Cin);
         e = hipGetLastError();
     }
-    const hipError_t ef = hipFreeAsync(part, stream);
-    return e != hipSuccess ? e : ef;
+    return e;
 }
 
 template <int N, int CO_R, int CI_R, typename TIn>
-hipError_t launch_gw(const Geom& g, const void* x, const void* dy, float* dw, hipStream_t stream)
+hipError_t launch_gw(const Geom& g, const void* x, const void* dy, float* dw, Workspace& ws,
+                     hipStream_t stream)
 {
     GradWArgs a;
     a.g = g;
@@ -1387,9 +1394,11 @@ hipError_t launch_gw(const Geom& g, const void* x, const void* dy, float* dw, hi
     const int copies = a.nSlices * a.SUB;
     const size_t elems = (size_t)g.Cout * g.Cin * N * N;
     if (elems > 0x7fffffffu) return hipErrorInvalidConfiguration;
-    float* part = nullptr;
+    const size_t need = elems * copies * sizeof(float);  // one copy of dw per (slice, wave group)
+    if (ws.query) { ws.need = need; return hipSuccess; }
+    if (ws.bytes < need) return kWorkspaceTooSmall;
+    float* part = (float*)ws.ptr;
     hipError_t e;
-    if ((e = hipMallocAsync((void**)&part, elems * copies * sizeof(float), stream)) != hipSuccess) return e;
     hipLaunchKernelGGL((ukst_grad_weight_kernel<N, CO_R, CI_R, TIn>), dim3((unsigned)nb), dim3(256), lds,
                        stream, (const TIn*)x, (const TIn*)dy, part, a);
     e = hipGetLastError();
@@ -1401,39 +1410,40 @@ hipError_t launch_gw(const Geom& g, const void* x, const void* dy, float* dw, hi
                            dim3(256), 0, stream, (const float*)part, dw, (int)elems, copies, logR);
         e = hipGetLastError();
     }
-    const hipError_t ef = hipFreeAsync(part, stream);
-    return e != hipSuccess ? e : ef;
+    return e;
 }
 
 // register block: CO_R x CI_R channel pairs x n*n taps per thread; layers with at most four
 // channels on a side take one channel per thread there, which leaves the block's threads to the
 // pixels and keeps the closing shuffle reduction short
 template <int N, typename TIn>
-hipError_t launch_gw_n(const Geom& g, const void* x, const void* dy, float* dw, hipStream_t stream)
+hipError_t launch_gw_n(const Geom& g, const void* x, const void* dy, float* dw, Workspace& ws,
+                       hipStream_t stream)
 {
     if constexpr (N >= 2) {
         GwMfmaArgs ma;
-        if (gw_mfma_args<gw_nc(N)>(g, ma)) return launch_gw_mfma<N, TIn>(ma, x, dy, dw, stream);
+        if (gw_mfma_args<gw_nc(N)>(g, ma)) return launch_gw_mfma<N, TIn>(ma, x, dy, dw, ws, stream);
     }
     constexpr int CO_W = N <= 3 ? 4 : N <= 5 ? 2 : 1;  // wide register block: CO_W x 4 pairs
     const bool thin_o = g.Cout <= 4, thin_i = g.Cin <= 4;
-    if (thin_o && thin_i) return launch_gw<N, 1, 1, TIn>(g, x, dy, dw, stream);
-    if (thin_o) return launch_gw<N, 1, 4, TIn>(g, x, dy, dw, stream);
-    if (thin_i) return launch_gw<N, CO_W, 1, TIn>(g, x, dy, dw, stream);
-    return launch_gw<N, CO_W, 4, TIn>(g, x, dy, dw, stream);
+    if (thin_o && thin_i) return launch_gw<N, 1, 1, TIn>(g, x, dy, dw, ws, stream);
+    if (thin_o) return launch_gw<N, 1, 4, TIn>(g, x, dy, dw, ws, stream);
+    if (thin_i) return launch_gw<N, CO_W, 1, TIn>(g, x, dy, dw, ws, stream);
+    return launch_gw<N, CO_W, 4, TIn>(g, x, dy, dw, ws, stream);
 }
 
 template <typename TIn>
-hipError_t launch_gw_t(const Geom& g, const void* x, const void* dy, float* dw, hipStream_t stream)
+hipError_t launch_gw_t(const Geom& g, const void* x, const void* dy, float* dw, Workspace& ws,
+                       hipStream_t stream)
 {
     switch (g.n) {
-        case 1: return launch_gw_n<1, TIn>(g, x, dy, dw, stream);
-        case 2: return launch_gw_n<2, TIn>(g, x, dy, dw, stream);
-        case 3: return launch_gw_n<3, TIn>(g, x, dy, dw, stream);
-        case 4: return launch_gw_n<4, TIn>(g, x, dy, dw, stream);
-        case 5: return launch_gw_n<5, TIn>(g, x, dy, dw, stream);
-        case 6: return launch_gw_n<6, TIn>(g, x, dy, dw, stream);
-        case 7: return launch_gw_n<7, TIn>(g, x, dy, dw, stream);
+        case 1: return launch_gw_n<1, TIn>(g, x, dy, dw, ws, stream);
+        case 2: return launch_gw_n<2, TIn>(g, x, dy, dw, ws, stream);
+        case 3: return launch_gw_n<3, TIn>(g, x, dy, dw, ws, stream);
+        case 4: return launch_gw_n<4, TIn>(g, x, dy, dw, ws, stream);
+        case 5: return launch_gw_n<5, TIn>(g, x, dy, dw, ws, stream);
+        case 6: return launch_gw_n<6, TIn>(g, x, dy, dw, ws, stream);
+        case 7: return launch_gw_n<7, TIn>(g, x, dy, dw, ws, stream);
         default: return hipErrorInvalidValue;
     }
 }
@@ -1453,25 +1463,25 @@ const char* grad_kernel_name(const Geom& g, int which, int dtype)
 }
 
 hipError_t launch_grad_input(const Geom& g, const void* dy, const void* w, float* dx, int dtype,
-                             hipStream_t stream)
+                             Workspace& ws, hipStream_t stream)
 {
     switch (g.n) {
-        case 1: return launch_gi_n<1>(g, dy, w, dx, dtype, stream);
-        case 2: return launch_gi_n<2>(g, dy, w, dx, dtype, stream);
-        case 3: return launch_gi_n<3>(g, dy, w, dx, dtype, stream);
-        case 4: return launch_gi_n<4>(g, dy, w, dx, dtype, stream);
-        case 5: return launch_gi_n<5>(g, dy, w, dx, dtype, stream);
-        case 6: return launch_gi_n<6>(g, dy, w, dx, dtype, stream);
-        case 7: return launch_gi_n<7>(g, dy, w, dx, dtype, stream);
+        case 1: return launch_gi_n<1>(g, dy, w, dx, dtype, ws, stream);
+        case 2: return launch_gi_n<2>(g, dy, w, dx, dtype, ws, stream);
+        case 3: return launch_gi_n<3>(g, dy, w, dx, dtype, ws, stream);
+        case 4: return launch_gi_n<4>(g, dy, w, dx, dtype, ws, stream);
+        case 5: return launch_gi_n<5>(g, dy, w, dx, dtype, ws, stream);
+        case 6: return launch_gi_n<6>(g, dy, w, dx, dtype, ws, stream);
+        case 7: return launch_gi_n<7>(g, dy, w, dx, dtype, ws, stream);
         default: return hipErrorInvalidValue;
     }
 }
 
 hipError_t launch_grad_weight(const Geom& g, const void* x, const void* dy, float* dw, int dtype,
-                              hipStream_t stream)
+                              Workspace& ws, hipStream_t stream)
 {
-    return dtype == 1 ? launch_gw_t<uint16_t>(g, x, dy, dw, stream)
-                      : launch_gw_t<float>(g, x, dy, dw, stream);
+    return dtype == 1 ? launch_gw_t<uint16_t>(g, x, dy, dw, ws, stream)
+                      : launch_gw_t<float>(g, x, dy, dw, ws, stream);
 }
 
 }  // namespace ukst

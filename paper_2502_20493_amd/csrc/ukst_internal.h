@@ -113,6 +113,20 @@ inline Geom make_geom(int B, int Cin, int Cout, int H, int W, int n, int P)
     return g;
 }
 
+// Scratch memory of one call, owned by the caller (the library never allocates).  Launchers that
+// use scratch compute the bytes they need from the shape alone.  With `query` set they record that
+// figure in `need` and launch nothing; otherwise they return kWorkspaceTooSmall when `bytes` is
+// below it.  ptr == nullptr asks for kernels that need no scratch where such kernels exist.
+struct Workspace {
+    void* ptr = nullptr;
+    size_t bytes = 0;
+    bool query = false;
+    size_t need = 0;
+};
+constexpr hipError_t kWorkspaceTooSmall = hipErrorOutOfMemory;  // reported as UKST_ERR_WORKSPACE
+// rounds a scratch sub-buffer size up so that the next one starts 256-byte aligned
+inline size_t ws_align(size_t b) { return (b + 255) & ~(size_t)255; }
+
 // Launchers.  Each returns hipSuccess or the launch error; none synchronises.
 hipError_t launch_direct(const Geom& g, const void* x, const void* w, float* y, int dtype,
                          hipStream_t stream);
@@ -128,7 +142,7 @@ hipError_t launch_thin(const Geom& g, const void* x, const void* w, float* y, hi
 
 bool mfma_supported(const Geom& g, int dtype);
 hipError_t launch_mfma(const Geom& g, const void* x, const void* w, float* y, int dtype,
-                       hipStream_t stream);
+                       Workspace& ws, hipStream_t stream);
 const char* mfma_kernel_name(const Geom& g, int dtype);
 
 // true if the kernel mfma_kernel_name() names also needs x aligned to 16 bytes (w always is)
@@ -137,15 +151,16 @@ bool mfma_needs_aligned_x(const Geom& g, int dtype);
 // fp32-operand MFMA kernels (used by the functions above for dtype 0): the general one, and the
 // one for layers with at most 4 output channels, where the parity classes fill the MFMA columns
 bool mfma_f32_supported(const Geom& g);
-hipError_t launch_mfma_f32(const Geom& g, const void* x, const void* w, float* y, hipStream_t stream);
+hipError_t launch_mfma_f32(const Geom& g, const void* x, const void* w, float* y, Workspace& ws,
+                           hipStream_t stream);
 bool thin_mfma_supported(const Geom& g, int dtype);
 hipError_t launch_thin_mfma(const Geom& g, const void* x, const void* w, float* y, hipStream_t stream);
 
 // Backward pass (vector-ALU kernels, any shape; dtype 0: fp32, 1: bf16 operands, fp32 result)
 hipError_t launch_grad_input(const Geom& g, const void* dy, const void* w, float* dx, int dtype,
-                             hipStream_t stream);
+                             Workspace& ws, hipStream_t stream);
 hipError_t launch_grad_weight(const Geom& g, const void* x, const void* dy, float* dw, int dtype,
-                              hipStream_t stream);
+                              Workspace& ws, hipStream_t stream);
 // which: 0 gradient w.r.t. the input, 1 w.r.t. the kernel
 const char* grad_kernel_name(const Geom& g, int which, int dtype);
 

@@ -460,11 +460,11 @@ bool mfma_needs_aligned_x(const Geom& g, int dtype)
 }
 
 hipError_t launch_mfma(const Geom& g, const void* x, const void* w, float* y, int dtype,
-                       hipStream_t stream)
+                       Workspace& ws, hipStream_t stream)
 {
-    if (dtype == 0)
-        return mfma_f32_supported(g) ? launch_mfma_f32(g, x, w, y, stream)
-                                     : launch_thin_mfma(g, x, w, y, stream);
+    if (dtype == 0 && mfma_f32_supported(g)) return launch_mfma_f32(g, x, w, y, ws, stream);
+    if (ws.query) return hipSuccess;  // the kernels below use no scratch
+    if (dtype == 0) return launch_thin_mfma(g, x, w, y, stream);
     MfmaArgs a;
     if (!make_args(g, dtype, a)) return hipErrorInvalidValue;
     constexpr int N = 4;

@@ -410,7 +410,7 @@ bool make_args(const Geom& g, F32Args& a)
 
 template <int N, int NW>
 hipError_t launch_t(const F32Args& a, const Epilogue& ep, const float* x, const float* w, float* y,
-                    hipStream_t stream)
+                    void* part, hipStream_t stream)
 {
     constexpr int KC = kc_for(N);
     const size_t lds = 2 * (size_t)(N * N * KC * PW * 4 + a.xs_stage_bytes);
@@ -432,31 +432,27 @@ hipError_t launch_t(const F32Args& a, const Epilogue& ep, const float* x, const 
                                stream, x, w, y, a, ep);
         return hipGetLastError();
     }
-    // partial outputs live in stream-ordered scratch memory for the duration of this call
+    // partial outputs live in the caller's workspace for the duration of this call
     const GeomBase& g = a.g;
     const size_t ybytes = (size_t)g.B * g.Cout * g.OH * g.OW * 4;
-    void* part = nullptr;
-    if ((e = hipMallocAsync(&part, ybytes * a.ksplit, stream)) != hipSuccess) return e;
     hipLaunchKernelGGL((ukst_mfma_f32_kernel<N, NW, KC, false>), dim3(nblocks), dim3(256), lds, stream,
                        x, w, (float*)part, a, ep);
     const int n4 = (int)(ybytes / 16);
     hipLaunchKernelGGL(ukst_sum_slices_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0,
                        stream, (const float4*)part, (float4*)y, n4, a.ksplit, ep.bias, ep.act,
                        (unsigned)(g.OH * g.OW), (unsigned)g.Cout);
-    e = hipGetLastError();
-    const hipError_t ef = hipFreeAsync(part, stream);
-    return e != hipSuccess ? e : ef;
+    return hipGetLastError();
 }
 
 template <int NW>
 hipError_t launch_n(const F32Args& a, const Epilogue& ep, const float* x, const float* w, float* y,
-                    hipStream_t st)
+                    void* part, hipStream_t st)
 {
     switch (a.g.n) {
-        case 2: return launch_t<2, NW>(a, ep, x, w, y, st);
-        case 3: return launch_t<3, NW>(a, ep, x, w, y, st);
-        case 4: return launch_t<4, NW>(a, ep, x, w, y, st);
-        case 5: return launch_t<5, NW>(a, ep, x, w, y, st);
+        case 2: return launch_t<2, NW>(a, ep, x, w, y, part, st);
+        case 3: return launch_t<3, NW>(a, ep, x, w, y, part, st);
+        case 4: return launch_t<4, NW>(a, ep, x, w, y, part, st);
+        case 5: return launch_t<5, NW>(a, ep, x, w, y, part, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -485,20 +481,30 @@ bool mfma_f32_supported(const Geom& g)
     return pick_nw(g, a) != 0;
 }
 
-hipError_t launch_mfma_f32(const Geom& g, const void* x, const void* w, float* y, hipStream_t stream)
+hipError_t launch_mfma_f32(const Geom& g, const void* x, const void* w, float* y, Workspace& ws,
+                           hipStream_t stream)
 {
     F32Args a;
     const int nw = pick_nw(g, a);
-    if (((uintptr_t)y & 15) != 0) {  // the slice sum moves 16-byte pieces: no split for such outputs
+    const size_t ybytes = (size_t)g.B * g.Cout * g.OH * g.OW * 4;
+    const size_t need = a.ksplit > 1 ? ybytes * (size_t)a.ksplit : 0;
+    if (ws.query) {
+        ws.need = need;
+        return hipSuccess;
+    }
+    // without a workspace, and for outputs the slice sum cannot move in 16-byte pieces, the K loop
+    // stays in one block per tile
+    if (a.ksplit > 1 && (ws.ptr == nullptr || ((uintptr_t)y & 15) != 0)) {
         a.kstages *= a.ksplit;
         a.ksplit = 1;
     }
+    if (a.ksplit > 1 && ws.bytes < need) return kWorkspaceTooSmall;
     const float* xf = (const float*)x;
     const float* wf = (const float*)w;
     switch (nw) {
-        case 4: return launch_n<4>(a, g.ep, xf, wf, y, stream);
-        case 2: return launch_n<2>(a, g.ep, xf, wf, y, stream);
-        case 1: return launch_n<1>(a, g.ep, xf, wf, y, stream);
+        case 4: return launch_n<4>(a, g.ep, xf, wf, y, ws.ptr, stream);
+        case 2: return launch_n<2>(a, g.ep, xf, wf, y, ws.ptr, stream);
+        case 1: return launch_n<1>(a, g.ep, xf, wf, y, ws.ptr, stream);
         default: return hipErrorInvalidValue;
     }
 }

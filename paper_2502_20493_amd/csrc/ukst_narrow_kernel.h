@@ -73,11 +73,13 @@ __global__ __launch_bounds__(256) void ukst_narrow_kernel(const float* __restric
     // as long for a 4-byte load as for a 16-byte one, and it is what bounds the read phase of
     // this kernel.  Dwords past the end of the row come back as 0 one by one, but a load whose
     // first byte lies left of the row returns nothing at all: a lane whose window starts left of
-    // the map (leftmost strip, floor(P/2) > 0) loads from column 0 instead and shifts the
+    // the map (floor(P/2) > 0) loads from column 0 instead and shifts the
     // result to the right afterwards.
     const int left = j0 < 0 ? (-j0 < WC ? -j0 : WC) : 0;  // window columns left of the map
     const unsigned woff = j0 < 0 ? 0u : (unsigned)j0 * 4u;
-    const bool shifts = strip == 0 && (P >> 1) > 0;        // wave-uniform
+    // wave-uniform: lane 0 of the wave has the leftmost window; with floor(P/2) > 128 the waves
+    // of later strips start left of the map too
+    const bool shifts = 128 * strip < (P >> 1);
     auto load_window = [&](int k0, float (&win)[WR][WC][CI]) {
         const int i0 = k0 - P;
 #pragma unroll

@@ -18,9 +18,11 @@ def to_device(data, dtype):
     return x.contiguous(), w.contiguous()
 
 
-def run_gpu(data, dtype, P, path=ukst.UKST_PATH_AUTO, guard=0, sentinel=-777.0):
+def run_gpu(data, dtype, P, path=ukst.UKST_PATH_AUTO, guard=0, sentinel=-777.0, workspace=False):
     """Returns y as a numpy fp32 array.  With guard > 0 the output lives in the middle of a larger
-    buffer filled with a sentinel, and the bands before/after are checked to be untouched."""
+    buffer filled with a sentinel, and the bands before/after are checked to be untouched.
+    workspace=False: ukst_conv_transpose2d_path; None: ukst_conv_transpose2d_ws with a workspace
+    of ukst_workspace_bytes allocated for the call."""
     import torch
     x, w = to_device(data, dtype)
     B, Cin, H, W = x.shape
@@ -29,7 +31,7 @@ def run_gpu(data, dtype, P, path=ukst.UKST_PATH_AUTO, guard=0, sentinel=-777.0):
     numel = B * Cout * OH * OW
     buf = torch.full((numel + 2 * guard,), sentinel, dtype=torch.float32, device="cuda")
     y = buf[guard:guard + numel].view(B, Cout, OH, OW)
-    ukst.ukst_conv_transpose2d(x, w, P, y=y, path=path)
+    ukst.ukst_conv_transpose2d(x, w, P, y=y, path=path, workspace=workspace)
     torch.cuda.synchronize()
     host = buf.cpu().numpy()
     if guard:

@@ -28,10 +28,24 @@ def test_library_exports_every_declared_symbol():
     assert sorted(ukst.EXPORTS) == declared
 
 
+def test_bench_library_exports_every_declared_symbol():
+    # the measured ceilings live in a library of their own: the product ABI has no benchmark kernel
+    text = open(os.path.join(ROOT, "include", "ukst_bench.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = sorted(set(re.findall(r"\b(ukst_[a-z0-9_]+)\s*\(", text)))
+    lib = ctypes.CDLL(ukst.BENCH_LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert sorted(ukst.BENCH_EXPORTS) == declared
+    product = ctypes.CDLL(ukst.LIB_PATH)
+    for name in declared:
+        assert not hasattr(product, name), name
+
+
 def test_version_and_status_strings():
     assert ukst.ukst_version() >= 100
-    seen = {ukst.ukst_status_string(s) for s in range(6)}
-    assert len(seen) == 6 and ukst.ukst_status_string(0) == "ok"
+    seen = {ukst.ukst_status_string(s) for s in range(7)}
+    assert len(seen) == 7 and ukst.ukst_status_string(0) == "ok"
     assert ukst.ukst_status_string(99) == "unknown status"
 
 
@@ -78,15 +92,64 @@ def test_validation_happens_on_the_host():
     assert fused(X, W, X + 2, Y, *ok_shape, 0, 1, 0, None) == ukst.UKST_ERR_UNSUPPORTED
     # the backward entry points validate the same way; gradients are fp32 only
     for back in (ukst.lib().ukst_conv_transpose2d_grad_input, ukst.lib().ukst_conv_transpose2d_grad_weight):
-        assert back(None, W, Y, *ok_shape, 0, None) == ukst.UKST_ERR_NULL
-        assert back(X, None, Y, *ok_shape, 0, None) == ukst.UKST_ERR_NULL
-        assert back(X, W, None, *ok_shape, 0, None) == ukst.UKST_ERR_NULL
-        assert back(X, W, Y, 1, 1, 1, 4, 1, 3, 0, 0, None) == ukst.UKST_ERR_SHAPE
-        assert back(X, W, Y, *ok_shape, 5, None) == ukst.UKST_ERR_DTYPE
-        assert back(X, W, Y, *ok_shape, ukst.UKST_BF16_BF16, None) == ukst.UKST_ERR_UNSUPPORTED
-        assert back(X, W, Y, 1, 1, 1, 8, 8, ukst.UKST_MAX_N + 1, 0, 0, None) == ukst.UKST_ERR_UNSUPPORTED
-        assert back(X + 2, W, Y, *ok_shape, 0, None) == ukst.UKST_ERR_UNSUPPORTED
-        assert back(X, W, Y + 2, *ok_shape, ukst.UKST_BF16_F32, None) == ukst.UKST_ERR_UNSUPPORTED
+        assert back(None, W, Y, *ok_shape, 0, None, 0, None) == ukst.UKST_ERR_NULL
+        assert back(X, None, Y, *ok_shape, 0, None, 0, None) == ukst.UKST_ERR_NULL
+        assert back(X, W, None, *ok_shape, 0, None, 0, None) == ukst.UKST_ERR_NULL
+        assert back(X, W, Y, 1, 1, 1, 4, 1, 3, 0, 0, None, 0, None) == ukst.UKST_ERR_SHAPE
+        assert back(X, W, Y, *ok_shape, 5, None, 0, None) == ukst.UKST_ERR_DTYPE
+        assert back(X, W, Y, *ok_shape, ukst.UKST_BF16_BF16, None, 0, None) == ukst.UKST_ERR_UNSUPPORTED
+        assert back(X, W, Y, 1, 1, 1, 8, 8, ukst.UKST_MAX_N + 1, 0, 0, None, 0, None) == ukst.UKST_ERR_UNSUPPORTED
+        assert back(X + 2, W, Y, *ok_shape, 0, None, 0, None) == ukst.UKST_ERR_UNSUPPORTED
+        assert back(X, W, Y + 2, *ok_shape, ukst.UKST_BF16_F32, None, 0, None) == ukst.UKST_ERR_UNSUPPORTED
+        # workspace: NULL with a size, or misaligned, is refused before anything else happens
+        assert back(X, W, Y, *ok_shape, 0, None, 64, None) == ukst.UKST_ERR_WORKSPACE
+        assert back(X, W, Y, *ok_shape, 0, 0x1010, 1 << 20, None) == ukst.UKST_ERR_WORKSPACE
+
+
+def test_workspace_sizes_are_host_arithmetic():
+    """ukst_workspace_bytes needs no GPU, and a call whose workspace is too small is refused on the
+    host (fake addresses: nothing may be launched)."""
+    wsb = ukst.ukst_workspace_bytes
+    F, GI, GW = ukst.UKST_OP_FORWARD, ukst.UKST_OP_GRAD_INPUT, ukst.UKST_OP_GRAD_WEIGHT
+    w = wl.WORKLOADS
+
+    def shape(k):
+        return (w[k].B, w[k].Cin, w[k].Cout, w[k].H, w[k].W, w[k].n, w[k].P)
+
+    # forward: only layers whose K loop is split want one (a whole number of copies of y)
+    for k in ("cfg1", "cfg2a", "cfg2b", "cfg3_L4", "cfg4a", "cfg4b"):
+        assert wsb(F, *shape(k), ukst.UKST_F32) == 0, k
+    for k in ("cfg5a", "cfg5b"):
+        assert wsb(F, *shape(k), ukst.UKST_BF16_F32) == 0, k
+    # kernel gradient: always a whole number of copies of dw, at least one
+    for k in ("cfg2a", "cfg3_L1", "cfg3_L4", "cfg4a"):
+        n_dw = w[k].Cout * w[k].Cin * w[k].n ** 2 * 4
+        got = wsb(GW, *shape(k), ukst.UKST_F32)
+        assert got >= n_dw and got % n_dw == 0, k
+    # input gradient: the vector-ALU kernels need none, the matrix-core kernels at least the
+    # packed weights
+    assert wsb(GI, *shape("cfg2a"), ukst.UKST_F32) == 0
+    assert wsb(GI, *shape("cfg4a"), ukst.UKST_F32) >= 128 * 128 * 25 * 4
+    assert wsb(GI, *shape("cfg5a"), ukst.UKST_BF16_F32) >= 128 * 256 * 16 * 2
+    # invalid arguments give 0
+    assert wsb(7, *shape("cfg4a"), ukst.UKST_F32) == 0
+    assert wsb(GW, 1, 1, 1, 1, 4, 3, 0, ukst.UKST_F32) == 0
+    assert wsb(GW, *shape("cfg4a"), ukst.UKST_BF16_BF16) == 0
+    # too small a workspace is a host-side error
+    X = W = Y = 0x1000
+    WS = 0x10000
+    need = wsb(GW, *shape("cfg4a"), ukst.UKST_F32)
+    gw = ukst.lib().ukst_conv_transpose2d_grad_weight
+    assert gw(X, W, Y, *shape("cfg4a"), ukst.UKST_F32, WS, need - 1, None) == ukst.UKST_ERR_WORKSPACE
+    assert gw(X, W, Y, *shape("cfg4a"), ukst.UKST_F32, None, 0, None) == ukst.UKST_ERR_WORKSPACE
+    gi = ukst.lib().ukst_conv_transpose2d_grad_input
+    need = wsb(GI, *shape("cfg4a"), ukst.UKST_F32)
+    assert gi(X, W, Y, *shape("cfg4a"), ukst.UKST_F32, WS, need - 1, None) == ukst.UKST_ERR_WORKSPACE
+    fw = ukst.lib().ukst_conv_transpose2d_ws
+    ok_shape = (1, 1, 1, 4, 4, 3, 0)
+    assert fw(X, W, None, Y, *ok_shape, 0, 0, 0, None, 16, None) == ukst.UKST_ERR_WORKSPACE
+    assert fw(X, W, None, Y, *ok_shape, 0, 0, 0, WS + 8, 1 << 20, None) == ukst.UKST_ERR_WORKSPACE
+    assert fw(None, W, None, Y, *ok_shape, 0, 0, 0, None, 0, None) == ukst.UKST_ERR_NULL
 
 
 def _brute_macs(H, W, n, P):

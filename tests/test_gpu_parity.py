@@ -27,12 +27,12 @@ def _supported(w, path):
     return bool(ukst.ukst_kernel_name(w.B, w.Cin, w.Cout, w.H, w.W, w.n, w.P, dt, path))
 
 
-def _parity(w, path, integer=False, guard=4096, planes=None):
+def _parity(w, path, integer=False, guard=4096, planes=None, workspace=False):
     print(f"case {w.name} B={w.B} Cin={w.Cin} Cout={w.Cout} H={w.H} W={w.W} n={w.n} P={w.P} "
-          f"{w.dtype} path={path} integer={integer}", flush=True)
+          f"{w.dtype} path={path} integer={integer} workspace={workspace}", flush=True)
     data = wl.generate(w, integer=integer)
     y_ref, S = oracle.naive(data["x"], data["w"], w.P, planes=planes)
-    y = run_gpu(data, w.dtype, w.P, path=path, guard=guard)
+    y = run_gpu(data, w.dtype, w.P, path=path, guard=guard, workspace=workspace)
     assert y.shape == y_ref.shape
     return check_against_oracle(y, y_ref, S, TOL[w.dtype], planes=planes, exact=integer)
 
@@ -78,10 +78,16 @@ def _sample_planes(w, k=16):
 
 @pytest.mark.parametrize("name", ["cfg3_L1", "cfg3_L2", "cfg3_L3", "cfg3_L4"])
 def test_cfg3_dcgan_layers_full_size(name):
+    # through the entry point that takes no workspace (K loop in one block per tile) and through
+    # ukst_conv_transpose2d_ws (L1, L2: K loop split over blocks, partial sums in the workspace)
     w = wl.WORKLOADS[name]
     planes = _sample_planes(w, 64)
-    _parity(w, PATHS["auto"], planes=planes)
-    _parity(w, PATHS["auto"], planes=planes, integer=True)
+    dt = ukst.UKST_F32
+    need = ukst.ukst_workspace_bytes(ukst.UKST_OP_FORWARD, w.B, w.Cin, w.Cout, w.H, w.W, w.n, w.P, dt)
+    assert (need > 0) == (name in ("cfg3_L1", "cfg3_L2"))
+    for workspace in (False, None):
+        _parity(w, PATHS["auto"], planes=planes, workspace=workspace)
+        _parity(w, PATHS["auto"], planes=planes, integer=True, workspace=workspace)
 
 
 def test_cfg3_generator_stack_chained():
@@ -93,9 +99,12 @@ def test_cfg3_generator_stack_chained():
     x = torch.from_numpy(wl.generate(layers[0])["x"]).cuda()
     ks = [torch.from_numpy(wl.generate(w)["w"]).cuda() for w in layers]
     outs = []
-    for w, k in zip(layers, ks):              # all four enqueued before anything is read back
+    spaces = [torch.empty(ukst.ukst_workspace_bytes(ukst.UKST_OP_FORWARD, w.B, w.Cin, w.Cout, w.H, w.W,
+                                                    w.n, w.P, ukst.UKST_F32), dtype=torch.uint8,
+                          device="cuda") for w in layers]
+    for w, k, ws in zip(layers, ks, spaces):  # all four enqueued before anything is read back
         assert tuple(x.shape) == (w.B, w.Cin, w.H, w.W)
-        x = ukst.ukst_conv_transpose2d(x, k, w.P)
+        x = ukst.ukst_conv_transpose2d_ws(x, k, w.P, workspace=ws)
         outs.append(x)
     torch.cuda.synchronize()
     xin = wl.generate(layers[0])["x"]
@@ -107,15 +116,28 @@ def test_cfg3_generator_stack_chained():
         xin = y.cpu().numpy()
 
 
+def _stratified_planes(w, block=64):
+    """One seeded (b, co) plane per (image, block of 64 output channels), plus the first and the
+    last plane: every (image, channel block) tile group of the matrix-core kernels meets the
+    oracle, whatever the tile walk."""
+    rng = np.random.default_rng(w.index + 77)
+    planes = {0, w.B * w.Cout - 1}
+    for b in range(w.B):
+        for c0 in range(0, w.Cout, block):
+            planes.add(b * w.Cout + c0 + int(rng.integers(min(block, w.Cout - c0))))
+    return sorted(planes)
+
+
 @pytest.mark.parametrize("name", ["cfg4a", "cfg4b", "cfg5a", "cfg5b"])
 def test_cfg45_full_size_sampled_planes(name):
-    # the naive oracle is too slow for every plane at these sizes: it computes a seeded sample of
-    # complete (b, co) planes (always the first and the last); each still reduces over all Cin and
-    # holds every parity class and edge
+    # the naive oracle is too slow for every plane at these sizes: it computes complete (b, co)
+    # planes, one per (image, 64-channel block) -- 64 to 512 planes; each still reduces over all
+    # Cin and holds every parity class and edge
     w = wl.WORKLOADS[name]
-    planes = _sample_planes(w, 16)
+    planes = _stratified_planes(w)
+    assert len(planes) >= w.B * ((w.Cout + 63) // 64)
     _parity(w, PATHS["auto"], planes=planes, guard=1 << 16)
-    _parity(w, PATHS["auto"], planes=planes, integer=True)
+    _parity(w, PATHS["auto"], planes=_sample_planes(w, 16), integer=True)
 
 
 @pytest.mark.parametrize("name", ["cfg3_L2", "cfg4a", "cfg4b", "cfg5b"])
@@ -178,6 +200,9 @@ def test_mfma_f32_small_shapes_every_element(shape):
     assert _supported(w, PATHS["mfma"]), "shape should be runnable by the MFMA path"
     _parity(w, PATHS["mfma"], integer=True)
     _parity(w, PATHS["mfma"], integer=False)
+    if ukst.ukst_workspace_bytes(ukst.UKST_OP_FORWARD, B, Cin, Cout, H, W, n, P, ukst.UKST_F32):
+        _parity(w, PATHS["mfma"], integer=True, workspace=None)   # split K loop
+        _parity(w, PATHS["mfma"], integer=False, workspace=None)
 
 
 THIN_MFMA_SHAPES = [
@@ -254,11 +279,12 @@ def test_matrix_core_shapes_beyond_their_buffer_limit_fall_back(dtype):
 
 
 def test_paths_agree_at_full_size():
-    # property that holds at any size: both kernel families compute the same tensor
+    # property that holds at any size: both kernel families compute the same tensor (every
+    # element of it, which the sampled planes above cannot show)
     import torch
     from gpu_util import to_device
     ran = 0
-    for name in ["cfg5b", "cfg4b", "cfg3_L3"]:
+    for name in ["cfg5b", "cfg4b", "cfg3_L3", "cfg4a", "cfg5a"]:
         w = wl.WORKLOADS[name]
         if not _supported(w, PATHS["mfma"]):
             continue
@@ -270,7 +296,9 @@ def test_paths_agree_at_full_size():
         scale = ukst.ukst_conv_transpose2d(x.abs(), wt.abs(), w.P, path=PATHS["direct"])
         torch.cuda.synchronize()
         tol = 2e-5 if w.dtype == "f32" else 2e-2
-        assert bool(((ya - yb).abs() <= tol * scale).all())
+        assert bool(((ya - yb).abs() <= tol * scale).all()), name
+        del ya, yb, scale, x, wt
+        torch.cuda.empty_cache()
     if not ran:
         pytest.skip("MFMA path not available for these shapes")
 
@@ -283,9 +311,49 @@ def test_repeat_runs_are_bit_identical():
     assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("name,kernel", [("cfg2a", "ukst_narrow_kernel"), ("cfg2b", "ukst_narrow_kernel"),
+                                         ("cfg3_L1", "ukst_mfma_f32_kernel"),
+                                         ("cfg3_L4", "ukst_thin_mfma_kernel"),
+                                         ("cfg4a", "ukst_mfma_f32_kernel"),
+                                         ("cfg5a", "ukst_mfma_bf16_kernel"),
+                                         ("cfg5b", "ukst_mfma_bf16_kernel")])
+def test_repeat_runs_are_bit_identical_at_full_size(name, kernel):
+    """Every kernel family at its benchmark shape, three launches into three different buffers:
+    the same bits every time (no atomics, fixed summation order, no store that depends on
+    timing)."""
+    import torch
+    from gpu_util import to_device
+    w = wl.WORKLOADS[name]
+    dt = ukst.UKST_F32 if w.dtype == "f32" else ukst.UKST_BF16_F32
+    assert ukst.ukst_kernel_name(w.B, w.Cin, w.Cout, w.H, w.W, w.n, w.P, dt) == kernel
+    x, wt = to_device(wl.generate(w), w.dtype)
+    ys = [ukst.ukst_conv_transpose2d_ws(x, wt, w.P) for _ in range(3)]
+    torch.cuda.synchronize()
+    assert torch.equal(ys[0], ys[1]) and torch.equal(ys[0], ys[2]), name
+
+
+@pytest.mark.parametrize("shape,kernel", [
+    ((1, 3, 3, 8, 8, 3, 300), "ukst_narrow_kernel"),    # floor(P/2) = 150 > 2 * 64 lanes: waves of
+    ((2, 2, 4, 5, 9, 4, 301), "ukst_narrow_kernel"),    # later strips start left of the map too
+    ((1, 1, 1, 4, 4, 5, 520), "ukst_narrow_kernel"),
+    ((1, 24, 3, 8, 8, 3, 300), "ukst_thin_kernel"),
+    ((1, 8, 2, 5, 9, 4, 301), "ukst_thin_kernel"),
+    ((1, 32, 3, 6, 8, 4, 300), "ukst_thin_mfma_kernel")])
+def test_padding_far_beyond_the_kernel(shape, kernel):
+    """P in the hundreds: most outputs meet no input at all (exact zeros), the map sits in the
+    middle of a wide zero border, and lanes whole strips away from the left edge still have
+    windows that start left of the map."""
+    B, Cin, Cout, H, W, n, P = shape
+    w = _mk("far_padding", 9400 + sum(shape), B, Cin, Cout, H, W, n, P)
+    assert ukst.ukst_kernel_name(B, Cin, Cout, H, W, n, P, ukst.UKST_F32) == kernel
+    _parity(w, PATHS["auto"], integer=True)
+    _parity(w, PATHS["auto"], integer=False)
+
+
 @pytest.mark.parametrize("case", ["narrow", "mfma_f32_split_k", "mfma_bf16"])
 def test_non_default_stream(case):
-    """Work (including the split-K scratch memory and its slice sum) follows the caller's stream."""
+    """Work (including the split-K partial sums in the workspace and their slice sum) follows the
+    caller's stream."""
     import torch
     from gpu_util import to_device
     w = {"narrow": wl.WORKLOADS["cfg1"],
@@ -295,9 +363,14 @@ def test_non_default_stream(case):
     x, wt = to_device(data, w.dtype)
     s = torch.cuda.Stream()
     torch.cuda.synchronize()
+    need = ukst.ukst_workspace_bytes(ukst.UKST_OP_FORWARD, w.B, w.Cin, w.Cout, w.H, w.W, w.n, w.P,
+                                     ukst.UKST_F32 if w.dtype == "f32" else ukst.UKST_BF16_F32)
+    assert (need > 0) == (case == "mfma_f32_split_k")
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
     with torch.cuda.stream(s):
-        y1 = ukst.ukst_conv_transpose2d(x, wt, w.P)
-        y2 = ukst.ukst_conv_transpose2d(x, wt, w.P)  # back to back: scratch is reused stream-ordered
+        y1 = ukst.ukst_conv_transpose2d_ws(x, wt, w.P, workspace=ws, stream=s)
+        y2 = ukst.ukst_conv_transpose2d_ws(x, wt, w.P, workspace=ws, stream=s)  # back to back, same workspace
     s.synchronize()
     y_ref, S = oracle.naive(data["x"], data["w"], w.P)
     check_against_oracle(y1.cpu().numpy(), y_ref, S, TOL[w.dtype])
@@ -408,8 +481,10 @@ def test_fused_bias_activation(case, act):
     code = {"none": ukst.UKST_ACT_NONE, "relu": ukst.UKST_ACT_RELU, "tanh": ukst.UKST_ACT_TANH}[act]
     ref = {"none": z, "relu": np.maximum(z, 0.0), "tanh": np.tanh(z)}[act]
     x, k = to_device(data, dtype)
+    # the split-K case needs the workspace entry point (the slice sum applies the epilogue there)
+    ws = None if name == "mfma_f32_split_k" else False
     y = ukst.ukst_conv_transpose2d_bias_act(x, k, P, bias=torch.from_numpy(bias).cuda(), act=code,
-                                            path=PATHS[pname])
+                                            path=PATHS[pname], workspace=ws)
     torch.cuda.synchronize()
     got = y.cpu().numpy().astype(np.float64)
     # the bias is added in fp32 to an fp32 sum: half an ulp of the biased value on top
@@ -419,9 +494,9 @@ def test_fused_bias_activation(case, act):
     assert (err <= slack).all(), f"worst excess {np.max(err - slack):.3e}"
     if act == "none":
         # no bias and no activation: bit-identical to the plain entry point
-        y0 = ukst.ukst_conv_transpose2d(x, k, P, path=PATHS[pname])
+        y0 = ukst.ukst_conv_transpose2d(x, k, P, path=PATHS[pname], workspace=ws)
         y1 = ukst.ukst_conv_transpose2d_bias_act(x, k, P, bias=None, act=ukst.UKST_ACT_NONE,
-                                                 path=PATHS[pname])
+                                                 path=PATHS[pname], workspace=ws)
         torch.cuda.synchronize()
         assert torch.equal(y0, y1)
 
@@ -439,7 +514,7 @@ def test_fused_bias_relu_full_size_sampled_planes(name):
     y_ref, S = oracle.naive(data["x"], data["w"], w.P, planes=planes)
     x, k = to_device(data, w.dtype)
     y = ukst.ukst_conv_transpose2d_bias_act(x, k, w.P, bias=torch.from_numpy(bias).cuda(),
-                                            act=ukst.UKST_ACT_RELU)
+                                            act=ukst.UKST_ACT_RELU, workspace=None)
     torch.cuda.synchronize()
     OH, OW = y.shape[2:]
     got = y.view(w.B * w.Cout, OH, OW)[planes].cpu().numpy().astype(np.float64)
