@@ -338,7 +338,7 @@ def test_repeat_runs_are_bit_identical_at_full_size(name, kernel):
     ((1, 1, 1, 4, 4, 5, 520), "ukst_narrow_kernel"),
     ((1, 24, 3, 8, 8, 3, 300), "ukst_thin_kernel"),
     ((1, 8, 2, 5, 9, 4, 301), "ukst_thin_kernel"),
-    ((1, 32, 3, 6, 8, 4, 300), "ukst_thin_mfma_kernel")])
+    ((1, 32, 3, 6, 8, 4, 300), "ukst_thin_kernel")])  # the class-column MFMA kernel bounds P
 def test_padding_far_beyond_the_kernel(shape, kernel):
     """P in the hundreds: most outputs meet no input at all (exact zeros), the map sits in the
     middle of a wide zero border, and lanes whole strips away from the left edge still have
