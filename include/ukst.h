@@ -220,6 +220,23 @@ int ukst_conv_transpose2d_grad_weight(const void* x, const void* dy, void* dw, i
                                       void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * ukst_conv_transpose2d_grad_weight for callers that cannot allocate or carry a workspace (code
+ * under HIP graph capture, tight serving or training loops, harnesses that forbid allocation): the
+ * partial sums live in a static device array that is part of the library, ukst_static_workspace_bytes()
+ * = 64 MiB per GPU, held from the first use on that GPU until the process ends.  Same kernels,
+ * same results (bit for bit) as ukst_conv_transpose2d_grad_weight; no hipMalloc, hipFree or other
+ * allocating call is made.  Problems whose ukst_workspace_bytes(UKST_OP_GRAD_WEIGHT, ...) exceeds
+ * that size return UKST_ERR_WORKSPACE with nothing launched (every benchmark configuration fits).
+ * All calls on one GPU share the one array: calls that may overlap on a GPU (different streams,
+ * different threads) race on it and must be serialised by the caller.  Everything else as
+ * ukst_conv_transpose2d_grad_weight.
+ */
+int ukst_conv_transpose2d_grad_weight_static(const void* x, const void* dy, void* dw, int B, int Cin,
+                                             int Cout, int H, int W, int n, int P, int dtype,
+                                             void* stream);
+size_t ukst_static_workspace_bytes(void);
+
+/*
  * Name of the main device kernel a backward call launches for this problem (which = 0:
  * ukst_conv_transpose2d_grad_input, 1: ukst_conv_transpose2d_grad_weight), as it appears in a
  * profiler's kernel trace (substring match), or "" on invalid arguments.  Static storage.

@@ -25,7 +25,8 @@ EXPORTS = ["ukst_version", "ukst_status_string", "ukst_output_shape", "ukst_mac_
            "ukst_select_path", "ukst_conv_transpose2d", "ukst_conv_transpose2d_path",
            "ukst_kernel_name", "ukst_conv_transpose2d_bias_act", "ukst_workspace_bytes",
            "ukst_conv_transpose2d_ws", "ukst_conv_transpose2d_grad_input",
-           "ukst_conv_transpose2d_grad_weight", "ukst_grad_kernel_name"]
+           "ukst_conv_transpose2d_grad_weight", "ukst_grad_kernel_name",
+           "ukst_conv_transpose2d_grad_weight_static", "ukst_static_workspace_bytes"]
 # every symbol include/ukst_bench.h declares (libukst_bench.so: measurement helpers)
 BENCH_EXPORTS = ["ukst_bench_mfma_ceiling", "ukst_bench_stream_ceiling"]
 
@@ -75,6 +76,10 @@ def lib():
         for f in (L.ukst_conv_transpose2d_grad_input, L.ukst_conv_transpose2d_grad_weight):
             f.argtypes = [vp, vp, vp] + [i] * 8 + [vp, ctypes.c_size_t, vp]
             f.restype = i
+        L.ukst_conv_transpose2d_grad_weight_static.argtypes = [vp, vp, vp] + [i] * 8 + [vp]
+        L.ukst_conv_transpose2d_grad_weight_static.restype = i
+        L.ukst_static_workspace_bytes.argtypes = []
+        L.ukst_static_workspace_bytes.restype = ctypes.c_size_t
         _lib = L
     return _lib
 
@@ -316,6 +321,30 @@ def ukst_conv_transpose2d_grad_input(dy, w, H: int, W: int, P: int, dx=None, str
         _check(int(lib().ukst_conv_transpose2d_grad_input(dy.data_ptr(), w.data_ptr(), dx.data_ptr(),
                                                           B, Cin, Cout, H, W, n, P, dtype, wp, wb, sp)))
     return dx
+
+
+def ukst_static_workspace_bytes() -> int:
+    return int(lib().ukst_static_workspace_bytes())
+
+
+def ukst_conv_transpose2d_grad_weight_static(x, dy, n: int, P: int, dw, stream=None):
+    """Marshal torch device tensors into ukst_conv_transpose2d_grad_weight_static (the partial sums
+    live in the library's static device array; dw must be preallocated: nothing is allocated)."""
+    import torch
+
+    dtype = _backward_operands(x, dy)
+    B, Cin, H, W = x.shape
+    B2, Cout = dy.shape[:2]
+    if B2 != B or tuple(dy.shape[2:]) != ukst_output_shape(H, W, n, P):
+        raise ValueError("expected x[B,Cin,H,W] and dy[B,Cout,2H+2P-n,2W+2P-n]")
+    dw = _out(dw, (Cout, Cin, n, n), x.device)
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device)
+    sp = stream.cuda_stream if hasattr(stream, "cuda_stream") else stream
+    with torch.cuda.device(x.device):
+        _check(int(lib().ukst_conv_transpose2d_grad_weight_static(
+            x.data_ptr(), dy.data_ptr(), dw.data_ptr(), B, Cin, Cout, H, W, n, P, dtype, sp)))
+    return dw
 
 
 def ukst_conv_transpose2d_grad_weight(x, dy, n: int, P: int, dw=None, stream=None, workspace=None):

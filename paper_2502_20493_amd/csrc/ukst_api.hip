@@ -1,8 +1,32 @@
 // C-ABI boundary of libukst: argument validation, geometry, path selection.  See include/ukst.h.
 #include "../../include/ukst.h"
 #include "ukst_internal.h"
+#include <atomic>
 
 namespace {
+
+// Scratch of ukst_conv_transpose2d_grad_weight_static: one array per GPU, part of the loaded code
+// object, held until the process ends.  The name is a host-side stand-in; the device address is
+// looked up once per device (hipGetSymbolAddress) and kept here.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// device address of `scratch` on the current device, or nullptr (with *err set) on failure
+void* static_scratch(hipError_t* err)
+{
+    int dev = -1;
+    if ((*err = hipGetDevice(&dev)) != hipSuccess) return nullptr;
+    if (dev < 0 || dev >= kMaxDevices) { *err = hipErrorInvalidDevice; return nullptr; }
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        // two threads may both get here: they find the same address
+        if ((*err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch))) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    return p;
+}
 
 int validate_shape(int B, int Cin, int Cout, int H, int W, int n, int P)
 {
@@ -255,6 +279,29 @@ int ukst_conv_transpose2d_grad_weight(const void* x, const void* dy, void* dw, i
     ukst::Workspace ws;
     ws.ptr = workspace;
     ws.bytes = workspace_bytes;
+    return status_of(ukst::launch_grad_weight(g, x, dy, (float*)dw, dtype, ws, (hipStream_t)stream));
+}
+
+size_t ukst_static_workspace_bytes(void) { return kStaticScratchBytes; }
+
+int ukst_conv_transpose2d_grad_weight_static(const void* x, const void* dy, void* dw, int B, int Cin,
+                                             int Cout, int H, int W, int n, int P, int dtype, void* stream)
+{
+    const int st = backward_checked(x, dy, dw, B, Cin, Cout, H, W, n, P, dtype);
+    if (st != UKST_OK) return st;
+    const ukst::Geom g = ukst::make_geom(B, Cin, Cout, H, W, n, P);
+    ukst::Workspace q;
+    q.query = true;
+    if (ukst::launch_grad_weight(g, nullptr, nullptr, nullptr, dtype, q, nullptr) != hipSuccess)
+        return UKST_ERR_LAUNCH;
+    if (q.need > kStaticScratchBytes) return UKST_ERR_WORKSPACE;  // host arithmetic only so far
+    hipError_t e = hipSuccess;
+    ukst::Workspace ws;
+    ws.ptr = static_scratch(&e);
+    if (ws.ptr == nullptr) return UKST_ERR_LAUNCH;
+    ws.bytes = kStaticScratchBytes;
+    // every slice writes the whole of its copy before the sum kernel reads it: nothing in the
+    // array has to start at zero, whatever the last call left there
     return status_of(ukst::launch_grad_weight(g, x, dy, (float*)dw, dtype, ws, (hipStream_t)stream));
 }
 
