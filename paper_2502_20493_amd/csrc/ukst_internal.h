@@ -145,6 +145,11 @@ hipError_t launch_mfma(const Geom& g, const void* x, const void* w, float* y, in
                        Workspace& ws, hipStream_t stream);
 const char* mfma_kernel_name(const Geom& g, int dtype);
 
+// bf16 operands, n = 4, even P: the same implicit GEMM on quads aligned to the output
+bool mfma_aligned_supported(const Geom& g, int dtype);
+hipError_t launch_mfma_aligned(const Geom& g, const void* x, const void* w, float* y, int dtype,
+                               hipStream_t stream);
+
 // true if the kernel mfma_kernel_name() names also needs x aligned to 16 bytes (w always is)
 bool mfma_needs_aligned_x(const Geom& g, int dtype);
 

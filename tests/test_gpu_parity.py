@@ -162,6 +162,15 @@ MFMA_BF16_SHAPES = [
     (5, 16, 64, 2, 8, 2),      # many tiny images inside one tile
     (1, 16, 64, 33, 64, 2),    # several row tiles of one image
     (1, 16, 64, 1, 8, 2),      # single input row
+    # even P on maps the output-aligned kernel takes (the small ones above stay with the shifted quads)
+    (2, 48, 128, 9, 16, 2),    # tiles span images
+    (3, 16, 64, 7, 24, 0),     # P = 0: no halo, window rows up to H - 1
+    (1, 32, 64, 6, 16, 6),     # P > n - 1: border quads meet no input
+    (2, 16, 64, 5, 40, 0),
+    (1, 16, 64, 3, 8, 18),     # padding far beyond the kernel
+    (2, 32, 64, 16, 16, 2),    # cfg5b's map: one image per tile
+    (1, 16, 64, 20, 128, 2),   # cfg5a's row length: two quad rows per tile
+    (2, 16, 64, 9, 136, 2),    # wide rows: three quad rows and an image boundary in one tile
 ]
 
 
@@ -316,14 +325,17 @@ def test_repeat_runs_are_bit_identical():
                                          ("cfg3_L4", "ukst_thin_mfma_kernel"),
                                          ("cfg4a", "ukst_mfma_f32_kernel"),
                                          ("cfg5a", "ukst_mfma_bf16_kernel"),
-                                         ("cfg5b", "ukst_mfma_bf16_kernel")])
+                                         ("cfg5a_32x32", "ukst_mfma_bf16_aligned_kernel"),
+                                         ("cfg5b", "ukst_mfma_bf16_aligned_kernel"),
+                                         ("cfg5b_P1", "ukst_mfma_bf16_kernel")])
 def test_repeat_runs_are_bit_identical_at_full_size(name, kernel):
     """Every kernel family at its benchmark shape, three launches into three different buffers:
     the same bits every time (no atomics, fixed summation order, no store that depends on
     timing)."""
     import torch
     from gpu_util import to_device
-    w = wl.WORKLOADS[name]
+    w = (wl.WORKLOADS["cfg5b"].with_(P=1) if name == "cfg5b_P1" else
+         wl.WORKLOADS["cfg5a"].with_(B=16, H=32, W=32) if name == "cfg5a_32x32" else wl.WORKLOADS[name])
     dt = ukst.UKST_F32 if w.dtype == "f32" else ukst.UKST_BF16_F32
     assert ukst.ukst_kernel_name(w.B, w.Cin, w.Cout, w.H, w.W, w.n, w.P, dt) == kernel
     x, wt = to_device(wl.generate(w), w.dtype)
@@ -422,7 +434,7 @@ def test_bf16_output_mfma_small_shapes_every_element(shape):
     B, Cin, Cout, H, W, P = shape
     w = _mk("mfma_bf16_out", 7500 + sum(shape), B, Cin, Cout, H, W, 4, P, dtype="bf16")
     assert ukst.ukst_kernel_name(B, Cin, Cout, H, W, 4, P, ukst.UKST_BF16_BF16,
-                                 PATHS["mfma"]) == "ukst_mfma_bf16_kernel"
+                                 PATHS["mfma"]).startswith("ukst_mfma_bf16_")
     _bf16_out_case(w, PATHS["mfma"], integer=True)
     _bf16_out_case(w, PATHS["mfma"], integer=False)
 
@@ -456,7 +468,8 @@ EPILOGUE_CASES = [
     ("thin_mfma", (2, 32, 3, 9, 12, 4, 2), "f32", "auto", "ukst_thin_mfma_kernel"),
     ("mfma_f32", (2, 16, 40, 23, 31, 3, 0), "f32", "mfma", "ukst_mfma_f32_kernel"),
     ("mfma_f32_split_k", (2, 64, 16, 5, 6, 4, 2), "f32", "mfma", "ukst_mfma_f32_kernel"),
-    ("mfma_bf16", (2, 32, 128, 9, 16, 4, 2), "bf16", "auto", "ukst_mfma_bf16_kernel"),
+    ("mfma_bf16", (2, 32, 128, 9, 16, 4, 1), "bf16", "auto", "ukst_mfma_bf16_kernel"),
+    ("mfma_bf16_aligned", (2, 32, 128, 9, 16, 4, 2), "bf16", "auto", "ukst_mfma_bf16_aligned_kernel"),
 ]
 
 
