@@ -12,6 +12,15 @@
 // instruction, so staging is cheap next to it: global loads for the next stage are issued before
 // the current stage is multiplied and written to the other LDS buffer afterwards.
 //
+// Even kernel sides with even padding (the generator layers: n = 4, P = 2) take quads that are
+// aligned to the OUTPUT instead (template flag AL): rows {2ky, 2ky+1} x cols {2kx, 2kx+1}, all inside
+// the even-sized output, where the shifted quads carry an extra row and column of half-empty quads
+// (25 instead of 16 quads on a 4x4 map).  Output row 2ky + rr then has row class rr and a window
+// starting at input row ky - P/2 + rr (Algorithm 2, Sec. 3.4), so a quad reads a
+// (ceil(n/2)+1)^2 window and class (rr, cc) multiplies position (a, b) by tap
+// w[rr + 2(a-rr)][cc + 2(b-cc)] where it has one: the same n*n MFMAs per quad tile and channel
+// pair, on fewer quads, and a drain without edge cases.
+//
 // Block = 4 waves; tile = 64 channels x (64*NW) quads x 4 classes; wave = 32 channels x 32*NW
 // quads (NW = 4, 2 or 1 so that small layers still fill the chip).  The epilogue stores the two
 // column classes of a quad as one 8-byte element, classes interleaved in place.
@@ -38,7 +47,10 @@ constexpr int LDS_LIMIT = 160 * 1024;
 
 struct F32Args {
     GeomBase g;
-    int Q;       // total quads = B * KH * KW
+    int aligned; // 1: quads aligned to the output (even n, even P), 0: shifted quads
+    int KHq, KWq; // quad rows / columns
+    int cb_major; // tile order: 1 = consecutive blocks share the channel block (big weights)
+    int Q;       // total quads = B * KHq * KWq
     int EH;      // input rows one image's quad rows touch = KH + ceil(n/2) - 1
     int ROWS;    // input rows an activation stage holds
     int LWX;     // floats per staged row: left halo + W + right halo
@@ -56,7 +68,17 @@ struct F32Args {
 // each other's staging latency; the widest tile needs the whole register file.
 // EPI: the fused epilogue (bias, activation) is compiled into the drain; the plain instance keeps
 // the register allocation and schedule of its drain to itself.
-template <int N, int NW, int KC, bool EPI>
+// tap of class c = 2*rr + cc (aligned) / 2*r + s (shifted) at window position (pa, pb), or -1
+template <int N, bool AL>
+constexpr int tap_at(int pa, int pb, int c)
+{
+    const int r = c >> 1, sc = c & 1;
+    const int u = AL ? pa - r : pa, v = AL ? pb - sc : pb;
+    if (u < 0 || v < 0 || r + 2 * u >= N || sc + 2 * v >= N) return -1;
+    return (r + 2 * u) * N + (sc + 2 * v);
+}
+
+template <int N, int NW, int KC, bool EPI, bool AL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, NW == 4 ? 1 : 2)))
 void ukst_mfma_f32_kernel(const float* __restrict__ x, const float* __restrict__ w,
                           float* __restrict__ y, F32Args a, Epilogue ep)
@@ -79,7 +101,7 @@ void ukst_mfma_f32_kernel(const float* __restrict__ x, const float* __restrict__
     const int cw = wave & 1;   // which 32-channel half of the block tile
     const int qh = wave >> 1;  // which half of the block's quads
     const int l32 = lane & 31, gk = lane >> 5;
-    const int KHW = g.KH * g.KW;
+    const int KHW = a.KHq * a.KWq;
 
     // Split K: when a layer has too few tiles to fill the chip (small maps, many channels), the
     // input channels of a tile are divided among `ksplit` blocks; slice ks writes its partial
@@ -87,7 +109,10 @@ void ukst_mfma_f32_kernel(const float* __restrict__ x, const float* __restrict__
     // in a fixed order.
     const int bid_all = xcd_contiguous(blockIdx.x, gridDim.x);
     const int ks = bid_all % a.ksplit, bid = bid_all / a.ksplit;
-    const int cb = bid % a.nco, qt = bid / a.nco;
+    // tile order: blocks of one XCD (consecutive numbers) share what is bigger, the weights of a
+    // channel block or the activations of a quad tile
+    const int cb = a.cb_major ? bid / a.nqt : bid % a.nco;
+    const int qt = a.cb_major ? bid % a.nqt : bid / a.nco;
     const int co0 = cb * TM;
     const int q0 = qt * TN;
     const int q_last = (q0 + TN - 1 < a.Q ? q0 + TN - 1 : a.Q - 1);
@@ -116,7 +141,7 @@ void ukst_mfma_f32_kernel(const float* __restrict__ x, const float* __restrict__
             if (k < KC) {
                 const int er = e_first + row;
                 const int b = fdiv(er, a.dEH), ii = er - b * a.EH;
-                const int i = g.k_min - g.P + ii;
+                const int i = ii - (g.P >> 1);  // = k_min - P + ii for the shifted quads
                 if (b < g.B && i >= 0 && i < g.H)
                     x_goff[j] = (unsigned)((((b * g.Cin + k) * g.H + i) * g.W + col) * 4);
                 x_loff[j] = k * a.XP + row * a.LWX + a.SH + col;
@@ -140,10 +165,11 @@ void ukst_mfma_f32_kernel(const float* __restrict__ x, const float* __restrict__
         if (q > q_last) q = q_last;
         const int b = fdiv(q, a.dKHW);
         const int rem = q - b * KHW;
-        const int kk = fdiv(rem, a.dKW), mm = rem - kk * g.KW;
+        const int kk = fdiv(rem, a.dKW), mm = rem - kk * a.KWq;
         const int r = b * a.EH + kk - e_first;
-        // window column v of quad column mm is input column m_min + mm - P + v
-        b_base[nt] = XS_OFF / 4 + gk * a.XP + r * a.LWX + mm + (a.SH + g.m_min - g.P);
+        // window column v of quad column mm is input column mm - floor(P/2) + v in either quad
+        // system (shifted: m_min + mm - P + v), i.e. LDS column mm + v
+        b_base[nt] = XS_OFF / 4 + gk * a.XP + r * a.LWX + mm;
     }
 
     f32x16 acc[NW][2][2];
@@ -197,37 +223,37 @@ void ukst_mfma_f32_kernel(const float* __restrict__ x, const float* __restrict__
     };
     // One step = one window position (u, v) at one K pair.  The fragments of step t+1 are
     // requested before the MFMAs of step t are issued, so LDS latency hides under the matrix pipe.
-    constexpr int NP = HI * HI, NSTEP = (KC / 2) * NP;
+    constexpr int NP1 = AL ? HI + 1 : HI;  // window positions per axis
+    constexpr int NP = NP1 * NP1, NSTEP = (KC / 2) * NP;
     auto compute = [&](int buf) {
         const float* ws = ldsf + buf * (WS_STAGE / 4) + a_base;
         const int xb = buf * (a.xs_stage_bytes / 4);
         auto load_step = [&](int t, float (&bfr)[NW], float (&afr)[4]) {
-            const int ks = t / NP, p = t % NP, u = p / HI, v = p % HI;
-            const int xo = xb + 2 * ks * a.XP + u * a.LWX + v;
+            const int ks = t / NP, p = t % NP, pa = p / NP1, pb = p % NP1;
+            const int xo = xb + 2 * ks * a.XP + pa * a.LWX + pb;
 #pragma unroll
             for (int nt = 0; nt < NW; ++nt) bfr[nt] = ldsf[b_base[nt] + xo];
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                const int r = c >> 1, sc = c & 1;
-                if (r + 2 * u >= N || sc + 2 * v >= N) continue;  // class has no tap here
-                afr[c] = ws[(2 * ks * NN + (r + 2 * u) * N + (sc + 2 * v)) * PW];
+                const int tap = tap_at<N, AL>(pa, pb, c);
+                if (tap < 0) continue;  // class has no tap here
+                afr[c] = ws[(2 * ks * NN + tap) * PW];
             }
         };
         float bfr[2][NW], afr[2][4];
         load_step(0, bfr[0], afr[0]);
 #pragma unroll
         for (int t = 0; t < NSTEP; ++t) {
-            const int p = t % NP, u = p / HI, v = p % HI;
+            const int p = t % NP, pa = p / NP1, pb = p % NP1;
             if (t + 1 < NSTEP) load_step(t + 1, bfr[(t + 1) & 1], afr[(t + 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                const int r = c >> 1, sc = c & 1;
-                if (r + 2 * u >= N || sc + 2 * v >= N) continue;
+                if (tap_at<N, AL>(pa, pb, c) < 0) continue;
 #pragma unroll
                 for (int nt = 0; nt < NW; ++nt)
-                    acc[nt][r][sc] = __builtin_amdgcn_mfma_f32_32x32x2f32(
-                        afr[t & 1][c], bfr[t & 1][nt], acc[nt][r][sc], 0, 0, 0);
+                    acc[nt][c >> 1][c & 1] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                        afr[t & 1][c], bfr[t & 1][nt], acc[nt][c >> 1][c & 1], 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -275,7 +301,32 @@ void ukst_mfma_f32_kernel(const float* __restrict__ x, const float* __restrict__
             const int qq = qv ? q : q_last;
             const int b = fdiv(qq, a.dKHW);
             const int rem = qq - b * KHW;
-            const int kk = fdiv(rem, a.dKW), mm = rem - kk * g.KW;
+            const int kk = fdiv(rem, a.dKW), mm = rem - kk * a.KWq;
+            if constexpr (AL) {
+                // quad (kk, mm) = output rows 2kk, 2kk+1 x columns 2mm, 2mm+1, all inside the
+                // output: one 8-byte store per row and channel, no edges
+                const unsigned y_off = qv ? (unsigned)((((b * g.Cout + co_w + 4 * gk) * g.OH + 2 * kk) * g.OW +
+                                                       2 * mm) * 4) : kInvalid;
+#pragma unroll
+                for (int rr = 0; rr < 2; ++rr) {
+                    const unsigned off = qv ? y_off + (unsigned)(rr * g.OW * 4) : kInvalid;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        if (co_w + 8 * (i / 4) >= g.Cout) continue;  // uniform: ragged last channel block
+                        const unsigned soff = (unsigned)(8 * (i / 4) + (i % 4)) * plane;
+                        float v0 = acc[nt][rr][0][i], v1 = acc[nt][rr][1][i];
+                        if constexpr (ACT >= 0) {
+                            v0 = epilogue_t<ACT>(v0, bias_i[i]);
+                            v1 = epilogue_t<ACT>(v1, bias_i[i]);
+                        }
+                        u2v d;
+                        d.x = __float_as_uint(v0);
+                        d.y = __float_as_uint(v1);
+                        __builtin_amdgcn_raw_buffer_store_b64(d, rs_y, off, soff, 0);
+                    }
+                }
+                continue;
+            }
             const int k = g.k_min + kk, m = g.m_min + mm;
             const int oy1 = 2 * k - 1 - g.P, ox1 = 2 * m - 1 - g.P;  // row / column of class 1
             const bool vcol1 = ox1 >= 0 && ox1 < g.OW, vcol0 = ox1 + 1 < g.OW;
@@ -358,17 +409,24 @@ bool make_args(const Geom& g, F32Args& a)
     if (xbytes > lim || wbytes > lim || ybytes > lim) return false;
     const int HI = (g.n + 1) / 2;
     a.g = g;
-    const long long Q = (long long)g.B * g.KH * g.KW;
+    // even kernel side and even padding: quads aligned to the (even-sized) output
+    a.aligned = (g.n % 2 == 0 && g.P % 2 == 0) ? 1 : 0;
+    a.KHq = a.aligned ? g.OH / 2 : g.KH;
+    a.KWq = a.aligned ? g.OW / 2 : g.KW;
+    const int wrows = a.aligned ? HI + 1 : HI;  // window rows / columns of a quad
+    const long long khw = (long long)a.KHq * a.KWq;
+    const long long Q = (long long)g.B * khw;
     if (Q > 0x3FFFFFFFLL) return false;
     a.Q = (int)Q;
-    a.EH = g.KH + HI - 1;
-    // TN consecutive flattened quads touch at most this many quad rows / images
-    const int nrho = (TN - 2) / g.KW + 2;
-    const int nimg = (TN - 2) / (g.KH * g.KW) + 2;
-    a.ROWS = nrho + (HI - 1) * nimg;
+    a.EH = a.KHq + wrows - 1;
+    // TN consecutive flattened quads touch at most this many quad rows / images (exactly TN/KWq
+    // rows / one image where tiles start on row / image boundaries)
+    const int nrho = (TN % a.KWq == 0) ? TN / a.KWq : (TN - 2) / a.KWq + 2;
+    const int nimg = (khw % TN == 0) ? 1 : (TN % khw == 0) ? (int)(TN / khw) : (int)((TN - 2) / khw) + 2;
+    a.ROWS = nrho + (wrows - 1) * nimg;
     a.SH = g.P >> 1;
     a.LWX = a.SH + g.W + HI;
-    const int need = g.KW + HI - 1;  // largest LDS column read: KW-1 + HI-1
+    const int need = a.KWq + wrows - 1;  // largest LDS column read: KWq-1 + wrows-1
     if (a.LWX < need + 1) a.LWX = need + 1;
     int xp = a.ROWS * a.LWX;
     xp = ((xp + 63) / 64) * 64 + 32;  // k planes 32 banks apart: the two k parities do not collide
@@ -382,8 +440,9 @@ bool make_args(const Geom& g, F32Args& a)
     a.nco = (g.Cout + TM - 1) / TM;
     a.nqt = (int)((Q + TN - 1) / TN);
     if ((long long)a.nco * a.nqt > 0x3FFFFFFFLL) return false;
-    a.dKHW = make_fastdiv((unsigned)(g.KH * g.KW));
-    a.dKW = make_fastdiv((unsigned)g.KW);
+    a.cb_major = wbytes > xbytes ? 1 : 0;
+    a.dKHW = make_fastdiv((unsigned)khw);
+    a.dKW = make_fastdiv((unsigned)a.KWq);
     a.dEH = make_fastdiv((unsigned)a.EH);
     a.dRW = make_fastdiv((unsigned)(a.ROWS * g.W));
     a.dW = make_fastdiv((unsigned)g.W);
@@ -408,8 +467,8 @@ bool make_args(const Geom& g, F32Args& a)
     return true;
 }
 
-template <int N, int NW>
-hipError_t launch_t(const F32Args& a, const Epilogue& ep, const float* x, const float* w, float* y,
+template <int N, int NW, bool AL>
+hipError_t launch_a(const F32Args& a, const Epilogue& ep, const float* x, const float* w, float* y,
                     void* part, hipStream_t stream)
 {
     constexpr int KC = kc_for(N);
@@ -418,30 +477,34 @@ hipError_t launch_t(const F32Args& a, const Epilogue& ep, const float* x, const 
     // kernel, not library state); cheap enough to repeat on every call
     // the epilogue belongs to whole sums: with a split K loop the slice sum applies it
     const bool epi = a.ksplit == 1 && has_epilogue(ep);
-    const void* kfn = epi ? (const void*)ukst_mfma_f32_kernel<N, NW, KC, true>
-                          : (const void*)ukst_mfma_f32_kernel<N, NW, KC, false>;
-    hipError_t e = hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    typedef void (*kernel_t)(const float*, const float*, float*, F32Args, Epilogue);
+    const kernel_t kfn = epi ? ukst_mfma_f32_kernel<N, NW, KC, true, AL> : ukst_mfma_f32_kernel<N, NW, KC, false, AL>;
+    hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     const unsigned nblocks = (unsigned)(a.nco * a.nqt * a.ksplit);
     if (a.ksplit == 1) {
-        if (epi)
-            hipLaunchKernelGGL((ukst_mfma_f32_kernel<N, NW, KC, true>), dim3(nblocks), dim3(256), lds,
-                               stream, x, w, y, a, ep);
-        else
-            hipLaunchKernelGGL((ukst_mfma_f32_kernel<N, NW, KC, false>), dim3(nblocks), dim3(256), lds,
-                               stream, x, w, y, a, ep);
+        hipLaunchKernelGGL(kfn, dim3(nblocks), dim3(256), lds, stream, x, w, y, a, ep);
         return hipGetLastError();
     }
     // partial outputs live in the caller's workspace for the duration of this call
     const GeomBase& g = a.g;
     const size_t ybytes = (size_t)g.B * g.Cout * g.OH * g.OW * 4;
-    hipLaunchKernelGGL((ukst_mfma_f32_kernel<N, NW, KC, false>), dim3(nblocks), dim3(256), lds, stream,
-                       x, w, (float*)part, a, ep);
+    hipLaunchKernelGGL(kfn, dim3(nblocks), dim3(256), lds, stream, x, w, (float*)part, a, ep);
     const int n4 = (int)(ybytes / 16);
     hipLaunchKernelGGL(ukst_sum_slices_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0,
                        stream, (const float4*)part, (float4*)y, n4, a.ksplit, ep.bias, ep.act,
                        (unsigned)(g.OH * g.OW), (unsigned)g.Cout);
     return hipGetLastError();
+}
+
+template <int N, int NW>
+hipError_t launch_t(const F32Args& a, const Epilogue& ep, const float* x, const float* w, float* y,
+                    void* part, hipStream_t stream)
+{
+    if constexpr (N % 2 == 0) {
+        if (a.aligned) return launch_a<N, NW, true>(a, ep, x, w, y, part, stream);
+    }
+    return launch_a<N, NW, false>(a, ep, x, w, y, part, stream);
 }
 
 template <int NW>
