@@ -5,6 +5,10 @@ import this package.  It shares nothing with the HIP library: no kernels, header
 tables.  The arithmetic lives in ``ukst_oracle.c`` (plain C, fp64); this module compiles it with
 gcc, loads it through ctypes and converts numpy arrays.
 
+``strided_naive`` / ``dilated_naive`` (``ukst_oracle_ext.c``) are the oracles of record for the two
+generalisations Sec. 5 points to (general stride s; dilated convolution), each pinned with its
+``*_segregated`` twin by ``tests/test_oracle_ext_pins.py``.
+
 ``naive`` is the oracle of record (Algorithm 1 of the paper: bed-of-nails upsample, pad by P,
 stride-1 n x n window).  ``scatter`` and ``segregated`` (Algorithm 2 / Eqs. 1-4 / Sec. 3.4) are
 independent formulations used only to pin ``naive``.  ``grad_input`` and ``grad_weight`` are the
@@ -22,15 +26,17 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ukst_oracle.c")
+_SRC_EXT = os.path.join(_HERE, "ukst_oracle_ext.c")
 _LIB = os.path.join(_HERE, "libukst_oracle.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
     """Compile the C oracle with gcc (-O2, OpenMP).  Returns the library path."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_EXT))
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-Wextra",
-               "-o", _LIB, _SRC, "-lm"]
+               "-o", _LIB, _SRC, _SRC_EXT, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -49,6 +55,10 @@ def _load():
             f.restype = i
         for f in (lib.ukst_oracle_grad_input, lib.ukst_oracle_grad_weight):
             f.argtypes = [dp, dp, dp, dp, i, i, i, i, i, i, i]
+            f.restype = i
+        for f in (lib.ukst_oracle_strided_naive, lib.ukst_oracle_strided_segregated,
+                  lib.ukst_oracle_dilated_naive, lib.ukst_oracle_dilated_segregated):
+            f.argtypes = [dp, dp, dp, dp, i, i, i, i, i, i, i, i]
             f.restype = i
         lib.ukst_oracle_threads.restype = i
         _lib = lib
@@ -155,3 +165,53 @@ def grad_weight(x, dy, n, P):
     if rc != 0:
         raise RuntimeError(f"oracle grad_weight failed with code {rc}")
     return dw, S
+
+
+def out_shape_strided(H: int, W: int, n: int, P: int, s: int):
+    """Stride-s transpose convolution: the map is upsampled to s(H-1)+1, padded by P, and an
+    n x n window slides over it with stride 1."""
+    return s * (H - 1) + 2 * P - n + 2, s * (W - 1) + 2 * P - n + 2
+
+
+def out_shape_dilated(H: int, W: int, n: int, P: int, d: int):
+    """Dilated convolution: the kernel is upsampled to d(n-1)+1 and slides over the input padded
+    by P."""
+    return H + 2 * P - d * (n - 1), W + 2 * P - d * (n - 1)
+
+
+def _call_ext(name, x, w, P, k, shape_fn):
+    x, w = _prep(x, w)
+    B, Cin, H, W = x.shape
+    Cout, _, n, _ = w.shape
+    OH, OW = shape_fn(H, W, n, P, k)
+    if OH < 1 or OW < 1 or P < 0 or k < 1:
+        raise ValueError("empty output")
+    y = np.zeros((B, Cout, OH, OW), dtype=np.float64)
+    S = np.zeros_like(y)
+    rc = getattr(_load(), "ukst_oracle_" + name)(_dp(x), _dp(w), _dp(y), _dp(S), B, Cin, Cout, H, W,
+                                                 n, P, k)
+    if rc != 0:
+        raise RuntimeError(f"oracle {name} failed with code {rc}")
+    return y, S
+
+
+def strided_naive(x, w, P, s):
+    """Oracle of record for stride-s transpose convolution (Algorithm 1 with s-1 inserted zeros).
+    Returns (y, S) in fp64."""
+    return _call_ext("strided_naive", x, w, P, s, out_shape_strided)
+
+
+def strided_segregated(x, w, P, s):
+    """Check-only formulation: s*s sub-kernels selected per output pixel."""
+    return _call_ext("strided_segregated", x, w, P, s, out_shape_strided)
+
+
+def dilated_naive(x, w, P, d):
+    """Oracle of record for dilated convolution (bed-of-nails upsampled kernel, stride-1 window
+    over the input padded by P).  Returns (y, S) in fp64."""
+    return _call_ext("dilated_naive", x, w, P, d, out_shape_dilated)
+
+
+def dilated_segregated(x, w, P, d):
+    """Check-only formulation: d*d sub-sampled input maps, each convolved with the dense kernel."""
+    return _call_ext("dilated_segregated", x, w, P, d, out_shape_dilated)
