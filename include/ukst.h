@@ -63,7 +63,8 @@ typedef enum {
     UKST_PATH_MFMA = 2    /* parity-class implicit GEMM on the matrix cores: wide channels, or <= 4 output channels (fp32) */
 } ukst_path;
 
-#define UKST_MAX_N 7 /* largest kernel side compiled in */
+#define UKST_MAX_N 7    /* largest kernel side compiled in */
+#define UKST_MAX_STEP 8 /* largest stride / dilation of the generalised operations */
 
 /* Library version: major*10000 + minor*100 + patch. */
 int ukst_version(void);
@@ -250,6 +251,43 @@ size_t ukst_static_workspace_bytes(void);
  */
 const char* ukst_grad_kernel_name(int which, int B, int Cin, int Cout, int H, int W, int n, int P,
                                   int dtype);
+
+/*
+ * The two generalisations the paper's discussion (Sec. 5) points to.  Both use the computation
+ * pattern of Algorithm 2 -- every output pixel selects, from its own coordinates, the taps that
+ * can meet data, and no inserted zero is ever multiplied -- in one general vector-ALU kernel.
+ *
+ * ukst_conv_transpose2d_strided: transpose convolution with stride s (Algorithm 1 with s-1 zeros
+ * between neighbouring pixels; s = 2 is ukst_conv_transpose2d).  s*s parity classes: output row oy
+ * has class r = (P - oy) mod s and uses taps r, r+s, ... on input rows (oy + r - P)/s + u.
+ *     y[b,co,oy,ox] = sum_ci sum_{a,c<n} U_P[b,ci,oy+a,ox+c] * w[co,ci,a,c],  U[s*i][s*j] = x[i][j]
+ *     OH = s(H-1) + 2P - n + 2,  OW = s(W-1) + 2P - n + 2
+ *
+ * ukst_dilated_conv2d: stride-1 convolution (correlation, no flip) with dilation d: the KERNEL is
+ * the bed of nails (d-1 zeros between neighbouring taps), the input is zero-padded by P, and the
+ * pattern is applied to the segregated input -- an output pixel only meets the sub-sampled input
+ * map of its own residue modulo d, read in place.
+ *     y[b,co,oy,ox] = sum_ci sum_{a,c<n} xpad[b,ci,oy+d*a,ox+d*c] * w[co,ci,a,c]
+ *     OH = H + 2P - d(n-1),  OW = W + 2P - d(n-1)
+ *
+ * Pointers, layouts ([B][Cin][H][W], [Cout][Cin][n][n], [B][Cout][OH][OW] fp32), alignment,
+ * ownership, asynchrony and error codes as for ukst_conv_transpose2d; dtype UKST_F32 or
+ * UKST_BF16_F32 (UKST_BF16_BF16: UKST_ERR_UNSUPPORTED); 1 <= s, d <= UKST_MAX_STEP (larger:
+ * UKST_ERR_UNSUPPORTED; < 1 or an empty output: UKST_ERR_SHAPE).  No workspace is used.
+ * ukst_output_shape_* and ukst_mac_count_* are host arithmetic only (kinds as ukst_mac_count:
+ * 0 exact in-range products, 1 what the segregated pattern executes, 2 what the definition with
+ * its inserted zeros executes; 0 on invalid arguments).
+ */
+int ukst_output_shape_strided(int H, int W, int n, int P, int s, int* OH, int* OW);
+int ukst_output_shape_dilated(int H, int W, int n, int P, int d, int* OH, int* OW);
+int ukst_conv_transpose2d_strided(const void* x, const void* w, void* y, int B, int Cin, int Cout,
+                                  int H, int W, int n, int P, int s, int dtype, void* stream);
+int ukst_dilated_conv2d(const void* x, const void* w, void* y, int B, int Cin, int Cout, int H,
+                        int W, int n, int P, int d, int dtype, void* stream);
+unsigned long long ukst_mac_count_strided(int B, int Cin, int Cout, int H, int W, int n, int P,
+                                          int s, int kind);
+unsigned long long ukst_mac_count_dilated(int B, int Cin, int Cout, int H, int W, int n, int P,
+                                          int d, int kind);
 
 /*
  * Name of the device kernel the given path launches for this problem, as it appears in a

@@ -26,7 +26,10 @@ EXPORTS = ["ukst_version", "ukst_status_string", "ukst_output_shape", "ukst_mac_
            "ukst_kernel_name", "ukst_conv_transpose2d_bias_act", "ukst_workspace_bytes",
            "ukst_conv_transpose2d_ws", "ukst_conv_transpose2d_grad_input",
            "ukst_conv_transpose2d_grad_weight", "ukst_grad_kernel_name",
-           "ukst_conv_transpose2d_grad_weight_static", "ukst_static_workspace_bytes"]
+           "ukst_conv_transpose2d_grad_weight_static", "ukst_static_workspace_bytes",
+           "ukst_output_shape_strided", "ukst_output_shape_dilated",
+           "ukst_conv_transpose2d_strided", "ukst_dilated_conv2d", "ukst_mac_count_strided",
+           "ukst_mac_count_dilated"]
 # every symbol include/ukst_bench.h declares (libukst_bench.so: measurement helpers)
 BENCH_EXPORTS = ["ukst_bench_mfma_ceiling", "ukst_bench_stream_ceiling"]
 
@@ -78,6 +81,12 @@ def lib():
             f.restype = i
         L.ukst_conv_transpose2d_grad_weight_static.argtypes = [vp, vp, vp] + [i] * 8 + [vp]
         L.ukst_conv_transpose2d_grad_weight_static.restype = i
+        for f in (L.ukst_output_shape_strided, L.ukst_output_shape_dilated):
+            f.argtypes, f.restype = [i] * 5 + [ip, ip], i
+        for f in (L.ukst_conv_transpose2d_strided, L.ukst_dilated_conv2d):
+            f.argtypes, f.restype = [vp, vp, vp] + [i] * 9 + [vp], i
+        for f in (L.ukst_mac_count_strided, L.ukst_mac_count_dilated):
+            f.argtypes, f.restype = [i] * 9, ctypes.c_ulonglong
         L.ukst_static_workspace_bytes.argtypes = []
         L.ukst_static_workspace_bytes.restype = ctypes.c_size_t
         _lib = L
@@ -369,3 +378,57 @@ def ukst_conv_transpose2d_grad_weight(x, dy, n: int, P: int, dw=None, stream=Non
         _check(int(lib().ukst_conv_transpose2d_grad_weight(x.data_ptr(), dy.data_ptr(), dw.data_ptr(),
                                                            B, Cin, Cout, H, W, n, P, dtype, wp, wb, sp)))
     return dw
+
+
+def ukst_output_shape_strided(H: int, W: int, n: int, P: int, s: int):
+    oh, ow = ctypes.c_int(0), ctypes.c_int(0)
+    _check(lib().ukst_output_shape_strided(H, W, n, P, s, ctypes.byref(oh), ctypes.byref(ow)))
+    return oh.value, ow.value
+
+
+def ukst_output_shape_dilated(H: int, W: int, n: int, P: int, d: int):
+    oh, ow = ctypes.c_int(0), ctypes.c_int(0)
+    _check(lib().ukst_output_shape_dilated(H, W, n, P, d, ctypes.byref(oh), ctypes.byref(ow)))
+    return oh.value, ow.value
+
+
+def ukst_mac_count_strided(B, Cin, Cout, H, W, n, P, s, kind: int) -> int:
+    return int(lib().ukst_mac_count_strided(B, Cin, Cout, H, W, n, P, s, kind))
+
+
+def ukst_mac_count_dilated(B, Cin, Cout, H, W, n, P, d, kind: int) -> int:
+    return int(lib().ukst_mac_count_dilated(B, Cin, Cout, H, W, n, P, d, kind))
+
+
+def _general(fn, shape_fn, x, w, P, k, y, stream):
+    import torch
+
+    if not (x.is_cuda and w.is_cuda and x.is_contiguous() and w.is_contiguous()):
+        raise ValueError("x and w must be contiguous device tensors")
+    if x.dtype != w.dtype or x.dtype not in (torch.float32, torch.bfloat16):
+        raise ValueError("x and w must both be float32 or both bfloat16")
+    if x.dim() != 4 or w.dim() != 4 or w.shape[2] != w.shape[3] or w.shape[1] != x.shape[1]:
+        raise ValueError("expected x[B,Cin,H,W] and w[Cout,Cin,n,n]")
+    B, Cin, H, W = x.shape
+    Cout, _, n, _ = w.shape
+    OH, OW = shape_fn(H, W, n, P, k)
+    y = _out(y, (B, Cout, OH, OW), x.device)
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device)
+    sp = stream.cuda_stream if hasattr(stream, "cuda_stream") else stream
+    dtype = UKST_F32 if x.dtype == torch.float32 else UKST_BF16_F32
+    with torch.cuda.device(x.device):
+        _check(int(fn(x.data_ptr(), w.data_ptr(), y.data_ptr(), B, Cin, Cout, H, W, n, P, k, dtype, sp)))
+    return y
+
+
+def ukst_conv_transpose2d_strided(x, w, P: int, s: int, y=None, stream=None):
+    """Marshal torch device tensors into ukst_conv_transpose2d_strided (stride-s transpose
+    convolution; float32 output [B,Cout,s(H-1)+2P-n+2,s(W-1)+2P-n+2])."""
+    return _general(lib().ukst_conv_transpose2d_strided, ukst_output_shape_strided, x, w, P, s, y, stream)
+
+
+def ukst_dilated_conv2d(x, w, P: int, d: int, y=None, stream=None):
+    """Marshal torch device tensors into ukst_dilated_conv2d (dilation-d convolution; float32
+    output [B,Cout,H+2P-d(n-1),W+2P-d(n-1)])."""
+    return _general(lib().ukst_dilated_conv2d, ukst_output_shape_dilated, x, w, P, d, y, stream)

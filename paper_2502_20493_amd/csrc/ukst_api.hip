@@ -58,6 +58,62 @@ unsigned long long nominal_line_taps(int OL, int n, int P)
     return t;
 }
 
+// Output size of the generalised operations, 0 on invalid arguments.
+// stride-k transpose convolution: the map is upsampled to k(H-1)+1, padded by P, n x n window;
+// dilation-k convolution: the kernel is upsampled to k(n-1)+1, the input padded by P.
+bool general_shape(int dilated, int H, int W, int n, int P, int k, int* OH, int* OW)
+{
+    if (H < 1 || W < 1 || n < 1 || P < 0 || k < 1 || k > UKST_MAX_STEP) return false;
+    if (H > (1 << 24) || W > (1 << 24) || P > (1 << 24)) return false;
+    const long long oh = dilated ? (long long)H + 2 * P - (long long)k * (n - 1)
+                                 : (long long)k * (H - 1) + 2 * P - n + 2;
+    const long long ow = dilated ? (long long)W + 2 * P - (long long)k * (n - 1)
+                                 : (long long)k * (W - 1) + 2 * P - n + 2;
+    if (oh < 1 || ow < 1 || oh > 0x3fffffffLL || ow > 0x3fffffffLL) return false;
+    *OH = (int)oh;
+    *OW = (int)ow;
+    return true;
+}
+
+// taps of one output line that meet an in-range input pixel (kind 0), that the segregated
+// algorithm executes (kind 1: its class's taps, padding included), or that the naive definition
+// multiplies (kind 2: every tap of the full or upsampled kernel)
+unsigned long long general_line_taps(int dilated, int L, int OL, int n, int P, int k, int kind)
+{
+    unsigned long long t = 0;
+    for (int o = 0; o < OL; ++o) {
+        if (kind == 2) { t += dilated ? (unsigned)(k * (n - 1) + 1) : (unsigned)n; continue; }
+        for (int a = 0; a < n; ++a) {
+            if (dilated) {
+                const int i = o + k * a - P;
+                if (kind == 1 || (i >= 0 && i < L)) ++t;
+            } else {
+                const int u = o + a - P;
+                if (((u % k) + k) % k != 0) continue;  // an inserted zero
+                const int i = (u - (((u % k) + k) % k)) / k;
+                if (kind == 1 || (u >= 0 && i < L)) ++t;
+            }
+        }
+    }
+    return t;
+}
+
+int general_checked(int dilated, const void* x, const void* w, void* y, int B, int Cin, int Cout, int H,
+                    int W, int n, int P, int k, int dtype, void* stream)
+{
+    if (!x || !w || !y) return UKST_ERR_NULL;
+    if (B < 1 || Cin < 1 || Cout < 1 || H < 1 || W < 1 || n < 1 || P < 0 || k < 1) return UKST_ERR_SHAPE;
+    if (dtype != UKST_F32 && dtype != UKST_BF16_F32 && dtype != UKST_BF16_BF16) return UKST_ERR_DTYPE;
+    if (dtype == UKST_BF16_BF16 || n > UKST_MAX_N || k > UKST_MAX_STEP) return UKST_ERR_UNSUPPORTED;
+    int OH = 0, OW = 0;
+    if (!general_shape(dilated, H, W, n, P, k, &OH, &OW)) return UKST_ERR_SHAPE;
+    const uintptr_t esz = dtype == UKST_F32 ? 4 : 2;
+    if ((((uintptr_t)x | (uintptr_t)w) & (esz - 1)) || ((uintptr_t)y & 3)) return UKST_ERR_UNSUPPORTED;
+    const hipError_t e = ukst::launch_general(dilated, B, Cin, Cout, H, W, n, P, k, OH, OW, x, w, (float*)y,
+                                              dtype, (hipStream_t)stream);
+    return e == hipSuccess ? UKST_OK : e == hipErrorInvalidConfiguration ? UKST_ERR_UNSUPPORTED : UKST_ERR_LAUNCH;
+}
+
 int resolve_path(const ukst::Geom& g, int dtype, int path)
 {
     if (path == UKST_PATH_DIRECT) return UKST_PATH_DIRECT;
@@ -303,6 +359,52 @@ int ukst_conv_transpose2d_grad_weight_static(const void* x, const void* dy, void
     // every slice writes the whole of its copy before the sum kernel reads it: nothing in the
     // array has to start at zero, whatever the last call left there
     return status_of(ukst::launch_grad_weight(g, x, dy, (float*)dw, dtype, ws, (hipStream_t)stream));
+}
+
+int ukst_output_shape_strided(int H, int W, int n, int P, int s, int* OH, int* OW)
+{
+    if (!OH || !OW) return UKST_ERR_NULL;
+    return general_shape(0, H, W, n, P, s, OH, OW) ? UKST_OK : UKST_ERR_SHAPE;
+}
+
+int ukst_output_shape_dilated(int H, int W, int n, int P, int d, int* OH, int* OW)
+{
+    if (!OH || !OW) return UKST_ERR_NULL;
+    return general_shape(1, H, W, n, P, d, OH, OW) ? UKST_OK : UKST_ERR_SHAPE;
+}
+
+static unsigned long long general_macs(int dilated, int B, int Cin, int Cout, int H, int W, int n, int P,
+                                       int k, int kind)
+{
+    int OH = 0, OW = 0;
+    if (B < 1 || Cin < 1 || Cout < 1 || kind < 0 || kind > 2) return 0;
+    if (!general_shape(dilated, H, W, n, P, k, &OH, &OW)) return 0;
+    return (unsigned long long)B * Cin * Cout * general_line_taps(dilated, H, OH, n, P, k, kind) *
+           general_line_taps(dilated, W, OW, n, P, k, kind);
+}
+
+unsigned long long ukst_mac_count_strided(int B, int Cin, int Cout, int H, int W, int n, int P, int s,
+                                          int kind)
+{
+    return general_macs(0, B, Cin, Cout, H, W, n, P, s, kind);
+}
+
+unsigned long long ukst_mac_count_dilated(int B, int Cin, int Cout, int H, int W, int n, int P, int d,
+                                          int kind)
+{
+    return general_macs(1, B, Cin, Cout, H, W, n, P, d, kind);
+}
+
+int ukst_conv_transpose2d_strided(const void* x, const void* w, void* y, int B, int Cin, int Cout, int H,
+                                  int W, int n, int P, int s, int dtype, void* stream)
+{
+    return general_checked(0, x, w, y, B, Cin, Cout, H, W, n, P, s, dtype, stream);
+}
+
+int ukst_dilated_conv2d(const void* x, const void* w, void* y, int B, int Cin, int Cout, int H, int W,
+                        int n, int P, int d, int dtype, void* stream)
+{
+    return general_checked(1, x, w, y, B, Cin, Cout, H, W, n, P, d, dtype, stream);
 }
 
 const char* ukst_grad_kernel_name(int which, int B, int Cin, int Cout, int H, int W, int n, int P,

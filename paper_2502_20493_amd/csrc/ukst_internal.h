@@ -161,6 +161,11 @@ hipError_t launch_mfma_f32(const Geom& g, const void* x, const void* w, float* y
 bool thin_mfma_supported(const Geom& g, int dtype);
 hipError_t launch_thin_mfma(const Geom& g, const void* x, const void* w, float* y, hipStream_t stream);
 
+// Stride-k transpose convolution (dilated == 0) / dilation-k convolution (dilated == 1), any shape
+hipError_t launch_general(int dilated, int B, int Cin, int Cout, int H, int W, int n, int P, int k,
+                          int OH, int OW, const void* x, const void* w, float* y, int dtype,
+                          hipStream_t stream);
+
 // Backward pass (vector-ALU kernels, any shape; dtype 0: fp32, 1: bf16 operands, fp32 result)
 hipError_t launch_grad_input(const Geom& g, const void* dy, const void* w, float* dx, int dtype,
                              Workspace& ws, hipStream_t stream);

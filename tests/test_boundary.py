@@ -233,3 +233,54 @@ def test_backward_kernel_selection_is_host_arithmetic():
     assert name(0, 1, 1, 1, 4, 4, 3, 0, ukst.UKST_BF16_BF16) == ""
     assert name(2, 1, 1, 1, 4, 4, 3, 0, ukst.UKST_F32) == ""
     assert name(0, 1, 1, 1, 1, 4, 3, 0, ukst.UKST_F32) == ""
+
+
+def test_generalised_operations_host_side():
+    """Stride-s transpose convolution and dilated convolution: shapes, multiply-add counts and
+    argument validation are host arithmetic (fake addresses: nothing may be launched)."""
+    assert ukst.ukst_output_shape_strided(4, 4, 3, 0, 2) == ukst.ukst_output_shape(4, 4, 3, 0)
+    assert ukst.ukst_output_shape_strided(2, 2, 2, 1, 3) == (5, 5)     # tests/golden/worked_stride3_2x2_k2.txt
+    assert ukst.ukst_output_shape_dilated(4, 4, 2, 0, 2) == (2, 2)     # tests/golden/worked_dilated2_4x4_k2.txt
+    assert ukst.ukst_output_shape_dilated(9, 7, 3, 2, 3) == (7, 5)
+    for bad in [(0, 4, 3, 0, 2), (4, 4, 0, 0, 2), (4, 4, 3, -1, 2), (4, 4, 3, 0, 0), (1, 1, 3, 0, 2)]:
+        with pytest.raises(ukst.UkstError) as e:
+            ukst.ukst_output_shape_strided(*bad)
+        assert e.value.status == ukst.UKST_ERR_SHAPE
+    with pytest.raises(ukst.UkstError):
+        ukst.ukst_output_shape_dilated(4, 4, 3, 0, 2)  # 4 - 2*2 = 0: empty output
+
+    def brute_strided(H, W, n, P, s):
+        OH, OW = s * (H - 1) + 2 * P - n + 2, s * (W - 1) + 2 * P - n + 2
+        U = np.zeros((s * (H - 1) + 1 + 2 * P, s * (W - 1) + 1 + 2 * P), dtype=np.int64)
+        U[P:P + s * (H - 1) + 1:s, P:P + s * (W - 1) + 1:s] = 1
+        return sum(int(U[oy:oy + n, ox:ox + n].sum()) for oy in range(OH) for ox in range(OW)), OH * OW * n * n
+
+    def brute_dilated(H, W, n, P, d):
+        OH, OW = H + 2 * P - d * (n - 1), W + 2 * P - d * (n - 1)
+        X = np.pad(np.ones((H, W), dtype=np.int64), P)
+        nd = d * (n - 1) + 1
+        return sum(int(X[oy:oy + nd:d, ox:ox + nd:d].sum()) for oy in range(OH) for ox in range(OW)), OH * OW * nd * nd
+
+    for (H, W, n, P, k) in [(4, 4, 3, 0, 2), (3, 5, 4, 2, 3), (5, 3, 5, 3, 4), (2, 2, 2, 1, 3), (6, 4, 3, 2, 1)]:
+        e, nv = brute_strided(H, W, n, P, k)
+        assert ukst.ukst_mac_count_strided(2, 3, 5, H, W, n, P, k, 0) == 30 * e
+        assert ukst.ukst_mac_count_strided(2, 3, 5, H, W, n, P, k, 2) == 30 * nv
+        assert e <= ukst.ukst_mac_count_strided(1, 1, 1, H, W, n, P, k, 1) <= nv
+    assert ukst.ukst_mac_count_strided(2, 3, 5, 4, 4, 3, 1, 2, 0) == ukst.ukst_mac_count(2, 3, 5, 4, 4, 3, 1, 0)
+    assert ukst.ukst_mac_count_strided(2, 3, 5, 4, 4, 3, 1, 2, 1) == ukst.ukst_mac_count(2, 3, 5, 4, 4, 3, 1, 1)
+    for (H, W, n, P, k) in [(9, 8, 3, 0, 2), (7, 7, 3, 3, 3), (6, 9, 2, 2, 4), (5, 5, 4, 1, 1)]:
+        e, nv = brute_dilated(H, W, n, P, k)
+        assert ukst.ukst_mac_count_dilated(2, 3, 5, H, W, n, P, k, 0) == 30 * e
+        assert ukst.ukst_mac_count_dilated(2, 3, 5, H, W, n, P, k, 2) == 30 * nv
+    X = W_ = Y = 0x1000
+    for f in (ukst.lib().ukst_conv_transpose2d_strided, ukst.lib().ukst_dilated_conv2d):
+        ok = (1, 1, 1, 8, 8, 3, 1, 2)
+        assert f(None, W_, Y, *ok, 0, None) == ukst.UKST_ERR_NULL
+        assert f(X, W_, None, *ok, 0, None) == ukst.UKST_ERR_NULL
+        assert f(X, W_, Y, 1, 1, 1, 8, 8, 3, 1, 0, 0, None) == ukst.UKST_ERR_SHAPE
+        assert f(X, W_, Y, 0, 1, 1, 8, 8, 3, 1, 2, 0, None) == ukst.UKST_ERR_SHAPE
+        assert f(X, W_, Y, *ok, 7, None) == ukst.UKST_ERR_DTYPE
+        assert f(X, W_, Y, *ok, ukst.UKST_BF16_BF16, None) == ukst.UKST_ERR_UNSUPPORTED
+        assert f(X, W_, Y, 1, 1, 1, 8, 8, 3, 1, 9, 0, None) == ukst.UKST_ERR_UNSUPPORTED
+        assert f(X + 2, W_, Y, *ok, 0, None) == ukst.UKST_ERR_UNSUPPORTED
+    assert ukst.lib().ukst_dilated_conv2d(X, W_, Y, 1, 1, 1, 4, 4, 3, 0, 2, 0, None) == ukst.UKST_ERR_SHAPE
