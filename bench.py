@@ -317,6 +317,45 @@ def measure_stack(steps, nsets=8):
             "roofline": roof}
 
 
+def measure_general(op, k, shape, steps):
+    """Time one of the generalised operations of Sec. 5 (op = "strided": stride-k transpose
+    convolution, "dilated": dilation-k convolution) on a synthetic fp32 layer; reported against the
+    fp32 vector peak (the kernel runs on the vector ALUs)."""
+    import torch
+    from paper_2502_20493_amd import binding as ukst
+    B, Cin, Cout, H, W, n, P = shape
+    g = torch.Generator(device="cuda").manual_seed(20493)
+    x = torch.randn((B, Cin, H, W), generator=g, device="cuda")
+    wt = torch.randn((Cout, Cin, n, n), generator=g, device="cuda") * 0.05
+    if op == "strided":
+        OH, OW = ukst.ukst_output_shape_strided(H, W, n, P, k)
+        fn, macs = ukst.lib().ukst_conv_transpose2d_strided, ukst.ukst_mac_count_strided(*shape, k, 0)
+        ukst.ukst_conv_transpose2d_strided(x, wt, P, k)
+    else:
+        OH, OW = ukst.ukst_output_shape_dilated(H, W, n, P, k)
+        fn, macs = ukst.lib().ukst_dilated_conv2d, ukst.ukst_mac_count_dilated(*shape, k, 0)
+        ukst.ukst_dilated_conv2d(x, wt, P, k)
+    nbytes = 4 * (x.numel() + wt.numel() + B * Cout * OH * OW)
+    nsets = max(1, min(8, -(-(LLC_BYTES + (64 << 20)) // nbytes)))
+    xs = [x] + [x.clone() for _ in range(nsets - 1)]
+    ys = [torch.empty((B, Cout, OH, OW), dtype=torch.float32, device="cuda") for _ in range(nsets)]
+    stream = torch.cuda.current_stream()
+    calls = [functools.partial(fn, xs[j].data_ptr(), wt.data_ptr(), ys[j].data_ptr(), *shape, k,
+                               ukst.UKST_F32, stream.cuda_stream) for j in range(nsets)]
+
+    def step(i):
+        if calls[i % nsets]() != 0:
+            raise RuntimeError(op + " failed")
+
+    med, best, per = time_windows(step, steps, 2, warm_seconds=0.2, windows=3, stream=stream)
+    roof = _roof("mfma_f32", 2 * macs, nbytes, med, "ukst_general_kernel", None)
+    roof["bound"] = "alu"  # fp32 vector peak: the same published 157.3 TFLOP/s
+    return {"workload": f"{op}{k}", "shape": f"B{B} {Cin}->{Cout} {H}x{W} n{n} P{P} f32, "
+            + (f"stride {k} transpose convolution" if op == "strided" else f"dilation {k} convolution"),
+            "out": f"{OH}x{OW}", "useful_gflops": round(2 * macs / med / 1e9, 1), "us": round(med * 1e6, 2),
+            "us_min": round(best * 1e6, 2), "buffer_sets": nsets, "roofline": roof}
+
+
 def cpu_baseline(w, data, budget_s=1.5, chunk=32):
     """Time the CPU oracle (as it stands) on complete (image, output channel) planes of the
     headline workload, all host cores: chunks of `chunk` seeded planes until about `budget_s`
@@ -410,6 +449,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-ws", action="store_true",
                     help="with --only: the entry point without a workspace (cfg3 L1, L2 differ)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="one device-to-device copy of 48 MiB before the timed work: the known-size "
+                         "copy kernel that scales the profiler's FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--grad", default=None, choices=["grad_input", "grad_weight"],
                     help="with --only: time this gradient of the workload instead of the forward "
                          "pass (used for the per-kernel counter runs)")
@@ -426,6 +468,10 @@ def main():
         b.build_library()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
 
+    if args.calibrate_copy:
+        src = torch.empty(12582912, dtype=torch.float32, device="cuda").normal_()
+        torch.empty_like(src).copy_(src)
+        torch.cuda.synchronize()
     head = wl.WORKLOADS[args.only or HEADLINE]
     if args.grad:
         if not args.only:
@@ -477,6 +523,10 @@ def main():
                 hbm = BOUND.get(w.name, "hbm") == "hbm"
                 rows.append(measure(w, 200 if hbm else max(5, min(args.steps, 50)), 2, **kw))
                 torch.cuda.empty_cache()
+            # the generalised operations (general stride, dilation): generator-sized fp32 layers
+            rows.append(measure_general("strided", 3, (16, 128, 64, 32, 32, 5, 2), max(5, min(args.steps, 20))))
+            rows.append(measure_general("dilated", 2, (16, 64, 64, 64, 64, 3, 2), max(5, min(args.steps, 20))))
+            torch.cuda.empty_cache()
             # backward pass: both gradients of every configuration
             for name in FORWARD[1:]:
                 for which in ("grad_input", "grad_weight"):

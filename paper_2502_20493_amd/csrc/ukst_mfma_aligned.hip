@@ -130,8 +130,7 @@ void ukst_mfma_bf16_aligned_kernel(const uint16_t* __restrict__ x, const uint16_
     const int w_lds = w_g * W_HALF + (8 * w_h) * W_PLANE + w_co * 16;  // + t * W_PLANE
     // activations: thread = (8-column group c8, row r, k-half g), c8 fastest; threads beyond the
     // unit count repeat a unit.  A staged row keeps even and odd columns in two regions (lanes of
-    // a fragment read hold every second column), column c in slot (c & 1) * HS + c/2 + c/8: one
-    // pad slot per 8 columns spreads the writes of neighbouring units over the banks.
+    // a fragment read hold every second column), column c in slot (c & 1) * HS + c/2.
     int x_r, x_g, x_c8;
     {
         const int units = a.ROWS * 2 * a.C8;
@@ -141,7 +140,7 @@ void ukst_mfma_bf16_aligned_kernel(const uint16_t* __restrict__ x, const uint16_
         x_g = fdiv(t2, a.dROWS);
         x_r = t2 - x_g * a.ROWS;
     }
-    const int x_lds0 = XS_OFF + ((x_g * a.ROWS + x_r) * a.LWS + 5 * (x_c8 + (a.OFFS >> 3))) * 16;
+    const int x_lds0 = XS_OFF + ((x_g * a.ROWS + x_r) * a.LWS + 4 * (x_c8 + (a.OFFS >> 3))) * 16;
     const int x_lds1 = x_lds0 + a.HS * 16;  // odd columns of the group
 
     // global offsets of this thread's staging units for tile (cb, qt)
@@ -301,7 +300,7 @@ void ukst_mfma_bf16_aligned_kernel(const uint16_t* __restrict__ x, const uint16_
 #pragma unroll
             for (int bb = 0; bb < 3; ++bb) {
                 const int c = kx - a.HP + a.OFFS + bb;  // staged column of window column bb
-                const int slot = (c & 1) * a.HS + (c >> 1) + (c >> 3);
+                const int slot = (c & 1) * a.HS + (c >> 1);
                 b_lds[nt][bb] = XS_OFF + ((gk * a.ROWS + r) * a.LWS + slot) * 16;
             }
         }
@@ -422,8 +421,14 @@ bool make_args(const Geom& g, int dtype, AArgs& a)
     a.OFFS = (a.HP + 7) & ~7;
     // staged columns: input columns -P/2 .. W + P/2 - 1, shifted by OFFS, rounded to groups of 8
     const int cw = (a.OFFS + g.W + a.HP + 7) & ~7;
-    a.HS = 5 * (cw / 8) + 1;
+    a.HS = cw / 2 + 1;
     a.LWS = 2 * a.HS;
+    // The 16 lanes of a fragment-read pass hold 32 consecutive quads, i.e. 32/KWa rows of KWa/2
+    // consecutive slots each: a row pitch of KWa/2 slots modulo the 16 slots the banks span lays
+    // them side by side (measured on 16x16 maps: 234 -> 224 us; padding inside the rows, which
+    // would spread the staging writes instead, was slower).
+    if (a.KWa < 32)
+        while (a.LWS % 16 != (a.KWa / 2) % 16) ++a.LWS;
     a.C8 = g.W / 8;
     if (2 * a.ROWS * a.LWS * 16 > XS_STAGE_MAX) return false;
     if (a.ROWS * 2 * a.C8 > 256) return false;   // one staging unit per thread
