@@ -155,8 +155,8 @@ bool mfma_needs_aligned_x(const Geom& g, int dtype);
 
 // fp32-operand MFMA kernels (used by the functions above for dtype 0): the general one, and the
 // one for layers with at most 4 output channels, where the parity classes fill the MFMA columns
-bool mfma_f32_supported(const Geom& g);
-hipError_t launch_mfma_f32(const Geom& g, const void* x, const void* w, float* y, Workspace& ws,
+bool mfma_f32_supported(const Geom& g, int dtype);
+hipError_t launch_mfma_f32(const Geom& g, const void* x, const void* w, float* y, int dtype, Workspace& ws,
                            hipStream_t stream);
 bool thin_mfma_supported(const Geom& g, int dtype);
 hipError_t launch_thin_mfma(const Geom& g, const void* x, const void* w, float* y, hipStream_t stream);

@@ -460,22 +460,32 @@ static bool prefer_aligned(const Geom& g, int dtype)
     return aligned * 21 <= shifted * 20;
 }
 
+// true if a bf16 layer runs on the bf16 matrix pipe (else, if at all, on the fp32 pipe with
+// widened operands: kernel sides other than 4)
+static bool bf16_pipe(const Geom& g, int dtype)
+{
+    MfmaArgs a;
+    return dtype != 0 && (mfma_aligned_supported(g, dtype) || make_args(g, dtype, a));
+}
+
 bool mfma_supported(const Geom& g, int dtype)
 {
-    if (dtype == 0) return mfma_f32_supported(g) || thin_mfma_supported(g, dtype);
+    if (dtype == 0) return mfma_f32_supported(g, dtype) || thin_mfma_supported(g, dtype);
     MfmaArgs a;
-    return mfma_aligned_supported(g, dtype) || make_args(g, dtype, a);
+    return mfma_aligned_supported(g, dtype) || make_args(g, dtype, a) || mfma_f32_supported(g, dtype);
 }
 
 bool mfma_needs_aligned_x(const Geom& g, int dtype)
 {
-    return dtype != 0 || (!mfma_f32_supported(g) && thin_mfma_supported(g, dtype));
+    if (dtype != 0) return bf16_pipe(g, dtype);  // the bf16 kernels move x in 16-byte pieces
+    return !mfma_f32_supported(g, dtype) && thin_mfma_supported(g, dtype);
 }
 
 hipError_t launch_mfma(const Geom& g, const void* x, const void* w, float* y, int dtype,
                        Workspace& ws, hipStream_t stream)
 {
-    if (dtype == 0 && mfma_f32_supported(g)) return launch_mfma_f32(g, x, w, y, ws, stream);
+    if (mfma_f32_supported(g, dtype) && (dtype == 0 || !bf16_pipe(g, dtype)))
+        return launch_mfma_f32(g, x, w, y, dtype, ws, stream);
     if (ws.query) return hipSuccess;  // the kernels below use no scratch
     if (dtype == 0) return launch_thin_mfma(g, x, w, y, stream);
     if (prefer_aligned(g, dtype)) return launch_mfma_aligned(g, x, w, y, dtype, stream);
@@ -515,9 +525,9 @@ hipError_t launch_mfma(const Geom& g, const void* x, const void* w, float* y, in
 
 const char* mfma_kernel_name(const Geom& g, int dtype)
 {
-    if (dtype != 0)  // bf16 in; fp32 or bf16 out
+    if (bf16_pipe(g, dtype))  // bf16 in; fp32 or bf16 out
         return prefer_aligned(g, dtype) ? "ukst_mfma_bf16_aligned_kernel" : "ukst_mfma_bf16_kernel";
-    return mfma_f32_supported(g) ? "ukst_mfma_f32_kernel" : "ukst_thin_mfma_kernel";
+    return mfma_f32_supported(g, dtype) ? "ukst_mfma_f32_kernel" : "ukst_thin_mfma_kernel";
 }
 
 }  // namespace ukst

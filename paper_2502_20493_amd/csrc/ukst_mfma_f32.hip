@@ -78,11 +78,16 @@ constexpr int tap_at(int pa, int pb, int c)
     return (r + 2 * u) * N + (sc + 2 * v);
 }
 
-template <int N, int NW, int KC, bool EPI, bool AL>
+// TIn = float, or uint16_t for bf16 operands: they are widened to fp32 on their way into LDS
+// (exact) and multiplied on the fp32 matrix pipe -- the path of bf16 layers whose kernel side the
+// bf16 kernels do not take (n = 2, 3, 5).
+template <int N, int NW, int KC, bool EPI, bool AL, typename TIn>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, NW == 4 ? 1 : 2)))
-void ukst_mfma_f32_kernel(const float* __restrict__ x, const float* __restrict__ w,
+void ukst_mfma_f32_kernel(const TIn* __restrict__ x, const TIn* __restrict__ w,
                           float* __restrict__ y, F32Args a, Epilogue ep)
 {
+    constexpr bool B16 = sizeof(TIn) == 2;
+    constexpr int ES = (int)sizeof(TIn);
     constexpr int HI = (N + 1) / 2;
     constexpr int NN = N * N;
     constexpr int TN = 64 * NW;                 // quads per block
@@ -143,16 +148,16 @@ void ukst_mfma_f32_kernel(const float* __restrict__ x, const float* __restrict__
                 const int b = fdiv(er, a.dEH), ii = er - b * a.EH;
                 const int i = ii - (g.P >> 1);  // = k_min - P + ii for the shifted quads
                 if (b < g.B && i >= 0 && i < g.H)
-                    x_goff[j] = (unsigned)((((b * g.Cin + k) * g.H + i) * g.W + col) * 4);
+                    x_goff[j] = (unsigned)((((b * g.Cin + k) * g.H + i) * g.W + col) * ES);
                 x_loff[j] = k * a.XP + row * a.LWX + a.SH + col;
             }
         }
     }
     const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)x, 0, (int)((size_t)g.B * g.Cin * g.H * g.W * 4), kRsrcFlags);
+        (void*)x, 0, (int)((size_t)g.B * g.Cin * g.H * g.W * ES), kRsrcFlags);
     const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)w, 0, (int)((size_t)g.Cout * g.Cin * NN * 4), kRsrcFlags);
-    const unsigned x_cstride = (unsigned)(g.H * g.W * 4);  // bytes between input channels
+        (void*)w, 0, (int)((size_t)g.Cout * g.Cin * NN * ES), kRsrcFlags);
+    const unsigned x_cstride = (unsigned)(g.H * g.W * ES);  // bytes between input channels
 
     // ---- per-lane operand positions
     // A (weights): lane = channel cw*32 + l32, k parity gk
@@ -193,15 +198,25 @@ void ukst_mfma_f32_kernel(const float* __restrict__ x, const float* __restrict__
         for (int j = 0; j < NWL; ++j) {
             const int e = (tid + 256 * j) * 4;
             const int co = e / (KC * NN), rem = e - co * (KC * NN);
-            const unsigned voff = (co < TM) ? (unsigned)(((co0 + co) * g.Cin * NN + rem) * 4) : kInvalid;
-            wreg[j] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, voff, (unsigned)(ci0 * NN * 4), 0);
+            const unsigned voff = (co < TM) ? (unsigned)(((co0 + co) * g.Cin * NN + rem) * ES) : kInvalid;
+            if constexpr (B16) {
+                const u2v t = __builtin_amdgcn_raw_buffer_load_b64(rs_w, voff, (unsigned)(ci0 * NN * ES), 0);
+                wreg[j] = u4v{t.x << 16, t.x & 0xFFFF0000u, t.y << 16, t.y & 0xFFFF0000u};
+            } else {
+                wreg[j] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, voff, (unsigned)(ci0 * NN * ES), 0);
+            }
         }
 #pragma unroll
         for (int j = 0; j < NXL_MAX; ++j)
-            if (j < a.nxl)
-                xreg[j] = __builtin_bit_cast(
-                    float, __builtin_amdgcn_raw_buffer_load_b32(rs_x, x_goff[j],
-                                                                (unsigned)ci0 * x_cstride, 0));
+            if (j < a.nxl) {
+                if constexpr (B16)
+                    xreg[j] = __uint_as_float((unsigned)(unsigned short)__builtin_amdgcn_raw_buffer_load_b16(
+                                                  rs_x, x_goff[j], (unsigned)ci0 * x_cstride, 0) << 16);
+                else
+                    xreg[j] = __builtin_bit_cast(
+                        float, __builtin_amdgcn_raw_buffer_load_b32(rs_x, x_goff[j],
+                                                                    (unsigned)ci0 * x_cstride, 0));
+            }
         __builtin_amdgcn_sched_barrier(0);  // requested before the stage is multiplied
     };
     auto stage_store = [&](int buf) {
@@ -395,15 +410,15 @@ __global__ __launch_bounds__(256) void ukst_sum_slices_kernel(const float4* __re
 }
 
 template <int NW>
-bool make_args(const Geom& g, F32Args& a)
+bool make_args(const Geom& g, F32Args& a, int es = 4)
 {
     constexpr int TN = 64 * NW;
     const int KC = kc_for(g.n);
     if (g.n < 2 || g.n > 5) return false;
     if (g.Cin % KC != 0) return false;  // a stage never straddles the channel count
     if (g.Cout % 8 != 0) return false;  // channel groups of the accumulator layout stay whole
-    const size_t xbytes = (size_t)g.B * g.Cin * g.H * g.W * 4;
-    const size_t wbytes = (size_t)g.Cout * g.Cin * g.n * g.n * 4;
+    const size_t xbytes = (size_t)g.B * g.Cin * g.H * g.W * es;
+    const size_t wbytes = (size_t)g.Cout * g.Cin * g.n * g.n * es;
     const size_t ybytes = (size_t)g.B * g.Cout * g.OH * g.OW * 4;
     const size_t lim = 0x7FFFFFF0u;  // single buffer descriptors, 32-bit byte offsets
     if (xbytes > lim || wbytes > lim || ybytes > lim) return false;
@@ -467,8 +482,8 @@ bool make_args(const Geom& g, F32Args& a)
     return true;
 }
 
-template <int N, int NW, bool AL>
-hipError_t launch_a(const F32Args& a, const Epilogue& ep, const float* x, const float* w, float* y,
+template <int N, int NW, bool AL, typename TIn>
+hipError_t launch_a(const F32Args& a, const Epilogue& ep, const TIn* x, const TIn* w, float* y,
                     void* part, hipStream_t stream)
 {
     constexpr int KC = kc_for(N);
@@ -477,8 +492,9 @@ hipError_t launch_a(const F32Args& a, const Epilogue& ep, const float* x, const 
     // kernel, not library state); cheap enough to repeat on every call
     // the epilogue belongs to whole sums: with a split K loop the slice sum applies it
     const bool epi = a.ksplit == 1 && has_epilogue(ep);
-    typedef void (*kernel_t)(const float*, const float*, float*, F32Args, Epilogue);
-    const kernel_t kfn = epi ? ukst_mfma_f32_kernel<N, NW, KC, true, AL> : ukst_mfma_f32_kernel<N, NW, KC, false, AL>;
+    typedef void (*kernel_t)(const TIn*, const TIn*, float*, F32Args, Epilogue);
+    const kernel_t kfn = epi ? ukst_mfma_f32_kernel<N, NW, KC, true, AL, TIn>
+                             : ukst_mfma_f32_kernel<N, NW, KC, false, AL, TIn>;
     hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     const unsigned nblocks = (unsigned)(a.nco * a.nqt * a.ksplit);
@@ -497,37 +513,37 @@ hipError_t launch_a(const F32Args& a, const Epilogue& ep, const float* x, const 
     return hipGetLastError();
 }
 
-template <int N, int NW>
-hipError_t launch_t(const F32Args& a, const Epilogue& ep, const float* x, const float* w, float* y,
+template <int N, int NW, typename TIn>
+hipError_t launch_t(const F32Args& a, const Epilogue& ep, const TIn* x, const TIn* w, float* y,
                     void* part, hipStream_t stream)
 {
     if constexpr (N % 2 == 0) {
-        if (a.aligned) return launch_a<N, NW, true>(a, ep, x, w, y, part, stream);
+        if (a.aligned) return launch_a<N, NW, true, TIn>(a, ep, x, w, y, part, stream);
     }
-    return launch_a<N, NW, false>(a, ep, x, w, y, part, stream);
+    return launch_a<N, NW, false, TIn>(a, ep, x, w, y, part, stream);
 }
 
-template <int NW>
-hipError_t launch_n(const F32Args& a, const Epilogue& ep, const float* x, const float* w, float* y,
+template <int NW, typename TIn>
+hipError_t launch_n(const F32Args& a, const Epilogue& ep, const TIn* x, const TIn* w, float* y,
                     void* part, hipStream_t st)
 {
     switch (a.g.n) {
-        case 2: return launch_t<2, NW>(a, ep, x, w, y, part, st);
-        case 3: return launch_t<3, NW>(a, ep, x, w, y, part, st);
-        case 4: return launch_t<4, NW>(a, ep, x, w, y, part, st);
-        case 5: return launch_t<5, NW>(a, ep, x, w, y, part, st);
+        case 2: return launch_t<2, NW, TIn>(a, ep, x, w, y, part, st);
+        case 3: return launch_t<3, NW, TIn>(a, ep, x, w, y, part, st);
+        case 4: return launch_t<4, NW, TIn>(a, ep, x, w, y, part, st);
+        case 5: return launch_t<5, NW, TIn>(a, ep, x, w, y, part, st);
         default: return hipErrorInvalidValue;
     }
 }
 
 // Quads per wave: as wide as possible while the grid still covers the chip about twice.
-int pick_nw(const Geom& g, F32Args& a)
+int pick_nw(const Geom& g, F32Args& a, int es)
 {
     const long long want = 512;
     F32Args t;
     int best = 0;
     for (int nw : {4, 2, 1}) {
-        bool ok = nw == 4 ? make_args<4>(g, t) : nw == 2 ? make_args<2>(g, t) : make_args<1>(g, t);
+        bool ok = nw == 4 ? make_args<4>(g, t, es) : nw == 2 ? make_args<2>(g, t, es) : make_args<1>(g, t, es);
         if (!ok) continue;
         best = nw;
         a = t;
@@ -538,17 +554,18 @@ int pick_nw(const Geom& g, F32Args& a)
 
 }  // namespace
 
-bool mfma_f32_supported(const Geom& g)
+// dtype 0: fp32 operands; 1: bf16 operands (fp32 output); a bf16 output is not produced here
+bool mfma_f32_supported(const Geom& g, int dtype)
 {
     F32Args a;
-    return pick_nw(g, a) != 0;
+    return (dtype == 0 || dtype == 1) && pick_nw(g, a, dtype == 0 ? 4 : 2) != 0;
 }
 
-hipError_t launch_mfma_f32(const Geom& g, const void* x, const void* w, float* y, Workspace& ws,
+hipError_t launch_mfma_f32(const Geom& g, const void* x, const void* w, float* y, int dtype, Workspace& ws,
                            hipStream_t stream)
 {
     F32Args a;
-    const int nw = pick_nw(g, a);
+    const int nw = pick_nw(g, a, dtype == 0 ? 4 : 2);
     const size_t ybytes = (size_t)g.B * g.Cout * g.OH * g.OW * 4;
     const size_t need = a.ksplit > 1 ? ybytes * (size_t)a.ksplit : 0;
     if (ws.query) {
@@ -562,12 +579,22 @@ hipError_t launch_mfma_f32(const Geom& g, const void* x, const void* w, float* y
         a.ksplit = 1;
     }
     if (a.ksplit > 1 && ws.bytes < need) return kWorkspaceTooSmall;
+    if (dtype == 1) {
+        const uint16_t* xh = (const uint16_t*)x;
+        const uint16_t* wh = (const uint16_t*)w;
+        switch (nw) {
+            case 4: return launch_n<4, uint16_t>(a, g.ep, xh, wh, y, ws.ptr, stream);
+            case 2: return launch_n<2, uint16_t>(a, g.ep, xh, wh, y, ws.ptr, stream);
+            case 1: return launch_n<1, uint16_t>(a, g.ep, xh, wh, y, ws.ptr, stream);
+            default: return hipErrorInvalidValue;
+        }
+    }
     const float* xf = (const float*)x;
     const float* wf = (const float*)w;
     switch (nw) {
-        case 4: return launch_n<4>(a, g.ep, xf, wf, y, ws.ptr, stream);
-        case 2: return launch_n<2>(a, g.ep, xf, wf, y, ws.ptr, stream);
-        case 1: return launch_n<1>(a, g.ep, xf, wf, y, ws.ptr, stream);
+        case 4: return launch_n<4, float>(a, g.ep, xf, wf, y, ws.ptr, stream);
+        case 2: return launch_n<2, float>(a, g.ep, xf, wf, y, ws.ptr, stream);
+        case 1: return launch_n<1, float>(a, g.ep, xf, wf, y, ws.ptr, stream);
         default: return hipErrorInvalidValue;
     }
 }

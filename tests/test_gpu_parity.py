@@ -214,6 +214,23 @@ def test_mfma_f32_small_shapes_every_element(shape):
         _parity(w, PATHS["mfma"], integer=False, workspace=None)
 
 
+@pytest.mark.parametrize("shape", MFMA_F32_SHAPES + [(4, 256, 128, 32, 32, 3, 1), (2, 64, 64, 40, 24, 5, 2)])
+def test_bf16_layers_with_other_kernel_sides_run_on_the_fp32_matrix_pipe(shape):
+    """bf16 layers whose kernel side the bf16 MFMA kernels do not take (n = 2, 3, 5: the dataset
+    kernels of Tables 2-3) are widened on their way into LDS and multiplied by the fp32 MFMA
+    kernel instead of falling to the vector ALUs."""
+    B, Cin, Cout, H, W, n, P = shape
+    w = _mk("mfma_f32_bf16in", 8300 + sum(shape), B, Cin, Cout, H, W, n, P, dtype="bf16")
+    name = ukst.ukst_kernel_name(B, Cin, Cout, H, W, n, P, ukst.UKST_BF16_F32, PATHS["mfma"])
+    if n != 4:
+        assert name == "ukst_mfma_f32_kernel"
+    assert name
+    _parity(w, PATHS["mfma"], integer=True)
+    _parity(w, PATHS["mfma"], integer=False)
+    if ukst.ukst_workspace_bytes(ukst.UKST_OP_FORWARD, B, Cin, Cout, H, W, n, P, ukst.UKST_BF16_F32):
+        _parity(w, PATHS["mfma"], integer=False, workspace=None)
+
+
 THIN_MFMA_SHAPES = [
     # B, Cin, Cout, H, W, n, P      (fp32, Cout <= 4, n in {3, 4}, Cin % 16 == 0, W % 4 == 0)
     (1, 16, 3, 4, 4, 4, 2),      # one partial tile
