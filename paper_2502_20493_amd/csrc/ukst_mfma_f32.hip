@@ -21,6 +21,16 @@
 // w[rr + 2(a-rr)][cc + 2(b-cc)] where it has one: the same n*n MFMAs per quad tile and channel
 // pair, on fewer quads, and a drain without edge cases.
 //
+// Tiny maps with many channels (the first generator layers: 4x4 and 8x8 maps, 512 and 256 input
+// channels) have far fewer 64 x 64 tiles than the chip has compute units.  They take NW = 0: block
+// tile 32 channels x 32 quads, all four waves on the SAME tile, each multiplying every fourth K
+// pair of a stage; at the end the waves park their accumulators in LDS and add them in wave order
+// (bit-reproducible) on their way to memory.  No partial sums leave the compute unit: no
+// workspace, no second kernel.  On such layers the weights are the traffic, and a wave is the only
+// reader of its K pairs' weights, so they skip LDS: a lane's A operands of one K pair -- all n*n
+// taps of its (channel, input channel) -- are n*n consecutive floats in memory, fetched with
+// 16-byte loads a stage ahead, straight into the registers the MFMAs read.
+//
 // Block = 4 waves; tile = 64 channels x (64*NW) quads x 4 classes; wave = 32 channels x 32*NW
 // quads (NW = 4, 2 or 1 so that small layers still fill the chip).  The epilogue stores the two
 // column classes of a quad as one 8-byte element, classes interleaved in place.
@@ -39,10 +49,16 @@ constexpr int TM = 64;      // output channels per block
 // input channels per K stage: small kernels get longer stages so that the fixed cost of a stage
 // (loads, LDS writes, barrier) is spread over enough MFMAs
 constexpr int kc_for(int n) { return n <= 3 ? 16 : 8; }
+// ... of the small-tile variant (NW = 0), whose waves each take a quarter of a stage's K pairs: long
+// stages, so that one stage of arithmetic covers the latency of the next one's loads
+constexpr int kc_small(int n) { return n <= 3 ? 64 : 32; }
 constexpr int PW = 65;      // floats per (k, tap) weight row in LDS: 64 channels + 1, so that the
                             // staging lanes (consecutive rows, one channel) hit consecutive banks
 // activation elements one thread stages per K stage, at most (register arrays of that size)
 constexpr int nxl_max_for(int n) { return n <= 3 ? 32 : 24; }
+// ... of the small-tile variant: every one of these slots is issued in every stage (a slot without an
+// element reads nothing and writes a zero to a spare word), one per multiplication step
+constexpr int NXS_SMALL = 8;
 constexpr int LDS_LIMIT = 160 * 1024;
 
 struct F32Args {
@@ -90,10 +106,16 @@ void ukst_mfma_f32_kernel(const TIn* __restrict__ x, const TIn* __restrict__ w,
     constexpr int ES = (int)sizeof(TIn);
     constexpr int HI = (N + 1) / 2;
     constexpr int NN = N * N;
-    constexpr int TN = 64 * NW;                 // quads per block
-    constexpr int WS_STAGE = NN * KC * PW * 4;  // bytes of one weight stage
-    constexpr int NXL_MAX = nxl_max_for(N);
-    constexpr int NWL = (TM * KC * NN / 4 + 255) / 256;  // 16-byte weight pieces per thread and stage
+    constexpr bool SK = NW == 0;                // the four waves split the K pairs of one small tile
+    constexpr int NWA = SK ? 1 : NW;            // groups of 32 quads per wave
+    constexpr int TMk = SK ? 32 : TM;           // output channels per block
+    constexpr int PWk = TMk + 1;                // floats per (k, tap) weight row in LDS
+    constexpr int TN = SK ? 32 : 64 * NW;       // quads per block
+    constexpr int WS_STAGE = SK ? 0 : NN * KC * PWk * 4; // bytes of one weight stage (NW = 0: none)
+    constexpr int NXL_MAX = SK ? NXS_SMALL : nxl_max_for(N);
+    constexpr int NWL = (TMk * KC * NN / 4 + 255) / 256;  // 16-byte weight pieces per thread and stage
+    static_assert(!SK || AL, "the split-K-in-block tile is built for the output-aligned quads");
+    static_assert(!SK || (sizeof(TIn) == 4 && NN % 4 == 0), "NW = 0: fp32 operands, 16-byte tap rows");
     extern __shared__ __align__(16) unsigned char lds[];
     float* const ldsf = reinterpret_cast<float*>(lds);
     // layout: weights stage 0 | weights stage 1 | activations stage 0 | activations stage 1
@@ -103,8 +125,9 @@ void ukst_mfma_f32_kernel(const TIn* __restrict__ x, const TIn* __restrict__ w,
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int cw = wave & 1;   // which 32-channel half of the block tile
-    const int qh = wave >> 1;  // which half of the block's quads
+    const int cw = SK ? 0 : wave & 1;   // which 32-channel half of the block tile
+    const int qh = SK ? 0 : wave >> 1;  // which half of the block's quads
+    const int kw = SK ? wave : 0;       // which K pairs of a stage (every fourth, starting here)
     const int l32 = lane & 31, gk = lane >> 5;
     const int KHW = a.KHq * a.KWq;
 
@@ -118,7 +141,7 @@ void ukst_mfma_f32_kernel(const TIn* __restrict__ x, const TIn* __restrict__ w,
     // channel block or the activations of a quad tile
     const int cb = a.cb_major ? bid / a.nqt : bid % a.nco;
     const int qt = a.cb_major ? bid % a.nqt : bid / a.nco;
-    const int co0 = cb * TM;
+    const int co0 = cb * TMk;
     const int q0 = qt * TN;
     const int q_last = (q0 + TN - 1 < a.Q ? q0 + TN - 1 : a.Q - 1);
     // quad row rho = b*KH + kk uses input rows e = b*EH + kk + u (u < HI)
@@ -137,7 +160,7 @@ void ukst_mfma_f32_kernel(const TIn* __restrict__ x, const TIn* __restrict__ w,
 #pragma unroll
     for (int j = 0; j < NXL_MAX; ++j) {
         x_goff[j] = kInvalid;
-        x_loff[j] = -1;
+        x_loff[j] = SK ? a.XP - 1 : -1;  // (the last word of a k plane is padding: never read)
         if (j < a.nxl) {
             const int e = tid + 256 * j;
             const int k = fdiv(e, a.dRW);
@@ -161,12 +184,12 @@ void ukst_mfma_f32_kernel(const TIn* __restrict__ x, const TIn* __restrict__ w,
 
     // ---- per-lane operand positions
     // A (weights): lane = channel cw*32 + l32, k parity gk
-    const int a_base = gk * NN * PW + cw * 32 + l32;  // + (2*ks*NN + tap) * PW
+    const int a_base = (gk + 2 * kw) * NN * PWk + cw * 32 + l32;  // + (2*ks*NN + tap) * PWk
     // B (activations): lane = quad q0 + (qh*NW + nt)*32 + l32, k parity gk
-    int b_base[NW];
+    int b_base[NWA];
 #pragma unroll
-    for (int nt = 0; nt < NW; ++nt) {
-        int q = q0 + (qh * NW + nt) * 32 + l32;
+    for (int nt = 0; nt < NWA; ++nt) {
+        int q = q0 + (qh * NWA + nt) * 32 + l32;
         if (q > q_last) q = q_last;
         const int b = fdiv(q, a.dKHW);
         const int rem = q - b * KHW;
@@ -174,12 +197,12 @@ void ukst_mfma_f32_kernel(const TIn* __restrict__ x, const TIn* __restrict__ w,
         const int r = b * a.EH + kk - e_first;
         // window column v of quad column mm is input column mm - floor(P/2) + v in either quad
         // system (shifted: m_min + mm - P + v), i.e. LDS column mm + v
-        b_base[nt] = XS_OFF / 4 + gk * a.XP + r * a.LWX + mm;
+        b_base[nt] = XS_OFF / 4 + (gk + 2 * kw) * a.XP + r * a.LWX + mm;
     }
 
-    f32x16 acc[NW][2][2];
+    f32x16 acc[NWA][2][2];
 #pragma unroll
-    for (int nt = 0; nt < NW; ++nt)
+    for (int nt = 0; nt < NWA; ++nt)
 #pragma unroll
         for (int r = 0; r < 2; ++r)
 #pragma unroll
@@ -195,10 +218,10 @@ void ukst_mfma_f32_kernel(const TIn* __restrict__ x, const TIn* __restrict__ w,
     // pieces
     auto stage_load = [&](int ci0) {
 #pragma unroll
-        for (int j = 0; j < NWL; ++j) {
+        for (int j = 0; j < (SK ? 0 : NWL); ++j) {
             const int e = (tid + 256 * j) * 4;
             const int co = e / (KC * NN), rem = e - co * (KC * NN);
-            const unsigned voff = (co < TM) ? (unsigned)(((co0 + co) * g.Cin * NN + rem) * ES) : kInvalid;
+            const unsigned voff = (co < TMk) ? (unsigned)(((co0 + co) * g.Cin * NN + rem) * ES) : kInvalid;
             if constexpr (B16) {
                 const u2v t = __builtin_amdgcn_raw_buffer_load_b64(rs_w, voff, (unsigned)(ci0 * NN * ES), 0);
                 wreg[j] = u4v{t.x << 16, t.x & 0xFFFF0000u, t.y << 16, t.y & 0xFFFF0000u};
@@ -222,13 +245,13 @@ void ukst_mfma_f32_kernel(const TIn* __restrict__ x, const TIn* __restrict__ w,
     auto stage_store = [&](int buf) {
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int j = 0; j < NWL; ++j) {
+        for (int j = 0; j < (SK ? 0 : NWL); ++j) {
             const int e = (tid + 256 * j) * 4;
             const int co = e / (KC * NN), rem = e - co * (KC * NN);  // rem = k*NN + tap, multiple of 4
-            if (co < TM) {
-                float* dst = ldsf + buf * (WS_STAGE / 4) + rem * PW + co;
+            if (co < TMk) {
+                float* dst = ldsf + buf * (WS_STAGE / 4) + rem * PWk + co;
 #pragma unroll
-                for (int t = 0; t < 4; ++t) dst[t * PW] = __uint_as_float(wreg[j][t]);
+                for (int t = 0; t < 4; ++t) dst[t * PWk] = __uint_as_float(wreg[j][t]);
             }
         }
 #pragma unroll
@@ -239,23 +262,25 @@ void ukst_mfma_f32_kernel(const TIn* __restrict__ x, const TIn* __restrict__ w,
     // One step = one window position (u, v) at one K pair.  The fragments of step t+1 are
     // requested before the MFMAs of step t are issued, so LDS latency hides under the matrix pipe.
     constexpr int NP1 = AL ? HI + 1 : HI;  // window positions per axis
-    constexpr int NP = NP1 * NP1, NSTEP = (KC / 2) * NP;
+    // K pairs of a stage this wave multiplies: all KC/2, or (NW = 0) every fourth one
+    constexpr int KSTEP = SK ? 4 : 1;
+    constexpr int NP = NP1 * NP1, NSTEP = (KC / 2 / KSTEP) * NP;
     auto compute = [&](int buf) {
         const float* ws = ldsf + buf * (WS_STAGE / 4) + a_base;
         const int xb = buf * (a.xs_stage_bytes / 4);
-        auto load_step = [&](int t, float (&bfr)[NW], float (&afr)[4]) {
-            const int ks = t / NP, p = t % NP, pa = p / NP1, pb = p % NP1;
+        auto load_step = [&](int t, float (&bfr)[NWA], float (&afr)[4]) {
+            const int ks = (t / NP) * KSTEP, p = t % NP, pa = p / NP1, pb = p % NP1;
             const int xo = xb + 2 * ks * a.XP + pa * a.LWX + pb;
 #pragma unroll
-            for (int nt = 0; nt < NW; ++nt) bfr[nt] = ldsf[b_base[nt] + xo];
+            for (int nt = 0; nt < NWA; ++nt) bfr[nt] = ldsf[b_base[nt] + xo];
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const int tap = tap_at<N, AL>(pa, pb, c);
                 if (tap < 0) continue;  // class has no tap here
-                afr[c] = ws[(2 * ks * NN + tap) * PW];
+                afr[c] = ws[(2 * ks * NN + tap) * PWk];
             }
         };
-        float bfr[2][NW], afr[2][4];
+        float bfr[2][NWA], afr[2][4];
         load_step(0, bfr[0], afr[0]);
 #pragma unroll
         for (int t = 0; t < NSTEP; ++t) {
@@ -266,7 +291,7 @@ void ukst_mfma_f32_kernel(const TIn* __restrict__ x, const TIn* __restrict__ w,
             for (int c = 0; c < 4; ++c) {
                 if (tap_at<N, AL>(pa, pb, c) < 0) continue;
 #pragma unroll
-                for (int nt = 0; nt < NW; ++nt)
+                for (int nt = 0; nt < NWA; ++nt)
                     acc[nt][c >> 1][c & 1] = __builtin_amdgcn_mfma_f32_32x32x2f32(
                         afr[t & 1][c], bfr[t & 1][nt], acc[nt][c >> 1][c & 1], 0, 0, 0);
             }
@@ -276,6 +301,88 @@ void ukst_mfma_f32_kernel(const TIn* __restrict__ x, const TIn* __restrict__ w,
 
     const int s0 = ks * a.kstages;              // this block's slice of the K stages
     const int stages = s0 + a.kstages;          // (ksplit * kstages covers Cin exactly)
+    if constexpr (SK) {
+        // One wave per SIMD: whatever is not an MFMA and does not sit between two MFMAs is time
+        // the matrix pipe idles.  So the whole stage pipeline is dealt out over the steps of the
+        // multiplication: step t < NXS hands activation element t of the NEXT stage (fetched a
+        // stage ago) to the other LDS buffer and requests its successor; the last step of a K pair
+        // requests that pair's weights of the stage after next into the registers just freed.
+        constexpr int PPS = KC / 8;   // K pairs per stage and wave
+        constexpr int NS = PPS * NP;  // steps per stage
+        static_assert(NS >= NXS_SMALL, "one activation element per step");
+        float areg[2][PPS][NN];
+        float xs[NXS_SMALL];
+        const unsigned a_voff = (co0 + l32 < g.Cout) ? (unsigned)((((co0 + l32) * g.Cin + gk) * NN) * 4) : kInvalid;
+        auto load_pair = [&](auto c_tag, int jj, int stage) {  // (jj: a constant once unrolled)
+            constexpr int C = decltype(c_tag)::value;
+            const unsigned soff = (unsigned)(((stage * KC + 2 * (kw + 4 * jj)) * NN) * 4);
+#pragma unroll
+            for (int q4 = 0; q4 < NN / 4; ++q4) {
+                const u4v t = __builtin_amdgcn_raw_buffer_load_b128(rs_w, a_voff + 16u * q4, soff, 0);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) areg[C][jj][4 * q4 + e] = __uint_as_float(t[e]);
+            }
+        };
+        auto load_x = [&](int j, int stage) {
+            xs[j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                                  rs_x, x_goff[j], (unsigned)(stage * KC) * x_cstride, 0));
+        };
+        auto store_x = [&](int j, int buf) {
+            ldsf[XS_OFF / 4 + buf * (a.xs_stage_bytes / 4) + x_loff[j]] = xs[j];
+        };
+        auto stage_sk = [&](int buf, auto c_tag, int sidx) {
+            constexpr int C = decltype(c_tag)::value;
+            const bool more1 = sidx + 1 < stages, more2 = sidx + 2 < stages;  // uniform
+            const int xb = buf * (a.xs_stage_bytes / 4);
+            auto b_at = [&](int t) {
+                const int jj = t / NP, p = t % NP;
+                return ldsf[b_base[0] + xb + 8 * jj * a.XP + (p / NP1) * a.LWX + (p % NP1)];
+            };
+            float bfr[3];
+            bfr[0] = b_at(0);
+            bfr[1] = b_at(1);
+#pragma unroll
+            for (int t = 0; t < NS; ++t) {
+                const int jj = t / NP, p = t % NP, pa = p / NP1, pb = p % NP1;
+                if (t + 2 < NS) bfr[(t + 2) % 3] = b_at(t + 2);
+                if (t < NXS_SMALL) {
+                    if (more1) store_x(t, buf ^ 1);
+                    if (more2) load_x(t, sidx + 2);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const int tap = tap_at<N, AL>(pa, pb, c);
+                    if (tap < 0) continue;
+                    acc[0][c >> 1][c & 1] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                        areg[C][jj][tap], bfr[t % 3], acc[0][c >> 1][c & 1], 0, 0, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                // this pair's registers are free: its weights of the stage after next
+                if (p == NP - 1 && more2) load_pair(c_tag, jj, sidx + 2);
+            }
+            __syncthreads();
+        };
+        const std::integral_constant<int, 0> i0;
+        const std::integral_constant<int, 1> i1;
+#pragma unroll
+        for (int jj = 0; jj < PPS; ++jj) load_pair(i0, jj, 0);
+#pragma unroll
+        for (int j = 0; j < NXS_SMALL; ++j) load_x(j, 0);
+        __syncthreads();  // zero fill done before the first activation writes
+#pragma unroll
+        for (int j = 0; j < NXS_SMALL; ++j) store_x(j, 0);
+#pragma unroll
+        for (int j = 0; j < NXS_SMALL; ++j) load_x(j, 1);  // (the stage count is even: stage 1 exists)
+#pragma unroll
+        for (int jj = 0; jj < PPS; ++jj) load_pair(i1, jj, 1);
+        __syncthreads();
+        for (int s = 0; s < stages; s += 2) {
+            stage_sk(0, i0, s);
+            stage_sk(1, i1, s + 1);
+        }
+    }
+    if constexpr (!SK) {
     stage_load(s0 * KC);
     __syncthreads();  // zero fill done before the first activation writes
     stage_store(0);
@@ -289,6 +396,7 @@ void ukst_mfma_f32_kernel(const TIn* __restrict__ x, const TIn* __restrict__ w,
         buf ^= 1;
     }
     compute(buf);
+    }
 
     // ---- epilogue: accumulator register i of a tile holds channel 8*(i/4) + 4*gk + (i%4) of the
     // wave's 32, for the lane's quad; column classes s = 1, 0 are neighbours in memory
@@ -307,11 +415,61 @@ void ukst_mfma_f32_kernel(const TIn* __restrict__ x, const TIn* __restrict__ w,
             bias_i[i] = (ep.bias && ch < g.Cout) ? ep.bias[ch] : 0.f;
         }
     }
+    if constexpr (SK) {
+        // The four waves hold partial sums of the same 32 x 32 x 4 tile.  Park them in LDS as
+        // [wave][row class][column class][register][lane]; wave w then finishes output row class
+        // w & 1 for registers 8*(w/2) .. +7, adding the four copies in wave order.
+        __syncthreads();  // every wave is done with the stage buffers
+#pragma unroll
+        for (int rr = 0; rr < 2; ++rr)
+#pragma unroll
+            for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    ldsf[(((wave * 2 + rr) * 2 + cc) * 16 + i) * 64 + lane] = acc[0][rr][cc][i];
+        __syncthreads();
+        const int rr = wave & 1, ih = wave >> 1;
+        const int q = q0 + l32;
+        const bool qv = q <= q_last;
+        const int qq = qv ? q : q_last;
+        const int b = fdiv(qq, a.dKHW);
+        const int rem = qq - b * KHW;
+        const int kk = fdiv(rem, a.dKW), mm = rem - kk * a.KWq;
+        const unsigned off = qv ? (unsigned)((((b * g.Cout + co0 + 4 * gk) * g.OH + 2 * kk + rr) * g.OW + 2 * mm) * 4)
+                                : kInvalid;
+        auto finish = [&](auto act_tag) {
+            constexpr int ACT = decltype(act_tag)::value;
+#pragma unroll
+            for (int ii = 0; ii < 8; ++ii) {
+                const int i = 8 * ih + ii;
+                if (co0 + 8 * (i / 4) >= g.Cout) continue;  // uniform: ragged last channel block
+                float v0 = 0.f, v1 = 0.f;
+#pragma unroll
+                for (int wv = 0; wv < 4; ++wv) {
+                    v0 += ldsf[(((wv * 2 + rr) * 2 + 0) * 16 + i) * 64 + lane];
+                    v1 += ldsf[(((wv * 2 + rr) * 2 + 1) * 16 + i) * 64 + lane];
+                }
+                if constexpr (ACT >= 0) {
+                    const int ch = co0 + 8 * (i / 4) + 4 * gk + (i % 4);
+                    const float bv = (ep.bias && ch < g.Cout) ? ep.bias[ch] : 0.f;
+                    v0 = epilogue_t<ACT>(v0, bv);
+                    v1 = epilogue_t<ACT>(v1, bv);
+                }
+                u2v d;
+                d.x = __float_as_uint(v0);
+                d.y = __float_as_uint(v1);
+                __builtin_amdgcn_raw_buffer_store_b64(d, rs_y, off, (unsigned)(8 * (i / 4) + (i % 4)) * plane, 0);
+            }
+        };
+        if constexpr (EPI) with_activation(ep.act, finish);
+        else finish(std::integral_constant<int, -1>{});
+        return;
+    }
     auto drain = [&](auto act_tag) {
         constexpr int ACT = decltype(act_tag)::value;  // -1: no epilogue at all
 #pragma unroll
-        for (int nt = 0; nt < NW; ++nt) {
-            const int q = q0 + (qh * NW + nt) * 32 + l32;
+        for (int nt = 0; nt < NWA; ++nt) {
+            const int q = q0 + (qh * NWA + nt) * 32 + l32;
             const bool qv = q <= q_last;
             const int qq = qv ? q : q_last;
             const int b = fdiv(qq, a.dKHW);
@@ -412,8 +570,9 @@ __global__ __launch_bounds__(256) void ukst_sum_slices_kernel(const float4* __re
 template <int NW>
 bool make_args(const Geom& g, F32Args& a, int es = 4)
 {
-    constexpr int TN = 64 * NW;
-    const int KC = kc_for(g.n);
+    constexpr int TN = NW == 0 ? 32 : 64 * NW;
+    constexpr int TMk = NW == 0 ? 32 : TM, PWk = TMk + 1;
+    const int KC = NW == 0 ? kc_small(g.n) : kc_for(g.n);
     if (g.n < 2 || g.n > 5) return false;
     if (g.Cin % KC != 0) return false;  // a stage never straddles the channel count
     if (g.Cout % 8 != 0) return false;  // channel groups of the accumulator layout stay whole
@@ -426,6 +585,9 @@ bool make_args(const Geom& g, F32Args& a, int es = 4)
     a.g = g;
     // even kernel side and even padding: quads aligned to the (even-sized) output
     a.aligned = (g.n % 2 == 0 && g.P % 2 == 0) ? 1 : 0;
+    // the small-tile variant: aligned quads, fp32 operands, an even number of stages (its A operands
+    // come from memory a stage at a time into one of two register sets)
+    if (NW == 0 && (!a.aligned || es != 4 || (g.Cin / KC) % 2 != 0)) return false;
     a.KHq = a.aligned ? g.OH / 2 : g.KH;
     a.KWq = a.aligned ? g.OW / 2 : g.KW;
     const int wrows = a.aligned ? HI + 1 : HI;  // window rows / columns of a quad
@@ -449,10 +611,10 @@ bool make_args(const Geom& g, F32Args& a, int es = 4)
     a.xs_stage_bytes = KC * xp * 4;
     const long long elems = (long long)KC * a.ROWS * g.W;
     a.nxl = (int)((elems + 255) / 256);
-    if (a.nxl > nxl_max_for(g.n)) return false;
-    const int ws_stage = g.n * g.n * KC * PW * 4;
+    if (a.nxl > (NW == 0 ? NXS_SMALL : nxl_max_for(g.n))) return false;
+    const int ws_stage = NW == 0 ? 0 : g.n * g.n * KC * PWk * 4;
     if (2 * (ws_stage + a.xs_stage_bytes) > LDS_LIMIT) return false;
-    a.nco = (g.Cout + TM - 1) / TM;
+    a.nco = (g.Cout + TMk - 1) / TMk;
     a.nqt = (int)((Q + TN - 1) / TN);
     if ((long long)a.nco * a.nqt > 0x3FFFFFFFLL) return false;
     a.cb_major = wbytes > xbytes ? 1 : 0;
@@ -468,7 +630,7 @@ bool make_args(const Geom& g, F32Args& a, int es = 4)
     a.ksplit = 1;
     const int stages = g.Cin / KC;
     const long long tiles = (long long)a.nco * a.nqt;
-    if (ybytes % 16 == 0 && tiles < 256) {
+    if (NW != 0 && ybytes % 16 == 0 && tiles < 256) {
         auto distance = [&](int ks) {
             const double r = (double)(tiles * ks) / 512.0;
             return r >= 1.0 ? r : 1.0 / r;
@@ -486,8 +648,10 @@ template <int N, int NW, bool AL, typename TIn>
 hipError_t launch_a(const F32Args& a, const Epilogue& ep, const TIn* x, const TIn* w, float* y,
                     void* part, hipStream_t stream)
 {
-    constexpr int KC = kc_for(N);
-    const size_t lds = 2 * (size_t)(N * N * KC * PW * 4 + a.xs_stage_bytes);
+    constexpr int KC = NW == 0 ? kc_small(N) : kc_for(N);
+    constexpr int PWk = (NW == 0 ? 32 : TM) + 1;
+    size_t lds = 2 * (size_t)((NW == 0 ? 0 : N * N * KC * PWk * 4) + a.xs_stage_bytes);
+    if (NW == 0 && lds < 65536) lds = 65536;  // the four waves' accumulators meet in LDS at the end
     // more than 64 KiB of dynamic LDS has to be allowed per device (a property of the loaded
     // kernel, not library state); cheap enough to repeat on every call
     // the epilogue belongs to whole sums: with a split K loop the slice sum applies it
@@ -520,7 +684,8 @@ hipError_t launch_t(const F32Args& a, const Epilogue& ep, const TIn* x, const TI
     if constexpr (N % 2 == 0) {
         if (a.aligned) return launch_a<N, NW, true, TIn>(a, ep, x, w, y, part, stream);
     }
-    return launch_a<N, NW, false, TIn>(a, ep, x, w, y, part, stream);
+    if constexpr (NW == 0) return hipErrorInvalidValue;  // only the aligned quads have that tile
+    else return launch_a<N, NW, false, TIn>(a, ep, x, w, y, part, stream);
 }
 
 template <int NW, typename TIn>
@@ -549,6 +714,12 @@ int pick_nw(const Geom& g, F32Args& a, int es)
         a = t;
         if ((long long)t.nco * t.nqt >= want) break;
     }
+    // layers that cannot give every compute unit a 64 x 64 tile: 32 x 32 tiles whose K loop the
+    // four waves of a block share (no workspace, no slice sum)
+    if (best != 0 && (long long)a.nco * a.nqt < 256 && make_args<0>(g, t, es)) {
+        a = t;
+        return -1;
+    }
     return best;
 }
 
@@ -558,7 +729,7 @@ int pick_nw(const Geom& g, F32Args& a, int es)
 bool mfma_f32_supported(const Geom& g, int dtype)
 {
     F32Args a;
-    return (dtype == 0 || dtype == 1) && pick_nw(g, a, dtype == 0 ? 4 : 2) != 0;
+    return (dtype == 0 || dtype == 1) && pick_nw(g, a, dtype == 0 ? 4 : 2) != 0;  // (-1: the split-K-in-block tile)
 }
 
 hipError_t launch_mfma_f32(const Geom& g, const void* x, const void* w, float* y, int dtype, Workspace& ws,
@@ -595,6 +766,7 @@ hipError_t launch_mfma_f32(const Geom& g, const void* x, const void* w, float* y
         case 4: return launch_n<4, float>(a, g.ep, xf, wf, y, ws.ptr, stream);
         case 2: return launch_n<2, float>(a, g.ep, xf, wf, y, ws.ptr, stream);
         case 1: return launch_n<1, float>(a, g.ep, xf, wf, y, ws.ptr, stream);
+        case -1: return launch_n<0, float>(a, g.ep, xf, wf, y, ws.ptr, stream);
         default: return hipErrorInvalidValue;
     }
 }

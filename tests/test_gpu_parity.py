@@ -78,13 +78,14 @@ def _sample_planes(w, k=16):
 
 @pytest.mark.parametrize("name", ["cfg3_L1", "cfg3_L2", "cfg3_L3", "cfg3_L4"])
 def test_cfg3_dcgan_layers_full_size(name):
-    # through the entry point that takes no workspace (K loop in one block per tile) and through
-    # ukst_conv_transpose2d_ws (L1, L2: K loop split over blocks, partial sums in the workspace)
+    # through the entry point that takes no workspace and through ukst_conv_transpose2d_ws (the
+    # tiny layers L1, L2 share the K loop of a 32 x 32 tile among the waves of a block: no
+    # workspace either way)
     w = wl.WORKLOADS[name]
     planes = _sample_planes(w, 64)
     dt = ukst.UKST_F32
     need = ukst.ukst_workspace_bytes(ukst.UKST_OP_FORWARD, w.B, w.Cin, w.Cout, w.H, w.W, w.n, w.P, dt)
-    assert (need > 0) == (name in ("cfg3_L1", "cfg3_L2"))
+    assert need == 0
     for workspace in (False, None):
         _parity(w, PATHS["auto"], planes=planes, workspace=workspace)
         _parity(w, PATHS["auto"], planes=planes, integer=True, workspace=workspace)
@@ -197,8 +198,13 @@ MFMA_F32_SHAPES = [
     (1, 16, 128, 33, 31, 3, 0),   # several row tiles of one image, two channel blocks
     (1, 8, 64, 1, 9, 4, 2),       # single input row
     (2, 32, 64, 63, 63, 3, 0),    # cfg4b spatial shape: wide tiles (NW = 4)
-    (2, 64, 16, 5, 6, 4, 2),      # few tiles, 8 K stages: the K loop is split over 4 blocks
+    (2, 64, 16, 5, 6, 4, 2),      # few tiles, even n and P: 32 x 32 tiles, K pairs dealt to the four waves
+    (2, 64, 16, 5, 6, 4, 1),      # few tiles, odd P: the K loop is split over 4 blocks (workspace)
     (1, 96, 8, 3, 5, 3, 1),       # 6 stages of 16: split in 2
+    (3, 128, 40, 4, 4, 4, 2),     # 4x4 maps, ragged channel block and ragged last quad tile, 4 stages
+    (3, 48, 40, 4, 4, 4, 2),      # same maps, a channel count the small tiles do not take
+    (2, 128, 32, 3, 7, 2, 0),     # n = 2 on small tiles (64 input channels per stage: 8 K pairs per wave)
+    (5, 64, 72, 2, 3, 4, 4),      # P > n - 1 on tiny maps
 ]
 
 
@@ -386,7 +392,7 @@ def test_non_default_stream(case):
     import torch
     from gpu_util import to_device
     w = {"narrow": wl.WORKLOADS["cfg1"],
-         "mfma_f32_split_k": _mk("stream_f32", 8201, 2, 64, 16, 5, 6, 4, 2),
+         "mfma_f32_split_k": _mk("stream_f32", 8201, 2, 64, 16, 5, 6, 4, 1),
          "mfma_bf16": _mk("stream_bf16", 8202, 2, 32, 64, 6, 16, 4, 2, dtype="bf16")}[case]
     data = wl.generate(w)
     x, wt = to_device(data, w.dtype)
@@ -484,7 +490,8 @@ EPILOGUE_CASES = [
     ("general_bf16", (2, 8, 8, 9, 11, 4, 2), "bf16", "auto", "ukst_direct_kernel"),
     ("thin_mfma", (2, 32, 3, 9, 12, 4, 2), "f32", "auto", "ukst_thin_mfma_kernel"),
     ("mfma_f32", (2, 16, 40, 23, 31, 3, 0), "f32", "mfma", "ukst_mfma_f32_kernel"),
-    ("mfma_f32_split_k", (2, 64, 16, 5, 6, 4, 2), "f32", "mfma", "ukst_mfma_f32_kernel"),
+    ("mfma_f32_split_k", (2, 64, 16, 5, 6, 4, 1), "f32", "mfma", "ukst_mfma_f32_kernel"),
+    ("mfma_f32_small_tiles", (2, 64, 24, 5, 6, 4, 2), "f32", "mfma", "ukst_mfma_f32_kernel"),
     ("mfma_bf16", (2, 32, 128, 9, 16, 4, 1), "bf16", "auto", "ukst_mfma_bf16_kernel"),
     ("mfma_bf16_aligned", (2, 32, 128, 9, 16, 4, 2), "bf16", "auto", "ukst_mfma_bf16_aligned_kernel"),
 ]
