@@ -156,11 +156,11 @@ void ukst_mfma_f32_kernel(const TIn* __restrict__ x, const TIn* __restrict__ w,
 
     // ---- activation staging: element e = tid + 256*j -> (k, row, col) of the stage
     unsigned x_goff[NXL_MAX];  // global byte offset (for ci0 = 0), kInvalid for rows that do not exist
-    int x_loff[NXL_MAX];       // LDS float index inside an activation stage, -1 = nothing to do
+    int x_loff[NXL_MAX];       // LDS float index inside an activation stage (padding where there is no element)
 #pragma unroll
     for (int j = 0; j < NXL_MAX; ++j) {
         x_goff[j] = kInvalid;
-        x_loff[j] = SK ? a.XP - 1 : -1;  // (the last word of a k plane is padding: never read)
+        x_loff[j] = a.XP - 1;  // (the last word of a k plane is padding: never read)
         if (j < a.nxl) {
             const int e = tid + 256 * j;
             const int k = fdiv(e, a.dRW);
@@ -212,60 +212,64 @@ void ukst_mfma_f32_kernel(const TIn* __restrict__ x, const TIn* __restrict__ w,
 
     u4v wreg[NWL];
     float xreg[NXL_MAX];
-    // weight piece e = tid + 256*j: four consecutive floats of channel co = 4e / (KC*NN); the
-    // (k, tap) pairs of a channel are contiguous in memory and a stage's chunk of a channel starts
-    // on a 16-byte boundary (Cin and ci0 are multiples of 8), so lanes read consecutive 16-byte
-    // pieces
-    auto stage_load = [&](int ci0) {
-#pragma unroll
-        for (int j = 0; j < (SK ? 0 : NWL); ++j) {
-            const int e = (tid + 256 * j) * 4;
+    // The staging work of a stage is cut into items: item i < NWL is weight piece e = tid + 256*i
+    // (four consecutive floats of channel co = 4e / (KC*NN); the (k, tap) pairs of a channel are
+    // contiguous in memory and a stage's chunk of a channel starts on a 16-byte boundary, so lanes
+    // read consecutive 16-byte pieces), item NWL + j is activation element j.  Slots without an
+    // element read nothing (zeros) and write to padding: no lane-divergent branches.
+    constexpr int NITEMS = NWL + NXL_MAX;
+    auto load_item = [&](int i, int ci0) {  // (i: a constant once unrolled)
+        if (i < NWL) {
+            const int e = (tid + 256 * i) * 4;
             const int co = e / (KC * NN), rem = e - co * (KC * NN);
             const unsigned voff = (co < TMk) ? (unsigned)(((co0 + co) * g.Cin * NN + rem) * ES) : kInvalid;
-            if constexpr (B16) {
+            if constexpr (B16) {  // (kept as loaded: widening here would wait for the load on the spot)
                 const u2v t = __builtin_amdgcn_raw_buffer_load_b64(rs_w, voff, (unsigned)(ci0 * NN * ES), 0);
-                wreg[j] = u4v{t.x << 16, t.x & 0xFFFF0000u, t.y << 16, t.y & 0xFFFF0000u};
+                wreg[i] = u4v{t.x, t.y, 0u, 0u};
             } else {
-                wreg[j] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, voff, (unsigned)(ci0 * NN * ES), 0);
+                wreg[i] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, voff, (unsigned)(ci0 * NN * ES), 0);
             }
+        } else if (i - NWL < a.nxl) {
+            const int j = i - NWL;
+            if constexpr (B16)
+                xreg[j] = __uint_as_float((unsigned)(unsigned short)__builtin_amdgcn_raw_buffer_load_b16(
+                    rs_x, x_goff[j], (unsigned)ci0 * x_cstride, 0));
+            else
+                xreg[j] = __builtin_bit_cast(
+                    float, __builtin_amdgcn_raw_buffer_load_b32(rs_x, x_goff[j], (unsigned)ci0 * x_cstride, 0));
         }
-#pragma unroll
-        for (int j = 0; j < NXL_MAX; ++j)
-            if (j < a.nxl) {
-                if constexpr (B16)
-                    xreg[j] = __uint_as_float((unsigned)(unsigned short)__builtin_amdgcn_raw_buffer_load_b16(
-                                                  rs_x, x_goff[j], (unsigned)ci0 * x_cstride, 0) << 16);
-                else
-                    xreg[j] = __builtin_bit_cast(
-                        float, __builtin_amdgcn_raw_buffer_load_b32(rs_x, x_goff[j],
-                                                                    (unsigned)ci0 * x_cstride, 0));
-            }
-        __builtin_amdgcn_sched_barrier(0);  // requested before the stage is multiplied
     };
-    auto stage_store = [&](int buf) {
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int j = 0; j < (SK ? 0 : NWL); ++j) {
-            const int e = (tid + 256 * j) * 4;
+    auto store_item = [&](int i, int buf) {
+        if (i < NWL) {
+            const int e = (tid + 256 * i) * 4;
             const int co = e / (KC * NN), rem = e - co * (KC * NN);  // rem = k*NN + tap, multiple of 4
-            if (co < TMk) {
-                float* dst = ldsf + buf * (WS_STAGE / 4) + rem * PWk + co;
+            // (a piece past the last channel lands in the padding column of its rows)
+            float* dst = ldsf + buf * (WS_STAGE / 4) + rem * PWk + (co < TMk ? co : TMk);
+            u4v v = wreg[i];
+            if constexpr (B16) v = u4v{v.x << 16, v.x & 0xFFFF0000u, v.y << 16, v.y & 0xFFFF0000u};
 #pragma unroll
-                for (int t = 0; t < 4; ++t) dst[t * PWk] = __uint_as_float(wreg[j][t]);
-            }
+            for (int t = 0; t < 4; ++t) dst[t * PWk] = __uint_as_float(v[t]);
+        } else if (i - NWL < a.nxl) {
+            const int j = i - NWL;
+            float v = xreg[j];
+            if constexpr (B16) v = __uint_as_float(__float_as_uint(v) << 16);
+            ldsf[XS_OFF / 4 + buf * (a.xs_stage_bytes / 4) + x_loff[j]] = v;
         }
-#pragma unroll
-        for (int j = 0; j < NXL_MAX; ++j)
-            if (j < a.nxl && x_loff[j] >= 0)
-                ldsf[XS_OFF / 4 + buf * (a.xs_stage_bytes / 4) + x_loff[j]] = xreg[j];
     };
     // One step = one window position (u, v) at one K pair.  The fragments of step t+1 are
     // requested before the MFMAs of step t are issued, so LDS latency hides under the matrix pipe.
+    // A wave is alone on its SIMD: whatever is not an MFMA and does not sit between two MFMAs is
+    // time the matrix pipe idles.  So the staging items are dealt out over the steps: an item's
+    // registers (fetched a stage ago, for the NEXT stage) go to the other LDS buffer and are
+    // refilled at once for the stage after next.
     constexpr int NP1 = AL ? HI + 1 : HI;  // window positions per axis
     // K pairs of a stage this wave multiplies: all KC/2, or (NW = 0) every fourth one
     constexpr int KSTEP = SK ? 4 : 1;
     constexpr int NP = NP1 * NP1, NSTEP = (KC / 2 / KSTEP) * NP;
-    auto compute = [&](int buf) {
+    constexpr int IPS = (NITEMS + NSTEP - 1) / NSTEP;  // items per step
+    auto compute = [&](int buf, int sidx, int last) {
+        // (the last two stages fetch the last stage again rather than branch: in bounds, unused)
+        const int ci_next = (sidx + 2 < last ? sidx + 2 : last - 1) * KC;
         const float* ws = ldsf + buf * (WS_STAGE / 4) + a_base;
         const int xb = buf * (a.xs_stage_bytes / 4);
         auto load_step = [&](int t, float (&bfr)[NWA], float (&afr)[4]) {
@@ -286,6 +290,14 @@ void ukst_mfma_f32_kernel(const TIn* __restrict__ x, const TIn* __restrict__ w,
         for (int t = 0; t < NSTEP; ++t) {
             const int p = t % NP, pa = p / NP1, pb = p % NP1;
             if (t + 1 < NSTEP) load_step(t + 1, bfr[(t + 1) & 1], afr[(t + 1) & 1]);
+#pragma unroll
+            for (int r = 0; r < IPS; ++r) {
+                const int i = t * IPS + r;
+                if (i < NITEMS) {
+                    store_item(i, buf ^ 1);
+                    load_item(i, ci_next);
+                }
+            }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -383,19 +395,20 @@ void ukst_mfma_f32_kernel(const TIn* __restrict__ x, const TIn* __restrict__ w,
         }
     }
     if constexpr (!SK) {
-    stage_load(s0 * KC);
-    __syncthreads();  // zero fill done before the first activation writes
-    stage_store(0);
-    __syncthreads();
-    int buf = 0;
-    for (int s = s0 + 1; s < stages; ++s) {
-        stage_load(s * KC);  // in flight while this stage is multiplied
-        compute(buf);
-        stage_store(buf ^ 1);
+#pragma unroll
+        for (int i = 0; i < NITEMS; ++i) load_item(i, s0 * KC);
+        __syncthreads();  // zero fill done before the first activation writes
+#pragma unroll
+        for (int i = 0; i < NITEMS; ++i) store_item(i, 0);
+#pragma unroll
+        for (int i = 0; i < NITEMS; ++i) load_item(i, (s0 + 1 < stages ? s0 + 1 : s0) * KC);
         __syncthreads();
-        buf ^= 1;
-    }
-    compute(buf);
+        int buf = 0;
+        for (int s = s0; s < stages; ++s) {
+            compute(buf, s, stages);
+            __syncthreads();
+            buf ^= 1;
+        }
     }
 
     // ---- epilogue: accumulator register i of a tile holds channel 8*(i/4) + 4*gk + (i%4) of the
