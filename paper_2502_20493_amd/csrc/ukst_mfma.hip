@@ -108,8 +108,12 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
     auto tile_of = [&](int rho, int& cb, int& qt) -> bool {
         const int t = rho * G + xcd_rank;
         if (t >= a.ntiles) return false;
-        if (a.cb_major) { cb = fdiv(t, a.dNQT); qt = t - cb * a.nqt; }
-        else            { qt = fdiv(t, a.dNCO); cb = t - qt * a.nco; }
+        // (both orders through the same assignments: a store to "cb or qt" picked by the flag
+        // would put the two in scratch memory, and every later read behind all loads in flight)
+        const int major = a.cb_major ? fdiv(t, a.dNQT) : fdiv(t, a.dNCO);
+        const int minor = t - major * (a.cb_major ? a.nqt : a.nco);
+        cb = a.cb_major ? major : minor;
+        qt = a.cb_major ? minor : major;
         return true;
     };
 
@@ -447,17 +451,13 @@ bool make_args(const Geom& g, int dtype, MfmaArgs& a)
 
 }  // namespace
 
-// The output-aligned kernel reads 9 instead of 4 activation fragments per K step and channel
-// tile, which costs about what it saves on large maps (measured: 128x128 maps 594 vs 586 us); it
-// wins where the shifted quads' extra row and column of half-empty quads are a visible share of
-// the matrix work (16x16 maps: 289 vs 256 quads per image, 279 -> 240 us).
+// The output-aligned kernel runs every layer it takes (even P): no edge quads, 16-byte drain
+// stores.  Measured against the shifted quads of this file: 128x128 maps 557 vs 584 us, 16x16 maps
+// (289 vs 256 quads per image) 227 vs 279 us.  The shifted quads keep odd P, where they ARE the
+// aligned ones.
 static bool prefer_aligned(const Geom& g, int dtype)
 {
-    if (!mfma_aligned_supported(g, dtype)) return false;
-    MfmaArgs a;
-    if (!make_args(g, dtype, a)) return true;
-    const long long shifted = (long long)g.KH * g.KW, aligned = (long long)(g.OH / 2) * (g.OW / 2);
-    return aligned * 21 <= shifted * 20;
+    return mfma_aligned_supported(g, dtype);
 }
 
 // true if a bf16 layer runs on the bf16 matrix pipe (else, if at all, on the fp32 pipe with

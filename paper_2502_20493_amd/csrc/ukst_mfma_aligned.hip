@@ -111,8 +111,12 @@ void ukst_mfma_bf16_aligned_kernel(const uint16_t* __restrict__ x, const uint16_
     auto tile_of = [&](int rho, int& cb, int& qt) -> bool {
         const int t = rho * G + xcd_rank;
         if (t >= a.ntiles) return false;
-        if (a.cb_major) { cb = fdiv(t, a.dNQT); qt = t - cb * a.nqt; }
-        else            { qt = fdiv(t, a.dNCO); cb = t - qt * a.nco; }
+        // (both orders through the same assignments: a store to "cb or qt" picked by the flag
+        // would put the two in scratch memory, and every later read behind all loads in flight)
+        const int major = a.cb_major ? fdiv(t, a.dNQT) : fdiv(t, a.dNCO);
+        const int minor = t - major * (a.cb_major ? a.nqt : a.nco);
+        cb = a.cb_major ? major : minor;
+        qt = a.cb_major ? minor : major;
         return true;
     };
 

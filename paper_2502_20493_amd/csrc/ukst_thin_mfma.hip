@@ -48,24 +48,6 @@ constexpr int NU = 4;                    // 16-byte activation pieces per thread
 constexpr int DEPTH = 2;                 // stages in flight ahead of the multiplication (register ring)
 constexpr int LDS_LIMIT = 64 * 1024;
 
-// Exact division of 0 <= n < 2^31 by a run-time constant: q = umulhi(n, M) >> sh.
-struct FastDiv { unsigned M; int sh; unsigned d; };
-inline FastDiv make_fastdiv(unsigned d)
-{
-    FastDiv f;
-    f.d = d; f.M = 0; f.sh = 0;
-    if (d <= 1) return f;
-    int l = 0;
-    while ((1ull << l) < d) ++l;
-    f.M = (unsigned)(((1ull << (31 + l)) / d) + 1);
-    f.sh = l - 1;
-    return f;
-}
-__device__ __forceinline__ int fdiv(int n, const FastDiv& f)
-{
-    return f.d == 1 ? n : (int)(__umulhi((unsigned)n, f.M) >> f.sh);
-}
-
 struct ThinMfmaArgs {
     GeomBase g;
     int Q;      // total quads = B * KH * KW

@@ -163,7 +163,13 @@ MFMA_BF16_SHAPES = [
     (5, 16, 64, 2, 8, 2),      # many tiny images inside one tile
     (1, 16, 64, 33, 64, 2),    # several row tiles of one image
     (1, 16, 64, 1, 8, 2),      # single input row
-    # even P on maps the output-aligned kernel takes (the small ones above stay with the shifted quads)
+    # odd P stays with the shifted quads (even P goes to the output-aligned kernel)
+    (2, 48, 128, 9, 16, 1),    # two channel blocks, several K stages
+    (3, 32, 64, 5, 8, 1),      # tiles span images, ragged last tile
+    (5, 16, 64, 2, 8, 3),      # many tiny images inside one tile
+    (1, 16, 64, 33, 64, 1),    # several row tiles of one image
+    (1, 16, 64, 20, 128, 5),   # cfg5a's row length, P > n - 1
+    # more even P
     (2, 48, 128, 9, 16, 2),    # tiles span images
     (3, 16, 64, 7, 24, 0),     # P = 0: no halo, window rows up to H - 1
     (1, 32, 64, 6, 16, 6),     # P > n - 1: border quads meet no input
@@ -347,8 +353,8 @@ def test_repeat_runs_are_bit_identical():
                                          ("cfg3_L1", "ukst_mfma_f32_kernel"),
                                          ("cfg3_L4", "ukst_thin_mfma_kernel"),
                                          ("cfg4a", "ukst_mfma_f32_kernel"),
-                                         ("cfg5a", "ukst_mfma_bf16_kernel"),
-                                         ("cfg5a_32x32", "ukst_mfma_bf16_aligned_kernel"),
+                                         ("cfg5a", "ukst_mfma_bf16_aligned_kernel"),
+                                         ("cfg5a_P1", "ukst_mfma_bf16_kernel"),
                                          ("cfg5b", "ukst_mfma_bf16_aligned_kernel"),
                                          ("cfg5b_P1", "ukst_mfma_bf16_kernel")])
 def test_repeat_runs_are_bit_identical_at_full_size(name, kernel):
@@ -358,7 +364,7 @@ def test_repeat_runs_are_bit_identical_at_full_size(name, kernel):
     import torch
     from gpu_util import to_device
     w = (wl.WORKLOADS["cfg5b"].with_(P=1) if name == "cfg5b_P1" else
-         wl.WORKLOADS["cfg5a"].with_(B=16, H=32, W=32) if name == "cfg5a_32x32" else wl.WORKLOADS[name])
+         wl.WORKLOADS["cfg5a"].with_(P=1) if name == "cfg5a_P1" else wl.WORKLOADS[name])
     dt = ukst.UKST_F32 if w.dtype == "f32" else ukst.UKST_BF16_F32
     assert ukst.ukst_kernel_name(w.B, w.Cin, w.Cout, w.H, w.W, w.n, w.P, dt) == kernel
     x, wt = to_device(wl.generate(w), w.dtype)
