@@ -1339,6 +1339,278 @@ hipError_t launch_gw_mfma(const GwMfmaArgs& a, const void* x, const void* dy, fl
     return e;
 }
 
+// ------------------------------------------------------------------------------------------
+// Gradient with respect to the kernel on the bf16 matrix pipe (bf16 layers, 2 <= n <= 4, rows of
+// 8-element pieces: W % 8 == 0).
+//
+// The same product as above, DW_tap[co][ci] += sum_pixel DY_tap[co][pixel] * X[ci][pixel], with the
+// pixel axis as the K axis of v_mfma_f32_32x32x16_bf16: a lane's operand is 8 consecutive pixels of
+// one channel, which is how NCHW rows lie in memory, so x goes to LDS as it is (16-byte pieces) and
+// dy rows are split by column parity on the way (one v_perm pair per piece), which makes the 8
+// pixels of any tap consecutive too.  A tap's lattice starts 0 or 1 elements into its half row:
+// half of the dy fragments are 16-byte LDS reads at a 2-byte-aligned address (the hardware's
+// unaligned DS access; no second, shifted copy of the tile is kept).  Tiles, slices, the dealing
+// of taps to waves and the partial-sum layout are those of the fp32 kernel above.
+struct GwB16Args {
+    GeomBase g;
+    int TJ, logTJ, TI, logTI, TB, TR, logPix;  // logPix = log2(TR * TJ)
+    int LR, HC, cols, DP, XP;                  // in bf16 elements
+    int tilesX, tilesY, nStages, stagesPerSlice, nSlices;
+    int coTiles, ciTiles;
+    int c8;                                    // 8-column pieces per staged dy row
+    FastDiv dC8, dRows, dLR;
+};
+
+typedef __bf16 gw_bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 gw_bf16x8u __attribute__((ext_vector_type(8), aligned(2)));
+typedef unsigned gw_u4 __attribute__((ext_vector_type(4)));
+typedef unsigned gw_u4u __attribute__((ext_vector_type(4), aligned(2)));
+typedef unsigned gw_u2 __attribute__((ext_vector_type(2)));
+
+template <int N, int NC>
+__global__ __launch_bounds__(256, 2) void ukst_grad_weight_mfma_bf16_kernel(const uint16_t* __restrict__ x,
+                                                                           const uint16_t* __restrict__ dy,
+                                                                           float* __restrict__ part, GwB16Args a)
+{
+    constexpr int NN = N * N, TS = (NN + 3) / 4, CI_T = 32 * NC;
+    extern __shared__ __align__(16) unsigned char lds_b[];
+    const GeomBase& g = a.g;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, kk = lane >> 5;
+    uint16_t* xs = reinterpret_cast<uint16_t*>(lds_b);  // [CI_T][XP]
+    uint16_t* dys = xs + CI_T * a.XP;                   // [32][DP]
+
+    int bid = xcd_contiguous(blockIdx.x, gridDim.x);  // neighbours in this numbering share an L2
+    const int cit = bid % a.ciTiles; bid /= a.ciTiles;
+    const int cot = bid % a.coTiles; bid /= a.coTiles;
+    const int slice = bid;
+    const int co0 = cot * 32, ci0 = cit * CI_T;
+
+    const int nts = (NN - wave + 3) / 4;   // taps of this wave: wave, wave + 4, ...
+    int tapoff[TS];
+#pragma unroll
+    for (int ts = 0; ts < TS; ++ts) {
+        const int t = wave + 4 * ts < NN ? wave + 4 * ts : 0;
+        const int ta = t / N, tc = t % N;
+        tapoff[ts] = (N - 1 - ta) * a.cols + ((N - 1 - tc) & 1) * a.HC + ((N - 1 - tc) >> 1);
+    }
+    f32x16 acc[TS][NC];
+#pragma unroll
+    for (int ts = 0; ts < TS; ++ts)
+#pragma unroll
+        for (int nc = 0; nc < NC; ++nc)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[ts][nc][i] = 0.f;
+
+    const int npix = 1 << a.logPix, rowsPerCo = a.TB * a.LR;
+    const int a_lane = l32 * a.DP + 8 * kk, b_lane = l32 * a.XP + 8 * kk;
+    const int st_end = (slice + 1) * a.stagesPerSlice < a.nStages ? (slice + 1) * a.stagesPerSlice : a.nStages;
+    for (int st = slice * a.stagesPerSlice; st < st_end; ++st) {
+        int t = st;
+        const int tx = t % a.tilesX; t /= a.tilesX;
+        const int ty = t % a.tilesY; t /= a.tilesY;
+        const int b0 = t * a.TB, i0 = ty * a.TI, j0 = tx * a.TJ;
+        const int oy_base = 2 * i0 + g.P - (N - 1), ox_base = 2 * j0 + g.P - (N - 1);
+        __syncthreads();
+        {
+            // x tile: 8 pixels of a row per piece; W % 8 == 0, so a piece lies in the row or past it
+            const int nq = (CI_T * npix) >> 3;
+            for (int e0 = tid; e0 < nq; e0 += 256 * 4) {
+                gw_u4 q[4];
+                int dst[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int e = e0 + 256 * u;
+                    dst[u] = -1;
+                    q[u] = gw_u4{0u, 0u, 0u, 0u};
+                    if (e < nq) {
+                        const int pix = (e << 3) & (npix - 1), cl = (e << 3) >> a.logPix;
+                        const int tr = pix >> a.logTJ, lj = pix & (a.TJ - 1);
+                        const int b = b0 + (tr >> a.logTI), i = i0 + (tr & (a.TI - 1)), j = j0 + lj, ci = ci0 + cl;
+                        dst[u] = cl * a.XP + pix;
+                        if (ci < g.Cin && b < g.B && i < g.H && j < g.W)
+                            q[u] = *reinterpret_cast<const gw_u4u*>(x + (((size_t)b * g.Cin + ci) * g.H + i) * g.W + j);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (dst[u] >= 0) *reinterpret_cast<gw_u4*>(xs + dst[u]) = q[u];
+            }
+        }
+        {
+            // dy tile: 8 columns per piece, split by column parity: column cc of a row sits at
+            // (cc & 1) * HC + (cc >> 1)
+            const int nq = 32 * rowsPerCo * a.c8;
+            for (int e0 = tid; e0 < nq; e0 += 256 * 4) {
+                gw_u4 q[4];
+                int dst[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int e = e0 + 256 * u;
+                    dst[u] = -1;
+                    q[u] = gw_u4{0u, 0u, 0u, 0u};
+                    if (e < nq) {
+                        const int row = fdiv(e, a.dC8), m = e - row * a.c8;
+                        const int col = fdiv(row, a.dRows), rem = row - col * rowsPerCo;
+                        const int bl = fdiv(rem, a.dLR), rr = rem - bl * a.LR;
+                        const int b = b0 + bl, co = co0 + col, oy = oy_base + rr, ox = ox_base + 8 * m;
+                        dst[u] = col * a.DP + rem * a.cols + 4 * m;
+                        if (co < g.Cout && b < g.B && oy >= 0 && oy < g.OH && ox + 7 >= 0 && ox < g.OW) {
+                            const uint16_t* src = dy + (((size_t)b * g.Cout + co) * g.OH + oy) * g.OW;
+                            if (ox >= 0 && ox + 7 < g.OW) {
+                                q[u] = *reinterpret_cast<const gw_u4u*>(src + ox);
+                            } else {
+#pragma unroll
+                                for (int k = 0; k < 8; ++k)
+                                    if (ox + k >= 0 && ox + k < g.OW)
+                                        q[u][k >> 1] |= (unsigned)src[ox + k] << (16 * (k & 1));
+                            }
+                        }
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (dst[u] >= 0) {
+                        const gw_u2 ev = {__builtin_amdgcn_perm(q[u].y, q[u].x, 0x05040100u),
+                                          __builtin_amdgcn_perm(q[u].w, q[u].z, 0x05040100u)};
+                        const gw_u2 od = {__builtin_amdgcn_perm(q[u].y, q[u].x, 0x07060302u),
+                                          __builtin_amdgcn_perm(q[u].w, q[u].z, 0x07060302u)};
+                        *reinterpret_cast<gw_u2*>(dys + dst[u]) = ev;
+                        *reinterpret_cast<gw_u2*>(dys + dst[u] + a.HC) = od;
+                    }
+            }
+        }
+        __syncthreads();
+        // K steps of 16 pixels along a row; pixels past the end of the row are zeros in x
+        const int wj = g.W - j0 < a.TJ ? g.W - j0 : a.TJ;
+        const int steps = (wj + 15) >> 4;
+        // the tap count of a wave is TS or TS - 1: one branch per stage picks a loop body whose
+        // taps are unrolled, so that all fragment reads of a step are in flight before its MFMAs
+        auto rows = [&](auto nts_tag) {
+            constexpr int NTS = decltype(nts_tag)::value;
+            for (int tr = 0; tr < a.TR; ++tr) {
+                const int bl = tr >> a.logTI, li = tr & (a.TI - 1);
+                if (b0 + bl >= g.B || i0 + li >= g.H) continue;  // uniform
+                const uint16_t* ap = dys + a_lane + (bl * a.LR + 2 * li) * a.cols;
+                const uint16_t* bp = xs + b_lane + tr * a.TJ;
+                for (int sp = 0; sp < steps; ++sp) {
+                    gw_bf16x8 bv[NC], av[NTS > 0 ? NTS : 1];
+#pragma unroll
+                    for (int nc = 0; nc < NC; ++nc)
+                        bv[nc] = *reinterpret_cast<const gw_bf16x8*>(bp + nc * 32 * a.XP + 16 * sp);
+#pragma unroll
+                    for (int ts = 0; ts < NTS; ++ts)
+                        av[ts] = *reinterpret_cast<const gw_bf16x8u*>(ap + 16 * sp + tapoff[ts]);
+#pragma unroll
+                    for (int ts = 0; ts < NTS; ++ts)
+#pragma unroll
+                        for (int nc = 0; nc < NC; ++nc)
+                            acc[ts][nc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[ts], bv[nc], acc[ts][nc], 0, 0, 0);
+                }
+            }
+        };
+        if (nts == TS) rows(std::integral_constant<int, TS>{});
+        else rows(std::integral_constant<int, TS - 1>{});
+    }
+
+    // accumulator register i: output channel 8*(i/4) + 4*kk + (i%4) of the 32, input channel l32
+    float* out = part + (size_t)slice * g.Cout * g.Cin * NN;
+#pragma unroll
+    for (int ts = 0; ts < TS; ++ts) {
+        if (ts >= nts) continue;
+        const int t = wave + 4 * ts;
+#pragma unroll
+        for (int nc = 0; nc < NC; ++nc) {
+            const int ci = ci0 + nc * 32 + l32;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int co = co0 + 8 * (i / 4) + 4 * kk + (i % 4);
+                if (co < g.Cout && ci < g.Cin) out[((size_t)co * NN + t) * g.Cin + ci] = acc[ts][nc][i];
+            }
+        }
+    }
+}
+
+constexpr int GW_B16_NC = 2;
+
+bool gw_b16_args(const Geom& g, GwB16Args& a)
+{
+    const int N = g.n, CI_T = 32 * GW_B16_NC;
+    if (g.Cin < 32 || g.Cout < 32 || N < 2 || N > 4) return false;
+    if (g.W % 8 != 0 || g.W < 16) return false;
+    a.g = g;
+    a.TJ = g.W >= 32 ? 32 : 16;
+    a.logTJ = log2_of(a.TJ);
+    a.HC = a.TJ + 8;  // half rows: TJ + 1 columns are read, TJ + 4 written, 16-byte multiples
+    a.cols = 2 * a.HC;
+    a.c8 = (2 * a.TJ + N - 2 + 7) / 8;
+    const size_t budget = 78 * 1024;
+    int TR = 512 / a.TJ;  // at most 512 pixels per stage
+    for (;; TR >>= 1) {
+        if (TR < 1) return false;
+        a.TI = pow2_ceil(g.H < TR ? g.H : TR);
+        a.TB = TR / a.TI;
+        a.LR = 2 * a.TI + N - 2;
+        // channel strides: a multiple of 8 elements (16-byte pieces) whose count of pieces is odd,
+        // so that the 16 lanes of a read pass fall into different bank groups
+        a.DP = a.TB * a.LR * a.cols;
+        if ((a.DP / 8) % 2 == 0) a.DP += 8;
+        a.XP = TR * a.TJ + 8;
+        if ((size_t)2 * (CI_T * a.XP + 32 * a.DP) <= budget) break;
+    }
+    a.TR = TR;
+    a.logTI = log2_of(a.TI);
+    a.logPix = log2_of(TR * a.TJ);
+    a.tilesX = (g.W + a.TJ - 1) / a.TJ;
+    a.tilesY = (g.H + a.TI - 1) / a.TI;
+    const long long stages = (long long)a.tilesX * a.tilesY * ((g.B + a.TB - 1) / a.TB);
+    if (stages > 0x7fffffffLL) return false;
+    a.nStages = (int)stages;
+    a.coTiles = (g.Cout + 31) / 32;
+    a.ciTiles = (g.Cin + CI_T - 1) / CI_T;
+    long long want = 512 / ((long long)a.coTiles * a.ciTiles);
+    if (want < 1) want = 1;
+    if (want > stages) want = stages;
+    a.stagesPerSlice = (int)((stages + want - 1) / want);
+    a.nSlices = (int)((stages + a.stagesPerSlice - 1) / a.stagesPerSlice);
+    a.dC8 = make_fastdiv((unsigned)a.c8);
+    a.dRows = make_fastdiv((unsigned)(a.TB * a.LR));
+    a.dLR = make_fastdiv((unsigned)a.LR);
+    if ((size_t)g.Cout * g.Cin * N * N > 0x7fffffffu) return false;
+    if ((size_t)32 * a.TB * a.LR * a.c8 > 0x7fffffffu) return false;
+    return true;
+}
+
+template <int N>
+hipError_t launch_gw_b16(const GwB16Args& a, const void* x, const void* dy, float* dw, Workspace& ws,
+                         hipStream_t stream)
+{
+    constexpr int NC = GW_B16_NC;
+    const GeomBase& g = a.g;
+    const size_t elems = (size_t)g.Cout * g.Cin * N * N;
+    const size_t need = elems * a.nSlices * sizeof(float);  // one copy of dw per slice
+    if (ws.query) { ws.need = need; return hipSuccess; }
+    if (ws.bytes < need) return kWorkspaceTooSmall;
+    float* part = (float*)ws.ptr;
+    hipError_t e;
+    const size_t lds = (size_t)2 * (32 * NC * a.XP + 32 * a.DP);
+    const void* kfn = (const void*)ukst_grad_weight_mfma_bf16_kernel<N, NC>;
+    e = hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e == hipSuccess) {
+        const unsigned nb = (unsigned)((long long)a.nSlices * a.coTiles * a.ciTiles);
+        hipLaunchKernelGGL((ukst_grad_weight_mfma_bf16_kernel<N, NC>), dim3(nb), dim3(256), lds, stream,
+                           (const uint16_t*)x, (const uint16_t*)dy, part, a);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(ukst_sum_taps_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, stream,
+                           (const float*)part, dw, (int)elems, a.nSlices, N * N, g.Cin);
+        e = hipGetLastError();
+    }
+    return e;
+}
+
 template <int N, int CO_R, int CI_R, typename TIn>
 hipError_t launch_gw(const Geom& g, const void* x, const void* dy, float* dw, Workspace& ws,
                      hipStream_t stream)
@@ -1420,6 +1692,10 @@ template <int N, typename TIn>
 hipError_t launch_gw_n(const Geom& g, const void* x, const void* dy, float* dw, Workspace& ws,
                        hipStream_t stream)
 {
+    if constexpr (N >= 2 && N <= 4 && sizeof(TIn) == 2) {
+        GwB16Args ba;  // bf16 layers: the bf16 matrix pipe where the kernel takes the shape
+        if (gw_b16_args(g, ba)) return launch_gw_b16<N>(ba, x, dy, dw, ws, stream);
+    }
     if constexpr (N >= 2) {
         GwMfmaArgs ma;
         if (gw_mfma_args<gw_nc(N)>(g, ma)) return launch_gw_mfma<N, TIn>(ma, x, dy, dw, ws, stream);
@@ -1453,6 +1729,8 @@ hipError_t launch_gw_t(const Geom& g, const void* x, const void* dy, float* dw, 
 const char* grad_kernel_name(const Geom& g, int which, int dtype)
 {
     if (which == 1) {
+        GwB16Args ba;
+        if (dtype == 1 && gw_b16_args(g, ba)) return "ukst_grad_weight_mfma_bf16_kernel";
         GwMfmaArgs wa;
         const bool m = g.n <= 4 ? gw_mfma_args<gw_nc(4)>(g, wa) : gw_mfma_args<gw_nc(5)>(g, wa);
         return m ? "ukst_grad_weight_mfma_kernel" : "ukst_grad_weight_kernel";

@@ -67,6 +67,27 @@ def test_backward_several_tiles_ragged_tails(shape):
     _both(w.with_(dtype="bf16"), integer=False)
 
 
+@pytest.mark.parametrize("shape", [
+    (2, 32, 32, 4, 16, 4, 2),      # one tile, 16-pixel rows
+    (1, 64, 40, 9, 24, 3, 1),      # W = 24 in a 32-wide tile: the second K step of a row is half empty
+    (3, 40, 33, 5, 40, 2, 0),      # two column tiles, ragged channel blocks
+    (2, 96, 64, 3, 64, 4, 3),      # P > n / 2, two input channel tiles
+    (5, 32, 32, 2, 16, 3, 0),      # several images per stage
+    (1, 32, 32, 20, 32, 4, 1),     # several row tiles, odd P
+    (2, 32, 32, 17, 16, 2, 1),     # ragged row tile
+    (4, 64, 32, 16, 16, 4, 2)])    # cfg5b's map
+def test_backward_bf16_kernel_gradient_on_the_bf16_matrix_pipe(shape):
+    """bf16 layers with both channel counts wide, n <= 4 and rows of 8-element pieces take the
+    kernel gradient on the bf16 MFMA pipe (pixels as the K axis, half of the dy fragments read at
+    2-byte-aligned LDS addresses): every element, integer-valued data exactly."""
+    B, Cin, Cout, H, W, n, P = shape
+    assert ukst.ukst_grad_kernel_name(1, B, Cin, Cout, H, W, n, P, ukst.UKST_BF16_F32) == \
+        "ukst_grad_weight_mfma_bf16_kernel"
+    w = _mk("bwd_b16pipe", 6500 + sum(shape), B, Cin, Cout, H, W, n, P, dtype="bf16")
+    _both(w, integer=True)
+    _both(w, integer=False)
+
+
 def test_backward_cfg2_images_full_size():
     for name in ("cfg2a", "cfg2b"):
         _both(wl.WORKLOADS[name], guard=1 << 16)
@@ -143,7 +164,7 @@ def test_backward_on_a_side_stream_is_bit_reproducible():
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("shape", [(2, 3, 3, 9, 21, 3, 0), (2, 40, 36, 6, 18, 4, 2)])
+@pytest.mark.parametrize("shape", [(2, 3, 3, 9, 21, 3, 0), (2, 40, 36, 6, 18, 4, 2), (2, 40, 36, 6, 24, 4, 2)])
 def test_backward_operands_with_element_alignment_only(dtype, shape):
     """x, w, dy one element past an aligned address (narrow layer: vector-ALU kernels, wide layer:
     matrix-core kernels): the four-element vector loads of the staging code may assume nothing
