@@ -1358,6 +1358,7 @@ struct GwB16Args {
     int tilesX, tilesY, nStages, stagesPerSlice, nSlices;
     int coTiles, ciTiles;
     int c8;                                    // 8-column pieces per staged dy row
+    int npass;                                 // passes of 64 lanes over a channel's (row, piece) pairs
     FastDiv dC8, dRows, dLR;
 };
 
@@ -1366,6 +1367,25 @@ typedef __bf16 gw_bf16x8u __attribute__((ext_vector_type(8), aligned(2)));
 typedef unsigned gw_u4 __attribute__((ext_vector_type(4)));
 typedef unsigned gw_u4u __attribute__((ext_vector_type(4), aligned(2)));
 typedef unsigned gw_u2 __attribute__((ext_vector_type(2)));
+
+constexpr unsigned kGwInvalid = 0xFFFFFF00u;  // byte offset that is out of range for any buffer
+constexpr int kGwRsrcFlags = 0x00020000;      // raw 32-bit buffer, gfx9 family
+
+// 8 packed 16-bit elements moved s places up (s > 0) or down (s < 0), zeros moving in; 0 < |s| < 8
+__device__ __forceinline__ gw_u4 shift_elements(gw_u4 v, int s)
+{
+    unsigned long long lo = v.x | ((unsigned long long)v.y << 32), hi = v.z | ((unsigned long long)v.w << 32);
+    if (s > 0) {
+        const int sh = 16 * s;
+        if (sh >= 64) { hi = lo << (sh - 64); lo = 0; }
+        else { hi = (hi << sh) | (lo >> (64 - sh)); lo <<= sh; }
+    } else {
+        const int sh = -16 * s;
+        if (sh >= 64) { lo = hi >> (sh - 64); hi = 0; }
+        else { lo = (lo >> sh) | (hi << (64 - sh)); hi >>= sh; }
+    }
+    return gw_u4{(unsigned)lo, (unsigned)(lo >> 32), (unsigned)hi, (unsigned)(hi >> 32)};
+}
 
 template <int N, int NC>
 __global__ __launch_bounds__(256, 2) void ukst_grad_weight_mfma_bf16_kernel(const uint16_t* __restrict__ x,
@@ -1380,6 +1400,10 @@ __global__ __launch_bounds__(256, 2) void ukst_grad_weight_mfma_bf16_kernel(cons
     const int l32 = lane & 31, kk = lane >> 5;
     uint16_t* xs = reinterpret_cast<uint16_t*>(lds_b);  // [CI_T][XP]
     uint16_t* dys = xs + CI_T * a.XP;                   // [32][DP]
+    const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)x, 0, (int)((size_t)g.B * g.Cin * g.H * g.W * 2), kGwRsrcFlags);
+    const __amdgpu_buffer_rsrc_t rs_dy = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)dy, 0, (int)((size_t)g.B * g.Cout * g.OH * g.OW * 2), kGwRsrcFlags);
 
     int bid = xcd_contiguous(blockIdx.x, gridDim.x);  // neighbours in this numbering share an L2
     const int cit = bid % a.ciTiles; bid /= a.ciTiles;
@@ -1413,24 +1437,31 @@ __global__ __launch_bounds__(256, 2) void ukst_grad_weight_mfma_bf16_kernel(cons
         const int b0 = t * a.TB, i0 = ty * a.TI, j0 = tx * a.TJ;
         const int oy_base = 2 * i0 + g.P - (N - 1), ox_base = 2 * j0 + g.P - (N - 1);
         __syncthreads();
+        // Staging without divergent address arithmetic per piece: every wave owns a quarter of
+        // the channels; what depends on the lane (row, piece, validity) is worked out once per
+        // stage, the channel enters through the scalar offset of a buffer load, and all loads of
+        // a group are in flight before the first LDS write.  Rows, images and channels that do
+        // not exist are read through an out-of-range offset and arrive as zeros.
         {
             // x tile: 8 pixels of a row per piece; W % 8 == 0, so a piece lies in the row or past it
-            const int nq = (CI_T * npix) >> 3;
-            for (int e0 = tid; e0 < nq; e0 += 256 * 4) {
+            const int logCPC = a.logPix - 3, CPC = 1 << logCPC;  // pieces per channel
+            const int cw0 = wave * (CI_T / 4);
+            const int xpasses = ((CI_T / 4) << logCPC) >> 6;     // >= 2
+            for (int p0 = 0; p0 < xpasses; p0 += 4) {
                 gw_u4 q[4];
                 int dst[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    const int e = e0 + 256 * u;
                     dst[u] = -1;
-                    q[u] = gw_u4{0u, 0u, 0u, 0u};
-                    if (e < nq) {
-                        const int pix = (e << 3) & (npix - 1), cl = (e << 3) >> a.logPix;
+                    if (p0 + u < xpasses) {
+                        const int flat = lane + 64 * (p0 + u);
+                        const int cl = cw0 + (flat >> logCPC), pix = (flat & (CPC - 1)) << 3;
                         const int tr = pix >> a.logTJ, lj = pix & (a.TJ - 1);
                         const int b = b0 + (tr >> a.logTI), i = i0 + (tr & (a.TI - 1)), j = j0 + lj, ci = ci0 + cl;
+                        const bool ok = ci < g.Cin && b < g.B && i < g.H && j < g.W;
+                        const unsigned voff = ok ? (unsigned)((((b * g.Cin + ci) * g.H + i) * g.W + j) * 2) : kGwInvalid;
+                        q[u] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, voff, 0, 0);
                         dst[u] = cl * a.XP + pix;
-                        if (ci < g.Cin && b < g.B && i < g.H && j < g.W)
-                            q[u] = *reinterpret_cast<const gw_u4u*>(x + (((size_t)b * g.Cin + ci) * g.H + i) * g.W + j);
                     }
                 }
 #pragma unroll
@@ -1440,45 +1471,47 @@ __global__ __launch_bounds__(256, 2) void ukst_grad_weight_mfma_bf16_kernel(cons
         }
         {
             // dy tile: 8 columns per piece, split by column parity: column cc of a row sits at
-            // (cc & 1) * HC + (cc >> 1)
-            const int nq = 32 * rowsPerCo * a.c8;
-            for (int e0 = tid; e0 < nq; e0 += 256 * 4) {
-                gw_u4 q[4];
-                int dst[4];
+            // (cc & 1) * HC + (cc >> 1).  A piece that hangs over the left or right end of its row
+            // is fetched from inside the row and shifted into place (zeros move in).
+            const int per_co = rowsPerCo * a.c8;
+            const unsigned co_bytes = (unsigned)(g.OH * g.OW * 2);
+            constexpr int GRP = 4;  // channels whose loads are in flight together
+#pragma unroll 1
+            for (int pp = 0; pp < a.npass; ++pp) {  // passes of 64 lanes over a channel's (row, piece) pairs
+                const int idx = lane + 64 * pp;
+                const int rem = fdiv(idx, a.dC8), m = idx - rem * a.c8;
+                const int bl = fdiv(rem, a.dLR), rr = rem - bl * a.LR;
+                const int b = b0 + bl, oy = oy_base + rr, ox = ox_base + 8 * m;
+                const bool ok = idx < per_co && b < g.B && oy >= 0 && oy < g.OH && ox + 7 >= 0 && ox < g.OW;
+                const int oxl = ox < 0 ? 0 : (ox > g.OW - 8 ? g.OW - 8 : ox);
+                const int dsh = oxl - ox;
+                const unsigned dvoff = ok ? (unsigned)((((b * g.Cout) * g.OH + oy) * g.OW + oxl) * 2) : kGwInvalid;
+                const int ddst = idx < per_co ? rem * a.cols + 4 * m : -1;
+#pragma unroll 1
+                for (int h = 0; h < 8 / GRP; ++h) {
+                    gw_u4 q[GRP];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int e = e0 + 256 * u;
-                    dst[u] = -1;
-                    q[u] = gw_u4{0u, 0u, 0u, 0u};
-                    if (e < nq) {
-                        const int row = fdiv(e, a.dC8), m = e - row * a.c8;
-                        const int col = fdiv(row, a.dRows), rem = row - col * rowsPerCo;
-                        const int bl = fdiv(rem, a.dLR), rr = rem - bl * a.LR;
-                        const int b = b0 + bl, co = co0 + col, oy = oy_base + rr, ox = ox_base + 8 * m;
-                        dst[u] = col * a.DP + rem * a.cols + 4 * m;
-                        if (co < g.Cout && b < g.B && oy >= 0 && oy < g.OH && ox + 7 >= 0 && ox < g.OW) {
-                            const uint16_t* src = dy + (((size_t)b * g.Cout + co) * g.OH + oy) * g.OW;
-                            if (ox >= 0 && ox + 7 < g.OW) {
-                                q[u] = *reinterpret_cast<const gw_u4u*>(src + ox);
-                            } else {
+                    for (int c4 = 0; c4 < GRP; ++c4) {
+                        const int co = co0 + wave * 8 + h * GRP + c4;  // uniform
+                        const bool cok = co < g.Cout;
+                        q[c4] = __builtin_amdgcn_raw_buffer_load_b128(rs_dy, cok ? dvoff : kGwInvalid,
+                                                                      cok ? (unsigned)co * co_bytes : 0u, 0);
+                    }
+                    if (ddst >= 0) {
 #pragma unroll
-                                for (int k = 0; k < 8; ++k)
-                                    if (ox + k >= 0 && ox + k < g.OW)
-                                        q[u][k >> 1] |= (unsigned)src[ox + k] << (16 * (k & 1));
-                            }
+                        for (int c4 = 0; c4 < GRP; ++c4) {
+                            uint16_t* base = dys + (wave * 8 + h * GRP + c4) * a.DP + ddst;
+                            gw_u4 v = q[c4];
+                            if (dsh != 0) v = shift_elements(v, dsh);
+                            const gw_u2 ev = {__builtin_amdgcn_perm(v.y, v.x, 0x05040100u),
+                                              __builtin_amdgcn_perm(v.w, v.z, 0x05040100u)};
+                            const gw_u2 od = {__builtin_amdgcn_perm(v.y, v.x, 0x07060302u),
+                                              __builtin_amdgcn_perm(v.w, v.z, 0x07060302u)};
+                            *reinterpret_cast<gw_u2*>(base) = ev;
+                            *reinterpret_cast<gw_u2*>(base + a.HC) = od;
                         }
                     }
                 }
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    if (dst[u] >= 0) {
-                        const gw_u2 ev = {__builtin_amdgcn_perm(q[u].y, q[u].x, 0x05040100u),
-                                          __builtin_amdgcn_perm(q[u].w, q[u].z, 0x05040100u)};
-                        const gw_u2 od = {__builtin_amdgcn_perm(q[u].y, q[u].x, 0x07060302u),
-                                          __builtin_amdgcn_perm(q[u].w, q[u].z, 0x07060302u)};
-                        *reinterpret_cast<gw_u2*>(dys + dst[u]) = ev;
-                        *reinterpret_cast<gw_u2*>(dys + dst[u] + a.HC) = od;
-                    }
             }
         }
         __syncthreads();
@@ -1578,7 +1611,11 @@ bool gw_b16_args(const Geom& g, GwB16Args& a)
     a.dRows = make_fastdiv((unsigned)(a.TB * a.LR));
     a.dLR = make_fastdiv((unsigned)a.LR);
     if ((size_t)g.Cout * g.Cin * N * N > 0x7fffffffu) return false;
-    if ((size_t)32 * a.TB * a.LR * a.c8 > 0x7fffffffu) return false;
+    a.npass = (a.TB * a.LR * a.c8 + 63) / 64;
+    if (g.OW < 8) return false;
+    // single buffer descriptors, 32-bit byte offsets
+    if ((size_t)g.B * g.Cin * g.H * g.W * 2 > 0x7FFFFFF0u || (size_t)g.B * g.Cout * g.OH * g.OW * 2 > 0x7FFFFFF0u)
+        return false;
     return true;
 }
 
