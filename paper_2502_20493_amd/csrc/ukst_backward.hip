@@ -1442,6 +1442,55 @@ __global__ __launch_bounds__(256, 2) void ukst_grad_weight_mfma_bf16_kernel(cons
         // stage, the channel enters through the scalar offset of a buffer load, and all loads of
         // a group are in flight before the first LDS write.  Rows, images and channels that do
         // not exist are read through an out-of-range offset and arrive as zeros.
+        // dy tile: 8 columns per piece, split by column parity: column cc of a row sits at
+        // (cc & 1) * HC + (cc >> 1).  A piece that hangs over the left or right end of its row is
+        // fetched from inside the row and shifted into place (zeros move in).  Per pass of 64
+        // lanes over a channel's (row, piece) pairs: the lane's part of the address, then the
+        // wave's 8 channels in two groups; a group's loads are requested before the previous
+        // group is written, so one memory round trip covers the whole stage.
+        constexpr int GRP = 4;
+        const int per_co = rowsPerCo * a.c8;
+        const unsigned co_bytes = (unsigned)(g.OH * g.OW * 2);
+        unsigned dvoff;
+        int dsh, ddst;
+        auto lane_pass = [&](int pp) {
+            const int idx = lane + 64 * pp;
+            const int rem = fdiv(idx, a.dC8), m = idx - rem * a.c8;
+            const int bl = fdiv(rem, a.dLR), rr = rem - bl * a.LR;
+            const int b = b0 + bl, oy = oy_base + rr, ox = ox_base + 8 * m;
+            const bool ok = idx < per_co && b < g.B && oy >= 0 && oy < g.OH && ox + 7 >= 0 && ox < g.OW;
+            const int oxl = ox < 0 ? 0 : (ox > g.OW - 8 ? g.OW - 8 : ox);
+            dsh = oxl - ox;
+            dvoff = ok ? (unsigned)((((b * g.Cout) * g.OH + oy) * g.OW + oxl) * 2) : kGwInvalid;
+            ddst = idx < per_co ? rem * a.cols + 4 * m : -1;
+        };
+        auto load_group = [&](int h, gw_u4 (&q)[GRP]) {
+#pragma unroll
+            for (int c4 = 0; c4 < GRP; ++c4) {
+                const int co = co0 + wave * 8 + h * GRP + c4;  // uniform
+                const bool cok = co < g.Cout;
+                q[c4] = __builtin_amdgcn_raw_buffer_load_b128(rs_dy, cok ? dvoff : kGwInvalid,
+                                                              cok ? (unsigned)co * co_bytes : 0u, 0);
+            }
+        };
+        auto write_group = [&](int h, int sh, int dst, const gw_u4 (&q)[GRP]) {
+            if (dst < 0) return;
+#pragma unroll
+            for (int c4 = 0; c4 < GRP; ++c4) {
+                uint16_t* base = dys + (wave * 8 + h * GRP + c4) * a.DP + dst;
+                gw_u4 v = q[c4];
+                if (sh != 0) v = shift_elements(v, sh);
+                const gw_u2 ev = {__builtin_amdgcn_perm(v.y, v.x, 0x05040100u),
+                                  __builtin_amdgcn_perm(v.w, v.z, 0x05040100u)};
+                const gw_u2 od = {__builtin_amdgcn_perm(v.y, v.x, 0x07060302u),
+                                  __builtin_amdgcn_perm(v.w, v.z, 0x07060302u)};
+                *reinterpret_cast<gw_u2*>(base) = ev;
+                *reinterpret_cast<gw_u2*>(base + a.HC) = od;
+            }
+        };
+        gw_u4 qa[GRP], qb[GRP];
+        lane_pass(0);
+        load_group(0, qa);
         {
             // x tile: 8 pixels of a row per piece; W % 8 == 0, so a piece lies in the row or past it
             const int logCPC = a.logPix - 3, CPC = 1 << logCPC;  // pieces per channel
@@ -1469,50 +1518,16 @@ __global__ __launch_bounds__(256, 2) void ukst_grad_weight_mfma_bf16_kernel(cons
                     if (dst[u] >= 0) *reinterpret_cast<gw_u4*>(xs + dst[u]) = q[u];
             }
         }
-        {
-            // dy tile: 8 columns per piece, split by column parity: column cc of a row sits at
-            // (cc & 1) * HC + (cc >> 1).  A piece that hangs over the left or right end of its row
-            // is fetched from inside the row and shifted into place (zeros move in).
-            const int per_co = rowsPerCo * a.c8;
-            const unsigned co_bytes = (unsigned)(g.OH * g.OW * 2);
-            constexpr int GRP = 4;  // channels whose loads are in flight together
 #pragma unroll 1
-            for (int pp = 0; pp < a.npass; ++pp) {  // passes of 64 lanes over a channel's (row, piece) pairs
-                const int idx = lane + 64 * pp;
-                const int rem = fdiv(idx, a.dC8), m = idx - rem * a.c8;
-                const int bl = fdiv(rem, a.dLR), rr = rem - bl * a.LR;
-                const int b = b0 + bl, oy = oy_base + rr, ox = ox_base + 8 * m;
-                const bool ok = idx < per_co && b < g.B && oy >= 0 && oy < g.OH && ox + 7 >= 0 && ox < g.OW;
-                const int oxl = ox < 0 ? 0 : (ox > g.OW - 8 ? g.OW - 8 : ox);
-                const int dsh = oxl - ox;
-                const unsigned dvoff = ok ? (unsigned)((((b * g.Cout) * g.OH + oy) * g.OW + oxl) * 2) : kGwInvalid;
-                const int ddst = idx < per_co ? rem * a.cols + 4 * m : -1;
-#pragma unroll 1
-                for (int h = 0; h < 8 / GRP; ++h) {
-                    gw_u4 q[GRP];
-#pragma unroll
-                    for (int c4 = 0; c4 < GRP; ++c4) {
-                        const int co = co0 + wave * 8 + h * GRP + c4;  // uniform
-                        const bool cok = co < g.Cout;
-                        q[c4] = __builtin_amdgcn_raw_buffer_load_b128(rs_dy, cok ? dvoff : kGwInvalid,
-                                                                      cok ? (unsigned)co * co_bytes : 0u, 0);
-                    }
-                    if (ddst >= 0) {
-#pragma unroll
-                        for (int c4 = 0; c4 < GRP; ++c4) {
-                            uint16_t* base = dys + (wave * 8 + h * GRP + c4) * a.DP + ddst;
-                            gw_u4 v = q[c4];
-                            if (dsh != 0) v = shift_elements(v, dsh);
-                            const gw_u2 ev = {__builtin_amdgcn_perm(v.y, v.x, 0x05040100u),
-                                              __builtin_amdgcn_perm(v.w, v.z, 0x05040100u)};
-                            const gw_u2 od = {__builtin_amdgcn_perm(v.y, v.x, 0x07060302u),
-                                              __builtin_amdgcn_perm(v.w, v.z, 0x07060302u)};
-                            *reinterpret_cast<gw_u2*>(base) = ev;
-                            *reinterpret_cast<gw_u2*>(base + a.HC) = od;
-                        }
-                    }
-                }
+        for (int pp = 0; pp < a.npass; ++pp) {
+            const int sh_c = dsh, dst_c = ddst;
+            load_group(1, qb);
+            write_group(0, sh_c, dst_c, qa);
+            if (pp + 1 < a.npass) {
+                lane_pass(pp + 1);
+                load_group(0, qa);
             }
+            write_group(1, sh_c, dst_c, qb);
         }
         __syncthreads();
         // K steps of 16 pixels along a row; pixels past the end of the row are zeros in x
