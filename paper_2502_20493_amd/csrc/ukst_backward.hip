@@ -1083,6 +1083,15 @@ __global__ __launch_bounds__(256) void ukst_grad_weight_kernel(const TIn* __rest
 // are odd so that the 32 channels of a fragment fall into 32 banks.  Blocks walk over slices of
 // the tiles and write partial results as [slice][co][tap][ci] (lanes along ci);
 // ukst_sum_taps_kernel adds the slices in a fixed order and stores dw[co][ci][tap].
+typedef __bf16 gw_bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 gw_bf16x8u __attribute__((ext_vector_type(8), aligned(2)));
+typedef unsigned gw_u4 __attribute__((ext_vector_type(4)));
+typedef unsigned gw_u4u __attribute__((ext_vector_type(4), aligned(2)));
+typedef unsigned gw_u2 __attribute__((ext_vector_type(2)));
+constexpr unsigned kGwInvalid = 0xFFFFFF00u;  // byte offset that is out of range for any buffer
+constexpr int kGwRsrcFlags = 0x00020000;      // raw 32-bit buffer, gfx9 family
+
+
 struct GwMfmaArgs {
     GeomBase g;
     int TJ, logTJ, TI, logTI, TB, TR, logPix;  // logPix = log2(TR * TJ)
@@ -1090,6 +1099,7 @@ struct GwMfmaArgs {
     int tilesX, tilesY, nStages, stagesPerSlice, nSlices;
     int coTiles, ciTiles;
     int cols4;                 // four-column pieces per staged dy row
+    int fast, npass;           // piecewise staging (rows of at least four elements), its passes per channel
     FastDiv dC4, dRows, dLR;
 };
 
@@ -1106,6 +1116,10 @@ __global__ __launch_bounds__(256, 2) void ukst_grad_weight_mfma_kernel(const TIn
     const int l32 = lane & 31, kk = lane >> 5;
     float* xs = lds_f;                     // [CI_T][XP]
     float* dys = lds_f + CI_T * a.XP;      // [32][DP]
+    const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)x, 0, (int)((size_t)g.B * g.Cin * g.H * g.W * sizeof(TIn)), kGwRsrcFlags);
+    const __amdgpu_buffer_rsrc_t rs_dy = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)dy, 0, (int)((size_t)g.B * g.Cout * g.OH * g.OW * sizeof(TIn)), kGwRsrcFlags);
 
     int bid = xcd_contiguous(blockIdx.x, gridDim.x);  // neighbours in this numbering share an L2
     const int cit = bid % a.ciTiles; bid /= a.ciTiles;
@@ -1139,6 +1153,126 @@ __global__ __launch_bounds__(256, 2) void ukst_grad_weight_mfma_kernel(const TIn
         const int b0 = t * a.TB, i0 = ty * a.TI, j0 = tx * a.TJ;
         const int oy_base = 2 * i0 + g.P - (N - 1), ox_base = 2 * j0 + g.P - (N - 1);
         __syncthreads();
+        if (a.fast) {
+            // Staging without divergent address arithmetic per piece (pieces of four elements):
+            // every wave owns a quarter of the channels; what depends on the lane (row, piece,
+            // validity) is worked out once per stage and pass, the channel enters through the
+            // scalar offset of a buffer load, and a group's loads are requested before the
+            // previous group is written.  Rows, images and channels that do not exist are read
+            // through an out-of-range offset and arrive as zeros; a piece that hangs over an end
+            // of its row is fetched from inside the row and shifted into place.
+            constexpr int ES = (int)sizeof(TIn);
+            constexpr int GRP = 4;
+            const int per_co = rowsPerCo * a.cols4;
+            const unsigned co_bytes = (unsigned)(g.OH * g.OW * ES);
+            unsigned dvoff;
+            int dsh, ddst, dnc;
+            auto lane_pass = [&](int pp) {
+                const int idx = lane + 64 * pp;
+                const int rem = fdiv(idx, a.dC4), m = idx - rem * a.cols4;
+                const int bl = fdiv(rem, a.dLR), rr = rem - bl * a.LR;
+                const int b = b0 + bl, oy = oy_base + rr, ox = ox_base + 4 * m;
+                const bool ok = idx < per_co && b < g.B && oy >= 0 && oy < g.OH && ox + 3 >= 0 && ox < g.OW;
+                const int oxl = ox < 0 ? 0 : (ox > g.OW - 4 ? g.OW - 4 : ox);
+                dsh = oxl - ox;
+                dvoff = ok ? (unsigned)((((b * g.Cout) * g.OH + oy) * g.OW + oxl) * ES) : kGwInvalid;
+                ddst = idx < per_co ? rem * a.cols + 2 * m : -1;
+                dnc = a.cols - 4 * m;  // columns of this piece that belong to the staged row (2 or >= 4)
+            };
+            auto load_piece = [&](const __amdgpu_buffer_rsrc_t& rs, unsigned voff, unsigned soff) -> Quad {
+                if constexpr (ES == 4) {
+                    const gw_u4 t = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soff, 0);
+                    return Quad{{__uint_as_float(t.x), __uint_as_float(t.y), __uint_as_float(t.z), __uint_as_float(t.w)}};
+                } else {
+                    const gw_u2 t = __builtin_amdgcn_raw_buffer_load_b64(rs, voff, soff, 0);
+                    return Quad{{__uint_as_float(t.x << 16), __uint_as_float(t.x & 0xFFFF0000u),
+                                 __uint_as_float(t.y << 16), __uint_as_float(t.y & 0xFFFF0000u)}};
+                }
+            };
+            // four elements moved sh places up (sh > 0) or down, zeros moving in; 0 < |sh| < 4
+            auto shifted = [&](const Quad& q, int sh) -> Quad {
+                Quad r;
+#pragma unroll
+                for (int k2 = 0; k2 < 4; ++k2) {
+                    const int src = k2 - sh;
+                    float v = 0.f;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v = src == e ? q.v[e] : v;
+                    r.v[k2] = v;
+                }
+                return r;
+            };
+            auto load_group = [&](int h, Quad (&q)[GRP]) {
+#pragma unroll
+                for (int c4 = 0; c4 < GRP; ++c4) {
+                    const int co = co0 + wave * 8 + h * GRP + c4;  // uniform
+                    const bool cok = co < g.Cout;
+                    q[c4] = load_piece(rs_dy, cok ? dvoff : kGwInvalid, cok ? (unsigned)co * co_bytes : 0u);
+                }
+            };
+            auto write_group = [&](int h, int sh, int dst, int nc, const Quad (&q)[GRP]) {
+                if (dst < 0) return;
+#pragma unroll
+                for (int c4 = 0; c4 < GRP; ++c4) {
+                    float* base = dys + (wave * 8 + h * GRP + c4) * a.DP + dst;
+                    const Quad v = sh != 0 ? shifted(q[c4], sh) : q[c4];
+                    base[0] = v.v[0];
+                    base[a.HC] = v.v[1];
+                    if (nc > 2) {
+                        base[1] = v.v[2];
+                        base[a.HC + 1] = v.v[3];
+                    }
+                }
+            };
+            Quad qa[GRP], qb[GRP];
+            lane_pass(0);
+            load_group(0, qa);
+            {
+                // x tile: four pixels of a row per piece
+                const int logCPC = a.logPix - 2, CPC = 1 << logCPC;  // pieces per channel
+                const int cw0 = wave * (CI_T / 4);
+                const int xpasses = ((CI_T / 4) << logCPC) >> 6;
+                for (int p0 = 0; p0 < xpasses; p0 += 4) {
+                    Quad q[4];
+                    int dst[4], sh[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        dst[u] = -1;
+                        sh[u] = 0;
+                        if (p0 + u < xpasses) {
+                            const int flat = lane + 64 * (p0 + u);
+                            const int cl = cw0 + (flat >> logCPC), pix = (flat & (CPC - 1)) << 2;
+                            const int tr = pix >> a.logTJ, lj = pix & (a.TJ - 1);
+                            const int b = b0 + (tr >> a.logTI), i = i0 + (tr & (a.TI - 1)), j = j0 + lj, ci = ci0 + cl;
+                            const bool ok = ci < g.Cin && b < g.B && i < g.H && j < g.W;
+                            const int jl = j > g.W - 4 ? g.W - 4 : j;
+                            sh[u] = jl - j;
+                            const unsigned voff = ok ? (unsigned)((((b * g.Cin + ci) * g.H + i) * g.W + jl) * ES) : kGwInvalid;
+                            q[u] = load_piece(rs_x, voff, 0u);
+                            dst[u] = cl * a.XP + pix;
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if (dst[u] >= 0) {
+                            const Quad v = sh[u] != 0 ? shifted(q[u], sh[u]) : q[u];
+#pragma unroll
+                            for (int k2 = 0; k2 < 4; ++k2) xs[dst[u] + k2] = v.v[k2];
+                        }
+                }
+            }
+#pragma unroll 1
+            for (int pp = 0; pp < a.npass; ++pp) {
+                const int sh_c = dsh, dst_c = ddst, nc_c = dnc;
+                load_group(1, qb);
+                write_group(0, sh_c, dst_c, nc_c, qa);
+                if (pp + 1 < a.npass) {
+                    lane_pass(pp + 1);
+                    load_group(0, qa);
+                }
+                write_group(1, sh_c, dst_c, nc_c, qb);
+            }
+        } else {
         if (a.logTJ >= 2) {
             // x tile, four pixels of a row per thread (one vector load unless they straddle the row end)
             const int nq = (CI_T * npix) >> 2;
@@ -1189,6 +1323,7 @@ __global__ __launch_bounds__(256, 2) void ukst_grad_weight_mfma_kernel(const TIn
             t.cols4 = a.cols4; t.HC = a.HC; t.LR = a.LR; t.co_first = co0; t.co_end = g.Cout; t.b0 = b0;
             t.oy_base = oy_base; t.ox_base = ox_base; t.dC4 = a.dC4; t.dRowsPerCo = a.dRows; t.dLR = a.dLR;
             stage_dy_tile<8>(dys, dy, g, t, tid);
+        }
         }
         __syncthreads();
         const int wj = g.W - j0 < a.TJ ? g.W - j0 : a.TJ;
@@ -1301,6 +1436,12 @@ bool gw_mfma_args(const Geom& g, GwMfmaArgs& a)
     a.stagesPerSlice = (int)((stages + want - 1) / want);
     a.nSlices = (int)((stages + a.stagesPerSlice - 1) / a.stagesPerSlice);
     a.cols4 = (a.cols + 3) / 4;
+    a.npass = (a.TB * a.LR * a.cols4 + 63) / 64;
+    // piecewise staging: rows of at least four elements (a row-end piece is fetched from inside
+    // the row), tiles of at least four columns, single buffer descriptors (4 bytes per element
+    // bounds both operand types)
+    a.fast = (g.W >= 4 && g.OW >= 4 && a.TJ >= 4 && (size_t)g.B * g.Cin * g.H * g.W * 4 <= 0x7FFFFFF0u &&
+              (size_t)g.B * g.Cout * g.OH * g.OW * 4 <= 0x7FFFFFF0u) ? 1 : 0;
     a.dC4 = make_fastdiv((unsigned)a.cols4);
     a.dRows = make_fastdiv((unsigned)(a.TB * a.LR));
     a.dLR = make_fastdiv((unsigned)a.LR);
@@ -1362,14 +1503,6 @@ struct GwB16Args {
     FastDiv dC8, dRows, dLR;
 };
 
-typedef __bf16 gw_bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 gw_bf16x8u __attribute__((ext_vector_type(8), aligned(2)));
-typedef unsigned gw_u4 __attribute__((ext_vector_type(4)));
-typedef unsigned gw_u4u __attribute__((ext_vector_type(4), aligned(2)));
-typedef unsigned gw_u2 __attribute__((ext_vector_type(2)));
-
-constexpr unsigned kGwInvalid = 0xFFFFFF00u;  // byte offset that is out of range for any buffer
-constexpr int kGwRsrcFlags = 0x00020000;      // raw 32-bit buffer, gfx9 family
 
 // 8 packed 16-bit elements moved s places up (s > 0) or down (s < 0), zeros moving in; 0 < |s| < 8
 __device__ __forceinline__ gw_u4 shift_elements(gw_u4 v, int s)
