@@ -1796,6 +1796,349 @@ hipError_t launch_gw_b16(const GwB16Args& a, const void* x, const void* dy, floa
     return e;
 }
 
+// ------------------------------------------------------------------------------------------
+// Gradient with respect to the kernel for layers with few output channels, on the matrix cores
+// (Cout * n*n <= 64: the last layer of a generator, 64 -> 3 channels; image-to-image layers).
+//
+// With so few output channels the channel axis cannot fill an MFMA tile, but (channel, tap) pairs
+// can -- the mirror image of the thin forward kernel: row r = co * n*n + tap of
+//     DW[r][ci] += sum_pixel DY_r[pixel] * X[ci][pixel],     DY_r[pixel] = dy[co][2i+P-a][2j+P-c]
+// is one row of a v_mfma_f32_32x32x2_f32 tile, each lane reading its own shifted view of the
+// parity-split dy tile.  The four waves of a block take every fourth pixel row of a stage, keep
+// MT x CT accumulator tiles each, and add them through LDS in wave order at the end of the block's
+// slice; blocks write one copy of dw per slice (dw's own layout), ukst_sum_partials_kernel adds
+// the copies in a fixed order.  Staging is the piecewise one of the kernels above.
+struct GwThinArgs {
+    GeomBase g;
+    int TJ, logTJ, TI, logTI, TB, TR, logPix;  // logPix = log2(TR * TJ)
+    int LR, HC, cols, DP, XP;
+    int tilesX, tilesY, nStages, stagesPerSlice, nSlices;
+    int ciTiles;
+    int cols4, npass;
+    FastDiv dC4, dLR;
+};
+
+template <int N, int MT, int CT, typename TIn>
+__global__ __launch_bounds__(256, 2) void ukst_grad_weight_thin_mfma_kernel(const TIn* __restrict__ x,
+                                                                           const TIn* __restrict__ dy,
+                                                                           float* __restrict__ part, GwThinArgs a)
+{
+    constexpr int NN = N * N, CI_T = 32 * CT;
+    constexpr int ES = (int)sizeof(TIn);
+    extern __shared__ __align__(16) float lds_f[];
+    const GeomBase& g = a.g;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, kk = lane >> 5;
+    float* xs = lds_f;                     // [CI_T][XP]
+    float* dys = lds_f + CI_T * a.XP;      // [Cout][DP]
+    const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)x, 0, (int)((size_t)g.B * g.Cin * g.H * g.W * ES), kGwRsrcFlags);
+    const __amdgpu_buffer_rsrc_t rs_dy = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)dy, 0, (int)((size_t)g.B * g.Cout * g.OH * g.OW * ES), kGwRsrcFlags);
+
+    int bid = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int cit = bid % a.ciTiles; bid /= a.ciTiles;
+    const int slice = bid;
+    const int ci0 = cit * CI_T;
+
+    // this lane's rows (channel, tap): LDS offset of its view of the dy tile, -1 if the row does not exist
+    int arow[MT];
+#pragma unroll
+    for (int mi = 0; mi < MT; ++mi) {
+        const int r = mi * 32 + l32, co = r / NN, t = r - co * NN;
+        const int ta = t / N, tc = t - ta * N;
+        arow[mi] = co < g.Cout ? co * a.DP + (N - 1 - ta) * a.cols + ((N - 1 - tc) & 1) * a.HC + ((N - 1 - tc) >> 1) + kk
+                               : -1;
+    }
+    f32x16 acc[MT][CT];
+#pragma unroll
+    for (int mi = 0; mi < MT; ++mi)
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[mi][ct][i] = 0.f;
+
+    const int rowsPerCo = a.TB * a.LR;
+    const int b_lane = l32 * a.XP + kk;
+    auto load_piece = [&](const __amdgpu_buffer_rsrc_t& rs, unsigned voff, unsigned soff) -> Quad {
+        if constexpr (ES == 4) {
+            const gw_u4 t = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soff, 0);
+            return Quad{{__uint_as_float(t.x), __uint_as_float(t.y), __uint_as_float(t.z), __uint_as_float(t.w)}};
+        } else {
+            const gw_u2 t = __builtin_amdgcn_raw_buffer_load_b64(rs, voff, soff, 0);
+            return Quad{{__uint_as_float(t.x << 16), __uint_as_float(t.x & 0xFFFF0000u),
+                         __uint_as_float(t.y << 16), __uint_as_float(t.y & 0xFFFF0000u)}};
+        }
+    };
+    // four elements moved sh places up (sh > 0) or down, zeros moving in; 0 < |sh| < 4
+    auto shifted = [&](const Quad& q, int sh) -> Quad {
+        Quad r;
+#pragma unroll
+        for (int k2 = 0; k2 < 4; ++k2) {
+            const int src = k2 - sh;
+            float v = 0.f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v = src == e ? q.v[e] : v;
+            r.v[k2] = v;
+        }
+        return r;
+    };
+    const int st_end = (slice + 1) * a.stagesPerSlice < a.nStages ? (slice + 1) * a.stagesPerSlice : a.nStages;
+    for (int st = slice * a.stagesPerSlice; st < st_end; ++st) {
+        int t = st;
+        const int tx = t % a.tilesX; t /= a.tilesX;
+        const int ty = t % a.tilesY; t /= a.tilesY;
+        const int b0 = t * a.TB, i0 = ty * a.TI, j0 = tx * a.TJ;
+        const int oy_base = 2 * i0 + g.P - (N - 1), ox_base = 2 * j0 + g.P - (N - 1);
+        __syncthreads();
+        // All loads of a batch (four x pieces per lane, with the first batch four dy pieces) are
+        // requested before the first LDS write.
+        const int logCPC = a.logPix - 2, CPC = 1 << logCPC;  // x pieces per channel
+        const int cw0 = wave * (CI_T / 4);
+        const int xpasses = (((CI_T / 4) << logCPC) + 63) >> 6;
+        const int per_co = rowsPerCo * a.cols4;
+        const unsigned dsoff = (unsigned)wave * (unsigned)(g.OH * g.OW * ES);
+        float* dbase = dys + wave * a.DP;
+        auto x_load = [&](int pass, Quad& q, int& dst, int& sh) {
+            dst = -1;
+            sh = 0;
+            const int flat = lane + 64 * pass;
+            if (pass < xpasses && (flat >> logCPC) < CI_T / 4) {
+                const int cl = cw0 + (flat >> logCPC), pix = (flat & (CPC - 1)) << 2;
+                const int tr = pix >> a.logTJ, lj = pix & (a.TJ - 1);
+                const int b = b0 + (tr >> a.logTI), i = i0 + (tr & (a.TI - 1)), j = j0 + lj, ci = ci0 + cl;
+                const bool ok = ci < g.Cin && b < g.B && i < g.H && j < g.W;
+                const int jl = j > g.W - 4 ? g.W - 4 : j;
+                sh = jl - j;
+                const unsigned voff = ok ? (unsigned)((((b * g.Cin + ci) * g.H + i) * g.W + jl) * ES) : kGwInvalid;
+                q = load_piece(rs_x, voff, 0u);
+                dst = cl * a.XP + pix;
+            }
+        };
+        auto x_store = [&](const Quad& q, int dst, int sh) {
+            if (dst < 0) return;
+            const Quad v = sh != 0 ? shifted(q, sh) : q;
+#pragma unroll
+            for (int k2 = 0; k2 < 4; ++k2) xs[dst + k2] = v.v[k2];
+        };
+        // dy tile: wave w stages output channel w (there are at most four)
+        auto d_load = [&](int pass, Quad& q, int& dst, int& sh, int& nc) {
+            const int idx = lane + 64 * pass;
+            dst = -1;
+            sh = 0;
+            nc = 0;
+            if (wave < g.Cout && idx < per_co) {
+                const int rem = fdiv(idx, a.dC4), m = idx - rem * a.cols4;
+                const int bl = fdiv(rem, a.dLR), rr = rem - bl * a.LR;
+                const int b = b0 + bl, oy = oy_base + rr, ox = ox_base + 4 * m;
+                const bool ok = b < g.B && oy >= 0 && oy < g.OH && ox + 3 >= 0 && ox < g.OW;
+                const int oxl = ox < 0 ? 0 : (ox > g.OW - 4 ? g.OW - 4 : ox);
+                sh = oxl - ox;
+                const unsigned voff = ok ? (unsigned)((((b * g.Cout) * g.OH + oy) * g.OW + oxl) * ES) : kGwInvalid;
+                q = load_piece(rs_dy, voff, dsoff);
+                dst = rem * a.cols + 2 * m;
+                nc = a.cols - 4 * m;
+            }
+        };
+        auto d_store = [&](const Quad& q, int dst, int sh, int nc) {
+            if (dst < 0) return;
+            const Quad v = sh != 0 ? shifted(q, sh) : q;
+            dbase[dst] = v.v[0];
+            dbase[dst + a.HC] = v.v[1];
+            if (nc > 2) {
+                dbase[dst + 1] = v.v[2];
+                dbase[dst + a.HC + 1] = v.v[3];
+            }
+        };
+        {
+            Quad xq[4], dq[4];
+            int xd[4], xsft[4], dd[4], dsft[4], dn[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) x_load(u, xq[u], xd[u], xsft[u]);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) d_load(u, dq[u], dd[u], dsft[u], dn[u]);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) x_store(xq[u], xd[u], xsft[u]);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) d_store(dq[u], dd[u], dsft[u], dn[u]);
+        }
+        for (int p0 = 4; p0 < xpasses; p0 += 4) {  // further batches
+            Quad xq[4];
+            int xd[4], xsft[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) x_load(p0 + u, xq[u], xd[u], xsft[u]);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) x_store(xq[u], xd[u], xsft[u]);
+        }
+        for (int p0 = 4; p0 < a.npass; p0 += 4) {
+            Quad dq[4];
+            int dd[4], dsft[4], dn[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) d_load(p0 + u, dq[u], dd[u], dsft[u], dn[u]);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) d_store(dq[u], dd[u], dsft[u], dn[u]);
+        }
+        __syncthreads();
+        const int wj = g.W - j0 < a.TJ ? g.W - j0 : a.TJ;
+        const int steps = (wj + 1) >> 1;
+        for (int tr = wave; tr < a.TR; tr += 4) {  // every fourth pixel row of the stage
+            const int bl = tr >> a.logTI, li = tr & (a.TI - 1);
+            if (b0 + bl >= g.B || i0 + li >= g.H) continue;  // uniform
+            const float* ap = dys + (bl * a.LR + 2 * li) * a.cols;
+            const float* bp = xs + b_lane + tr * a.TJ;
+            for (int sp = 0; sp < steps; ++sp) {
+                float bv[CT], av[MT];
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) bv[ct] = bp[ct * 32 * a.XP + 2 * sp];
+#pragma unroll
+                for (int mi = 0; mi < MT; ++mi) av[mi] = arow[mi] >= 0 ? ap[arow[mi] + 2 * sp] : 0.f;
+#pragma unroll
+                for (int mi = 0; mi < MT; ++mi)
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct)
+                        acc[mi][ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mi], bv[ct], acc[mi][ct], 0, 0, 0);
+            }
+        }
+    }
+
+    // the four waves' sums meet in LDS: waves 1..3 park theirs, wave 0 adds them in that order
+    __syncthreads();
+    constexpr int TILE = 16 * 64;  // floats of one accumulator tile over the wave
+    if (wave > 0) {
+#pragma unroll
+        for (int mi = 0; mi < MT; ++mi)
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    lds_f[((wave - 1) * MT * CT + mi * CT + ct) * TILE + i * 64 + lane] = acc[mi][ct][i];
+    }
+    __syncthreads();
+    if (wave != 0) return;
+    // accumulator register i: row 8*(i/4) + 4*kk + (i%4) of the tile's 32, input channel l32
+    float* out = part + (size_t)slice * g.Cout * g.Cin * NN;
+#pragma unroll
+    for (int mi = 0; mi < MT; ++mi)
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+            const int ci = ci0 + ct * 32 + l32;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                float v = acc[mi][ct][i];
+#pragma unroll
+                for (int w2 = 0; w2 < 3; ++w2) v += lds_f[(w2 * MT * CT + mi * CT + ct) * TILE + i * 64 + lane];
+                const int r = mi * 32 + 8 * (i / 4) + 4 * kk + (i % 4);
+                const int co = r / NN, tap = r - co * NN;
+                if (co < g.Cout && ci < g.Cin) out[((size_t)co * g.Cin + ci) * NN + tap] = v;
+            }
+        }
+}
+
+template <int N>
+bool gw_thin_args(const Geom& g, GwThinArgs& a, int CT)
+{
+    constexpr int NN = N * N;
+    if (g.Cout > 4 || g.Cout * NN > 64) return false;
+    if (g.Cin < 16) return false;  // fewer input channels leave the MFMA columns empty: the vector ALUs are faster
+    if (g.W < 4 || g.OW < 4) return false;  // piecewise staging: rows of at least four elements
+    if ((size_t)g.B * g.Cin * g.H * g.W * 4 > 0x7FFFFFF0u || (size_t)g.B * g.Cout * g.OH * g.OW * 4 > 0x7FFFFFF0u)
+        return false;
+    const int CI_T = 32 * CT;
+    a.g = g;
+    a.TJ = pow2_ceil(g.W < 32 ? g.W : 32);
+    if (a.TJ < 4) a.TJ = 4;
+    a.logTJ = log2_of(a.TJ);
+    a.HC = a.TJ + N / 2;
+    a.cols = 2 * a.HC;
+    const size_t budget = 64 * 1024;
+    int TR = 256 / a.TJ;  // at most 256 pixels per stage; at least 4 rows so that every wave has one
+    if (TR < 4) TR = 4;
+    for (;; TR >>= 1) {
+        if (TR < 4) return false;
+        a.TI = pow2_ceil(g.H < TR ? g.H : TR);
+        a.TB = TR / a.TI;
+        a.LR = 2 * a.TI + N - 2;
+        a.DP = (a.TB * a.LR * a.cols) | 1;
+        a.XP = (TR * a.TJ) | 1;
+        if ((size_t)4 * (CI_T * a.XP + g.Cout * a.DP) <= budget) break;
+    }
+    a.TR = TR;
+    a.logTI = log2_of(a.TI);
+    a.logPix = log2_of(TR * a.TJ);
+    a.tilesX = (g.W + a.TJ - 1) / a.TJ;
+    a.tilesY = (g.H + a.TI - 1) / a.TI;
+    const long long stages = (long long)a.tilesX * a.tilesY * ((g.B + a.TB - 1) / a.TB);
+    if (stages > 0x7fffffffLL) return false;
+    a.nStages = (int)stages;
+    a.ciTiles = (g.Cin + CI_T - 1) / CI_T;
+    long long want = 1024 / (long long)a.ciTiles;  // blocks to cover the chip four times
+    if (want < 1) want = 1;
+    if (want > stages) want = stages;
+    a.stagesPerSlice = (int)((stages + want - 1) / want);
+    a.nSlices = (int)((stages + a.stagesPerSlice - 1) / a.stagesPerSlice);
+    a.cols4 = (a.cols + 3) / 4;
+    a.npass = (a.TB * a.LR * a.cols4 + 63) / 64;
+    a.dC4 = make_fastdiv((unsigned)a.cols4);
+    a.dLR = make_fastdiv((unsigned)a.LR);
+    if ((size_t)g.Cout * g.Cin * NN > 0x7fffffffu) return false;
+    return true;
+}
+
+template <int N, int MT, int CT, typename TIn>
+hipError_t launch_gw_thin_t(const GwThinArgs& a, const void* x, const void* dy, float* dw, Workspace& ws,
+                            hipStream_t stream)
+{
+    const GeomBase& g = a.g;
+    const size_t elems = (size_t)g.Cout * g.Cin * N * N;
+    const int copies = a.nSlices;
+    const size_t need = elems * copies * sizeof(float);  // one copy of dw per slice
+    if (ws.query) { ws.need = need; return hipSuccess; }
+    if (ws.bytes < need) return kWorkspaceTooSmall;
+    float* part = (float*)ws.ptr;
+    size_t lds = (size_t)4 * (32 * CT * a.XP + g.Cout * a.DP);
+    const size_t red = (size_t)3 * MT * CT * 16 * 64 * 4;  // three waves' accumulators
+    if (lds < red) lds = red;
+    const void* kfn = (const void*)ukst_grad_weight_thin_mfma_kernel<N, MT, CT, TIn>;
+    hipError_t e = hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    const unsigned nb = (unsigned)((long long)a.nSlices * a.ciTiles);
+    hipLaunchKernelGGL((ukst_grad_weight_thin_mfma_kernel<N, MT, CT, TIn>), dim3(nb), dim3(256), lds, stream,
+                       (const TIn*)x, (const TIn*)dy, part, a);
+    e = hipGetLastError();
+    if (e == hipSuccess) {
+        int logR = 0;  // lanes per element: until the sum kernel has about 64k threads
+        while (logR < 8 && (elems << logR) < 65536 && (2 << logR) <= copies) ++logR;
+        const unsigned per_block = 256u >> logR;
+        hipLaunchKernelGGL(ukst_sum_partials_kernel, dim3((unsigned)((elems + per_block - 1) / per_block)),
+                           dim3(256), 0, stream, (const float*)part, dw, (int)elems, copies, logR);
+        e = hipGetLastError();
+    }
+    return e;
+}
+
+// true (and a filled description) if the thin matrix-core kernel gradient takes the layer
+template <int N>
+bool gw_thin_pick(const Geom& g, GwThinArgs& a, int& MT, int& CT)
+{
+    if constexpr (N < 2 || N > 5) return false;
+    else {
+        CT = g.Cin > 32 ? 2 : 1;
+        MT = g.Cout * N * N > 32 ? 2 : 1;
+        return gw_thin_args<N>(g, a, CT);
+    }
+}
+
+template <int N, typename TIn>
+hipError_t launch_gw_thin(const GwThinArgs& a, int MT, int CT, const void* x, const void* dy, float* dw,
+                          Workspace& ws, hipStream_t stream)
+{
+    if (MT == 1 && CT == 1) return launch_gw_thin_t<N, 1, 1, TIn>(a, x, dy, dw, ws, stream);
+    if (MT == 1 && CT == 2) return launch_gw_thin_t<N, 1, 2, TIn>(a, x, dy, dw, ws, stream);
+    if (MT == 2 && CT == 1) return launch_gw_thin_t<N, 2, 1, TIn>(a, x, dy, dw, ws, stream);
+    return launch_gw_thin_t<N, 2, 2, TIn>(a, x, dy, dw, ws, stream);
+}
+
 template <int N, int CO_R, int CI_R, typename TIn>
 hipError_t launch_gw(const Geom& g, const void* x, const void* dy, float* dw, Workspace& ws,
                      hipStream_t stream)
@@ -1885,6 +2228,11 @@ hipError_t launch_gw_n(const Geom& g, const void* x, const void* dy, float* dw, 
         GwMfmaArgs ma;
         if (gw_mfma_args<gw_nc(N)>(g, ma)) return launch_gw_mfma<N, TIn>(ma, x, dy, dw, ws, stream);
     }
+    if constexpr (N >= 2 && N <= 5) {
+        GwThinArgs ta;  // few output channels: (channel, tap) pairs as MFMA rows
+        int MT = 1, CT = 1;
+        if (gw_thin_pick<N>(g, ta, MT, CT)) return launch_gw_thin<N, TIn>(ta, MT, CT, x, dy, dw, ws, stream);
+    }
     constexpr int CO_W = N <= 3 ? 4 : N <= 5 ? 2 : 1;  // wide register block: CO_W x 4 pairs
     const bool thin_o = g.Cout <= 4, thin_i = g.Cin <= 4;
     if (thin_o && thin_i) return launch_gw<N, 1, 1, TIn>(g, x, dy, dw, ws, stream);
@@ -1918,7 +2266,12 @@ const char* grad_kernel_name(const Geom& g, int which, int dtype)
         if (dtype == 1 && gw_b16_args(g, ba)) return "ukst_grad_weight_mfma_bf16_kernel";
         GwMfmaArgs wa;
         const bool m = g.n <= 4 ? gw_mfma_args<gw_nc(4)>(g, wa) : gw_mfma_args<gw_nc(5)>(g, wa);
-        return m ? "ukst_grad_weight_mfma_kernel" : "ukst_grad_weight_kernel";
+        if (m) return "ukst_grad_weight_mfma_kernel";
+        GwThinArgs ta;
+        int MT = 1, CT = 1;
+        const bool th = g.n == 2 ? gw_thin_pick<2>(g, ta, MT, CT) : g.n == 3 ? gw_thin_pick<3>(g, ta, MT, CT)
+                      : g.n == 4 ? gw_thin_pick<4>(g, ta, MT, CT) : g.n == 5 ? gw_thin_pick<5>(g, ta, MT, CT) : false;
+        return th ? "ukst_grad_weight_thin_mfma_kernel" : "ukst_grad_weight_kernel";
     }
     GiMfmaArgs ma;
     if (dtype == 1 && gi_mfma_args(g, ma, true)) return "ukst_grad_input_mfma_bf16_kernel";

@@ -219,9 +219,12 @@ def test_backward_kernel_selection_is_host_arithmetic():
     def shape(k):
         return (w[k].B, w[k].Cin, w[k].Cout, w[k].H, w[k].W, w[k].n, w[k].P)
     assert name(0, *shape("cfg2a"), ukst.UKST_F32) == "ukst_grad_input_kernel"
-    assert name(1, *shape("cfg2a"), ukst.UKST_F32) == "ukst_grad_weight_kernel"
+    assert name(1, *shape("cfg2a"), ukst.UKST_F32) == "ukst_grad_weight_kernel"      # 3 input channels
     assert name(0, *shape("cfg3_L4"), ukst.UKST_F32) == "ukst_grad_input_kernel"      # Cout = 3
-    assert name(1, *shape("cfg3_L4"), ukst.UKST_F32) == "ukst_grad_weight_kernel"
+    assert name(1, *shape("cfg3_L4"), ukst.UKST_F32) == "ukst_grad_weight_thin_mfma_kernel"  # 3 x 16 rows
+    assert name(1, 2, 16, 5, 16, 16, 4, 2, ukst.UKST_F32) == "ukst_grad_weight_kernel"   # 5 x 16 rows: too many
+    assert name(1, 2, 16, 3, 16, 2, 3, 0, ukst.UKST_F32) == "ukst_grad_weight_kernel"    # rows of two pixels
+    assert name(1, 2, 16, 3, 16, 16, 3, 0, ukst.UKST_F32) == "ukst_grad_weight_thin_mfma_kernel"
     for k in ("cfg3_L1", "cfg3_L2", "cfg3_L3", "cfg4a", "cfg4b"):
         assert name(0, *shape(k), ukst.UKST_F32) == "ukst_grad_input_mfma_kernel", k
         assert name(1, *shape(k), ukst.UKST_F32) == "ukst_grad_weight_mfma_kernel", k

@@ -88,6 +88,26 @@ def test_backward_bf16_kernel_gradient_on_the_bf16_matrix_pipe(shape):
     _both(w, integer=False)
 
 
+@pytest.mark.parametrize("shape", [
+    (2, 64, 3, 8, 8, 4, 2),        # the last generator layer in small: 3 x 16 (channel, tap) rows, two channel tiles
+    (3, 16, 4, 5, 9, 4, 1),        # four output channels fill both row tiles; odd P, rows that are no multiple of 4
+    (2, 40, 2, 7, 37, 5, 0),       # n = 5: 2 x 25 rows; two column tiles, ragged row ends
+    (1, 100, 3, 33, 6, 3, 3),      # n = 3: one row tile; several row tiles of a narrow map, two channel tiles
+    (5, 24, 1, 2, 4, 2, 0),        # a single output channel, rows of exactly four pixels
+    (2, 32, 4, 12, 64, 4, 2)])     # several stages per slice
+def test_backward_thin_kernel_gradient_on_the_matrix_cores(shape):
+    """Few output channels, at least 16 input channels, 2 <= n <= 5, rows of at least four pixels:
+    (channel, tap) pairs fill the MFMA rows of the kernel gradient.  Every element, integer data
+    exactly, fp32 and bf16 operands."""
+    B, Cin, Cout, H, W, n, P = shape
+    assert ukst.ukst_grad_kernel_name(1, B, Cin, Cout, H, W, n, P, ukst.UKST_F32) == \
+        "ukst_grad_weight_thin_mfma_kernel"
+    w = _mk("bwd_thin_gw", 6700 + sum(shape), B, Cin, Cout, H, W, n, P)
+    _both(w, integer=True)
+    _both(w, integer=False)
+    _both(w.with_(dtype="bf16"), integer=False)
+
+
 def test_backward_cfg2_images_full_size():
     for name in ("cfg2a", "cfg2b"):
         _both(wl.WORKLOADS[name], guard=1 << 16)
