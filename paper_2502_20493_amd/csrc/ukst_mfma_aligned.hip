@@ -10,7 +10,8 @@
 // of a quad therefore read a 3x3 input window: class (rr, cc) multiplies window position (a, b),
 // a - rr and b - cc in {0, 1}, by tap w[2a - rr][2b - cc] (Eqs. 1-4).  One B fragment (activations
 // at window position (a, b), 16 channels) feeds 1, 2 or 4 classes: 16 MFMA groups per K step as
-// before, 9 B fragment positions instead of 4 (fragment reads are cheap next to the rest).
+// before, 9 window positions instead of 4 -- but column-neighbouring quads share window columns,
+// and a lane holds two such quads, so a K step reads 24 B fragments for its 4 accumulator tiles.
 //
 // Lanes of two neighbouring accumulator tiles hold column-neighbouring quads, so the drain writes
 // four consecutive output floats (both column classes of two quads) as one aligned 16-byte store:
@@ -79,11 +80,7 @@ constexpr Grp kGrp[16] = {{0, 0, 0, 0}, {0, 1, 0, 0}, {0, 1, 0, 1}, {0, 2, 0, 1}
                           {1, 0, 0, 0}, {1, 0, 1, 0}, {1, 1, 0, 0}, {1, 1, 0, 1},
                           {1, 1, 1, 0}, {1, 1, 1, 1}, {1, 2, 0, 1}, {1, 2, 1, 1},
                           {2, 0, 1, 0}, {2, 1, 1, 0}, {2, 1, 1, 1}, {2, 2, 1, 1}};
-constexpr int grp_pos(int g) { return kGrp[g].a * 3 + kGrp[g].b; }
 constexpr int grp_tap(int g) { return (2 * kGrp[g].a - kGrp[g].rr) * 4 + (2 * kGrp[g].b - kGrp[g].cc); }
-// true if group g is the first group of its window position
-constexpr bool grp_first(int g) { return g == 0 || grp_pos(g) != grp_pos(g - 1); }
-
 // EPI: the fused epilogue (bias, activation) is compiled into the drain.  OUT16: y is bf16, each
 // sum rounded once (to nearest even) at the store.
 template <bool EPI, bool OUT16>
@@ -180,7 +177,7 @@ void ukst_mfma_bf16_aligned_kernel(const uint16_t* __restrict__ x, const uint16_
     const int stages_even = (stages + 1) & ~1;  // an odd count is padded with a stage of zeros
     u4v wreg[2][8], xreg[2][8];
     f32x16 acc[4][2][2];
-    int b_lds[4][3];  // per accumulator tile and window column b: LDS byte address at window row 0
+    int b_lds[2][4];  // per pair of accumulator tiles (2h, 2h+1) and column j of their joint window: LDS byte address at window row 0
 
     auto load_one = [&](int ci0, unsigned wv, unsigned xv, int j, u4v (&wr)[8], u4v (&xr)[8]) {
         if (j < 8)
@@ -200,62 +197,59 @@ void ukst_mfma_bf16_aligned_kernel(const uint16_t* __restrict__ x, const uint16_
     auto a_frag = [&](int buf, int grp) {
         return *reinterpret_cast<const bf16x8*>(lds + buf * WS_STAGE + a_lds + grp_tap(grp) * W_PLANE);
     };
-    auto b_frag = [&](int buf, int pos, int nt) {
-        return *reinterpret_cast<const bf16x8*>(lds + b_lds[nt][pos % 3] + (pos / 3) * xrow_lds +
-                                                buf * XS_STAGE_MAX);
+    // B fragment: window row a, tile pair h, column j of the pair's joint window
+    auto b_frag = [&](int buf, int a_row, int h, int j) {
+        return *reinterpret_cast<const bf16x8*>(lds + b_lds[h][j] + a_row * xrow_lds + buf * XS_STAGE_MAX);
     };
     // one K stage; `set` is a literal at every call site so that all indices fold.  (ci_next, wv,
     // xv) describe the stage requested from memory during this one.
+    // Tiles 2h and 2h+1 hold column-neighbouring quads, so window column b of the odd tile is window
+    // column b + 1 of the even one: a tile pair reads 4 distinct columns per window row instead of
+    // 2 x 3, 24 B fragments per K step instead of 36 (the fragment reads, not the MFMAs, were what
+    // filled LDS: 68 KiB per wave and stage against 128 B/clk).  Position (a, b) of tile nt uses
+    // column j = b + (nt & 1) of pair nt >> 1.  The 8 fragments of a window row sit in one of two
+    // register sets; the next row's are read while this row's groups multiply.
     auto stage = [&](int set, int ci_next, unsigned wv, unsigned xv) {
-        bf16x8 bf[3][4], af[3];  // B fragments of up to three window positions in flight
+        bf16x8 fr[2][2][4], af[3];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) bf[0][i] = b_frag(set, grp_pos(0), i);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) bf[1][i] = b_frag(set, grp_pos(1), i);
+        for (int i = 0; i < 8; ++i) fr[0][i >> 2][i & 3] = b_frag(set, 0, i >> 2, i & 3);
         af[0] = a_frag(set, 0);
         af[1] = a_frag(set, 1);
 #pragma unroll
         for (int grp = 0; grp < 16; ++grp) {
-            const int pos = grp_pos(grp), rr = kGrp[grp].rr, cc = kGrp[grp].cc;
-            // number of window positions started before this group: its fragments sit in bf[ord % 3]
-            int ord = 0;
-#pragma unroll
-            for (int t = 1; t <= grp; ++t) ord += grp_first(t) ? 1 : 0;
+            const int wa = kGrp[grp].a, wb = kGrp[grp].b, rr = kGrp[grp].rr, cc = kGrp[grp].cc;
             // A wave issues in order and waits for the matrix pipe at every MFMA, so the other
             // instructions are spread one by one into the shadows of the four MFMAs of a group:
-            // one global load | fragment reads for two groups ahead | v_perm | LDS write.  (All 16
-            // loads in the first groups of a stage, for a longer flight time, was measured slower:
-            // several memory instructions in one MFMA shadow hold up the next MFMA.)
+            // one global load | fragment reads | v_perm | LDS write.  (All 16 loads in the first
+            // groups of a stage, for a longer flight time, was measured slower: several memory
+            // instructions in one MFMA shadow hold up the next MFMA.)
             auto mfma = [&](int nt) {
                 __builtin_amdgcn_sched_barrier(0);
                 acc[nt][rr][cc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    af[grp % 3], bf[ord % 3][nt], acc[nt][rr][cc], 0, 0, 0);
+                    af[grp % 3], fr[wa & 1][nt >> 1][wb + (nt & 1)], acc[nt][rr][cc], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             };
-            // fragments of the window position that starts two groups ahead: one read per slot
-            const bool bnext = grp + 2 < 16 && grp_first(grp + 2);
-            const int posn = grp_pos(grp + 2 < 16 ? grp + 2 : 0);
-            int ordn = 0;
-#pragma unroll
-            for (int t = 1; t <= grp + 2 && t < 16; ++t) ordn += grp_first(t) ? 1 : 0;
+            // fragments of the next window row: row 0's four groups read two each, row 1's eight
+            // groups one each, into the set the row before this one has left
+            auto next_row = [&](int i) {
+                fr[(wa + 1) & 1][i >> 2][i & 3] = b_frag(set, wa + 1, i >> 2, i & 3);
+            };
             mfma(0);
             load_one(ci_next, wv, xv, grp, wreg[set], xreg[set]);
-            if (bnext) bf[ordn % 3][0] = b_frag(set, posn, 0);
+            if (wa == 0) next_row(2 * grp);
+            if (wa == 1) next_row(grp - 4);
             mfma(1);
-            if (bnext) bf[ordn % 3][1] = b_frag(set, posn, 1);
+            if (wa == 0) next_row(2 * grp + 1);
             if (grp + 2 < 16) af[(grp + 2) % 3] = a_frag(set, grp + 2);
             mfma(2);
-            if (bnext) bf[ordn % 3][2] = b_frag(set, posn, 2);
             const u4v t = grp < 8 ? transposed_row(wreg[set ^ 1], grp)
                                   : transposed_row(xreg[set ^ 1], grp - 8);
             mfma(3);
-            if (bnext) bf[ordn % 3][3] = b_frag(set, posn, 3);
             if (grp < 8)
                 *reinterpret_cast<u4v*>(lds + (set ^ 1) * WS_STAGE + w_lds + grp * W_PLANE) = t;
             else
                 *reinterpret_cast<u4v*>(lds + (set ^ 1) * XS_STAGE_MAX + ((grp & 1) ? x_lds1 : x_lds0) +
                                         ((grp - 8) >> 1) * 16) = t;
-            (void)pos;
         }
         __builtin_amdgcn_sched_barrier(0);
     };
@@ -294,18 +288,18 @@ void ukst_mfma_bf16_aligned_kernel(const uint16_t* __restrict__ x, const uint16_
         const int bf0 = fdiv(q0, a.dKHW), kf0 = fdiv(q0 - bf0 * KHW, a.dKW);
         const int e_first = bf0 * a.EH + kf0;
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt) {
-            int q = q0 + qh * 128 + 64 * (nt >> 1) + 2 * l32 + (nt & 1);
-            if (q > q_last) q = q_last;
+        for (int h = 0; h < 2; ++h) {
+            int q = q0 + qh * 128 + 64 * h + 2 * l32;  // the even quad of the lane's pair
+            if (q > q_last) q = q_last;                 // (past the end of the batch: results dropped)
             const int b = fdiv(q, a.dKHW);
             const int rem = q - b * KHW;
             const int ky = fdiv(rem, a.dKW), kx = rem - ky * a.KWa;
             const int r = b * a.EH + ky - e_first;  // staged row of window row 0
 #pragma unroll
-            for (int bb = 0; bb < 3; ++bb) {
-                const int c = kx - a.HP + a.OFFS + bb;  // staged column of window column bb
+            for (int j = 0; j < 4; ++j) {
+                const int c = kx - a.HP + a.OFFS + j;  // staged column of joint window column j
                 const int slot = (c & 1) * a.HS + (c >> 1);
-                b_lds[nt][bb] = XS_OFF + ((gk * a.ROWS + r) * a.LWS + slot) * 16;
+                b_lds[h][j] = XS_OFF + ((gk * a.ROWS + r) * a.LWS + slot) * 16;
             }
         }
 #pragma unroll
