@@ -36,6 +36,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef unsigned u2v __attribute__((ext_vector_type(2)));
 typedef unsigned u4v __attribute__((ext_vector_type(4)));
+typedef const float __attribute__((address_space(4)))* bias_cptr;
 
 constexpr int kRsrcFlags = 0x00020000;      // raw 32-bit buffer, gfx9 family
 constexpr unsigned kInvalid = 0xFFFFFF00u;  // byte offset that is out of range for any buffer
@@ -364,7 +365,15 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
                 const unsigned soff = (unsigned)(8 * (i / 4) + (i % 4)) * plane;
                 float bv = 0.f;
                 if constexpr (ACT >= 0)
-                    if (ep.bias) bv = ep.bias[co0 + cw * 32 + 8 * (i / 4) + 4 * gk + (i % 4)];
+                    if (ep.bias) {
+                        // both candidates through wave-uniform indices of a constant-address-space
+                        // view (the bias is never written here): scalar loads, which do not queue
+                        // behind the drain's stores the way a per-lane vector load would
+                        const int ch = co0 + cw * 32 + 8 * (i / 4) + (i % 4);
+                        const bias_cptr bp = (bias_cptr)(unsigned long long)ep.bias;
+                        const float b_lo = bp[ch], b_hi = bp[ch + 4];
+                        bv = gk ? b_hi : b_lo;
+                    }
 #pragma unroll
                 for (int r = 1; r >= 0; --r)
 #pragma unroll
