@@ -76,6 +76,45 @@ __device__ __forceinline__ u4v transposed_row(const u4v (&in)[8], int k)
     return t;
 }
 
+// The MFMA groups of a K step: one group = one parity class c = 2r + s at one window position
+// p = u * HI + v that holds a tap for it, w[r + 2u][s + 2v] (Eqs. 1-4): 16 groups for n = 4 (every
+// class has 2 x 2 taps), 9 for n = 3 (4 / 2 / 2 / 1 taps: the classes of Sec. 3.2 with unequal
+// sub-kernels).  Groups are ordered by window position so that a B fragment is fetched once.
+constexpr bool grp_valid(int n, int p, int c)
+{
+    const int hi = (n + 1) / 2, u = p / hi, v = p % hi, r = c >> 1, sc = c & 1;
+    return r + 2 * u < n && sc + 2 * v < n;
+}
+constexpr int grp_count(int n)
+{
+    const int hi = (n + 1) / 2;
+    int k = 0;
+    for (int p = 0; p < hi * hi; ++p)
+        for (int c = 0; c < 4; ++c) k += grp_valid(n, p, c) ? 1 : 0;
+    return k;
+}
+// group gi -> p * 4 + c
+constexpr int grp_at(int n, int gi)
+{
+    const int hi = (n + 1) / 2;
+    int k = 0;
+    for (int p = 0; p < hi * hi; ++p)
+        for (int c = 0; c < 4; ++c)
+            if (grp_valid(n, p, c)) {
+                if (k == gi) return p * 4 + c;
+                ++k;
+            }
+    return -1;
+}
+// how many groups of the same window position come before group gi
+constexpr int grp_rank(int n, int gi)
+{
+    const int p = grp_at(n, gi) >> 2;
+    int k = 0;
+    for (int j = 0; j < gi; ++j) k += (grp_at(n, j) >> 2) == p ? 1 : 0;
+    return k;
+}
+
 // EPI: the fused epilogue (bias, activation) is compiled into the drain; the plain instance keeps
 // the register allocation of its drain to itself.  OUT16: y is bf16, each sum rounded once (to
 // nearest even) at the store, the two column classes of a quad packed into one 4-byte store.
@@ -84,7 +123,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w,
                            void* __restrict__ y, MfmaArgs a, Epilogue ep)
 {
-    static_assert(N == 4, "bf16 MFMA path: in-register sub-kernel gather is written for n = 4");
+    static_assert(N == 4 || N == 3, "bf16 MFMA path: the in-register sub-kernel gather handles 9 or 16 taps");
     constexpr int HI = (N + 1) / 2;
     constexpr int NN = N * N;
     constexpr int WS_STAGE = 2 * W_HALF;  // 33408 bytes: [k-half][tap][channel][8 ci]
@@ -132,7 +171,11 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
     // the planes are skewed so that the 16 lanes of a write phase (4 channels x g x h) hit
     // distinct bank groups: co -> +1 slot, g -> +4 slots, h (8 planes) -> +8 slots (mod 16).
     const int w_co = tid >> 2, w_g = (tid >> 1) & 1, w_h = tid & 1;
-    const int w_lds = w_g * W_HALF + (8 * w_h) * W_PLANE + w_co * 16;  // + t * W_PLANE
+    // n = 4: the tap-halves are taps 0-7 and 8-15.  n = 3 (9 taps, 18-byte rows, 16-byte loads at
+    // 2-byte alignment): half 0 fetches taps 0-7, half 1 taps 1-8, whose rows go to planes 1-8 --
+    // planes 1-7 are written twice with the same values, plane 8 is tap 8.
+    constexpr int W_H_PLANES = N == 4 ? 8 : 1, W_H_BYTES = N == 4 ? 16 : 2;
+    const int w_lds = w_g * W_HALF + (W_H_PLANES * w_h) * W_PLANE + w_co * 16;  // + t * W_PLANE
     // activations: thread = (8-column group c8, row r, k-half g), c8 fastest so that lanes walk
     // contiguous memory; threads beyond the unit count repeat a unit (same loads, same LDS
     // writes, no branch).  Column c sits in slot c + c/8: the pad slot after every 8 columns
@@ -150,7 +193,7 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
 
     // global offsets of this thread's staging units for tile (cb, qt)
     auto staging_offsets = [&](int cb, int qt, unsigned& wv, unsigned& xv) {
-        wv = (unsigned)(((cb * TM + w_co) * g.Cin + 8 * w_g) * (NN * 2) + w_h * 16);
+        wv = (unsigned)(((cb * TM + w_co) * g.Cin + 8 * w_g) * (NN * 2) + w_h * W_H_BYTES);
         const int q0 = qt * TN;
         const int bf = fdiv(q0, a.dKHW), kf = fdiv(q0 - bf * KHW, a.dKW);
         const int e = bf * a.EH + kf + x_r;  // input row index over the whole batch
@@ -214,14 +257,18 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
     // one K stage; `set` is a literal at every call site so that all indices fold.  (ci_next, wv,
     // xv) describe the stage requested from memory during this one.
     auto stage = [&](int set, int ci_next, unsigned wv, unsigned xv) {
+        constexpr int NG = grp_count(N);  // 16 or 9
         bf16x8 bf[2][4], af[3];
 #pragma unroll
         for (int i = 0; i < 4; ++i) bf[0][i] = b_frag(set, 0, i);
-        af[0] = a_frag(set, 0, 0);
-        af[1] = a_frag(set, 0, 1);
+        af[0] = a_frag(set, grp_at(N, 0) >> 2, grp_at(N, 0) & 3);
+        af[1] = a_frag(set, grp_at(N, 1) >> 2, grp_at(N, 1) & 3);
 #pragma unroll
-        for (int grp = 0; grp < 16; ++grp) {
-            const int p = grp >> 2, c = grp & 3;
+        for (int gi = 0; gi < NG; ++gi) {
+            const int p = grp_at(N, gi) >> 2, c = grp_at(N, gi) & 3, rank = grp_rank(N, gi);
+            // the 16 staging items of a stage (8 weight rows, 8 activation rows) are dealt to
+            // the groups: one each for n = 4, one or two for n = 3
+            const int it0 = gi * 16 / NG, it1 = (gi + 1) * 16 / NG;
             // A wave issues in order and waits for the matrix pipe at every MFMA, so the other
             // instructions are spread one by one into the shadows of the four MFMAs of a group:
             // global load | fragment reads (two groups ahead: LDS latency under load exceeds
@@ -229,26 +276,35 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
             auto mfma = [&](int nt) {
                 __builtin_amdgcn_sched_barrier(0);
                 acc[nt][c >> 1][c & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    af[grp % 3], bf[p & 1][nt], acc[nt][c >> 1][c & 1], 0, 0, 0);
+                    af[gi % 3], bf[p & 1][nt], acc[nt][c >> 1][c & 1], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             };
+            auto item_row = [&](int it) {
+                return it < 8 ? transposed_row(wreg[set ^ 1], it) : transposed_row(xreg[set ^ 1], it - 8);
+            };
+            auto item_write = [&](int it, const u4v& t) {
+                if (it < 8)
+                    *reinterpret_cast<u4v*>(lds + (set ^ 1) * WS_STAGE + w_lds + it * W_PLANE) = t;
+                else
+                    *reinterpret_cast<u4v*>(lds + XS_OFF + (set ^ 1) * XS_STAGE_MAX + x_lds + (it - 8) * 16) = t;
+            };
             mfma(0);
-            load_one(ci_next, wv, xv, grp, wreg[set], xreg[set]);
+            load_one(ci_next, wv, xv, it0, wreg[set], xreg[set]);
             mfma(1);
-            if (grp + 2 < 16) af[(grp + 2) % 3] = a_frag(set, (grp + 2) >> 2, (grp + 2) & 3);
-            if (p + 1 < 4 && c < 2) {
-                bf[(p + 1) & 1][2 * c] = b_frag(set, p + 1, 2 * c);
-                bf[(p + 1) & 1][2 * c + 1] = b_frag(set, p + 1, 2 * c + 1);
+            if (gi + 2 < NG) af[(gi + 2) % 3] = a_frag(set, grp_at(N, gi + 2) >> 2, grp_at(N, gi + 2) & 3);
+            // the first two groups of a window position fetch the next position's fragments
+            if (p + 1 < HI * HI && rank < 2) {
+                bf[(p + 1) & 1][2 * rank] = b_frag(set, p + 1, 2 * rank);
+                bf[(p + 1) & 1][2 * rank + 1] = b_frag(set, p + 1, 2 * rank + 1);
             }
+            if (it1 - it0 > 1) load_one(ci_next, wv, xv, it0 + 1, wreg[set], xreg[set]);
             mfma(2);
-            const u4v t = grp < 8 ? transposed_row(wreg[set ^ 1], grp)
-                                  : transposed_row(xreg[set ^ 1], grp - 8);
+            const u4v t0 = item_row(it0);
+            u4v t1 = t0;
+            if (it1 - it0 > 1) t1 = item_row(it0 + 1);
             mfma(3);
-            if (grp < 8)
-                *reinterpret_cast<u4v*>(lds + (set ^ 1) * WS_STAGE + w_lds + grp * W_PLANE) = t;
-            else
-                *reinterpret_cast<u4v*>(lds + XS_OFF + (set ^ 1) * XS_STAGE_MAX + x_lds +
-                                        (grp - 8) * 16) = t;
+            item_write(it0, t0);
+            if (it1 - it0 > 1) item_write(it0 + 1, t1);
         }
         __builtin_amdgcn_sched_barrier(0);
     };
@@ -416,7 +472,7 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
 bool make_args(const Geom& g, int dtype, MfmaArgs& a)
 {
     if (dtype != 1 && dtype != 2) return false;  // fp32 operands: see ukst_mfma_f32.hip
-    if (g.n != 4) return false;
+    if (g.n != 4 && g.n != 3) return false;
     if (g.Cin % KC != 0 || g.Cout % TM != 0) return false;
     if (g.W % 8 != 0) return false;              // 16-byte row chunks
     const size_t xbytes = (size_t)g.B * g.Cin * g.H * g.W * 2;
@@ -500,14 +556,16 @@ hipError_t launch_mfma(const Geom& g, const void* x, const void* w, float* y, in
     if (prefer_aligned(g, dtype)) return launch_mfma_aligned(g, x, w, y, dtype, stream);
     MfmaArgs a;
     if (!make_args(g, dtype, a)) return hipErrorInvalidValue;
-    constexpr int N = 4;
     const size_t lds = 2 * (size_t)(2 * W_HALF) + 2 * (size_t)XS_STAGE_MAX;
     // more than 64 KiB of dynamic LDS has to be allowed per device (a property of the loaded
     // kernel, not library state); cheap enough to repeat on every call
     const bool epi = has_epilogue(g.ep), out16 = dtype == 2;
     typedef void (*kernel_t)(const uint16_t*, const uint16_t*, void*, MfmaArgs, Epilogue);
-    const kernel_t kfn = out16 ? (epi ? ukst_mfma_bf16_kernel<N, true, true> : ukst_mfma_bf16_kernel<N, false, true>)
-                               : (epi ? ukst_mfma_bf16_kernel<N, true, false> : ukst_mfma_bf16_kernel<N, false, false>);
+    const kernel_t k4 = out16 ? (epi ? ukst_mfma_bf16_kernel<4, true, true> : ukst_mfma_bf16_kernel<4, false, true>)
+                              : (epi ? ukst_mfma_bf16_kernel<4, true, false> : ukst_mfma_bf16_kernel<4, false, false>);
+    const kernel_t k3 = out16 ? (epi ? ukst_mfma_bf16_kernel<3, true, true> : ukst_mfma_bf16_kernel<3, false, true>)
+                              : (epi ? ukst_mfma_bf16_kernel<3, true, false> : ukst_mfma_bf16_kernel<3, false, false>);
+    const kernel_t kfn = g.n == 3 ? k3 : k4;
     hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     // persistent blocks: one per compute unit (a multiple of the 8 XCDs), never more than tiles

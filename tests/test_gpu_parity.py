@@ -192,6 +192,33 @@ def test_mfma_bf16_small_shapes_every_element(shape):
     _parity(w, PATHS["direct"], integer=False)
 
 
+MFMA_BF16_N3_SHAPES = [
+    # B, Cin, Cout, H, W, P        (n = 3: 4 / 2 / 2 / 1 taps per class, 18-byte weight rows)
+    (1, 16, 64, 4, 8, 0),      # one partial tile, odd output 5 x 13
+    (3, 32, 64, 5, 8, 1),      # P = 1: even output, tiles span images
+    (2, 48, 128, 9, 16, 0),    # two channel blocks, several K stages (three: an odd count)
+    (2, 16, 64, 7, 24, 2),     # P = 2
+    (1, 32, 64, 3, 40, 3),     # P > n - 1: the outer ring meets no input
+    (5, 16, 64, 2, 8, 1),      # many tiny images inside one tile
+    (1, 16, 64, 33, 64, 0),    # several row tiles of one image
+    (1, 16, 64, 20, 128, 1),   # cfg5a's row length
+    (2, 64, 64, 16, 16, 1),    # cfg5b's map
+]
+
+
+@pytest.mark.parametrize("shape", MFMA_BF16_N3_SHAPES)
+def test_mfma_bf16_kernel_side_3_every_element(shape):
+    """n = 3 on the bf16 matrix pipe: the classes have unequal sub-kernels (Sec. 3.2), so a K step
+    has 9 MFMA groups instead of 16; the weight rows are 18 bytes and are fetched with 16-byte
+    loads at 2-byte alignment."""
+    B, Cin, Cout, H, W, P = shape
+    w = _mk("mfma_bf16_n3", 7300 + sum(shape), B, Cin, Cout, H, W, 3, P, dtype="bf16")
+    assert ukst.ukst_kernel_name(B, Cin, Cout, H, W, 3, P, ukst.UKST_BF16_F32, PATHS["mfma"]) == \
+        "ukst_mfma_bf16_kernel"
+    _parity(w, PATHS["mfma"], integer=True)
+    _parity(w, PATHS["mfma"], integer=False)
+
+
 MFMA_F32_SHAPES = [
     # B, Cin, Cout, H, W, n, P   (Cout % 8 == 0, Cin % 8 == 0 for n = 4, 5 and % 16 for n = 2, 3; any W)
     (1, 8, 64, 4, 8, 4, 2),
@@ -234,7 +261,9 @@ def test_bf16_layers_with_other_kernel_sides_run_on_the_fp32_matrix_pipe(shape):
     B, Cin, Cout, H, W, n, P = shape
     w = _mk("mfma_f32_bf16in", 8300 + sum(shape), B, Cin, Cout, H, W, n, P, dtype="bf16")
     name = ukst.ukst_kernel_name(B, Cin, Cout, H, W, n, P, ukst.UKST_BF16_F32, PATHS["mfma"])
-    if n != 4:
+    if n == 3 and Cin % 16 == 0 and Cout % 64 == 0 and W % 8 == 0:
+        assert name == "ukst_mfma_bf16_kernel"   # 9 taps: the bf16 pipe takes them
+    elif n != 4:
         assert name == "ukst_mfma_f32_kernel"
     assert name
     _parity(w, PATHS["mfma"], integer=True)
