@@ -193,7 +193,9 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
 
     // global offsets of this thread's staging units for tile (cb, qt)
     auto staging_offsets = [&](int cb, int qt, unsigned& wv, unsigned& xv) {
-        wv = (unsigned)(((cb * TM + w_co) * g.Cin + 8 * w_g) * (NN * 2) + w_h * W_H_BYTES);
+        wv = cb * TM + w_co < g.Cout
+                 ? (unsigned)(((cb * TM + w_co) * g.Cin + 8 * w_g) * (NN * 2) + w_h * W_H_BYTES)
+                 : kInvalid;  // channels past the last one: zeros
         const int q0 = qt * TN;
         const int bf = fdiv(q0, a.dKHW), kf = fdiv(q0 - bf * KHW, a.dKW);
         const int e = bf * a.EH + kf + x_r;  // input row index over the whole batch
@@ -418,6 +420,8 @@ void ukst_mfma_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __res
             constexpr int ACT = decltype(act_tag)::value;  // -1: no epilogue at all
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
+                // (a partial last channel block: groups of 8 channels exist or not as a whole)
+                if (co0 + cw * 32 + 8 * (i / 4) >= g.Cout) continue;
                 const unsigned soff = (unsigned)(8 * (i / 4) + (i % 4)) * plane;
                 float bv = 0.f;
                 if constexpr (ACT >= 0)
@@ -473,7 +477,8 @@ bool make_args(const Geom& g, int dtype, MfmaArgs& a)
 {
     if (dtype != 1 && dtype != 2) return false;  // fp32 operands: see ukst_mfma_f32.hip
     if (g.n != 4 && g.n != 3) return false;
-    if (g.Cin % KC != 0 || g.Cout % TM != 0) return false;
+    // (whole groups of 8 output channels: a partial last channel block skips the missing groups)
+    if (g.Cin % KC != 0 || g.Cout % 8 != 0) return false;
     if (g.W % 8 != 0) return false;              // 16-byte row chunks
     const size_t xbytes = (size_t)g.B * g.Cin * g.H * g.W * 2;
     const size_t wbytes = (size_t)g.Cout * g.Cin * g.n * g.n * 2;
@@ -498,7 +503,7 @@ bool make_args(const Geom& g, int dtype, MfmaArgs& a)
     a.C8 = g.W / 8;
     if (2 * a.ROWS * a.LWS * 16 > XS_STAGE_MAX) return false;
     if (a.ROWS * 2 * a.C8 > 256) return false;   // one staging unit per thread
-    a.nco = g.Cout / TM;
+    a.nco = (g.Cout + TM - 1) / TM;
     a.nqt = (int)((Q + TN - 1) / TN);
     if ((long long)a.nco * a.nqt > 0x3FFFFFFFLL) return false;
     a.ntiles = a.nco * a.nqt;

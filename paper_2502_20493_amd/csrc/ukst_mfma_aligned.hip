@@ -147,7 +147,8 @@ void ukst_mfma_bf16_aligned_kernel(const uint16_t* __restrict__ x, const uint16_
 
     // global offsets of this thread's staging units for tile (cb, qt)
     auto staging_offsets = [&](int cb, int qt, unsigned& wv, unsigned& xv) {
-        wv = (unsigned)(((cb * TM + w_co) * g.Cin + 8 * w_g) * (NN * 2) + w_h * 16);
+        wv = cb * TM + w_co < g.Cout ? (unsigned)(((cb * TM + w_co) * g.Cin + 8 * w_g) * (NN * 2) + w_h * 16)
+                                     : kInvalid;  // channels past the last one: zeros
         const int q0 = qt * TN;
         const int bf = fdiv(q0, a.dKHW), kf = fdiv(q0 - bf * KHW, a.dKW);
         const int e = bf * a.EH + kf + x_r;  // input row index over the whole batch
@@ -355,6 +356,8 @@ void ukst_mfma_bf16_aligned_kernel(const uint16_t* __restrict__ x, const uint16_
                 if (!qv[h]) continue;  // quads past the end of the batch (last tile only)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
+                    // (a partial last channel block: groups of 8 channels exist or not as a whole)
+                    if (co0 + cw * 32 + 8 * (i / 4) >= g.Cout) continue;
                     // The channel offset goes into the vector offset: a store of more than 8 bytes
                     // whose data registers are rewritten by the next instruction needs a wait state
                     // that the compiler only inserts for stores without a scalar offset register.
@@ -404,7 +407,8 @@ bool make_args(const Geom& g, int dtype, AArgs& a)
 {
     if (dtype != 1 && dtype != 2) return false;
     if (g.n != 4 || (g.P & 1)) return false;     // odd P: the shifted quads are the aligned ones
-    if (g.Cin % KC != 0 || g.Cout % TM != 0) return false;
+    // (whole groups of 8 output channels: a partial last channel block skips the missing groups)
+    if (g.Cin % KC != 0 || g.Cout % 8 != 0) return false;
     if (g.W % 8 != 0) return false;              // 16-byte row chunks; makes OW a multiple of 4
     const size_t xbytes = (size_t)g.B * g.Cin * g.H * g.W * 2;
     const size_t wbytes = (size_t)g.Cout * g.Cin * g.n * g.n * 2;
@@ -439,7 +443,7 @@ bool make_args(const Geom& g, int dtype, AArgs& a)
     a.C8 = g.W / 8;
     if (2 * a.ROWS * a.LWS * 16 > XS_STAGE_MAX) return false;
     if (a.ROWS * 2 * a.C8 > 256) return false;   // one staging unit per thread
-    a.nco = g.Cout / TM;
+    a.nco = (g.Cout + TM - 1) / TM;
     a.nqt = (int)((Q + TN - 1) / TN);
     if ((long long)a.nco * a.nqt > 0x3FFFFFFFLL) return false;
     a.ntiles = a.nco * a.nqt;

@@ -153,7 +153,7 @@ def test_reduced_configs_every_element_both_paths(name):
 
 
 MFMA_BF16_SHAPES = [
-    # B, Cin, Cout, H, W, P        (n = 4; Cin % 16 == 0, Cout % 64 == 0, W % 8 == 0)
+    # B, Cin, Cout, H, W, P        (n = 4; Cin % 16 == 0, Cout % 8 == 0, W % 8 == 0)
     (1, 16, 64, 4, 8, 2),      # one partial tile
     (3, 32, 64, 5, 8, 2),      # tiles span images, ragged last tile
     (2, 48, 128, 9, 16, 2),    # two channel blocks, several K stages
@@ -178,6 +178,11 @@ MFMA_BF16_SHAPES = [
     (2, 32, 64, 16, 16, 2),    # cfg5b's map: one image per tile
     (1, 16, 64, 20, 128, 2),   # cfg5a's row length: two quad rows per tile
     (2, 16, 64, 9, 136, 2),    # wide rows: three quad rows and an image boundary in one tile
+    # channel counts that are no multiple of 64: the last channel block is partial
+    (2, 32, 96, 9, 16, 2),     # one and a half blocks
+    (1, 16, 40, 5, 8, 1),      # odd P (shifted quads), 40 channels: 5 groups of 8
+    (2, 16, 8, 6, 16, 2),      # a single group of 8
+    (3, 32, 72, 4, 8, 0),      # P = 0, one block and one group
 ]
 
 
@@ -203,6 +208,8 @@ MFMA_BF16_N3_SHAPES = [
     (1, 16, 64, 33, 64, 0),    # several row tiles of one image
     (1, 16, 64, 20, 128, 1),   # cfg5a's row length
     (2, 64, 64, 16, 16, 1),    # cfg5b's map
+    (2, 32, 72, 7, 16, 0),     # 72 channels: a partial second channel block
+    (1, 16, 24, 5, 8, 1),      # less than half a block
 ]
 
 
@@ -261,7 +268,7 @@ def test_bf16_layers_with_other_kernel_sides_run_on_the_fp32_matrix_pipe(shape):
     B, Cin, Cout, H, W, n, P = shape
     w = _mk("mfma_f32_bf16in", 8300 + sum(shape), B, Cin, Cout, H, W, n, P, dtype="bf16")
     name = ukst.ukst_kernel_name(B, Cin, Cout, H, W, n, P, ukst.UKST_BF16_F32, PATHS["mfma"])
-    if n == 3 and Cin % 16 == 0 and Cout % 64 == 0 and W % 8 == 0:
+    if n == 3 and Cin % 16 == 0 and Cout % 8 == 0 and W % 8 == 0:
         assert name == "ukst_mfma_bf16_kernel"   # 9 taps: the bf16 pipe takes them
     elif n != 4:
         assert name == "ukst_mfma_f32_kernel"
