@@ -141,6 +141,23 @@ def test_cfg45_full_size_sampled_planes(name):
     _parity(w, PATHS["auto"], planes=_sample_planes(w, 16), integer=True)
 
 
+def test_cfg5a_shape_with_kernel_side_3_full_size_sampled_planes():
+    """The benchmark row cfg5a_n3 (cfg5a's shape with n = 3, P = 1) in the launch configuration
+    bench.py times: one plane per (image, 64-channel block) against the oracle, integer data
+    exactly, and three launches bit-identical."""
+    import torch
+    from gpu_util import to_device
+    w = wl.WORKLOADS["cfg5a"].with_(n=3, P=1)
+    assert ukst.ukst_kernel_name(w.B, w.Cin, w.Cout, w.H, w.W, w.n, w.P, ukst.UKST_BF16_F32) == \
+        "ukst_mfma_bf16_kernel"
+    _parity(w, PATHS["auto"], planes=_stratified_planes(w), guard=1 << 16)
+    _parity(w, PATHS["auto"], planes=_sample_planes(w, 16), integer=True)
+    x, wt = to_device(wl.generate(w), w.dtype)
+    ys = [ukst.ukst_conv_transpose2d_ws(x, wt, w.P) for _ in range(3)]
+    torch.cuda.synchronize()
+    assert torch.equal(ys[0], ys[1]) and torch.equal(ys[0], ys[2])
+
+
 @pytest.mark.parametrize("name", ["cfg3_L2", "cfg4a", "cfg4b", "cfg5b"])
 def test_reduced_configs_every_element_both_paths(name):
     # same layer shapes with fewer images / channels so that the oracle covers every element
