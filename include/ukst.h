@@ -246,8 +246,13 @@ size_t ukst_static_workspace_bytes(void);
  * kernel sides up to about 5;
  * "ukst_grad_input_mfma_kernel": fp32 MFMA otherwise; weights packed once per call into the
  * workspace, which also holds the copies of dx when the sum over output channels is split),
- * layers with Cin, Cout >= 32 run the kernel gradient there ("ukst_grad_weight_mfma_kernel", fp32
- * MFMA for either dtype); everything else runs on the vector ALUs.
+ * layers with Cin, Cout >= 32 run the kernel gradient there too
+ * ("ukst_grad_weight_mfma_bf16_kernel": bf16 MFMA with the pixel axis as the contraction, for bf16
+ * operands with kernel sides 2 to 4, W a multiple of 8 and at least 16;
+ * "ukst_grad_weight_mfma_kernel": fp32 MFMA for everything else of that width, either dtype).
+ * Layers with at most 4 output channels, Cout * n * n <= 64 and Cin >= 16 run the kernel gradient
+ * as "ukst_grad_weight_thin_mfma_kernel" (fp32 MFMA whose rows are (channel, tap) pairs).
+ * Everything else runs on the vector ALUs.
  */
 const char* ukst_grad_kernel_name(int which, int B, int Cin, int Cout, int H, int W, int n, int P,
                                   int dtype);
