@@ -171,6 +171,11 @@ hipError_t launch_grad_input(const Geom& g, const void* dy, const void* w, float
                              Workspace& ws, hipStream_t stream);
 hipError_t launch_grad_weight(const Geom& g, const void* x, const void* dy, float* dw, int dtype,
                               Workspace& ws, hipStream_t stream);
+// Input gradient of bf16 layers with 4 x 4 kernels and at least 65 input channels: bf16 MFMA with a
+// channel's 16 taps as the contraction (weights packed once per call into the workspace)
+bool grad_input_window_supported(const Geom& g, int dtype);
+hipError_t launch_grad_input_window(const Geom& g, const void* dy, const void* w, float* dx, Workspace& ws,
+                                    hipStream_t stream);
 // which: 0 gradient w.r.t. the input, 1 w.r.t. the kernel
 const char* grad_kernel_name(const Geom& g, int which, int dtype);
 

@@ -89,6 +89,27 @@ def test_backward_bf16_kernel_gradient_on_the_bf16_matrix_pipe(shape):
 
 
 @pytest.mark.parametrize("shape", [
+    (2, 128, 16, 8, 16, 4, 2),     # 16-pixel rows: a tile is 4 images x 8 rows, two of the images absent
+    (3, 160, 32, 20, 40, 4, 1),    # one 64-column tile wider than the map; dy rows of 78: the last piece moves
+    (1, 130, 48, 9, 70, 4, 0),     # two column tiles, P = 0, two input channels in the second channel tile
+    (2, 96, 16, 16, 32, 4, 3),     # 32-column tiles, P > n / 2, fewer channels than a channel tile
+    (2, 72, 32, 5, 17, 4, 2),      # W = 17 in a 32-column tile, rows beyond the map
+    (4, 256, 32, 16, 16, 4, 2),    # cfg5b's map: two images per tile, two channel tiles
+    (1, 128, 64, 24, 128, 4, 2)])  # cfg5a's rows: both column tiles touch one end of the dy rows
+def test_backward_bf16_input_gradient_with_the_taps_in_the_contraction(shape):
+    """bf16 layers with 4 x 4 kernels, more than 64 input channels, output channels in multiples of
+    16 and maps at least 16 wide take the input gradient on the bf16 MFMA pipe with a channel's 16
+    taps as the contraction (dy staged as it lies in memory, row-end pieces written at 2-byte-aligned
+    LDS addresses): every element, integer-valued data exactly."""
+    B, Cin, Cout, H, W, n, P = shape
+    assert ukst.ukst_grad_kernel_name(0, B, Cin, Cout, H, W, n, P, ukst.UKST_BF16_F32) == \
+        "ukst_grad_input_window_bf16_kernel"
+    w = _mk("bwd_window", 6900 + sum(shape), B, Cin, Cout, H, W, n, P, dtype="bf16")
+    _both(w, integer=True)
+    _both(w, integer=False)
+
+
+@pytest.mark.parametrize("shape", [
     (2, 64, 3, 8, 8, 4, 2),        # the last generator layer in small: 3 x 16 (channel, tap) rows, two channel tiles
     (3, 16, 4, 5, 9, 4, 1),        # four output channels fill both row tiles; odd P, rows that are no multiple of 4
     (2, 40, 2, 7, 37, 5, 0),       # n = 5: 2 x 25 rows; two column tiles, ragged row ends
