@@ -51,8 +51,9 @@ struct GiWinArgs {
     int rows;                  // staged dy rows per channel: TB * LR
     int coBytes;               // rows * S
     int bBytes;                // dy bytes of a stage in LDS, with the 16 spare bytes absent pieces go to
-    int tilesX, tilesY, tilesB, ciTiles;
+    int tilesX, tilesY, tilesB, ciTiles, nTiles;
     int nStages;
+    FastDiv dC8, dRows, dLR;
 };
 
 // The value, through an empty statement the compiler cannot see through: sums of a per-thread base
@@ -81,206 +82,286 @@ __global__ __launch_bounds__(256) void ukst_pack_w_window_kernel(const uint16_t*
     wp[idx] = ci < Cin ? w[((size_t)co * Cin + ci) * 16 + (3 - kr) * 4 + (3 - lr)] : (uint16_t)0;
 }
 
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void ukst_grad_input_window_bf16_kernel(const uint16_t* __restrict__ dy,
-                                                                            const uint16_t* __restrict__ wp,
-                                                                            float* __restrict__ dx, GiWinArgs a)
+template <int SD>  // dwords per staged dy row
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void ukst_grad_input_window_bf16_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict__ wp,
+                                        float* __restrict__ dx, GiWinArgs a)
 {
+    constexpr int S = 4 * SD;
     extern __shared__ __align__(16) unsigned char lds[];  // A[2][A_BYTES], then B[2][bBytes]
     const GeomBase& g = a.g;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, kk = lane >> 5;
     const int tid16 = 16 * tid;
-
-    int bid = xcd_contiguous(blockIdx.x, gridDim.x);  // neighbours in this numbering share an L2
-    const int cit = bid % a.ciTiles; bid /= a.ciTiles;
-    const int tx = bid % a.tilesX; bid /= a.tilesX;
-    const int ty = bid % a.tilesY; bid /= a.tilesY;
-    const int b0 = bid * a.TB, i0 = ty * a.TI, j0 = tx * a.TJ, ci0 = cit * CI_T;
-    const int oy_base = 2 * i0 + g.P - 3, ox_base = 2 * j0 + g.P - 3;
     const size_t plane = (size_t)g.OH * g.OW;
-
-    // dy of the tile's images, and this channel tile's packed weights, as raw buffers
-    const size_t img0 = (size_t)b0 * g.Cout * plane;
-    const size_t left = ((size_t)g.B * g.Cout * plane - img0) * 2;
-    const __amdgpu_buffer_rsrc_t rs_dy = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)(dy + img0), 0, (int)(left < 0xFFFFFF00u ? left : 0xFFFFFF00u), kRsrcFlags);
-    const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)(wp + (size_t)cit * g.Cout * (2 * CI_T * 8)), 0, a.nStages * A_BYTES, kRsrcFlags);
     const unsigned co_stage_bytes = (unsigned)(KC * plane * 2);
+    const int ns = a.nStages;
+    const int G = gridDim.x;
 
-    // this thread's dy pieces: global offset (channel 0 of a stage) and LDS offset.  A piece that
-    // straddles an end of its dy row is fetched from the nearest position inside the row and written
-    // to where those columns belong, 2-byte aligned (it rewrites part of its neighbour with the same
-    // values); the columns outside the row are never written and keep the zeros of the first fill.
-    unsigned b_voff[NPB];
-    int b_loff[NPB];
-    {
-        const int npieces = KC * a.rows * a.c8;
+    // tile of a position in the walk: channel tile fastest, so that the blocks of one XCD (which
+    // take neighbouring positions) read the same dy through one L2
+    struct Tile { int cit, tx, b0, i0, j0; };
+    auto tile_at = [&](int lin) {
+        Tile t;
+        t.cit = lin % a.ciTiles; lin /= a.ciTiles;
+        t.tx = lin % a.tilesX; lin /= a.tilesX;
+        const int ty = lin % a.tilesY; lin /= a.tilesY;
+        t.b0 = lin * a.TB; t.i0 = ty * a.TI; t.j0 = t.tx * a.TJ;
+        return t;
+    };
+
+    // Load side of the staging pipeline (it runs two stages ahead and therefore moves to the next
+    // tile two stages early): dy of the tile's images and the channel tile's packed weights as raw
+    // buffers, and this thread's dy pieces as byte offsets of channel 0 of a stage.  A piece that
+    // straddles an end of its dy row is fetched from the nearest position inside the row and
+    // written to where those columns belong, 2-byte aligned (it rewrites part of its neighbour
+    // with the same values); columns outside the row are never written and stay zero.
+    __amdgpu_buffer_rsrc_t rs_dy, rs_w;
+    unsigned a_voff, b_voff[NPB];
+    int b_loff[NPB];  // LDS address of the piece in the buffer written next
+    const int npieces = KC * a.rows * a.c8;
+    auto piece_start = [&](int ox) {  // first column fetched for the piece that begins at column ox
+        return (ox < 0 && ox + 7 >= 0) ? 0 : (ox < g.OW && ox + 8 > g.OW) ? g.OW - 8 : ox;
+    };
+    auto aim_loads = [&](const Tile& t, bool present) {
+        const size_t img0 = (size_t)t.b0 * g.Cout * plane;
+        const size_t left = ((size_t)g.B * g.Cout * plane - img0) * 2;
+        rs_dy = __builtin_amdgcn_make_buffer_rsrc((void*)(dy + img0), 0,
+                                                  (int)(left < 0xFFFFFF00u ? left : 0xFFFFFF00u), kRsrcFlags);
+        rs_w = __builtin_amdgcn_make_buffer_rsrc((void*)(wp + (size_t)t.cit * g.Cout * (2 * CI_T * 8)), 0,
+                                                 ns * A_BYTES, kRsrcFlags);
+        a_voff = present ? (unsigned)tid16 : kInvalid;
+        const int oy_base = 2 * t.i0 + g.P - 3, ox_base = 2 * t.j0 + g.P - 3;
+        const int tid_o = opaque(tid);  // nothing of this is to be kept from tile to tile
 #pragma unroll
         for (int u = 0; u < NPB; ++u) {
-            const int e = tid + 256 * u;
-            b_voff[u] = kInvalid; b_loff[u] = KC * a.coBytes;
-            if (e < npieces) {
-                const int row_all = e / a.c8, pc = e - row_all * a.c8;
-                const int co_l = row_all / a.rows, rem = row_all - co_l * a.rows;
-                const int bl = rem / a.LR, rr = rem - bl * a.LR;
-                const int b = b0 + bl, oy = oy_base + rr, ox = ox_base + 8 * pc;
-                int start = ox;
-                if (b < g.B && oy >= 0 && oy < g.OH && ox + 7 >= 0 && ox < g.OW) {
-                    start = ox < 0 ? 0 : (ox + 8 > g.OW ? g.OW - 8 : ox);
-                    b_voff[u] = (unsigned)((((size_t)bl * g.Cout + co_l) * plane + (size_t)oy * g.OW + start) * 2);
-                }
-                b_loff[u] = co_l * a.coBytes + rem * a.S + 2 * (start - ox_base);
+            const int e = tid_o + 256 * u;
+            b_voff[u] = kInvalid;
+            if (present && e < npieces) {
+                const int row_all = fdiv(e, a.dC8), pc = e - row_all * a.c8;
+                const int co_l = fdiv(row_all, a.dRows), rem = row_all - co_l * a.rows;
+                const int bl = fdiv(rem, a.dLR), rr = rem - bl * a.LR;
+                const int b = t.b0 + bl, oy = oy_base + rr, ox = ox_base + 8 * pc;
+                if (b < g.B && oy >= 0 && oy < g.OH && ox + 7 >= 0 && ox < g.OW)
+                    b_voff[u] = (unsigned)((((size_t)bl * g.Cout + co_l) * plane + (size_t)oy * g.OW +
+                                            piece_start(ox)) * 2);
             }
         }
-    }
+    };
+    // Store side: where the pieces go in buffer `buf` (depends on the tile's columns only)
+    auto aim_stores = [&](const Tile& t, int buf) {
+        const int ox_base = 2 * t.j0 + g.P - 3;
+        const int tid_o = opaque(tid);
+#pragma unroll
+        for (int u = 0; u < NPB; ++u) {
+            const int e = tid_o + 256 * u;
+            b_loff[u] = 2 * A_BYTES + buf * a.bBytes + KC * a.coBytes;  // the spare 16 bytes
+            if (e < npieces) {
+                const int row_all = fdiv(e, a.dC8), pc = e - row_all * a.c8;
+                const int ox = ox_base + 8 * pc;
+                b_loff[u] = 2 * A_BYTES + buf * a.bBytes + row_all * S + 2 * (piece_start(ox) - ox_base);
+            }
+        }
+    };
+    auto zero_fill = [&](int buf) {
+        for (int o = tid16; o < a.bBytes; o += 4096)
+            *reinterpret_cast<u32x4*>(lds + 2 * A_BYTES + buf * a.bBytes + o) = u32x4{0u, 0u, 0u, 0u};
+    };
 
     u32x4 R[NIT];
     auto load_item = [&](int it, int stage) {
         if (it < NPA)
-            R[it] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, (unsigned)tid16,
-                                                          (unsigned)(stage * A_BYTES + 4096 * it), 0);
+            R[it] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, a_voff, (unsigned)(stage * A_BYTES + 4096 * it), 0);
         else
             R[it] = __builtin_amdgcn_raw_buffer_load_b128(rs_dy, b_voff[it - NPA],
                                                           (unsigned)stage * co_stage_bytes, 0);
     };
-    auto store_item = [&](int it, int buf) {
+    // writes the item into buffer `buf`; dtoggle turns its LDS address to the other buffer afterwards
+    auto store_item = [&](int it, int buf, int dtoggle) {
         if (it < NPA) {
-            *reinterpret_cast<u32x4*>(lds + buf * A_BYTES + opaque(tid16) + 4096 * it) = R[it];
+            *reinterpret_cast<u32x4*>(lds + tid16 + (buf * A_BYTES + 4096 * it)) = R[it];
         } else {
-            *reinterpret_cast<u32x4a2*>(lds + 2 * A_BYTES + buf * a.bBytes + opaque(b_loff[it - NPA])) = R[it];
+            *reinterpret_cast<u32x4a2*>(lds + b_loff[it - NPA]) = R[it];
+            b_loff[it - NPA] += dtoggle;
         }
     };
 
-    // window origin of this lane's pixel in each of the wave's four column tiles
+    // window origin of this lane's pixel in each of the wave's four column tiles (buffer 0, channel 0)
     int boff[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
         const int p = (wave * 4 + t) * 32 + l32;
         const int tr = p >> a.logTJ, lj = p & (a.TJ - 1);
         const int bl = tr >> a.logTI, li = tr & (a.TI - 1);
-        boff[t] = 2 * A_BYTES + (bl * a.LR + 2 * li + 2 * kk) * a.S + 4 * lj;
+        boff[t] = 2 * A_BYTES + (bl * a.LR + 2 * li + 2 * kk) * S + 4 * lj;
     }
     const int aoff = (kk * CI_T + l32) * 16;
 
-    bf16x8 fa[2][4], fb[2][4];
-    auto load_fa = [&](int buf, int k, int slot, int mi) {
-        fa[slot][mi] = *reinterpret_cast<const bf16x8*>(lds + buf * A_BYTES + k * (2 * CI_T * 16) + opaque(aoff) + mi * 512);
+    bf16x8 fa[4], fb[2][4];  // weights: one set, each reloaded right after its last use in a step
+    int bp[4];  // LDS address of the window rows the next B fragment is read from
+    auto load_fa = [&](int buf, int k, int mi) {
+        fa[mi] = *reinterpret_cast<const bf16x8*>(lds + aoff + (buf * A_BYTES + k * (2 * CI_T * 16) + mi * 512));
     };
-    auto load_fb = [&](int buf, int k, int slot, int t) {
-        const unsigned char* p = lds + opaque(boff[t]) + (buf * a.bBytes + k * a.coBytes);
+    auto load_fb = [&](int slot, int t, int advance) {
+        const unsigned char* p = lds + bp[t];
         const u32x2a4 lo = *reinterpret_cast<const u32x2a4*>(p);
-        const u32x2a4 hi = *reinterpret_cast<const u32x2a4*>(p + a.S);
+        const u32x2a4 hi = *reinterpret_cast<const u32x2a4*>(p + S);
         fb[slot][t] = __builtin_bit_cast(bf16x8, u32x4{lo.x, lo.y, hi.x, hi.y});
+        bp[t] += advance;
     };
 
-    f32x16 acc[4][4];
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[mi][t][i] = 0.f;
+    int lin = xcd_contiguous(blockIdx.x, G);
+    Tile cur = tile_at(lin);
 
-    const int ns = a.nStages;
-    // stage 0 into buffer 0, stage 1 into the registers
+    // first tile: zeros everywhere, stage 0 into buffer 0, stage 1 into the registers
+    aim_loads(cur, true);
+    aim_stores(cur, 0);
 #pragma unroll
     for (int it = 0; it < NIT; ++it) load_item(it, 0);
-    for (int o = tid16; o < 2 * a.bBytes; o += 4096)
-        *reinterpret_cast<u32x4*>(lds + 2 * A_BYTES + o) = u32x4{0u, 0u, 0u, 0u};
+    zero_fill(0);
+    zero_fill(1);
     __syncthreads();
 #pragma unroll
-    for (int it = 0; it < NIT; ++it) store_item(it, 0);
+    for (int it = 0; it < NIT; ++it) store_item(it, 0, a.bBytes);
 #pragma unroll
-    for (int it = 0; it < NIT; ++it) load_item(it, ns > 1 ? 1 : 0);
+    for (int it = 0; it < NIT; ++it) load_item(it, 1);
     __syncthreads();
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi) load_fa(0, 0, 0, mi);
+    for (int t = 0; t < 4; ++t) bp[t] = boff[t];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) load_fb(0, 0, 0, t);
+    for (int mi = 0; mi < 3; ++mi) load_fa(0, 0, mi);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) load_fb(0, t, a.coBytes);
 
-    // one stage: 8 steps of 16 MFMAs; after each MFMA one side operation (a fragment of the next
-    // step, or one staging item: its data goes to the other buffer, its registers are refilled)
-    auto stage = [&](auto buf_tag, int s) {
-        constexpr int BUF = decltype(buf_tag)::value;
-        const int s2 = s + 2 < ns ? s + 2 : ns - 1;
-#pragma unroll
-        for (int k = 0; k < KC; ++k) {
-            const int cur = k & 1, nxt = cur ^ 1;
-            const int fbuf = k + 1 < KC ? BUF : BUF ^ 1, fk = k + 1 < KC ? k + 1 : 0;
-#pragma unroll
-            for (int m = 0; m < 16; ++m) {
-                const int mi = m >> 2, t = m & 3;
-                if (k == KC - 1 && m == 0) {
-                    // every wave has read its last fragments of this buffer and written the other one
-                    __syncthreads();
-                }
-                acc[mi][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][mi], fb[cur][t], acc[mi][t], 0, 0, 0);
-                if (m == 0) load_fa(fbuf, fk, nxt, 0);
-                else if (m <= 4) load_fb(fbuf, fk, nxt, m - 1);
-                else if (m <= 7) load_fa(fbuf, fk, nxt, m - 4);
-                else if (k < KC - 1 && m - 8 < IPS) {
-                    const int it = k * IPS + (m - 8);
-                    if (it < NIT) { store_item(it, BUF ^ 1); load_item(it, s2); }
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-    };
     const std::integral_constant<int, 0> t0;
     const std::integral_constant<int, 1> t1;
-    for (int s = 0; s < ns; s += 2) {  // ns is even (a second stage under a condition of its own spills)
-        stage(t0, s);
-        stage(t1, s + 1);
-    }
+    bool stale1 = false;  // buffer 1 still holds columns of a tile whose rows ended elsewhere
+    for (;;) {
+        const int nlin = lin + G;
+        const bool more = nlin < a.nTiles;  // uniform
+        const Tile nxt = tile_at(more ? nlin : lin);
+        const bool refill = more && nxt.tx != cur.tx;  // the next tile's rows end at other LDS columns
 
-    // drain: lanes along the pixel columns, a lane's 16 values of a tile are 16 input channels
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        const int p = (wave * 4 + t) * 32 + l32;
-        const int tr = p >> a.logTJ, lj = p & (a.TJ - 1);
-        const int b = b0 + (tr >> a.logTI), i = i0 + (tr & (a.TI - 1)), j = j0 + lj;
-        if (b >= g.B || i >= g.H || j >= g.W) continue;
-        float* out = dx + (((size_t)b * g.Cin + ci0) * g.H + i) * g.W + j;
-        const size_t cs = (size_t)g.H * g.W;
+        f32x16 acc[4][4];
 #pragma unroll
         for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int cl = mi * 32 + 8 * (r / 4) + 4 * kk + (r % 4);
-                if (ci0 + cl < g.Cin) out[cl * cs] = acc[mi][t][r];
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[mi][t][i] = 0.f;
+
+        // one stage: 8 steps of 16 MFMAs; after an MFMA at most one side operation (a fragment of
+        // the next step, or one staging item: its data goes to the other buffer, its registers are
+        // refilled for the stage after next)
+        auto stage = [&](auto buf_tag, int s) {
+            constexpr int BUF = decltype(buf_tag)::value;
+            if constexpr (BUF == 0) {
+                if (s == 0 && stale1) {
+                    zero_fill(1);  // free since the last stage of the tile before
+                    __syncthreads();
+                }
+                if (s == ns - 2) aim_loads(nxt, more);  // the loads of this stage are the next tile's first
+            } else {
+                if (s == ns - 1 && refill) {
+                    // buffer 0 is free: its stale columns beside the next tile's rows go, then its pieces
+                    zero_fill(0);
+                    aim_stores(nxt, 0);
+                    __syncthreads();
+                }
             }
+            const int s2 = s + 2 < ns ? s + 2 : s + 2 - ns;
+            // values the compiler shall not trace through the stages (it would keep every sum of a
+            // base and a (buffer, step) offset in a register of its own, and spill)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) asm volatile("" : "+v"(bp[t]));
+#pragma unroll
+            for (int u = 0; u < NPB; ++u) asm volatile("" : "+v"(b_loff[u]));
+#pragma unroll
+            for (int k = 0; k < KC; ++k) {
+                const int cur_f = k & 1, nxt_f = cur_f ^ 1;
+                const int fbuf = k + 1 < KC ? BUF : BUF ^ 1, fk = k + 1 < KC ? k + 1 : 0;
+                // after this step's reads: one channel on; from channel 7 to channel 0 of the other buffer
+                const int adv = k == KC - 2 ? (BUF == 0 ? a.bBytes : -a.bBytes) - (KC - 1) * a.coBytes : a.coBytes;
+#pragma unroll
+                for (int m = 0; m < 16; ++m) {
+                    const int mi = m >> 2, t = m & 3;
+                    if (k == KC - 1 && m == 1) {
+                        // every wave has read its last fragments of this buffer and written the other one
+                        __syncthreads();
+                    }
+                    acc[mi][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[cur_f][t], acc[mi][t], 0, 0, 0);
+                    if (m == 0) load_fa(BUF, k, 3);                       // this step's last weights
+                    else if (m <= 4) load_fb(nxt_f, m - 1, adv);
+                    else if (m == 5) load_fa(fbuf, fk, 0);                // the next step's, as they fall free
+                    else if (m == 8) load_fa(fbuf, fk, 1);
+                    else if (m == 12) load_fa(fbuf, fk, 2);
+                    else if (k < KC - 1 && (m == 6 || m == 7 || m == 9)) {
+                        const int it = k * IPS + (m == 9 ? 2 : m - 6);
+                        if (it < NIT) {
+                            store_item(it, BUF ^ 1, BUF == 0 ? -a.bBytes : a.bBytes);
+                            load_item(it, s2);
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        };
+        for (int s = 0; s < ns; s += 2) {  // ns is even (a second stage under a condition of its own spills)
+            stage(t0, s);
+            stage(t1, s + 1);
+        }
+
+        // drain: lanes along the pixel columns, a lane's 16 values of a tile are 16 input channels.
+        // Raw buffer stores: the pixel (and the lane's half of the channel octet) is the vector
+        // offset, the channel the scalar offset; absent pixels carry the invalid offset and drop out.
+        {
+            const int ci0 = cur.cit * CI_T;
+            const size_t cs = (size_t)g.H * g.W;
+            const size_t base = ((size_t)cur.b0 * g.Cin + ci0) * cs;
+            const size_t left = ((size_t)g.B * g.Cin * cs - base) * 4;
+            const __amdgpu_buffer_rsrc_t rs_dx = __builtin_amdgcn_make_buffer_rsrc(
+                (void*)(dx + base), 0, (int)(left < 0xFFFFFF00u ? left : 0xFFFFFF00u), kRsrcFlags);
+            const unsigned cs4 = (unsigned)(cs * 4);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int p = (wave * 4 + t) * 32 + l32;
+                const int tr = p >> a.logTJ, lj = p & (a.TJ - 1);
+                const int bl = tr >> a.logTI, i = cur.i0 + (tr & (a.TI - 1)), j = cur.j0 + lj;
+                const bool ok = cur.b0 + bl < g.B && i < g.H && j < g.W;
+                const unsigned voff = ok ? (unsigned)(((size_t)bl * g.Cin * cs + (size_t)i * g.W + j) * 4) + 4 * kk * cs4
+                                         : kInvalid;
+#pragma unroll
+                for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        if (ci0 + mi * 32 + 8 * q >= g.Cin) continue;  // uniform: Cin is a multiple of 8
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            // through a vector register: as a direct operand of the store every
+                            // element of the accumulator tile came out as its first one
+                            float v = acc[mi][t][4 * q + r];
+                            asm volatile("" : "+v"(v));
+                            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), rs_dx, voff,
+                                                                  (unsigned)(mi * 32 + 8 * q + r) * cs4, 0);
+                        }
+                    }
+            }
+        }
+        if (!more) break;
+        lin = nlin;
+        cur = nxt;
+        stale1 = refill;
     }
 }
 
 int log2_of(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
 
-// bank pressure of the window reads of one wave for a row stride of S bytes: dwords that share a
-// bank with another dword of the same read, summed over the 64 banks
-int window_conflicts(int S, int TJ)
-{
-    int count[64], extra = 0;
-    for (int b = 0; b < 64; ++b) count[b] = 0;
-    bool seen[4096] = {false};
-    for (int lane = 0; lane < 64; ++lane) {
-        const int l32 = lane & 31, kk = lane >> 5;
-        const int lj = l32 & (TJ - 1), lsub = TJ >= 32 ? 0 : l32 / TJ;
-        for (int d = 0; d < 2; ++d) {
-            const int dw = ((2 * lsub + 2 * kk) * S + 4 * lj) / 4 + d;
-            if (dw >= 4096 || seen[dw]) continue;
-            seen[dw] = true;
-            if (count[dw & 63]++ > 0) ++extra;
-        }
-    }
-    return extra;
-}
-
 }  // namespace
 
 static bool gi_win_args(const Geom& g, GiWinArgs& a)
 {
-    if (g.n != 4 || g.Cout % (2 * KC) != 0 || g.Cin <= 64 || g.W < 16 || g.OW < 8 || g.H < 1)
+    if (g.n != 4 || g.Cout % (2 * KC) != 0 || g.Cin <= 64 || g.Cin % 8 != 0 || g.W < 16 || g.OW < 8 || g.H < 1)
         return false;
     a.g = g;
     a.TJ = g.W <= 16 ? 16 : g.W <= 32 ? 32 : 64;
@@ -293,13 +374,13 @@ static bool gi_win_args(const Geom& g, GiWinArgs& a)
     a.rows = a.TB * a.LR;
     a.c8 = (2 * a.TJ + 2 + 7) / 8;
     if ((KC * a.rows * a.c8 + 255) / 256 > NPB) return false;
-    // row stride: the smallest multiple of 16 bytes with the fewest bank clashes that still fits
-    int best = -1, best_cost = 1 << 30;
-    for (int m = 0; m <= 8; ++m) {
-        const int S = 16 * (a.c8 + m);
-        if (2 * (size_t)A_BYTES + 2 * ((size_t)KC * a.rows * S + 16) > 160 * 1024) break;
-        const int c = window_conflicts(S, a.TJ);
-        if (c < best_cost) { best_cost = c; best = S; }
+    // row stride: 2 S = 128 (mod 256) keeps the two row pairs of a window read in different banks;
+    // 16-column tiles need 2 S = 96 (mod 128) for their two pixel rows per read
+    const int cand[3][2] = {{80, 80}, {192, 160}, {320, 320}};
+    int best = -1;
+    for (int c = 0; c < 2 && best < 0; ++c) {
+        const int S = cand[a.logTJ - 4][c];
+        if (S >= 16 * a.c8 && 2 * (size_t)A_BYTES + 2 * ((size_t)KC * a.rows * S + 16) <= 160 * 1024) best = S;
     }
     if (best < 0) return false;
     a.S = best;
@@ -310,13 +391,19 @@ static bool gi_win_args(const Geom& g, GiWinArgs& a)
     a.tilesB = (g.B + a.TB - 1) / a.TB;
     a.ciTiles = (g.Cin + CI_T - 1) / CI_T;
     a.nStages = g.Cout / KC;
+    a.dC8 = make_fastdiv((unsigned)a.c8);
+    a.dRows = make_fastdiv((unsigned)a.rows);
+    a.dLR = make_fastdiv((unsigned)a.LR);
     // a piece moved back inside its row must not start before its tile's first column
     if (2 * (a.tilesX - 1) * a.TJ + g.P - 3 + 8 > g.OW) return false;
     const size_t plane = (size_t)g.OH * g.OW;
     // offsets inside a tile's images and inside a channel tile's weights stay below the invalid mark
     if ((size_t)a.TB * g.Cout * plane * 2 + 64 >= 0xFFFFFF00u) return false;
     if ((size_t)a.nStages * A_BYTES >= 0x7FFFFFFFu) return false;
-    if ((long long)a.tilesX * a.tilesY * a.tilesB * a.ciTiles > 0x7fffffffLL) return false;
+    if ((size_t)a.TB * g.Cin * g.H * g.W * 4 + 64 >= 0xFFFFFF00u) return false;
+    const long long nt = (long long)a.tilesX * a.tilesY * a.tilesB * a.ciTiles;
+    if (nt > 0x3fffffffLL) return false;
+    a.nTiles = (int)nt;
     return true;
 }
 
@@ -341,12 +428,20 @@ hipError_t launch_grad_input_window(const Geom& g, const void* dy, const void* w
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const size_t lds = 2 * (size_t)A_BYTES + 2 * (size_t)a.bBytes;
-    e = hipFuncSetAttribute((const void*)ukst_grad_input_window_bf16_kernel,
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    typedef void (*kernel_t)(const uint16_t*, const uint16_t*, float*, GiWinArgs);
+    const kernel_t kfn = a.S == 80 ? ukst_grad_input_window_bf16_kernel<20>
+                       : a.S == 160 ? ukst_grad_input_window_bf16_kernel<40>
+                       : a.S == 192 ? ukst_grad_input_window_bf16_kernel<48>
+                                    : ukst_grad_input_window_bf16_kernel<80>;
+    e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    const unsigned nb = (unsigned)((long long)a.tilesX * a.tilesY * a.tilesB * a.ciTiles);
-    hipLaunchKernelGGL(ukst_grad_input_window_bf16_kernel, dim3(nb), dim3(256), lds, stream,
-                       (const uint16_t*)dy, (const uint16_t*)wp, dx, a);
+    // one block per compute unit (its LDS holds one), each walking over every cus-th tile
+    int dev = 0, cus = 0;
+    e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return e;
+    const unsigned nb = (unsigned)(a.nTiles < cus ? a.nTiles : cus);
+    hipLaunchKernelGGL(kfn, dim3(nb), dim3(256), lds, stream, (const uint16_t*)dy, (const uint16_t*)wp, dx, a);
     return hipGetLastError();
 }
 

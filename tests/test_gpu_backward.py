@@ -91,7 +91,7 @@ def test_backward_bf16_kernel_gradient_on_the_bf16_matrix_pipe(shape):
 @pytest.mark.parametrize("shape", [
     (2, 128, 16, 8, 16, 4, 2),     # 16-pixel rows: a tile is 4 images x 8 rows, two of the images absent
     (3, 160, 32, 20, 40, 4, 1),    # one 64-column tile wider than the map; dy rows of 78: the last piece moves
-    (1, 130, 48, 9, 70, 4, 0),     # two column tiles, P = 0, two input channels in the second channel tile
+    (1, 136, 48, 9, 70, 4, 0),     # two column tiles, P = 0, eight input channels in the second channel tile
     (2, 96, 16, 16, 32, 4, 3),     # 32-column tiles, P > n / 2, fewer channels than a channel tile
     (2, 72, 32, 5, 17, 4, 2),      # W = 17 in a 32-column tile, rows beyond the map
     (4, 256, 32, 16, 16, 4, 2),    # cfg5b's map: two images per tile, two channel tiles
@@ -178,6 +178,18 @@ def test_backward_cfg5_wide_bf16_full_size(name):
     _sampled(wl.WORKLOADS[name], n_planes=6, n_co=3, n_ci=3)
     if name == "cfg5b":
         _sampled(wl.WORKLOADS[name], n_planes=4, n_co=2, n_ci=2, integer=True)  # exact
+
+
+def test_backward_window_kernel_walks_over_tiles_whose_rows_end_elsewhere():
+    """288 tiles of the bf16 window kernel on 256 compute units: blocks take a second tile, and with
+    three column tiles per row it lies in another column, so the staging buffers are cleared and
+    re-aimed between the two.  Sampled planes (the last image is second-round work), integer data
+    exactly."""
+    w = _mk("bwd_window_walk", 6990, 12, 128, 16, 64, 192, 4, 2, dtype="bf16")
+    assert ukst.ukst_grad_kernel_name(0, w.B, w.Cin, w.Cout, w.H, w.W, w.n, w.P, ukst.UKST_BF16_F32) == \
+        "ukst_grad_input_window_bf16_kernel"
+    _sampled(w, n_planes=10, n_co=2, n_ci=2, integer=True)
+    _sampled(w, n_planes=6, n_co=2, n_ci=2)
 
 
 def test_backward_on_a_side_stream_is_bit_reproducible():
