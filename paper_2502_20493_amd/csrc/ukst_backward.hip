@@ -2274,7 +2274,7 @@ const char* grad_kernel_name(const Geom& g, int which, int dtype)
                       : g.n == 4 ? gw_thin_pick<4>(g, ta, MT, CT) : g.n == 5 ? gw_thin_pick<5>(g, ta, MT, CT) : false;
         return th ? "ukst_grad_weight_thin_mfma_kernel" : "ukst_grad_weight_kernel";
     }
-    if (grad_input_window_supported(g, dtype)) return "ukst_grad_input_window_bf16_kernel";
+    if (grad_input_window_supported(g, dtype)) return "ukst_grad_input_window_mfma_bf16_kernel";
     GiMfmaArgs ma;
     if (dtype == 1 && gi_mfma_args(g, ma, true)) return "ukst_grad_input_mfma_bf16_kernel";
     return gi_mfma_args(g, ma) ? "ukst_grad_input_mfma_kernel" : "ukst_grad_input_kernel";

@@ -84,7 +84,7 @@ __global__ __launch_bounds__(256) void ukst_pack_w_window_kernel(const uint16_t*
 
 template <int SD>  // dwords per staged dy row
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
-void ukst_grad_input_window_bf16_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict__ wp,
+void ukst_grad_input_window_mfma_bf16_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict__ wp,
                                         float* __restrict__ dx, GiWinArgs a)
 {
     constexpr int S = 4 * SD;
@@ -429,10 +429,10 @@ hipError_t launch_grad_input_window(const Geom& g, const void* dy, const void* w
     if (e != hipSuccess) return e;
     const size_t lds = 2 * (size_t)A_BYTES + 2 * (size_t)a.bBytes;
     typedef void (*kernel_t)(const uint16_t*, const uint16_t*, float*, GiWinArgs);
-    const kernel_t kfn = a.S == 80 ? ukst_grad_input_window_bf16_kernel<20>
-                       : a.S == 160 ? ukst_grad_input_window_bf16_kernel<40>
-                       : a.S == 192 ? ukst_grad_input_window_bf16_kernel<48>
-                                    : ukst_grad_input_window_bf16_kernel<80>;
+    const kernel_t kfn = a.S == 80 ? ukst_grad_input_window_mfma_bf16_kernel<20>
+                       : a.S == 160 ? ukst_grad_input_window_mfma_bf16_kernel<40>
+                       : a.S == 192 ? ukst_grad_input_window_mfma_bf16_kernel<48>
+                                    : ukst_grad_input_window_mfma_bf16_kernel<80>;
     e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     // one block per compute unit (its LDS holds one), each walking over every cus-th tile

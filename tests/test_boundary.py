@@ -229,7 +229,7 @@ def test_backward_kernel_selection_is_host_arithmetic():
         assert name(0, *shape(k), ukst.UKST_F32) == "ukst_grad_input_mfma_kernel", k
         assert name(1, *shape(k), ukst.UKST_F32) == "ukst_grad_weight_mfma_kernel", k
     for k in ("cfg5a", "cfg5b"):
-        assert name(0, *shape(k), ukst.UKST_BF16_F32) == "ukst_grad_input_window_bf16_kernel", k
+        assert name(0, *shape(k), ukst.UKST_BF16_F32) == "ukst_grad_input_window_mfma_bf16_kernel", k
         assert name(1, *shape(k), ukst.UKST_BF16_F32) == "ukst_grad_weight_mfma_bf16_kernel", k
     # bf16 layers the bf16-pipe kernel gradient does not take (n = 5, rows that are no multiple of 8)
     assert name(1, 2, 64, 64, 16, 16, 5, 2, ukst.UKST_BF16_F32) == "ukst_grad_weight_mfma_kernel"
@@ -241,7 +241,7 @@ def test_backward_kernel_selection_is_host_arithmetic():
     assert name(0, 2, 64, 32, 16, 16, 4, 2, ukst.UKST_BF16_F32) == "ukst_grad_input_mfma_bf16_kernel"
     assert name(0, 2, 128, 40, 16, 16, 4, 2, ukst.UKST_BF16_F32) == "ukst_grad_input_mfma_bf16_kernel"
     assert name(0, 2, 128, 32, 16, 8, 4, 2, ukst.UKST_BF16_F32) == "ukst_grad_input_mfma_bf16_kernel"
-    assert name(0, 2, 128, 32, 16, 16, 4, 2, ukst.UKST_BF16_F32) == "ukst_grad_input_window_bf16_kernel"
+    assert name(0, 2, 128, 32, 16, 16, 4, 2, ukst.UKST_BF16_F32) == "ukst_grad_input_window_mfma_bf16_kernel"
     # kernel sides whose tile does not fit the bf16 kernel's LDS budget fall back to the fp32 pipe
     assert name(0, 2, 64, 32, 40, 40, 7, 3, ukst.UKST_BF16_F32) == "ukst_grad_input_mfma_kernel"
     assert name(0, 1, 1, 1, 4, 4, 3, 0, ukst.UKST_BF16_BF16) == ""

@@ -103,7 +103,7 @@ def test_backward_bf16_input_gradient_with_the_taps_in_the_contraction(shape):
     LDS addresses): every element, integer-valued data exactly."""
     B, Cin, Cout, H, W, n, P = shape
     assert ukst.ukst_grad_kernel_name(0, B, Cin, Cout, H, W, n, P, ukst.UKST_BF16_F32) == \
-        "ukst_grad_input_window_bf16_kernel"
+        "ukst_grad_input_window_mfma_bf16_kernel"
     w = _mk("bwd_window", 6900 + sum(shape), B, Cin, Cout, H, W, n, P, dtype="bf16")
     _both(w, integer=True)
     _both(w, integer=False)
@@ -187,7 +187,7 @@ def test_backward_window_kernel_walks_over_tiles_whose_rows_end_elsewhere():
     exactly."""
     w = _mk("bwd_window_walk", 6990, 12, 128, 16, 64, 192, 4, 2, dtype="bf16")
     assert ukst.ukst_grad_kernel_name(0, w.B, w.Cin, w.Cout, w.H, w.W, w.n, w.P, ukst.UKST_BF16_F32) == \
-        "ukst_grad_input_window_bf16_kernel"
+        "ukst_grad_input_window_mfma_bf16_kernel"
     _sampled(w, n_planes=10, n_co=2, n_ci=2, integer=True)
     _sampled(w, n_planes=6, n_co=2, n_ci=2)
 
