@@ -217,7 +217,8 @@ def test_backward_on_a_side_stream_is_bit_reproducible():
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("shape", [(2, 3, 3, 9, 21, 3, 0), (2, 40, 36, 6, 18, 4, 2), (2, 40, 36, 6, 24, 4, 2)])
+@pytest.mark.parametrize("shape", [(2, 3, 3, 9, 21, 3, 0), (2, 40, 36, 6, 18, 4, 2), (2, 40, 36, 6, 24, 4, 2),
+                                   (2, 128, 32, 6, 24, 4, 2)])  # the last: the bf16 window kernel
 def test_backward_operands_with_element_alignment_only(dtype, shape):
     """x, w, dy one element past an aligned address (narrow layer: vector-ALU kernels, wide layer:
     matrix-core kernels): the four-element vector loads of the staging code may assume nothing
@@ -278,3 +279,25 @@ def test_backward_beyond_32bit_byte_offsets():
     for b in range(B):
         Sw += oracle.grad_weight(x[b:b + 1].cpu().numpy(), dy[b:b + 1].cpu().numpy(), n, P)[1]
     assert (np.abs(dw.cpu().numpy().astype(np.float64) - ref) <= 1e-5 * Sw).all()
+
+
+def test_backward_window_kernel_beyond_32bit_byte_offsets():
+    """bf16 dy of 4.4 GB and dx of 17.7 GB through the window kernel: 67584 tiles, 264 per block, the
+    buffer descriptors re-based for every tile.  Integer data, exact comparison of sampled dx planes
+    (first and last image, channels of both ends)."""
+    import torch
+    B, Cin, Cout, H, W, n, P = 33, 128, 16, 1024, 1024, 4, 2
+    OH, OW = oracle.out_shape(H, W, n, P)
+    assert B * Cout * OH * OW * 2 > 1 << 32
+    assert ukst.ukst_grad_kernel_name(0, B, Cin, Cout, H, W, n, P, ukst.UKST_BF16_F32) == \
+        "ukst_grad_input_window_mfma_bf16_kernel"
+    print(f"case bwd_window_big B={B} Cin={Cin} Cout={Cout} H={H} W={W} n={n} P={P}", flush=True)
+    g = torch.Generator(device="cuda").manual_seed(20493)
+    k = torch.randint(-3, 4, (Cout, Cin, n, n), generator=g, device="cuda", dtype=torch.int8).to(torch.bfloat16)
+    dy = torch.randint(-3, 4, (B, Cout, OH, OW), generator=g, device="cuda", dtype=torch.int8).to(torch.bfloat16)
+    dx = ukst.ukst_conv_transpose2d_grad_input(dy, k, H, W, P)
+    torch.cuda.synchronize()
+    kh = k.float().cpu().numpy()
+    for b, ci in ((0, 0), (B - 1, Cin - 1), (B - 1, 5), (17, 64)):
+        ref, _ = oracle.grad_input(dy[b:b + 1].float().cpu().numpy(), kh[:, ci:ci + 1], H, W, P)
+        assert np.array_equal(dx[b, ci].cpu().numpy().astype(np.float64), ref[0, 0]), (b, ci)
