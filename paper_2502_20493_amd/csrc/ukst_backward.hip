@@ -829,6 +829,7 @@ hipError_t launch_gi_n(const Geom& g, const void* dy, const void* w, float* dx, 
                        Workspace& ws, hipStream_t stream)
 {
     if (grad_input_window_supported(g, dtype)) return launch_grad_input_window(g, dy, w, dx, ws, stream);
+    if (grad_narrow_supported(g, dtype)) return launch_grad_narrow(0, g, dy, w, dx, ws, stream);
     GiMfmaArgs ma;
     if (dtype == 1 && gi_mfma_args(g, ma, true)) return launch_gi_mfma_bf16<N>(ma, dy, w, dx, ws, stream);
     if (gi_mfma_args(g, ma))
@@ -2263,6 +2264,7 @@ hipError_t launch_gw_t(const Geom& g, const void* x, const void* dy, float* dw, 
 const char* grad_kernel_name(const Geom& g, int which, int dtype)
 {
     if (which == 1) {
+        if (grad_narrow_supported(g, dtype)) return "ukst_grad_weight_narrow_kernel";
         GwB16Args ba;
         if (dtype == 1 && gw_b16_args(g, ba)) return "ukst_grad_weight_mfma_bf16_kernel";
         GwMfmaArgs wa;
@@ -2275,6 +2277,7 @@ const char* grad_kernel_name(const Geom& g, int which, int dtype)
         return th ? "ukst_grad_weight_thin_mfma_kernel" : "ukst_grad_weight_kernel";
     }
     if (grad_input_window_supported(g, dtype)) return "ukst_grad_input_window_mfma_bf16_kernel";
+    if (grad_narrow_supported(g, dtype)) return "ukst_grad_input_narrow_kernel";
     GiMfmaArgs ma;
     if (dtype == 1 && gi_mfma_args(g, ma, true)) return "ukst_grad_input_mfma_bf16_kernel";
     return gi_mfma_args(g, ma) ? "ukst_grad_input_mfma_kernel" : "ukst_grad_input_kernel";
@@ -2298,6 +2301,7 @@ hipError_t launch_grad_input(const Geom& g, const void* dy, const void* w, float
 hipError_t launch_grad_weight(const Geom& g, const void* x, const void* dy, float* dw, int dtype,
                               Workspace& ws, hipStream_t stream)
 {
+    if (grad_narrow_supported(g, dtype)) return launch_grad_narrow(1, g, x, dy, dw, ws, stream);
     return dtype == 1 ? launch_gw_t<uint16_t>(g, x, dy, dw, ws, stream)
                       : launch_gw_t<float>(g, x, dy, dw, ws, stream);
 }

@@ -338,8 +338,8 @@ void ukst_grad_input_window_mfma_bf16_kernel(const uint16_t* __restrict__ dy, co
                         if (ci0 + mi * 32 + 8 * q >= g.Cin) continue;  // uniform: Cin is a multiple of 8
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
-                            // through a vector register: as a direct operand of the store every
-                            // element of the accumulator tile came out as its first one
+                            // element by value, through a register of its own: a bit cast applied to
+                            // an element of a vector reads element 0
                             float v = acc[mi][t][4 * q + r];
                             asm volatile("" : "+v"(v));
                             __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), rs_dx, voff,

@@ -176,6 +176,12 @@ hipError_t launch_grad_weight(const Geom& g, const void* x, const void* dy, floa
 bool grad_input_window_supported(const Geom& g, int dtype);
 hipError_t launch_grad_input_window(const Geom& g, const void* dy, const void* w, float* dx, Workspace& ws,
                                     hipStream_t stream);
+// Both gradients of narrow fp32 layers (Cin, Cout <= 4, 2 <= n <= 5, maps at least 32 wide):
+// register-blocked strips, edges by buffer addressing.  which 0: (p0, p1) = (dy, w) -> dx, no scratch;
+// which 1: (p0, p1) = (x, dy) -> dw, one copy of dw per block in the workspace
+bool grad_narrow_supported(const Geom& g, int dtype);
+hipError_t launch_grad_narrow(int which, const Geom& g, const void* p0, const void* p1, float* out, Workspace& ws,
+                              hipStream_t stream);
 // which: 0 gradient w.r.t. the input, 1 w.r.t. the kernel
 const char* grad_kernel_name(const Geom& g, int which, int dtype);
 

@@ -218,8 +218,15 @@ def test_backward_kernel_selection_is_host_arithmetic():
     w = wl.WORKLOADS
     def shape(k):
         return (w[k].B, w[k].Cin, w[k].Cout, w[k].H, w[k].W, w[k].n, w[k].P)
-    assert name(0, *shape("cfg2a"), ukst.UKST_F32) == "ukst_grad_input_kernel"
-    assert name(1, *shape("cfg2a"), ukst.UKST_F32) == "ukst_grad_weight_kernel"      # 3 input channels
+    for k in ("cfg2a", "cfg2b"):  # narrow fp32 image layers: register-blocked strips
+        assert name(0, *shape(k), ukst.UKST_F32) == "ukst_grad_input_narrow_kernel"
+        assert name(1, *shape(k), ukst.UKST_F32) == "ukst_grad_weight_narrow_kernel"
+    # narrow layers those kernels do not take: bf16 operands, maps narrower than 32, n = 1 or n > 5
+    assert name(0, *shape("cfg2a"), ukst.UKST_BF16_F32) == "ukst_grad_input_kernel"
+    assert name(1, *shape("cfg2a"), ukst.UKST_BF16_F32) == "ukst_grad_weight_kernel"
+    assert name(0, 2, 3, 3, 40, 24, 3, 0, ukst.UKST_F32) == "ukst_grad_input_kernel"
+    assert name(1, 2, 3, 3, 40, 40, 6, 0, ukst.UKST_F32) == "ukst_grad_weight_kernel"
+    assert name(1, 2, 3, 3, 40, 40, 1, 0, ukst.UKST_F32) == "ukst_grad_weight_kernel"
     assert name(0, *shape("cfg3_L4"), ukst.UKST_F32) == "ukst_grad_input_kernel"      # Cout = 3
     assert name(1, *shape("cfg3_L4"), ukst.UKST_F32) == "ukst_grad_weight_thin_mfma_kernel"  # 3 x 16 rows
     assert name(1, 2, 16, 5, 16, 16, 4, 2, ukst.UKST_F32) == "ukst_grad_weight_kernel"   # 5 x 16 rows: too many

@@ -129,6 +129,26 @@ def test_backward_thin_kernel_gradient_on_the_matrix_cores(shape):
     _both(w.with_(dtype="bf16"), integer=False)
 
 
+@pytest.mark.parametrize("shape", [
+    (2, 3, 3, 19, 45, 3, 0),       # the image layer in small: windows begin two columns left of the rows
+    (1, 4, 4, 9, 300, 4, 2),       # two 256-column chunks, four channels on both sides
+    (2, 1, 2, 7, 33, 2, 1),        # n = 2, one input channel, odd H (a row pair with one row)
+    (3, 2, 4, 5, 64, 5, 4),        # n = 5 with P = n - 1: no window begins left of its row
+    (2, 3, 3, 8, 40, 3, 3),        # P > n - 1: the first dy rows and columns meet nothing
+    (1, 3, 1, 33, 257, 5, 0),      # n = 5, P = 0: windows begin four columns left; one pixel in the second chunk
+    (5, 4, 3, 3, 32, 4, 0)])       # the narrowest map the kernels take
+def test_backward_narrow_layers_register_blocked_strips(shape):
+    """fp32 layers with at most 4 channels on both sides, 2 <= n <= 5 and maps at least 32 wide:
+    both gradients from register-blocked four-column strips with the edges left to the buffer
+    addressing hardware.  Every element, integer-valued data exactly."""
+    B, Cin, Cout, H, W, n, P = shape
+    assert ukst.ukst_grad_kernel_name(0, B, Cin, Cout, H, W, n, P, ukst.UKST_F32) == "ukst_grad_input_narrow_kernel"
+    assert ukst.ukst_grad_kernel_name(1, B, Cin, Cout, H, W, n, P, ukst.UKST_F32) == "ukst_grad_weight_narrow_kernel"
+    w = _mk("bwd_narrow", 7300 + sum(shape), B, Cin, Cout, H, W, n, P)
+    _both(w, integer=True)
+    _both(w, integer=False)
+
+
 def test_backward_cfg2_images_full_size():
     for name in ("cfg2a", "cfg2b"):
         _both(wl.WORKLOADS[name], guard=1 << 16)
