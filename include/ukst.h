@@ -254,7 +254,9 @@ size_t ukst_static_workspace_bytes(void);
  * "ukst_grad_weight_mfma_kernel": fp32 MFMA for everything else of that width, either dtype).
  * Layers with at most 4 output channels, Cout * n * n <= 64 and Cin >= 16 run the kernel gradient
  * as "ukst_grad_weight_thin_mfma_kernel" (fp32 MFMA whose rows are (channel, tap) pairs).
- * Everything else runs on the vector ALUs.
+ * Narrow fp32 layers (Cin, Cout <= 4, 2 <= n <= 5, W >= 32) run both gradients as
+ * "ukst_grad_input_narrow_kernel" / "ukst_grad_weight_narrow_kernel" (register-blocked strips on
+ * the vector ALUs, no LDS).  Everything else runs on the general vector-ALU kernels.
  */
 const char* ukst_grad_kernel_name(int which, int B, int Cin, int Cout, int H, int W, int n, int P,
                                   int dtype);

@@ -86,22 +86,24 @@ struct NarrowGradArgs {
     int unitsPerWave;   // kernel gradient: consecutive items a wave adds up
 };
 
-// Kernel gradient.  grid = (blocks, Cout): a block's four waves each add up unitsPerWave
+// Kernel gradient.  grid = (blocks, Cout): a block's eight waves each add up unitsPerWave
 // (image, row, chunk) items of one output channel in CI * n * n registers per lane, the lanes are
 // summed with row shifts, the waves through LDS in wave order, and the block writes its copy of
 // dw[co]; the copies are added in a fixed order afterwards.
+constexpr int GW_WAVES = 8;  // waves per block of the kernel gradient: one copy of dw per 8 waves
+
 template <int N, int CI>
-__global__ __launch_bounds__(256) void ukst_grad_weight_narrow_kernel(const float* __restrict__ x,
+__global__ __launch_bounds__(64 * GW_WAVES) void ukst_grad_weight_narrow_kernel(const float* __restrict__ x,
                                                                      const float* __restrict__ dy,
                                                                      float* __restrict__ part, NarrowGradArgs a)
 {
     constexpr int NWP = window_regs(N), NN = N * N;
-    __shared__ float red[4][CI * NN];
+    __shared__ float red[GW_WAVES][CI * NN];
     const GeomBase& g = a.g;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int co = blockIdx.y;
-    const int wid = blockIdx.x * 4 + wave;
+    const int wid = blockIdx.x * GW_WAVES + wave;
     const size_t xplane = (size_t)g.H * g.W, yplane = (size_t)g.OH * g.OW;
     const unsigned xrow = (unsigned)g.W * 4u, yrow = (unsigned)g.OW * 4u;
 
@@ -162,7 +164,9 @@ __global__ __launch_bounds__(256) void ukst_grad_weight_narrow_kernel(const floa
     __syncthreads();
     if (threadIdx.x < CI * NN) {
         const int t = threadIdx.x;
-        const float s = ((red[0][t] + red[1][t]) + red[2][t]) + red[3][t];
+        float s = red[0][t];
+#pragma unroll
+        for (int wv = 1; wv < GW_WAVES; ++wv) s += red[wv][t];
         part[((size_t)blockIdx.x * g.Cout + co) * (CI * NN) + t] = s;
     }
 }
@@ -213,31 +217,44 @@ __global__ __launch_bounds__(256) void ukst_grad_input_narrow_kernel(const float
             for (int p = 0; p < 4; ++p) acc[h][c][p] = 0.f;
 
     const int oy0 = 2 * i0 + g.P - (N - 1);  // first dy row the row pair meets
-    for (int co = 0; co < g.Cout; ++co) {
-        const float* plane = dy + ((size_t)b * g.Cout + co) * yplane;
-        float row[N + 2][NWP];
+    // output channels per group whose dy rows are all requested before the first is used.  One at a
+    // time is fastest (cfg2a 16.8 us; two 18.0, all three 18.9): the 64 registers of that form let
+    // every wave of the grid be resident at once, and that, not a wave's own round trips, is what
+    // covers the memory latency here
+    constexpr int CG = 1;
+    for (int cg = 0; cg < g.Cout; cg += CG) {
+        float row[CG][N + 2][NWP];
 #pragma unroll
-        for (int rr = 0; rr < N + 2; ++rr) {
-            const int oy = oy0 + rr;
-            const bool have = oy >= 0 && oy < g.OH;
-            const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
-                (void*)plane, 0, have ? (int)((unsigned)(oy + 1) * yrow) : 0, kRsrcFlags);
-            load_window<N>(rs, 2 * j0 + g.P - (N - 1), have ? (unsigned)oy * yrow : 0u, lane, row[rr]);
+        for (int q = 0; q < CG; ++q) {
+            const bool chan = cg + q < g.Cout;  // uniform
+            const float* plane = dy + ((size_t)b * g.Cout + (chan ? cg + q : 0)) * yplane;
+#pragma unroll
+            for (int rr = 0; rr < N + 2; ++rr) {
+                const int oy = oy0 + rr;
+                const bool have = chan && oy >= 0 && oy < g.OH;
+                const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+                    (void*)plane, 0, have ? (int)((unsigned)(oy + 1) * yrow) : 0, kRsrcFlags);
+                load_window<N>(rs, 2 * j0 + g.P - (N - 1), have ? (unsigned)oy * yrow : 0u, lane, row[q][rr]);
+            }
         }
         // input row i0 + h meets dy row 2 (i0 + h) + P - k = oy0 + 2 h + (N - 1 - k)
 #pragma unroll
-        for (int c = 0; c < CI; ++c)
+        for (int q = 0; q < CG; ++q) {
+            if (cg + q >= g.Cout) break;  // uniform
 #pragma unroll
-            for (int k = 0; k < N; ++k)
+            for (int c = 0; c < CI; ++c)
 #pragma unroll
-                for (int l = 0; l < N; ++l) {
-                    const float wv = ws[((size_t)co * g.Cin + c) * NN + k * N + l];
+                for (int k = 0; k < N; ++k)
 #pragma unroll
-                    for (int h = 0; h < 2; ++h)
+                    for (int l = 0; l < N; ++l) {
+                        const float wv = ws[((size_t)(cg + q) * g.Cin + c) * NN + k * N + l];
 #pragma unroll
-                        for (int p = 0; p < 4; ++p)
-                            acc[h][c][p] = fmaf(row[2 * h + (N - 1 - k)][2 * p + (N - 1 - l)], wv, acc[h][c][p]);
-                }
+                        for (int h = 0; h < 2; ++h)
+#pragma unroll
+                            for (int p = 0; p < 4; ++p)
+                                acc[h][c][p] = fmaf(row[q][2 * h + (N - 1 - k)][2 * p + (N - 1 - l)], wv, acc[h][c][p]);
+                    }
+        }
     }
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
@@ -275,21 +292,22 @@ hipError_t launch_gw_narrow(NarrowGradArgs a, const void* x, const void* dy, flo
     const long long units = (long long)g.B * g.H * a.chunks;
     if (units > 0x3fffffffLL) return hipErrorInvalidConfiguration;
     a.nUnits = (int)units;
-    // about 2048 waves over the whole grid (eight per compute unit of the chip this is written
-    // for); a figure of the shape alone, so that the workspace size is host arithmetic
+    // about 8192 waves over the whole grid (one or two work items each: what hides the memory
+    // latency is the number of waves in flight); a figure of the shape alone, so that the workspace
+    // size is host arithmetic
     hipError_t e;
-    long long waves = 2048 / g.Cout;
-    if (waves < 4) waves = 4;
+    long long waves = 8192 / g.Cout;
+    if (waves < GW_WAVES) waves = GW_WAVES;
     if (waves > units) waves = units;
     a.unitsPerWave = (int)((units + waves - 1) / waves);
     const int nwaves = (int)((units + a.unitsPerWave - 1) / a.unitsPerWave);
-    const int blocks = (nwaves + 3) / 4;
+    const int blocks = (nwaves + GW_WAVES - 1) / GW_WAVES;
     const int elems = g.Cout * CI * N * N;
     const size_t need = (size_t)blocks * elems * sizeof(float);
     if (ws.query) { ws.need = need; return hipSuccess; }
     if (ws.bytes < need) return kWorkspaceTooSmall;
     float* part = (float*)ws.ptr;
-    hipLaunchKernelGGL((ukst_grad_weight_narrow_kernel<N, CI>), dim3((unsigned)blocks, (unsigned)g.Cout), dim3(256), 0,
+    hipLaunchKernelGGL((ukst_grad_weight_narrow_kernel<N, CI>), dim3((unsigned)blocks, (unsigned)g.Cout), dim3(64 * GW_WAVES), 0,
                        stream, (const float*)x, (const float*)dy, part, a);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
