@@ -136,7 +136,8 @@ def test_backward_thin_kernel_gradient_on_the_matrix_cores(shape):
     (3, 2, 4, 5, 64, 5, 4),        # n = 5 with P = n - 1: no window begins left of its row
     (2, 3, 3, 8, 40, 3, 3),        # P > n - 1: the first dy rows and columns meet nothing
     (1, 3, 1, 33, 257, 5, 0),      # n = 5, P = 0: windows begin four columns left; one pixel in the second chunk
-    (5, 4, 3, 3, 32, 4, 0)])       # the narrowest map the kernels take
+    (5, 4, 3, 3, 32, 4, 0),        # the narrowest map the kernels take
+    (1, 3, 3, 8, 40, 3, 300)])     # padding far beyond the kernel: most of dy meets no input at all
 def test_backward_narrow_layers_register_blocked_strips(shape):
     """fp32 layers with at most 4 channels on both sides, 2 <= n <= 5 and maps at least 32 wide:
     both gradients from register-blocked four-column strips with the edges left to the buffer
