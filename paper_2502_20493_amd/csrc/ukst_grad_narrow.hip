@@ -4,7 +4,7 @@
 // Input pixel (i,j) meets output pixel (2i+P-k, 2j+P-l) through tap (k,l) (Eqs. 1-4 read
 // backwards), so four consecutive input columns j0..j0+3 meet the n+6 dy columns that start at
 // 2 j0 + P - (n-1), in the rows 2i + P - k.  A lane owns such a strip of four columns, a wave 256
-// consecutive columns of one row (or row pair), and every index of the arithmetic is a
+// consecutive columns of one row, and every index of the arithmetic is a
 // compile-time constant: the dy window of a row sits in n+6 registers.  No LDS staging.
 //
 // Edges are left to the buffer addressing hardware, as in the narrow forward kernel: a row is
@@ -19,11 +19,14 @@ namespace ukst {
 namespace {
 
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 typedef const float __attribute__((address_space(4)))* scalar_fptr;  // read through the scalar cache
 constexpr int kRsrcFlags = 0x00020000;      // raw 32-bit buffer, gfx9 family
 constexpr unsigned kLeftOfRow = 0x7FFF0000u;  // plus any row start below 2^31: beyond every row end
 
-constexpr int window_regs(int n) { return 12; }  // 8 own columns + n - 2 <= 3 of the next lane
+constexpr int PXL = 4;  // input columns per lane: a wave covers 64 * PXL columns of a row (2 was no faster)
+constexpr int OWN = 2 * PXL;  // dy columns a lane fetches itself
+constexpr int window_regs(int n) { return OWN + 4; }  // + n - 2 <= 3 columns of the next lane
 
 // The n+6 dy columns that start at column c0 = 8 * lane + const (may be negative in lane 0) of the
 // row described by (rs, row_off).  Neighbouring lanes' windows overlap in n-2 columns: a lane
@@ -41,11 +44,12 @@ __device__ __forceinline__ void load_window(__amdgpu_buffer_rsrc_t rs, int c0, u
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = __uint_as_float(t[e]);
     }
-    {   // c0 + 4 >= 0: a window begins at most four columns left of its row
-        const u32x4 q = __builtin_amdgcn_raw_buffer_load_b128(rs, (unsigned)(4 * (c0 + 4)), row_off, 0);
+#pragma unroll
+    for (int m = 4; m < OWN; m += 4) {  // c0 + 4 >= 0: a window begins at most four columns left of its row
+        const u32x4 q = __builtin_amdgcn_raw_buffer_load_b128(rs, (unsigned)(4 * (c0 + m)), row_off, 0);
         const unsigned t[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[4 + e] = __uint_as_float(t[e]);
+        for (int e = 0; e < 4; ++e) v[m + e] = __uint_as_float(t[e]);
     }
     if (c0 < 0) {
 #pragma unroll
@@ -54,12 +58,12 @@ __device__ __forceinline__ void load_window(__amdgpu_buffer_rsrc_t rs, int c0, u
     }
 #pragma unroll
     for (int e = 0; e < 4; ++e)  // lane i takes lane i + 1's (wave_shl:1), zeros into lane 63
-        v[8 + e] = e < N - 2 ? __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v[e]), 0x130, 0xF, 0xF, true)) : 0.f;
+        v[OWN + e] = e < N - 2 ? __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v[e]), 0x130, 0xF, 0xF, true)) : 0.f;
     if (N > 2 && lane == 63) {
-        const u32x4 q = __builtin_amdgcn_raw_buffer_load_b128(rs, (unsigned)(4 * (c0 + 8)), row_off, 0);
+        const u32x4 q = __builtin_amdgcn_raw_buffer_load_b128(rs, (unsigned)(4 * (c0 + OWN)), row_off, 0);
         const unsigned t[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[8 + e] = __uint_as_float(t[e]);
+        for (int e = 0; e < 4; ++e) v[OWN + e] = __uint_as_float(t[e]);
     }
 }
 
@@ -82,7 +86,7 @@ __device__ __forceinline__ float wave_sum_to_last(float v)
 struct NarrowGradArgs {
     GeomBase g;
     int chunks;         // 256-column chunks per row
-    int nUnits;         // wave work items: (image, row or row pair, chunk)
+    int nUnits;         // wave work items: (image, row, chunk)
     int unitsPerWave;   // kernel gradient: consecutive items a wave adds up
 };
 
@@ -119,17 +123,24 @@ __global__ __launch_bounds__(64 * GW_WAVES) void ukst_grad_weight_narrow_kernel(
     for (int u = wid * a.unitsPerWave; u < u_end; ++u) {  // uniform
         const int chunk = u % a.chunks, r = u / a.chunks;
         const int i = r % g.H, b = r / g.H;
-        const int j0 = chunk * 256 + 4 * lane;
-        float xv[CI][4];
+        const int j0 = chunk * (64 * PXL) + PXL * lane;
+        float xv[CI][PXL];
 #pragma unroll
         for (int c = 0; c < CI; ++c) {
             // row i of plane (b, c): dwords past its end are zeros
             const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
                 (void*)(x + ((size_t)b * g.Cin + c) * xplane), 0, (int)((unsigned)(i + 1) * xrow), kRsrcFlags);
-            const u32x4 q = __builtin_amdgcn_raw_buffer_load_b128(rs, (unsigned)(4 * j0), (unsigned)i * xrow, 0);
-            const unsigned t[4] = {q.x, q.y, q.z, q.w};
+            if constexpr (PXL == 4) {
+                const u32x4 q = __builtin_amdgcn_raw_buffer_load_b128(rs, (unsigned)(4 * j0), (unsigned)i * xrow, 0);
+                const unsigned t[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
-            for (int e = 0; e < 4; ++e) xv[c][e] = __uint_as_float(t[e]);
+                for (int e = 0; e < PXL; ++e) xv[c][e] = __uint_as_float(t[e]);
+            } else {
+                const u32x2 q = __builtin_amdgcn_raw_buffer_load_b64(rs, (unsigned)(4 * j0), (unsigned)i * xrow, 0);
+                const unsigned t[2] = {q.x, q.y};
+#pragma unroll
+                for (int e = 0; e < PXL; ++e) xv[c][e] = __uint_as_float(t[e]);
+            }
         }
         float row[N][NWP];
         const float* plane = dy + ((size_t)b * g.Cout + co) * yplane;
@@ -149,7 +160,7 @@ __global__ __launch_bounds__(64 * GW_WAVES) void ukst_grad_weight_narrow_kernel(
 #pragma unroll
                 for (int l = 0; l < N; ++l)
 #pragma unroll
-                    for (int p = 0; p < 4; ++p) acc[c][k][l] = fmaf(row[k][2 * p + (N - 1 - l)], xv[c][p], acc[c][k][l]);
+                    for (int p = 0; p < PXL; ++p) acc[c][k][l] = fmaf(row[k][2 * p + (N - 1 - l)], xv[c][p], acc[c][k][l]);
     }
 
 #pragma unroll
@@ -185,10 +196,11 @@ __global__ __launch_bounds__(256) void ukst_sum_copies_narrow_kernel(const float
     if (lane == 63) dw[e] = s;
 }
 
-// Input gradient.  A wave owns 256 columns of two consecutive rows of one image, a lane four of
-// the columns for every input channel; per output channel the n+2 dy rows the two rows meet are
-// fetched (n+6 dwords each) and multiplied with the channel's weights, which come through the
-// scalar cache.  One 16-byte store per lane, channel and row.
+// Input gradient.  A wave owns 256 columns of one row of one image (two rows per wave share a dy
+// row but halve the waves: 16.8 us instead of 14.7 on the 224 x 224 image layer, four rows 24.3), a
+// lane four of the columns for every input channel; per output channel the n dy rows the row meets
+// are fetched (n+6 dwords each) and multiplied with the channel's weights, which come through the
+// scalar cache.  One 16-byte store per lane and channel.
 template <int N, int CI>
 __global__ __launch_bounds__(256) void ukst_grad_input_narrow_kernel(const float* __restrict__ dy,
                                                                     const float* __restrict__ w,
@@ -201,20 +213,21 @@ __global__ __launch_bounds__(256) void ukst_grad_input_narrow_kernel(const float
     const int u = xcd_contiguous(blockIdx.x, gridDim.x) * 4 + wave;
     if (u >= a.nUnits) return;  // whole waves, no barrier below
     const int chunk = u % a.chunks, r = u / a.chunks;
-    const int hp = (g.H + 1) >> 1;
-    const int i0 = 2 * (r % hp), b = r / hp;
-    const int j0 = chunk * 256 + 4 * lane;
+    constexpr int RH = 1;  // input rows per wave
+    const int hp = (g.H + RH - 1) / RH;
+    const int i0 = RH * (r % hp), b = r / hp;
+    const int j0 = chunk * (64 * PXL) + PXL * lane;
     const size_t xplane = (size_t)g.H * g.W, yplane = (size_t)g.OH * g.OW;
     const unsigned xrow = (unsigned)g.W * 4u, yrow = (unsigned)g.OW * 4u;
     const scalar_fptr ws = (scalar_fptr)(unsigned long long)w;
 
-    float acc[2][CI][4];
+    float acc[RH][CI][PXL];
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
+    for (int h = 0; h < RH; ++h)
 #pragma unroll
         for (int c = 0; c < CI; ++c)
 #pragma unroll
-            for (int p = 0; p < 4; ++p) acc[h][c][p] = 0.f;
+            for (int p = 0; p < PXL; ++p) acc[h][c][p] = 0.f;
 
     const int oy0 = 2 * i0 + g.P - (N - 1);  // first dy row the row pair meets
     // output channels per group whose dy rows are all requested before the first is used.  One at a
@@ -223,13 +236,13 @@ __global__ __launch_bounds__(256) void ukst_grad_input_narrow_kernel(const float
     // covers the memory latency here
     constexpr int CG = 1;
     for (int cg = 0; cg < g.Cout; cg += CG) {
-        float row[CG][N + 2][NWP];
+        float row[CG][N + 2 * RH - 2][NWP];
 #pragma unroll
         for (int q = 0; q < CG; ++q) {
             const bool chan = cg + q < g.Cout;  // uniform
             const float* plane = dy + ((size_t)b * g.Cout + (chan ? cg + q : 0)) * yplane;
 #pragma unroll
-            for (int rr = 0; rr < N + 2; ++rr) {
+            for (int rr = 0; rr < N + 2 * RH - 2; ++rr) {
                 const int oy = oy0 + rr;
                 const bool have = chan && oy >= 0 && oy < g.OH;
                 const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
@@ -249,27 +262,34 @@ __global__ __launch_bounds__(256) void ukst_grad_input_narrow_kernel(const float
                     for (int l = 0; l < N; ++l) {
                         const float wv = ws[((size_t)(cg + q) * g.Cin + c) * NN + k * N + l];
 #pragma unroll
-                        for (int h = 0; h < 2; ++h)
+                        for (int h = 0; h < RH; ++h)
 #pragma unroll
-                            for (int p = 0; p < 4; ++p)
+                            for (int p = 0; p < PXL; ++p)
                                 acc[h][c][p] = fmaf(row[q][2 * h + (N - 1 - k)][2 * p + (N - 1 - l)], wv, acc[h][c][p]);
                     }
         }
     }
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
+    for (int h = 0; h < RH; ++h) {
         const int i = i0 + h;
         const bool have = i < g.H;
 #pragma unroll
         for (int c = 0; c < CI; ++c) {
             const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
                 (void*)(dx + ((size_t)b * g.Cin + c) * xplane), 0, have ? (int)((unsigned)(i + 1) * xrow) : 0, kRsrcFlags);
-            u32x4 q;
-            q.x = __float_as_uint(acc[h][c][0]); q.y = __float_as_uint(acc[h][c][1]);
-            q.z = __float_as_uint(acc[h][c][2]); q.w = __float_as_uint(acc[h][c][3]);
             // the whole offset in the vector offset, scalar offset a literal 0: the form of a 16-byte
             // store whose data registers the compiler keeps apart from the next write to them
-            __builtin_amdgcn_raw_buffer_store_b128(q, rs, (unsigned)(4 * j0) + (have ? (unsigned)i * xrow : 0u), 0, 0);
+            const unsigned off = (unsigned)(4 * j0) + (have ? (unsigned)i * xrow : 0u);
+            if constexpr (PXL == 4) {
+                u32x4 q;
+                q.x = __float_as_uint(acc[h][c][0]); q.y = __float_as_uint(acc[h][c][1]);
+                q.z = __float_as_uint(acc[h][c][2]); q.w = __float_as_uint(acc[h][c][3]);
+                __builtin_amdgcn_raw_buffer_store_b128(q, rs, off, 0, 0);
+            } else {
+                u32x2 q;
+                q.x = __float_as_uint(acc[h][c][0]); q.y = __float_as_uint(acc[h][c][1]);
+                __builtin_amdgcn_raw_buffer_store_b64(q, rs, off, 0, 0);
+            }
         }
     }
 }
@@ -280,7 +300,7 @@ bool narrow_args(const Geom& g, int dtype, NarrowGradArgs& a)
     // rows are addressed with 32-bit byte offsets inside their plane
     if ((size_t)g.H * g.W * 4 >= 0x7FFF0000u || (size_t)g.OH * g.OW * 4 >= 0x7FFF0000u) return false;
     a.g = g;
-    a.chunks = (g.W + 255) / 256;
+    a.chunks = (g.W + 64 * PXL - 1) / (64 * PXL);
     return true;
 }
 
@@ -320,7 +340,7 @@ template <int N, int CI>
 hipError_t launch_gi_narrow(NarrowGradArgs a, const void* dy, const void* w, float* dx, hipStream_t stream)
 {
     const GeomBase& g = a.g;
-    const long long units = (long long)g.B * ((g.H + 1) / 2) * a.chunks;
+    const long long units = (long long)g.B * ((g.H + 1 - 1) / 1) * a.chunks;
     if (units > 0x3fffffffLL) return hipErrorInvalidConfiguration;
     a.nUnits = (int)units;
     a.unitsPerWave = 1;
