@@ -96,7 +96,8 @@ void ukst_grad_input_window_mfma_bf16_kernel(const uint16_t* __restrict__ dy, co
     const int tid16 = 16 * tid;
     const size_t plane = (size_t)g.OH * g.OW;
     const unsigned co_stage_bytes = (unsigned)(KC * plane * 2);
-    const int ns = a.nStages;
+    const int nreal = a.nStages;          // stages of 8 output channels that exist
+    const int ns = (nreal + 1) & ~1;      // an odd count is padded with a stage of zeros
     const int G = gridDim.x;
 
     // tile of a position in the walk: channel tile fastest, so that the blocks of one XCD (which
@@ -130,7 +131,7 @@ void ukst_grad_input_window_mfma_bf16_kernel(const uint16_t* __restrict__ dy, co
         rs_dy = __builtin_amdgcn_make_buffer_rsrc((void*)(dy + img0), 0,
                                                   (int)(left < 0xFFFFFF00u ? left : 0xFFFFFF00u), kRsrcFlags);
         rs_w = __builtin_amdgcn_make_buffer_rsrc((void*)(wp + (size_t)t.cit * g.Cout * (2 * CI_T * 8)), 0,
-                                                 ns * A_BYTES, kRsrcFlags);
+                                                 nreal * A_BYTES, kRsrcFlags);
         a_voff = present ? (unsigned)tid16 : kInvalid;
         const int oy_base = 2 * t.i0 + g.P - 3, ox_base = 2 * t.j0 + g.P - 3;
         const int tid_o = opaque(tid);  // nothing of this is to be kept from tile to tile
@@ -171,11 +172,13 @@ void ukst_grad_input_window_mfma_bf16_kernel(const uint16_t* __restrict__ dy, co
 
     u32x4 R[NIT];
     auto load_item = [&](int it, int stage) {
+        const bool real = stage < nreal;  // uniform; the padding stage reads zeros through the invalid offset
         if (it < NPA)
-            R[it] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, a_voff, (unsigned)(stage * A_BYTES + 4096 * it), 0);
+            R[it] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, real ? a_voff : kInvalid,
+                                                          real ? (unsigned)(stage * A_BYTES + 4096 * it) : 0u, 0);
         else
-            R[it] = __builtin_amdgcn_raw_buffer_load_b128(rs_dy, b_voff[it - NPA],
-                                                          (unsigned)stage * co_stage_bytes, 0);
+            R[it] = __builtin_amdgcn_raw_buffer_load_b128(rs_dy, real ? b_voff[it - NPA] : kInvalid,
+                                                          real ? (unsigned)stage * co_stage_bytes : 0u, 0);
     };
     // writes the item into buffer `buf`; dtoggle turns its LDS address to the other buffer afterwards
     auto store_item = [&](int it, int buf, int dtoggle) {
@@ -307,7 +310,7 @@ void ukst_grad_input_window_mfma_bf16_kernel(const uint16_t* __restrict__ dy, co
                 }
             }
         };
-        for (int s = 0; s < ns; s += 2) {  // ns is even (a second stage under a condition of its own spills)
+        for (int s = 0; s < ns; s += 2) {  // ns is even (a second stage call under a condition of its own spills)
             stage(t0, s);
             stage(t1, s + 1);
         }
@@ -361,7 +364,7 @@ int log2_of(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
 
 static bool gi_win_args(const Geom& g, GiWinArgs& a)
 {
-    if (g.n != 4 || g.Cout % (2 * KC) != 0 || g.Cin <= 64 || g.Cin % 8 != 0 || g.W < 16 || g.OW < 8 || g.H < 1)
+    if (g.n != 4 || g.Cout % KC != 0 || g.Cin <= 64 || g.Cin % 8 != 0 || g.W < 16 || g.OW < 8 || g.H < 1)
         return false;
     a.g = g;
     a.TJ = g.W <= 16 ? 16 : g.W <= 32 ? 32 : 64;

@@ -95,10 +95,12 @@ def test_backward_bf16_kernel_gradient_on_the_bf16_matrix_pipe(shape):
     (2, 96, 16, 16, 32, 4, 3),     # 32-column tiles, P > n / 2, fewer channels than a channel tile
     (2, 72, 32, 5, 17, 4, 2),      # W = 17 in a 32-column tile, rows beyond the map
     (4, 256, 32, 16, 16, 4, 2),    # cfg5b's map: two images per tile, two channel tiles
-    (1, 128, 64, 24, 128, 4, 2)])  # cfg5a's rows: both column tiles touch one end of the dy rows
+    (1, 128, 64, 24, 128, 4, 2),   # cfg5a's rows: both column tiles touch one end of the dy rows
+    (2, 128, 24, 8, 16, 4, 2),     # three stages of output channels: padded with a stage of zeros
+    (1, 72, 8, 5, 40, 4, 1)])      # a single stage
 def test_backward_bf16_input_gradient_with_the_taps_in_the_contraction(shape):
-    """bf16 layers with 4 x 4 kernels, more than 64 input channels, output channels in multiples of
-    16 and maps at least 16 wide take the input gradient on the bf16 MFMA pipe with a channel's 16
+    """bf16 layers with 4 x 4 kernels, more than 64 input channels in multiples of 8, output channels
+    in multiples of 8 and maps at least 16 wide take the input gradient on the bf16 MFMA pipe with a channel's 16
     taps as the contraction (dy staged as it lies in memory, row-end pieces written at 2-byte-aligned
     LDS addresses): every element, integer-valued data exactly."""
     B, Cin, Cout, H, W, n, P = shape
