@@ -11,14 +11,16 @@
 //   B (columns = pixels): lane (pixel, kk) holds dy rows 2i+P-3+2kk and +1, columns 2j+P-3 .. +3 --
 //     two 8-byte reads from a dy tile that sits in LDS exactly as it sits in memory.
 // Nothing is transposed or parity-split on the way in: staging is a copy (16-byte pieces, the tile
-// origin at an even LDS element so that the window reads are 4-byte aligned; pieces that straddle
-// an end of their dy row are fetched from inside the row and shifted into place).
+// origin at an even LDS element so that the window reads are 4-byte aligned; a piece that hangs
+// over an end of its dy row is fetched from inside the row and written where those columns belong,
+// at a 2-byte-aligned LDS address).
 //
 // Block = 4 waves, tile = 128 input channels x 512 pixels ((image, row) pairs x TJ columns); a wave
 // owns all 128 channels of 128 pixels: 16 accumulator tiles in 256 accumulation registers, one wave
 // per SIMD.  A stage is 8 output channels (8 x 16 MFMAs per wave); both operands are double
 // buffered in LDS and the next stage's pieces are written, and the registers refilled for the
-// stage after next, one item after one MFMA, so that the matrix pipe never waits for staging.
+// stage after next, one item after one MFMA.  Blocks are persistent: one per compute unit, each
+// walking over every gridDim.x-th tile with the staging pipeline running on into the next tile.
 #include "ukst_internal.h"
 
 namespace ukst {
