@@ -301,6 +301,7 @@ bool narrow_args(const Geom& g, int dtype, NarrowGradArgs& a)
     if ((size_t)g.H * g.W * 4 >= 0x7FFF0000u || (size_t)g.OH * g.OW * 4 >= 0x7FFF0000u) return false;
     a.g = g;
     a.chunks = (g.W + 64 * PXL - 1) / (64 * PXL);
+    if ((long long)g.B * g.H * a.chunks > 0x3fffffffLL) return false;  // work items are counted in an int
     return true;
 }
 
