@@ -97,7 +97,8 @@ def test_backward_bf16_kernel_gradient_on_the_bf16_matrix_pipe(shape):
     (4, 256, 32, 16, 16, 4, 2),    # cfg5b's map: two images per tile, two channel tiles
     (1, 128, 64, 24, 128, 4, 2),   # cfg5a's rows: both column tiles touch one end of the dy rows
     (2, 128, 24, 8, 16, 4, 2),     # three stages of output channels: padded with a stage of zeros
-    (1, 72, 8, 5, 40, 4, 1)])      # a single stage
+    (1, 72, 8, 5, 40, 4, 1),       # a single stage
+    (2, 128, 16, 6, 20, 4, 5)])    # P > n - 1: no window begins left of its row, the first dy rows meet nothing
 def test_backward_bf16_input_gradient_with_the_taps_in_the_contraction(shape):
     """bf16 layers with 4 x 4 kernels, more than 64 input channels in multiples of 8, output channels
     in multiples of 8 and maps at least 16 wide take the input gradient on the bf16 MFMA pipe with a channel's 16
