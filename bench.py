@@ -127,7 +127,8 @@ def _roof(bound, exact_flop, nbytes, per_s, kernel, traffic):
 def measure(w, steps, warmup, rotate_bytes=LLC_BYTES + (64 << 20), fused=False, out_bf16=False,
             workspace=True, keep_data=False):
     """Time launches of workload w.  workspace=True: ukst_conv_transpose2d_ws with a workspace of
-    ukst_workspace_bytes allocated once, outside the timed region (only cfg3 L1/L2 use one);
+    ukst_workspace_bytes allocated once, outside the timed region (no benchmark shape asks for one
+    any more: the figure is zero and the call equals the plain one);
     False: ukst_conv_transpose2d, the entry point that takes none."""
     import torch
     from paper_2502_20493_amd import binding as ukst
