@@ -1,5 +1,9 @@
-// Gradient with respect to the input for bf16 operands and 4 x 4 kernels, on the bf16 matrix pipe
-// with the taps inside the contraction.
+// Gradient with respect to the input for bf16 operands and 4 x 4 (or 3 x 3) kernels, on the bf16
+// matrix pipe with the taps inside the contraction.  (Written for n = 4 below; a 3 x 3 kernel sits in
+// the same 4 x 4 frame, which then starts at (2i+P-2, 2j+P-2) and has zero weights in its last row and
+// column: 9 of the 16 K slots do useful work, which is still twice as fast as transposing dy.  A dy
+// value that is not finite therefore also reaches the one input pixel whose frame holds it in a
+// zero-weight slot.)
 //
 // Differentiating Eqs. 1-4 gives dx[b,ci,i,j] = sum_co sum_{k,l} dy[b,co,2i+P-k,2j+P-l] w[co,ci,k,l]:
 // a stride-2 convolution of dy with the kernel, in which every tap meets data (no inserted zeros
@@ -67,10 +71,11 @@ __device__ __forceinline__ int opaque(int v)
     return v;
 }
 
-// wp[cit][co][kk][ci % 128][e]: tap (kr, lr) = (2 kk + e / 4, e % 4) is w[co][ci][3 - kr][3 - lr]
+// wp[cit][co][kk][ci % 128][e]: slot (kr, lr) = (2 kk + e / 4, e % 4) of the 4 x 4 frame is
+// w[co][ci][n-1-kr][n-1-lr], zero where that tap does not exist (n = 3: the last frame row and column)
 __global__ __launch_bounds__(256) void ukst_pack_w_window_kernel(const uint16_t* __restrict__ w,
                                                                 uint16_t* __restrict__ wp, int Cout, int Cin,
-                                                                int CIp)
+                                                                int CIp, int n)
 {
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (size_t)CIp * Cout * 16) return;
@@ -81,7 +86,8 @@ __global__ __launch_bounds__(256) void ukst_pack_w_window_kernel(const uint16_t*
     const int co = (int)(r % Cout), cit = (int)(r / Cout);
     const int ci = cit * CI_T + cil;
     const int kr = 2 * kk + (e >> 2), lr = e & 3;
-    wp[idx] = ci < Cin ? w[((size_t)co * Cin + ci) * 16 + (3 - kr) * 4 + (3 - lr)] : (uint16_t)0;
+    const int k = n - 1 - kr, l = n - 1 - lr;
+    wp[idx] = ci < Cin && k >= 0 && l >= 0 ? w[((size_t)co * Cin + ci) * (n * n) + k * n + l] : (uint16_t)0;
 }
 
 template <int SD>  // dwords per staged dy row
@@ -135,7 +141,7 @@ void ukst_grad_input_window_mfma_bf16_kernel(const uint16_t* __restrict__ dy, co
         rs_w = __builtin_amdgcn_make_buffer_rsrc((void*)(wp + (size_t)t.cit * g.Cout * (2 * CI_T * 8)), 0,
                                                  nreal * A_BYTES, kRsrcFlags);
         a_voff = present ? (unsigned)tid16 : kInvalid;
-        const int oy_base = 2 * t.i0 + g.P - 3, ox_base = 2 * t.j0 + g.P - 3;
+        const int oy_base = 2 * t.i0 + g.P - (g.n - 1), ox_base = 2 * t.j0 + g.P - (g.n - 1);
         const int tid_o = opaque(tid);  // nothing of this is to be kept from tile to tile
 #pragma unroll
         for (int u = 0; u < NPB; ++u) {
@@ -154,7 +160,7 @@ void ukst_grad_input_window_mfma_bf16_kernel(const uint16_t* __restrict__ dy, co
     };
     // Store side: where the pieces go in buffer `buf` (depends on the tile's columns only)
     auto aim_stores = [&](const Tile& t, int buf) {
-        const int ox_base = 2 * t.j0 + g.P - 3;
+        const int ox_base = 2 * t.j0 + g.P - (g.n - 1);
         const int tid_o = opaque(tid);
 #pragma unroll
         for (int u = 0; u < NPB; ++u) {
@@ -366,7 +372,7 @@ int log2_of(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
 
 static bool gi_win_args(const Geom& g, GiWinArgs& a)
 {
-    if (g.n != 4 || g.Cout % KC != 0 || g.Cin <= 64 || g.Cin % 8 != 0 || g.W < 16 || g.OW < 8 || g.H < 1)
+    if ((g.n != 4 && g.n != 3) || g.Cout % KC != 0 || g.Cin <= 64 || g.Cin % 8 != 0 || g.W < 16 || g.OW < 8 || g.H < 1)
         return false;
     a.g = g;
     a.TJ = g.W <= 16 ? 16 : g.W <= 32 ? 32 : 64;
@@ -400,7 +406,7 @@ static bool gi_win_args(const Geom& g, GiWinArgs& a)
     a.dRows = make_fastdiv((unsigned)a.rows);
     a.dLR = make_fastdiv((unsigned)a.LR);
     // a piece moved back inside its row must not start before its tile's first column
-    if (2 * (a.tilesX - 1) * a.TJ + g.P - 3 + 8 > g.OW) return false;
+    if (2 * (a.tilesX - 1) * a.TJ + g.P - (g.n - 1) + 8 > g.OW) return false;
     const size_t plane = (size_t)g.OH * g.OW;
     // offsets inside a tile's images and inside a channel tile's weights stay below the invalid mark
     if ((size_t)a.TB * g.Cout * plane * 2 + 64 >= 0xFFFFFF00u) return false;
@@ -429,7 +435,7 @@ hipError_t launch_grad_input_window(const Geom& g, const void* dy, const void* w
     if (ws.bytes < need) return kWorkspaceTooSmall;
     uint16_t* wp = (uint16_t*)ws.ptr;
     hipLaunchKernelGGL(ukst_pack_w_window_kernel, dim3((unsigned)((pelems + 255) / 256)), dim3(256), 0, stream,
-                       (const uint16_t*)w, wp, g.Cout, g.Cin, a.ciTiles * CI_T);
+                       (const uint16_t*)w, wp, g.Cout, g.Cin, a.ciTiles * CI_T, g.n);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const size_t lds = 2 * (size_t)A_BYTES + 2 * (size_t)a.bBytes;

@@ -98,9 +98,12 @@ def test_backward_bf16_kernel_gradient_on_the_bf16_matrix_pipe(shape):
     (1, 128, 64, 24, 128, 4, 2),   # cfg5a's rows: both column tiles touch one end of the dy rows
     (2, 128, 24, 8, 16, 4, 2),     # three stages of output channels: padded with a stage of zeros
     (1, 72, 8, 5, 40, 4, 1),       # a single stage
-    (2, 128, 16, 6, 20, 4, 5)])    # P > n - 1: no window begins left of its row, the first dy rows meet nothing
+    (2, 128, 16, 6, 20, 4, 5),     # P > n - 1: no window begins left of its row, the first dy rows meet nothing
+    (2, 128, 16, 8, 16, 3, 1),     # 3 x 3 kernels in the 4 x 4 frame: 16-pixel rows
+    (1, 136, 24, 9, 70, 3, 0),     # ... two column tiles, P = 0, three stages
+    (3, 160, 32, 20, 40, 3, 2)])   # ... P = n - 1
 def test_backward_bf16_input_gradient_with_the_taps_in_the_contraction(shape):
-    """bf16 layers with 4 x 4 kernels, more than 64 input channels in multiples of 8, output channels
+    """bf16 layers with 4 x 4 or 3 x 3 kernels, more than 64 input channels in multiples of 8, output channels
     in multiples of 8 and maps at least 16 wide take the input gradient on the bf16 MFMA pipe with a channel's 16
     taps as the contraction (dy staged as it lies in memory, row-end pieces written at 2-byte-aligned
     LDS addresses): every element, integer-valued data exactly."""
