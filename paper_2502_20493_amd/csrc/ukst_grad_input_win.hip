@@ -77,17 +77,35 @@ __global__ __launch_bounds__(256) void ukst_pack_w_window_kernel(const uint16_t*
                                                                 uint16_t* __restrict__ wp, int Cout, int Cin,
                                                                 int CIp, int n)
 {
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (size_t)CIp * Cout * 16) return;
-    const int e = (int)(idx & 7);
-    const int cil = (int)((idx >> 3) & (CI_T - 1));
-    const int kk = (int)((idx >> 10) & 1);
-    const size_t r = idx >> 11;
+    // one thread per 16-byte piece: the eight slots e of (cit, co, kk, ci)
+    const size_t piece = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (piece >= (size_t)CIp * Cout * 2) return;
+    const int cil = (int)(piece & (CI_T - 1));
+    const int kk = (int)((piece >> 7) & 1);
+    const size_t r = piece >> 8;
     const int co = (int)(r % Cout), cit = (int)(r / Cout);
     const int ci = cit * CI_T + cil;
-    const int kr = 2 * kk + (e >> 2), lr = e & 3;
-    const int k = n - 1 - kr, l = n - 1 - lr;
-    wp[idx] = ci < Cin && k >= 0 && l >= 0 ? w[((size_t)co * Cin + ci) * (n * n) + k * n + l] : (uint16_t)0;
+    u32x4 out = {0u, 0u, 0u, 0u};
+    if (ci < Cin) {
+        const uint16_t* src = w + ((size_t)co * Cin + ci) * (n * n);
+        if (n == 4) {
+            // slots 8 kk .. 8 kk + 7 are taps 15 - 8 kk down to 8 - 8 kk: eight consecutive taps, reversed
+            const u32x4a2 q = *reinterpret_cast<const u32x4a2*>(src + 8 * (1 - kk));
+            const unsigned t[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) out[j] = __builtin_amdgcn_alignbit(t[3 - j], t[3 - j], 16);  // halves swapped
+        } else {
+            unsigned h[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int k = n - 1 - (2 * kk + (e >> 2)), l = n - 1 - (e & 3);
+                h[e] = k >= 0 && l >= 0 ? src[k * n + l] : 0u;
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) out[j] = h[2 * j] | (h[2 * j + 1] << 16);
+        }
+    }
+    *reinterpret_cast<u32x4*>(wp + piece * 8) = out;
 }
 
 template <int SD>  // dwords per staged dy row
@@ -434,7 +452,7 @@ hipError_t launch_grad_input_window(const Geom& g, const void* dy, const void* w
     if (ws.query) { ws.need = need; return hipSuccess; }
     if (ws.bytes < need) return kWorkspaceTooSmall;
     uint16_t* wp = (uint16_t*)ws.ptr;
-    hipLaunchKernelGGL(ukst_pack_w_window_kernel, dim3((unsigned)((pelems + 255) / 256)), dim3(256), 0, stream,
+    hipLaunchKernelGGL(ukst_pack_w_window_kernel, dim3((unsigned)((pelems / 8 + 255) / 256)), dim3(256), 0, stream,
                        (const uint16_t*)w, wp, g.Cout, g.Cin, a.ciTiles * CI_T, g.n);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
