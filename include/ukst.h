@@ -242,7 +242,7 @@ size_t ukst_static_workspace_bytes(void);
  * ukst_conv_transpose2d_grad_input, 1: ukst_conv_transpose2d_grad_weight), as it appears in a
  * profiler's kernel trace (substring match), or "" on invalid arguments.  Static storage.
  * Wide layers (Cin >= 32, Cout >= 16) run the input gradient on the matrix cores
- * ("ukst_grad_input_window_mfma_bf16_kernel": bf16 operands, n = 4 or 3, Cin > 64 and a multiple of 8,
+ * ("ukst_grad_input_window_mfma_bf16_kernel": bf16 operands, 2 <= n <= 4, Cin > 64 and a multiple of 8,
  * Cout a multiple of 8, W >= 16 -- bf16 MFMA with an output channel's 16 taps as the contraction;
  * "ukst_grad_input_mfma_bf16_kernel": bf16 MFMA for other bf16 operands where its LDS tile fits,
  * i.e. kernel sides up to about 5;

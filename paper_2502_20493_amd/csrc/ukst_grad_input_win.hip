@@ -1,9 +1,9 @@
-// Gradient with respect to the input for bf16 operands and 4 x 4 (or 3 x 3) kernels, on the bf16
-// matrix pipe with the taps inside the contraction.  (Written for n = 4 below; a 3 x 3 kernel sits in
-// the same 4 x 4 frame, which then starts at (2i+P-2, 2j+P-2) and has zero weights in its last row and
-// column: 9 of the 16 K slots do useful work, which is still twice as fast as transposing dy.  A dy
-// value that is not finite therefore also reaches the one input pixel whose frame holds it in a
-// zero-weight slot.)
+// Gradient with respect to the input for bf16 operands and kernels of up to 4 x 4, on the bf16
+// matrix pipe with the taps inside the contraction.  (Written for n = 4 below; a smaller kernel sits
+// in the same 4 x 4 frame, which then starts at (2i+P-(n-1), 2j+P-(n-1)) and has zero weights in its
+// last 4-n rows and columns: 9 (n = 3) or 4 (n = 2) of the 16 K slots do useful work, which is still
+// twice as fast as transposing dy.  A dy value that is not finite therefore also reaches the input
+// pixels whose frames hold it in a zero-weight slot.)
 //
 // Differentiating Eqs. 1-4 gives dx[b,ci,i,j] = sum_co sum_{k,l} dy[b,co,2i+P-k,2j+P-l] w[co,ci,k,l]:
 // a stride-2 convolution of dy with the kernel, in which every tap meets data (no inserted zeros
@@ -72,7 +72,7 @@ __device__ __forceinline__ int opaque(int v)
 }
 
 // wp[cit][co][kk][ci % 128][e]: slot (kr, lr) = (2 kk + e / 4, e % 4) of the 4 x 4 frame is
-// w[co][ci][n-1-kr][n-1-lr], zero where that tap does not exist (n = 3: the last frame row and column)
+// w[co][ci][n-1-kr][n-1-lr], zero where that tap does not exist (n < 4: the last frame rows and columns)
 __global__ __launch_bounds__(256) void ukst_pack_w_window_kernel(const uint16_t* __restrict__ w,
                                                                 uint16_t* __restrict__ wp, int Cout, int Cin,
                                                                 int CIp, int n)
@@ -390,7 +390,7 @@ int log2_of(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
 
 static bool gi_win_args(const Geom& g, GiWinArgs& a)
 {
-    if ((g.n != 4 && g.n != 3) || g.Cout % KC != 0 || g.Cin <= 64 || g.Cin % 8 != 0 || g.W < 16 || g.OW < 8 || g.H < 1)
+    if (g.n < 2 || g.n > 4 || g.Cout % KC != 0 || g.Cin <= 64 || g.Cin % 8 != 0 || g.W < 16 || g.OW < 8 || g.H < 1)
         return false;
     a.g = g;
     a.TJ = g.W <= 16 ? 16 : g.W <= 32 ? 32 : 64;

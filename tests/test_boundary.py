@@ -241,10 +241,11 @@ def test_backward_kernel_selection_is_host_arithmetic():
     # bf16 layers the bf16-pipe kernel gradient does not take (n = 5, rows that are no multiple of 8)
     assert name(1, 2, 64, 64, 16, 16, 5, 2, ukst.UKST_BF16_F32) == "ukst_grad_weight_mfma_kernel"
     assert name(1, 2, 64, 64, 16, 20, 4, 2, ukst.UKST_BF16_F32) == "ukst_grad_weight_mfma_kernel"
-    # bf16 layers the window kernel does not take: n other than 3 or 4, at most 64 input channels or no multiple of
+    # bf16 layers the window kernel does not take: n other than 2, 3 or 4, at most 64 input channels or no multiple of
     # 8, output channels that are no multiple of 8, maps narrower than 16
     assert name(0, 2, 132, 32, 16, 16, 4, 2, ukst.UKST_BF16_F32) == "ukst_grad_input_mfma_bf16_kernel"
-    assert name(0, 2, 128, 32, 16, 16, 2, 0, ukst.UKST_BF16_F32) == "ukst_grad_input_mfma_bf16_kernel"
+    assert name(0, 2, 128, 32, 16, 16, 2, 0, ukst.UKST_BF16_F32) == "ukst_grad_input_window_mfma_bf16_kernel"
+    assert name(0, 2, 128, 32, 16, 16, 1, 0, ukst.UKST_BF16_F32) != "ukst_grad_input_window_mfma_bf16_kernel"
     assert name(0, 2, 128, 32, 16, 16, 5, 2, ukst.UKST_BF16_F32) == "ukst_grad_input_mfma_bf16_kernel"
     assert name(0, 2, 128, 32, 16, 16, 3, 1, ukst.UKST_BF16_F32) == "ukst_grad_input_window_mfma_bf16_kernel"
     assert name(0, 2, 64, 32, 16, 16, 4, 2, ukst.UKST_BF16_F32) == "ukst_grad_input_mfma_bf16_kernel"

@@ -101,9 +101,11 @@ def test_backward_bf16_kernel_gradient_on_the_bf16_matrix_pipe(shape):
     (2, 128, 16, 6, 20, 4, 5),     # P > n - 1: no window begins left of its row, the first dy rows meet nothing
     (2, 128, 16, 8, 16, 3, 1),     # 3 x 3 kernels in the 4 x 4 frame: 16-pixel rows
     (1, 136, 24, 9, 70, 3, 0),     # ... two column tiles, P = 0, three stages
-    (3, 160, 32, 20, 40, 3, 2)])   # ... P = n - 1
+    (3, 160, 32, 20, 40, 3, 2),    # ... P = n - 1
+    (2, 128, 16, 8, 16, 2, 0),     # 2 x 2 kernels in the frame: 16-pixel rows
+    (1, 136, 24, 9, 70, 2, 1)])    # ... two column tiles, P = n - 1
 def test_backward_bf16_input_gradient_with_the_taps_in_the_contraction(shape):
-    """bf16 layers with 4 x 4 or 3 x 3 kernels, more than 64 input channels in multiples of 8, output channels
+    """bf16 layers with kernels of 2 x 2 to 4 x 4, more than 64 input channels in multiples of 8, output channels
     in multiples of 8 and maps at least 16 wide take the input gradient on the bf16 MFMA pipe with a channel's 16
     taps as the contraction (dy staged as it lies in memory, row-end pieces written at 2-byte-aligned
     LDS addresses): every element, integer-valued data exactly."""
