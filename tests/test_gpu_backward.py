@@ -212,7 +212,7 @@ def test_backward_cfg5_wide_bf16_full_size(name):
 def test_backward_window_kernel_walks_over_tiles_whose_rows_end_elsewhere():
     """288 tiles of the bf16 window kernel on 256 compute units: blocks take a second tile, and with
     three column tiles per row it lies in another column, so the staging buffers are cleared and
-    re-aimed between the two.  Sampled planes (the last image is second-round work), integer data
+    re-aimed between the two.  Sampled planes (the last image is among the second tiles of their blocks), integer data
     exactly."""
     w = _mk("bwd_window_walk", 6990, 12, 128, 16, 64, 192, 4, 2, dtype="bf16")
     assert ukst.ukst_grad_kernel_name(0, w.B, w.Cin, w.Cout, w.H, w.W, w.n, w.P, ukst.UKST_BF16_F32) == \
